@@ -1,0 +1,209 @@
+/*
+ * rsd.h - C ABI of the Reward-Guided Speculative Decoding (RSD) hot path for
+ * AMD MI355X (gfx950).
+ *
+ * One context runs the loop of the paper's Algorithm 1 (Section 2.1) for a
+ * batch of independent sequences: per reasoning step the draft model m decodes
+ * a candidate step, the process reward model r scores it with one scalar, the
+ * acceptance criterion A_omega (Algorithm 2, Section 2.2; weighting functions
+ * of Table 1) keeps it or the target model M regenerates the step from the
+ * same context z_i = [x, y_1..i-1].  Inputs follow Algorithm 1's list: prompts
+ * x, the three models, the criterion (delta, omega), the EOS token and the
+ * length limits; the reasoning-step separator of Section 3 ("Default
+ * Setting") and the sampling uniforms are explicit arguments.
+ *
+ * Conventions
+ *  - "dev" pointers are device (HBM) addresses, "host" pointers are ordinary
+ *    host memory.  The library never frees or writes caller memory except the
+ *    output buffers named below.  Weights, uniforms and teacher buffers are
+ *    BORROWED: they must stay valid and unchanged while the context lives.
+ *  - All GPU work is enqueued on the HIP stream given to rsd_init.  Calls
+ *    return after their host-visible outputs are valid.
+ *  - Every entry point returns RSD_OK (0) or a negative code; the text of the
+ *    last failure is available from rsd_last_error.  Nothing aborts or throws.
+ *  - A context is not thread-safe; distinct contexts may be used concurrently.
+ */
+#ifndef RSD_H
+#define RSD_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define RSD_OK       0
+#define RSD_EINVAL  (-1)  /* bad shape or argument */
+#define RSD_ENOMEM  (-2)  /* KV page pool exhausted; sequence state is as before the call */
+#define RSD_ESTATE  (-3)  /* call not valid in the current state (e.g. step after all finished) */
+#define RSD_EHIP    (-4)  /* HIP runtime error */
+
+enum { RSD_F32 = 0, RSD_BF16 = 1 };                 /* storage type of weights and KV cache */
+enum { RSD_HEAD_LM = 0, RSD_HEAD_REWARD = 1 };
+enum { RSD_DRAFT = 0, RSD_TARGET = 1, RSD_PRM = 2 };
+/* weighting functions omega(r) of Table 1 */
+enum { RSD_OMEGA_BINARY = 0,    /* 1(r >= delta): the paper's default                */
+       RSD_OMEGA_CONSTANT = 1,  /* omega_a                                             */
+       RSD_OMEGA_CLIP = 2,      /* min(1, max(0, r))                                   */
+       RSD_OMEGA_RATIO = 3,     /* max(0, r / (1 + r))                                 */
+       RSD_OMEGA_LOGISTIC = 4   /* 1 / (1 + exp(-omega_a (r - delta)))                 */ };
+/* why a sequence stopped */
+enum { RSD_RUNNING = 0, RSD_FIN_EOS = 1, RSD_FIN_MAX_CTX = 2, RSD_FIN_MAX_STEPS = 3 };
+
+/* Decoder-only transformer: RMSNorm, rotary embedding (rotate-half pairing,
+ * angle pos * theta^(-2i/hd)), grouped-query attention with head_dim =
+ * d_model / n_heads (32 or 128), SwiGLU MLP, untied head.  Constraints:
+ * d_model, d_ffn and head_dim multiples of 8; n_heads % n_kv_heads == 0 with a
+ * group of at most 8 query heads per KV head. */
+typedef struct rsd_model_shape {
+    int32_t n_layers, d_model, n_heads, n_kv_heads, d_ffn, vocab;
+    float   rope_theta, rms_eps;
+    int32_t dtype;       /* RSD_F32 | RSD_BF16 */
+    int32_t head_kind;   /* RSD_HEAD_LM: lm_head[vocab][d] | RSD_HEAD_REWARD: w_r[d], b_r */
+} rsd_model_shape;
+
+/* One model's weights: a single dev blob, row-major [out][in] matrices of the
+ * model's dtype in this order:
+ *   embed[vocab][d];
+ *   per layer: attn_norm[d], wq[H*hd][d], wk[Hkv*hd][d], wv[Hkv*hd][d],
+ *              wo[d][H*hd], ffn_norm[d], w_gate[F][d], w_up[F][d], w_down[d][F];
+ *   final_norm[d];
+ *   lm_head[vocab][d]            (RSD_HEAD_LM)
+ *   w_r[d], b_r[8] (b_r[0] used) (RSD_HEAD_REWARD; reward = logistic(w_r.y + b_r),
+ *                                 the scalar projection on the last layer described
+ *                                 in the appendix section "Model Merge")
+ * The blob must be 16-byte aligned. */
+typedef struct rsd_weights { const void *blob; uint64_t nbytes; } rsd_weights;
+
+typedef struct rsd_params {
+    float   delta;          /* threshold of the binary step / centre of the logistic */
+    int32_t omega_kind;     /* RSD_OMEGA_* */
+    float   omega_a;        /* constant p, or logistic slope alpha */
+    int32_t sep_id;         /* token that ends a reasoning step (the step includes it) */
+    int32_t eos_id;         /* -1: none */
+    int32_t step_cap;       /* most tokens in one step */
+    int32_t max_steps;      /* iterations of Algorithm 1's loop */
+    int32_t max_ctx;        /* most tokens per sequence, prompt included */
+    float   temperature;    /* 0: greedy (lowest id on ties) */
+    float   top_p;          /* nucleus mass, used when temperature > 0 */
+    float   sep_logit_bias; /* added to the separator's logit before sampling (synthetic workloads) */
+    int32_t page_tokens;    /* tokens per KV page; must be 16 */
+    uint64_t kv_pool_bytes[3]; /* KV page pool per model (draft, target, reward); 0: enough for batch * max_ctx */
+    int32_t use_graphs;     /* 1: replay single-token decode iterations as HIP graphs */
+    int32_t reserved;
+} rsd_params;
+
+/* Per-step record, all HOST buffers supplied by the caller (any may be NULL).
+ * Index b is the sequence. */
+typedef struct rsd_step_out {
+    int32_t *draft_len;     /* [B]            tokens in the draft step (0 if the sequence was finished) */
+    int32_t *draft_tokens;  /* [B][step_cap]  the draft step as appended                                 */
+    float   *reward;        /* [B]            r_i of the draft step                                      */
+    int32_t *accepted;      /* [B]            decision applied                                           */
+    int32_t *own_accept;    /* [B]            decision the criterion took (differs only under a teacher) */
+    int32_t *final_len;     /* [B]            tokens in the committed step                               */
+    int32_t *final_tokens;  /* [B][step_cap]                                                             */
+    int32_t *finished;      /* [B]            RSD_RUNNING or a RSD_FIN_* reason, after this step         */
+} rsd_step_out;
+
+typedef struct rsd_gen_out {
+    int32_t *tokens;        /* host [B][max_ctx] or NULL */
+    int32_t *ctx_len;       /* host [B] or NULL */
+    int32_t *finished;      /* host [B] or NULL */
+    int32_t  steps_run;
+    int64_t  n_committed;   /* tokens committed over all sequences (what tokens/s counts) */
+    int64_t  n_draft;       /* tokens the draft model sampled (rejected ones included)    */
+    int64_t  n_target;      /* tokens the target model sampled                            */
+    int64_t  n_accept;      /* accepted steps */
+    int64_t  n_reject;      /* rejected steps */
+} rsd_gen_out;
+
+typedef struct rsd_ctx rsd_ctx;
+
+/* Create a context for `batch` sequences.  shape[i]/w[i] with i = RSD_DRAFT,
+ * RSD_TARGET, RSD_PRM; draft and target need RSD_HEAD_LM and one common
+ * vocabulary, the reward model RSD_HEAD_REWARD.  Allocates the KV page pools,
+ * block tables, rotary tables and workspaces (library-owned, freed by
+ * rsd_destroy).  hip_stream is a hipStream_t (NULL: the default stream). */
+int rsd_init(rsd_ctx **out, const rsd_model_shape shape[3], const rsd_weights w[3],
+             const rsd_params *p, int32_t batch, void *hip_stream);
+
+/* Load prompts x and reset every sequence to "no step taken": tokens is dev
+ * [B][max_ctx] int32 (only the first prompt_len[b] entries of a row are read),
+ * prompt_len is host [B], each in [1, max_ctx]. */
+int rsd_set_prompts(rsd_ctx *c, const int32_t *tokens_dev, const int32_t *prompt_len_host);
+
+/* Uniforms in [0,1), BORROWED dev arrays: u_draft/u_target [B][max_ctx], the
+ * token placed at absolute position i of sequence b is drawn with u[b][i];
+ * u_gate [B][max_steps] is the draw of Algorithm 2 for step i (only read when
+ * omega(r) is strictly between 0 and 1).  May be NULL when never needed
+ * (greedy decoding / binary omega). */
+int rsd_set_uniforms(rsd_ctx *c, const float *u_draft_dev, const float *u_target_dev,
+                     const float *u_gate_dev);
+
+/* Change delta / omega without rebuilding the context (takes effect at the next step). */
+int rsd_set_criterion(rsd_ctx *c, float delta, int32_t omega_kind, float omega_a);
+
+/* One iteration of Algorithm 1's loop body for all unfinished sequences:
+ * draft step, reward, criterion, target step for the rejected ones, EOS test.
+ * On RSD_ENOMEM the sequences are left as before the call. */
+int rsd_step(rsd_ctx *c, rsd_step_out *out);
+
+/* Algorithm 1's loop: rsd_step until every sequence has finished or max_steps
+ * (<= params.max_steps, 0 = params.max_steps) steps have run since the prompts
+ * were set. */
+int rsd_generate(rsd_ctx *c, int32_t max_steps, rsd_gen_out *out);
+
+/* Sequence state for bit-exact checks, HOST buffers (any may be NULL):
+ * ctx_len [B]; kv_len [3][B] = leading tokens each model holds keys/values
+ * for; n_pages [3][B] = KV pages owned; tokens [B][max_ctx]. */
+int rsd_export_state(rsd_ctx *c, int32_t *ctx_len, int32_t *kv_len, int32_t *n_pages,
+                     int32_t *tokens);
+
+/* Page bookkeeping of one model, HOST buffers: block_table [B][max_pages]
+ * (physical page of each logical page, -1 beyond n_pages), *max_pages,
+ * *pool_pages, *free_pages. */
+int rsd_export_pages(rsd_ctx *c, int32_t model, int32_t *block_table, int32_t *max_pages,
+                     int32_t *pool_pages, int32_t *free_pages);
+
+/* Teacher forcing for parity tests, BORROWED dev arrays (NULL switches a part
+ * off): forced_draft / forced_target [B][max_ctx]: when >= 0, the token
+ * appended at that position by that model is the forced one (the model's own
+ * choice is still recorded, see rsd_export_sampled); forced_accept
+ * [B][max_steps]: when >= 0, the decision applied at that step. */
+int rsd_set_teacher(rsd_ctx *c, const int32_t *forced_draft_dev, const int32_t *forced_target_dev,
+                    const int32_t *forced_accept_dev);
+
+/* The tokens each model's sampler chose, by absolute position: HOST
+ * [B][max_ctx] each, -1 where the model sampled nothing. */
+int rsd_export_sampled(rsd_ctx *c, int32_t *sampled_draft, int32_t *sampled_target);
+
+/* Teacher-forced evaluation of one model for parity tests.  tokens is host
+ * [B][T], lens host [B] (<= T).  Sequence b is fed in pieces of `chunk` tokens
+ * (chunk == 1 runs the single-token decode kernels, larger values the chunked
+ * prefill kernels) through the model's own paged KV cache, starting empty.
+ * out is dev fp32: [B][T][vocab] logits for RSD_HEAD_LM models, [B][T] rewards
+ * for the reward model; entries at positions >= lens[b] are not written.
+ * Resets the sequences: call rsd_set_prompts before stepping again. */
+int rsd_forward(rsd_ctx *c, int32_t model, const int32_t *tokens_host, const int32_t *lens_host,
+                int32_t T, int32_t chunk, float *out_dev);
+
+/* The sampler alone: for each of n rows pick a token from logits[row][vocab]
+ * (dev fp32) with uniform u[row] (dev), at the given temperature / top_p
+ * (temperature 0: arg max).  out_dev is dev int32 [n]. */
+int rsd_sample(rsd_ctx *c, const float *logits_dev, const float *u_dev, int32_t n, int32_t vocab,
+               float temperature, float top_p, int32_t *out_dev);
+
+/* Wall-clock milliseconds spent in the stages of rsd_step since the context was
+ * created or the counters were last reset (host timers around synchronised
+ * stages): ms[0] draft, ms[1] reward model, ms[2] criterion + rollback,
+ * ms[3] target.  reset != 0 clears them after reading. */
+int rsd_stage_ms(rsd_ctx *c, double ms[4], int32_t reset);
+
+const char *rsd_last_error(const rsd_ctx *c);
+void rsd_destroy(rsd_ctx *c);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RSD_H */

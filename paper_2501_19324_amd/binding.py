@@ -1,0 +1,257 @@
+"""Thin ctypes binding of the C ABI declared in ``include/rsd.h``.
+
+Argument marshalling only: every function here forwards to the entry point of
+the same name in ``librsd.so``.  Device buffers are torch tensors (torch is
+used for device memory and the stream handle, nothing else); host buffers are
+NumPy arrays.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+
+__all__ = ["RSD_OK", "RSD_EINVAL", "RSD_ENOMEM", "RSD_ESTATE", "RSD_EHIP", "RSD_DRAFT", "RSD_TARGET", "RSD_PRM",
+           "RsdError", "Context", "load_library", "rsd_init", "rsd_set_prompts", "rsd_set_uniforms",
+           "rsd_set_criterion", "rsd_step", "rsd_generate", "rsd_export_state", "rsd_export_pages",
+           "rsd_set_teacher", "rsd_export_sampled", "rsd_forward", "rsd_sample", "rsd_stage_ms", "rsd_destroy",
+           "EXPORTED_SYMBOLS"]
+
+RSD_OK, RSD_EINVAL, RSD_ENOMEM, RSD_ESTATE, RSD_EHIP = 0, -1, -2, -3, -4
+RSD_DRAFT, RSD_TARGET, RSD_PRM = 0, 1, 2
+EXPORTED_SYMBOLS = ["rsd_init", "rsd_set_prompts", "rsd_set_uniforms", "rsd_set_criterion", "rsd_step",
+                    "rsd_generate", "rsd_export_state", "rsd_export_pages", "rsd_set_teacher",
+                    "rsd_export_sampled", "rsd_forward", "rsd_sample", "rsd_stage_ms", "rsd_last_error",
+                    "rsd_destroy"]
+LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "librsd.so")
+
+
+class RsdError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__(f"rsd error {code}: {text}")
+        self.code = code
+
+
+class _Shape(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("d_model", C.c_int32), ("n_heads", C.c_int32), ("n_kv_heads", C.c_int32),
+                ("d_ffn", C.c_int32), ("vocab", C.c_int32), ("rope_theta", C.c_float), ("rms_eps", C.c_float),
+                ("dtype", C.c_int32), ("head_kind", C.c_int32)]
+
+
+class _Weights(C.Structure):
+    _fields_ = [("blob", C.c_void_p), ("nbytes", C.c_uint64)]
+
+
+class _Params(C.Structure):
+    _fields_ = [("delta", C.c_float), ("omega_kind", C.c_int32), ("omega_a", C.c_float), ("sep_id", C.c_int32),
+                ("eos_id", C.c_int32), ("step_cap", C.c_int32), ("max_steps", C.c_int32), ("max_ctx", C.c_int32),
+                ("temperature", C.c_float), ("top_p", C.c_float), ("sep_logit_bias", C.c_float),
+                ("page_tokens", C.c_int32), ("kv_pool_bytes", C.c_uint64 * 3), ("use_graphs", C.c_int32),
+                ("reserved", C.c_int32)]
+
+
+class _StepOut(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("draft_len", "draft_tokens", "reward", "accepted", "own_accept",
+                                          "final_len", "final_tokens", "finished")]
+
+
+class _GenOut(C.Structure):
+    _fields_ = [("tokens", C.c_void_p), ("ctx_len", C.c_void_p), ("finished", C.c_void_p), ("steps_run", C.c_int32),
+                ("n_committed", C.c_int64), ("n_draft", C.c_int64), ("n_target", C.c_int64),
+                ("n_accept", C.c_int64), ("n_reject", C.c_int64)]
+
+
+_lib = None
+
+
+def load_library(path: Optional[str] = None):
+    """Load ``librsd.so``; raises if it has not been built."""
+    global _lib
+    if _lib is None or path is not None:
+        p = path or LIB_PATH
+        if not os.path.exists(p):
+            raise RuntimeError(f"{p} is missing: build it first (python -m paper_2501_19324_amd.build); "
+                               "there is no fallback path")
+        lib = C.CDLL(p)
+        lib.rsd_last_error.restype = C.c_char_p
+        lib.rsd_last_error.argtypes = [C.c_void_p]
+        lib.rsd_destroy.restype = None
+        lib.rsd_destroy.argtypes = [C.c_void_p]
+        _lib = lib
+    return _lib
+
+
+def _np_ptr(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _dev_ptr(t):
+    if t is None:
+        return None
+    assert t.is_cuda and t.is_contiguous()
+    return C.c_void_p(t.data_ptr())
+
+
+class Context:
+    """Owner of one ``rsd_ctx``.  Keeps references to every borrowed buffer."""
+
+    def __init__(self):
+        self.handle = C.c_void_p()
+        self.keep = {}
+        self.batch = 0
+        self.max_ctx = 0
+        self.step_cap = 0
+        self.max_steps = 0
+        self.vocab = 0
+
+    def check(self, rc: int):
+        if rc != RSD_OK:
+            raise RsdError(rc, load_library().rsd_last_error(self.handle).decode())
+
+    def __del__(self):
+        try:
+            rsd_destroy(self)
+        except Exception:
+            pass
+
+
+def _shape_struct(s) -> _Shape:
+    dtype = {"f32": 0, "bf16": 1}[s.dtype] if isinstance(s.dtype, str) else int(s.dtype)
+    head = {"lm": 0, "reward": 1}[s.head_kind] if isinstance(s.head_kind, str) else int(s.head_kind)
+    return _Shape(s.n_layers, s.d_model, s.n_heads, s.n_kv_heads, s.d_ffn, s.vocab, s.rope_theta, s.rms_eps, dtype, head)
+
+
+def rsd_init(shapes: Sequence, weights: Sequence, *, batch: int, delta: float, sep_id: int, step_cap: int,
+             max_steps: int, max_ctx: int, eos_id: int = -1, temperature: float = 0.0, top_p: float = 1.0,
+             sep_logit_bias: float = 0.0, omega_kind: int = 0, omega_a: float = 0.0, page_tokens: int = 16,
+             kv_pool_bytes=(0, 0, 0), use_graphs: int = 1, stream=None) -> Context:
+    """``weights``: three device tensors holding each model's blob."""
+    import torch
+
+    lib = load_library()
+    ctx = Context()
+    sh = (_Shape * 3)(*[_shape_struct(s) for s in shapes])
+    ws = (_Weights * 3)(*[_Weights(w.data_ptr(), w.numel() * w.element_size()) for w in weights])
+    p = _Params(delta, omega_kind, omega_a, sep_id, eos_id, step_cap, max_steps, max_ctx, temperature, top_p,
+                sep_logit_bias, page_tokens, (C.c_uint64 * 3)(*[int(x) for x in kv_pool_bytes]), use_graphs, 0)
+    st = stream if stream is not None else torch.cuda.current_stream()
+    ctx.keep["weights"] = list(weights)
+    ctx.keep["stream"] = st
+    ctx.batch, ctx.max_ctx, ctx.step_cap, ctx.max_steps, ctx.vocab = batch, max_ctx, step_cap, max_steps, shapes[0].vocab
+    ctx.shapes = list(shapes)
+    rc = lib.rsd_init(C.byref(ctx.handle), sh, ws, C.byref(p), C.c_int32(batch), C.c_void_p(st.cuda_stream))
+    ctx.check(rc)
+    return ctx
+
+
+def rsd_destroy(ctx: Context) -> None:
+    if ctx.handle:
+        load_library().rsd_destroy(ctx.handle)
+        ctx.handle = C.c_void_p()
+        ctx.keep.clear()
+
+
+def rsd_set_prompts(ctx: Context, tokens_dev, prompt_len: np.ndarray) -> None:
+    pl = np.ascontiguousarray(prompt_len, dtype=np.int32)
+    assert tuple(tokens_dev.shape) == (ctx.batch, ctx.max_ctx) and tokens_dev.dtype.itemsize == 4
+    ctx.check(load_library().rsd_set_prompts(ctx.handle, _dev_ptr(tokens_dev), _np_ptr(pl)))
+
+
+def rsd_set_uniforms(ctx: Context, u_draft=None, u_target=None, u_gate=None) -> None:
+    for u, cols in ((u_draft, ctx.max_ctx), (u_target, ctx.max_ctx), (u_gate, ctx.max_steps)):
+        assert u is None or tuple(u.shape) == (ctx.batch, cols)
+    ctx.keep["uniforms"] = (u_draft, u_target, u_gate)
+    ctx.check(load_library().rsd_set_uniforms(ctx.handle, _dev_ptr(u_draft), _dev_ptr(u_target), _dev_ptr(u_gate)))
+
+
+def rsd_set_criterion(ctx: Context, delta: float, omega_kind: int = 0, omega_a: float = 0.0) -> None:
+    ctx.check(load_library().rsd_set_criterion(ctx.handle, C.c_float(delta), C.c_int32(omega_kind), C.c_float(omega_a)))
+
+
+def rsd_set_teacher(ctx: Context, forced_draft=None, forced_target=None, forced_accept=None) -> None:
+    ctx.keep["teacher"] = (forced_draft, forced_target, forced_accept)
+    ctx.check(load_library().rsd_set_teacher(ctx.handle, _dev_ptr(forced_draft), _dev_ptr(forced_target),
+                                             _dev_ptr(forced_accept)))
+
+
+def rsd_step(ctx: Context) -> dict:
+    B, cap = ctx.batch, ctx.step_cap
+    o = dict(draft_len=np.zeros(B, np.int32), draft_tokens=np.full((B, cap), -1, np.int32),
+             reward=np.zeros(B, np.float32), accepted=np.zeros(B, np.int32), own_accept=np.zeros(B, np.int32),
+             final_len=np.zeros(B, np.int32), final_tokens=np.full((B, cap), -1, np.int32),
+             finished=np.zeros(B, np.int32))
+    so = _StepOut(*[_np_ptr(o[n]) for n, _ in _StepOut._fields_])
+    ctx.check(load_library().rsd_step(ctx.handle, C.byref(so)))
+    return o
+
+
+def rsd_generate(ctx: Context, max_steps: int = 0, want_tokens: bool = True) -> dict:
+    B = ctx.batch
+    toks = np.zeros((B, ctx.max_ctx), np.int32) if want_tokens else None
+    cl, fin = np.zeros(B, np.int32), np.zeros(B, np.int32)
+    g = _GenOut(_np_ptr(toks), _np_ptr(cl), _np_ptr(fin), 0, 0, 0, 0, 0, 0)
+    rc = load_library().rsd_generate(ctx.handle, C.c_int32(max_steps), C.byref(g))
+    out = dict(tokens=toks, ctx_len=cl, finished=fin, steps_run=g.steps_run, n_committed=g.n_committed,
+               n_draft=g.n_draft, n_target=g.n_target, n_accept=g.n_accept, n_reject=g.n_reject, rc=rc)
+    ctx.check(rc)
+    return out
+
+
+def rsd_export_state(ctx: Context, want_tokens: bool = True) -> dict:
+    B = ctx.batch
+    cl, kv, npg = np.zeros(B, np.int32), np.zeros((3, B), np.int32), np.zeros((3, B), np.int32)
+    toks = np.zeros((B, ctx.max_ctx), np.int32) if want_tokens else None
+    ctx.check(load_library().rsd_export_state(ctx.handle, _np_ptr(cl), _np_ptr(kv), _np_ptr(npg), _np_ptr(toks)))
+    return dict(ctx_len=cl, kv_len=kv, n_pages=npg, tokens=toks)
+
+
+def rsd_export_pages(ctx: Context, model: int) -> dict:
+    mp, pp, fp = C.c_int32(), C.c_int32(), C.c_int32()
+    lib = load_library()
+    ctx.check(lib.rsd_export_pages(ctx.handle, C.c_int32(model), None, C.byref(mp), C.byref(pp), C.byref(fp)))
+    bt = np.zeros((ctx.batch, mp.value), np.int32)
+    ctx.check(lib.rsd_export_pages(ctx.handle, C.c_int32(model), _np_ptr(bt), None, None, None))
+    return dict(block_table=bt, max_pages=mp.value, pool_pages=pp.value, free_pages=fp.value)
+
+
+def rsd_export_sampled(ctx: Context):
+    a = np.zeros((ctx.batch, ctx.max_ctx), np.int32)
+    b = np.zeros((ctx.batch, ctx.max_ctx), np.int32)
+    ctx.check(load_library().rsd_export_sampled(ctx.handle, _np_ptr(a), _np_ptr(b)))
+    return a, b
+
+
+def rsd_forward(ctx: Context, model: int, tokens: np.ndarray, lens: np.ndarray, chunk: int):
+    """Teacher-forced logits ``[B, T, vocab]`` (LM models) or rewards ``[B, T]``
+    as a device tensor; positions beyond ``lens`` hold NaN."""
+    import torch
+
+    tokens = np.ascontiguousarray(tokens, dtype=np.int32)
+    lens = np.ascontiguousarray(lens, dtype=np.int32)
+    B, T = tokens.shape
+    assert B == ctx.batch
+    shape = (B, T, ctx.vocab) if model != RSD_PRM else (B, T)
+    out = torch.full(shape, float("nan"), dtype=torch.float32, device="cuda")
+    torch.cuda.current_stream().synchronize()
+    ctx.check(load_library().rsd_forward(ctx.handle, C.c_int32(model), _np_ptr(tokens), _np_ptr(lens), C.c_int32(T),
+                                         C.c_int32(chunk), _dev_ptr(out)))
+    return out
+
+
+def rsd_sample(ctx: Context, logits, u, temperature: float, top_p: float):
+    import torch
+
+    n, V = logits.shape
+    out = torch.empty(n, dtype=torch.int32, device=logits.device)
+    torch.cuda.current_stream().synchronize()
+    ctx.check(load_library().rsd_sample(ctx.handle, _dev_ptr(logits), _dev_ptr(u), C.c_int32(n), C.c_int32(V),
+                                        C.c_float(temperature), C.c_float(top_p), _dev_ptr(out)))
+    return out
+
+
+def rsd_stage_ms(ctx: Context, reset: bool = False) -> np.ndarray:
+    ms = (C.c_double * 4)()
+    ctx.check(load_library().rsd_stage_ms(ctx.handle, ms, C.c_int32(int(reset))))
+    return np.array(list(ms))

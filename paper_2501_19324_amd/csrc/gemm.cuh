@@ -1,0 +1,182 @@
+// Tiled GEMMs for more than 8 activation rows (chunked prefill, large decode
+// batches): Y[m][n] (+)= sum_k X[m][k] * W[n][k]; X fp32 [M][ldx], W row-major
+// [N][K], Y fp32 [M][ldy].  Both operands are contiguous along K ("NT" form).
+//   * fp32 weights: plain VALU tile kernel (the tiny configuration only).
+//   * bf16 weights: MFMA kernel; activations are rounded to bf16 while they are
+//     staged into LDS, products accumulate in fp32.
+// Requirements checked by the caller: K % 32 == 0; N, M arbitrary.
+#pragma once
+#include "common.cuh"
+#include "gemv.cuh"
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+
+// ---------------------------------------------------------------- fp32 tiles
+// 64x64 output tile, 16x16 threads, 4x4 outputs per thread, BK = 16.
+template <int EPI>
+__global__ __launch_bounds__(256) void sgemm_nt_kernel(const float* __restrict__ W, int N, int K,
+                                                       const float* __restrict__ X, int ldx,
+                                                       float* __restrict__ Y, int ldy, int M) {
+    __shared__ float As[16][64 + 4];
+    __shared__ float Bs[16][64 + 4];
+    const int tid = threadIdx.x;
+    const int tx = tid & 15, ty = tid >> 4;
+    const int m0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
+    float acc[4][4] = {};
+    for (int k0 = 0; k0 < K; k0 += 16) {
+        // 64 rows x 16 k = 1024 elements per operand: 4 per thread
+        {
+            const int row = tid >> 2, kq = (tid & 3) * 4;
+            float4 a = make_float4(0.f, 0.f, 0.f, 0.f), b = a;
+            if (m0 + row < M) a = *reinterpret_cast<const float4*>(X + (size_t)(m0 + row) * ldx + k0 + kq);
+            if (n0 + row < N) b = *reinterpret_cast<const float4*>(W + (size_t)(n0 + row) * K + k0 + kq);
+            As[kq + 0][row] = a.x; As[kq + 1][row] = a.y; As[kq + 2][row] = a.z; As[kq + 3][row] = a.w;
+            Bs[kq + 0][row] = b.x; Bs[kq + 1][row] = b.y; Bs[kq + 2][row] = b.z; Bs[kq + 3][row] = b.w;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            float a[4], b[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { a[i] = As[k][ty * 4 + i]; b[i] = Bs[k][tx * 4 + i]; }
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc[i][j] += a[i] * b[j];
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int m = m0 + ty * 4 + i;
+        if (m >= M) continue;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int n = n0 + tx * 4 + j;
+            if (n < N) {
+                float* yp = Y + (size_t)m * ldy + n;
+                *yp = (EPI == EPI_RESID) ? (*yp + acc[i][j]) : acc[i][j];
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------- bf16 MFMA
+// Block tile BM x 128 (BM = 64 or 128), K step 32, 256 threads = 4 waves.
+// v_mfma_f32_32x32x16_bf16: per lane 8 consecutive-k bf16 of row (lane % 32) at
+// k offset 8 * (lane / 32) for each operand; the 16 results of a lane sit at
+// rows 8 * (v / 4) + 4 * (lane / 32) + v % 4, column lane % 32.
+template <int BM, int EPI>
+__global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict__ W, int N, int K,
+                                                        const float* __restrict__ X, int ldx,
+                                                        float* __restrict__ Y, int ldy, int M) {
+    constexpr int BN = 128, BK = 32, LDS_STRIDE = BK + 8;   // 80-byte rows: 16-byte aligned, conflict-free
+    constexpr int WM = BM / 2;                               // rows of the tile per wave (2 x 2 waves)
+    constexpr int TI = WM / 32;                              // 32-row MFMA tiles per wave along M
+    __shared__ __attribute__((aligned(16))) uint16_t As[BM * LDS_STRIDE];
+    __shared__ __attribute__((aligned(16))) uint16_t Bs[BN * LDS_STRIDE];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+
+    f32x16_t acc[TI][2];
+#pragma unroll
+    for (int i = 0; i < TI; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+    constexpr int A_F4 = BM * BK / 4 / 256;   // float4 loads of X per thread (2 or 4)
+    for (int k0 = 0; k0 < K; k0 += BK) {
+        float4 av[A_F4];
+        uint4 bv[2];
+#pragma unroll
+        for (int i = 0; i < A_F4; ++i) {
+            const int idx = tid + i * 256, row = idx >> 3, c4 = idx & 7;
+            av[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (m0 + row < M) av[i] = *reinterpret_cast<const float4*>(X + (size_t)(m0 + row) * ldx + k0 + c4 * 4);
+        }
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int idx = tid + i * 256, row = idx >> 2, c8 = idx & 3;
+            bv[i] = make_uint4(0u, 0u, 0u, 0u);
+            if (n0 + row < N) bv[i] = *reinterpret_cast<const uint4*>(W + (size_t)(n0 + row) * K + k0 + c8 * 8);
+        }
+        __syncthreads();          // previous tile fully consumed
+#pragma unroll
+        for (int i = 0; i < A_F4; ++i) {
+            const int idx = tid + i * 256, row = idx >> 3, c4 = idx & 7;
+            uint2 p;
+            p.x = (uint32_t)f2bf(av[i].x) | ((uint32_t)f2bf(av[i].y) << 16);
+            p.y = (uint32_t)f2bf(av[i].z) | ((uint32_t)f2bf(av[i].w) << 16);
+            *reinterpret_cast<uint2*>(&As[row * LDS_STRIDE + c4 * 4]) = p;
+        }
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int idx = tid + i * 256, row = idx >> 2, c8 = idx & 3;
+            *reinterpret_cast<uint4*>(&Bs[row * LDS_STRIDE + c8 * 8]) = bv[i];
+        }
+        __syncthreads();
+#pragma unroll
+        for (int kk = 0; kk < BK; kk += 16) {
+            bf16x8_t a[TI], b[2];
+#pragma unroll
+            for (int i = 0; i < TI; ++i) {
+                const uint4 r = *reinterpret_cast<const uint4*>(
+                    &As[(wm * WM + i * 32 + (lane & 31)) * LDS_STRIDE + kk + (lane >> 5) * 8]);
+                a[i] = __builtin_bit_cast(bf16x8_t, r);
+            }
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const uint4 r = *reinterpret_cast<const uint4*>(
+                    &Bs[(wn * 64 + j * 32 + (lane & 31)) * LDS_STRIDE + kk + (lane >> 5) * 8]);
+                b[j] = __builtin_bit_cast(bf16x8_t, r);
+            }
+#pragma unroll
+            for (int i = 0; i < TI; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < TI; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int n = n0 + wn * 64 + j * 32 + (lane & 31);
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int m = m0 + wm * WM + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+                if (m < M && n < N) {
+                    float* yp = Y + (size_t)m * ldy + n;
+                    *yp = (EPI == EPI_RESID) ? (*yp + acc[i][j][v]) : acc[i][j][v];
+                }
+            }
+        }
+}
+
+// ---------------------------------------------------------------- dispatch
+static void gemm_launch(hipStream_t st, int epi, const float* W, int N, int K, const float* X, int ldx,
+                        float* Y, int ldy, int M) {
+    if (M <= 8) { gemv_launch<float>(st, PRO_NONE, epi, W, N, K, X, ldx, nullptr, 0.f, Y, ldy, M); return; }
+    const dim3 grid((N + 63) / 64, (M + 63) / 64), block(256);
+    if (epi == EPI_RESID) hipLaunchKernelGGL((sgemm_nt_kernel<EPI_RESID>), grid, block, 0, st, W, N, K, X, ldx, Y, ldy, M);
+    else                  hipLaunchKernelGGL((sgemm_nt_kernel<EPI_STORE>), grid, block, 0, st, W, N, K, X, ldx, Y, ldy, M);
+}
+
+static void gemm_launch(hipStream_t st, int epi, const bf16_t* W, int N, int K, const float* X, int ldx,
+                        float* Y, int ldy, int M) {
+    if (M <= 8) { gemv_launch<bf16_t>(st, PRO_NONE, epi, W, N, K, X, ldx, nullptr, 0.f, Y, ldy, M); return; }
+    const dim3 block(256);
+    if (M <= 64) {
+        const dim3 grid((N + 127) / 128, (M + 63) / 64);
+        if (epi == EPI_RESID) hipLaunchKernelGGL((gemm_bf16_kernel<64, EPI_RESID>), grid, block, 0, st, W, N, K, X, ldx, Y, ldy, M);
+        else                  hipLaunchKernelGGL((gemm_bf16_kernel<64, EPI_STORE>), grid, block, 0, st, W, N, K, X, ldx, Y, ldy, M);
+    } else {
+        const dim3 grid((N + 127) / 128, (M + 127) / 128);
+        if (epi == EPI_RESID) hipLaunchKernelGGL((gemm_bf16_kernel<128, EPI_RESID>), grid, block, 0, st, W, N, K, X, ldx, Y, ldy, M);
+        else                  hipLaunchKernelGGL((gemm_bf16_kernel<128, EPI_STORE>), grid, block, 0, st, W, N, K, X, ldx, Y, ldy, M);
+    }
+}

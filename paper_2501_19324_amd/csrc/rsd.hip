@@ -1,0 +1,939 @@
+// Host side of the RSD library: context, KV page bookkeeping, the per-model
+// forward passes built from the kernels in this directory, and the loop of
+// Algorithm 1 (Section 2.1) with the acceptance criterion of Algorithm 2.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <chrono>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "rsd.h"
+#include "common.cuh"
+#include "gemv.cuh"
+#include "gemm.cuh"
+#include "attn.cuh"
+#include "misc.cuh"
+#include "sample.cuh"
+
+namespace {
+
+constexpr int kMaxRows = 8192;   // rows of one chunked-prefill pass (bounds the workspaces)
+constexpr int kPoll = 16;        // decode iterations between looks at the active counter
+
+struct LayerOff { size_t attn_norm, wqkv, wo, ffn_norm, wgu, wdown; };
+
+struct Model {
+    rsd_model_shape s{};
+    const char* blob = nullptr;
+    int hd = 0, q_dim = 0, kv_dim = 0, n_qkv = 0, G = 0, esz = 0;
+    size_t off_embed = 0, off_final_norm = 0, off_head = 0, off_br = 0, n_elts = 0;
+    std::vector<LayerOff> layers;
+    // paged KV
+    char* pool = nullptr;
+    size_t page_elts = 0;        // elements of one page of one layer (K and V, all KV heads)
+    int pool_pages = 0, max_pages = 0, splits = 1;
+    std::vector<int> free_list;
+    int* bt_host = nullptr;      // pinned [B][max_pages]
+    int* bt_dev = nullptr;
+    std::vector<int> n_pages;
+    bool bt_dirty = false;
+    float2* rope = nullptr;      // [max_ctx][hd/2]
+};
+
+struct Piece { int b, start, end; };
+
+}  // namespace
+
+struct rsd_ctx {
+    Model m[3];
+    rsd_params p{};
+    int B = 0;
+    hipStream_t st = nullptr;
+    std::string err;
+    // device state block and its pinned mirror (ints; reward stored as float bits)
+    int* sb_dev = nullptr;
+    int* sb = nullptr;
+    size_t sb_ints = 0;
+    SeqState ds{};               // device pointers into sb_dev and friends
+    int* in_step_dev = nullptr;
+    // mirror accessors
+    int* ctx_len() { return sb; }
+    int* kv_len(int model) { return sb + (1 + model) * B; }
+    int* active() { return sb + 4 * B; }
+    int* step_len() { return sb + 5 * B; }
+    int* finished() { return sb + 6 * B; }
+    int* ctx_pre() { return sb + 7 * B; }
+    int* accepted() { return sb + 8 * B; }
+    int* own_accept() { return sb + 9 * B; }
+    float* reward() { return reinterpret_cast<float*>(sb + 10 * B); }
+    int* in_step() { return sb + 11 * B; }
+    int* n_active() { return sb + 12 * B; }
+    std::vector<int> prompt_len;
+    int steps_done = 0;
+    bool have_prompts = false;
+    // borrowed
+    const float *u_draft = nullptr, *u_target = nullptr, *u_gate = nullptr;
+    const int *forced_draft = nullptr, *forced_target = nullptr, *forced_accept = nullptr;
+    // workspaces (fp32 unless noted)
+    int ws_rows = 0;
+    float *h = nullptr, *xn = nullptr, *qkv = nullptr, *att = nullptr, *gu = nullptr, *act = nullptr;
+    float *part_acc = nullptr, *part_ml = nullptr;
+    float *hl = nullptr, *xl = nullptr, *logits = nullptr, *tmp_reward = nullptr;
+    int *chosen = nullptr, *steptok_dev = nullptr;
+    int *row_seq_dev = nullptr, *row_pos_dev = nullptr, *last_row_dev = nullptr;
+    int *row_seq_h = nullptr, *row_pos_h = nullptr, *last_row_h = nullptr, *steptok_h = nullptr;
+    int *poll_h = nullptr;
+    double stage_ms[4] = {0, 0, 0, 0};
+};
+
+namespace {
+
+int fail(rsd_ctx* c, int code, const char* fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    if (c) c->err = buf;
+    return code;
+}
+
+#define HIPCHK(c, call)                                                                         \
+    do {                                                                                        \
+        hipError_t e_ = (call);                                                                 \
+        if (e_ != hipSuccess)                                                                   \
+            return fail(c, RSD_EHIP, "%s failed: %s (%s:%d)", #call, hipGetErrorString(e_), __FILE__, __LINE__); \
+    } while (0)
+
+template <typename T>
+hipError_t dev_alloc(T** p, size_t n) { return hipMalloc(reinterpret_cast<void**>(p), std::max<size_t>(n, 1) * sizeof(T)); }
+template <typename T>
+hipError_t pin_alloc(T** p, size_t n) { return hipHostMalloc(reinterpret_cast<void**>(p), std::max<size_t>(n, 1) * sizeof(T), hipHostMallocDefault); }
+
+int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+// ------------------------------------------------------------------ model set-up
+int setup_model(rsd_ctx* c, Model& m, const rsd_model_shape& s, const rsd_weights& w, int which) {
+    m.s = s;
+    if (s.n_layers < 1 || s.d_model < 64 || s.n_heads < 1 || s.n_kv_heads < 1 || s.vocab < 2 || s.d_ffn < 64)
+        return fail(c, RSD_EINVAL, "model %d: non-positive dimension", which);
+    if (s.d_model % s.n_heads) return fail(c, RSD_EINVAL, "model %d: d_model %% n_heads != 0", which);
+    m.hd = s.d_model / s.n_heads;
+    if (m.hd != 32 && m.hd != 128) return fail(c, RSD_EINVAL, "model %d: head_dim %d not in {32,128}", which, m.hd);
+    if (s.n_heads % s.n_kv_heads) return fail(c, RSD_EINVAL, "model %d: n_heads %% n_kv_heads != 0", which);
+    m.G = s.n_heads / s.n_kv_heads;
+    if (!(m.G == 1 || m.G == 2 || m.G == 4 || m.G == 6 || m.G == 7 || m.G == 8))
+        return fail(c, RSD_EINVAL, "model %d: query group of %d heads unsupported", which, m.G);
+    if (s.d_model % 64 || s.d_ffn % 64) return fail(c, RSD_EINVAL, "model %d: d_model and d_ffn must be multiples of 64", which);
+    if (s.dtype != RSD_F32 && s.dtype != RSD_BF16) return fail(c, RSD_EINVAL, "model %d: bad dtype", which);
+    if (s.head_kind != (which == RSD_PRM ? RSD_HEAD_REWARD : RSD_HEAD_LM))
+        return fail(c, RSD_EINVAL, "model %d: wrong head kind", which);
+    m.esz = s.dtype == RSD_F32 ? 4 : 2;
+    m.q_dim = s.n_heads * m.hd;
+    m.kv_dim = s.n_kv_heads * m.hd;
+    m.n_qkv = m.q_dim + 2 * m.kv_dim;
+    const size_t d = s.d_model, F = s.d_ffn;
+    size_t off = 0;
+    m.off_embed = off; off += (size_t)s.vocab * d;
+    m.layers.resize(s.n_layers);
+    for (int l = 0; l < s.n_layers; ++l) {
+        LayerOff& o = m.layers[l];
+        o.attn_norm = off; off += d;
+        o.wqkv = off; off += (size_t)m.n_qkv * d;
+        o.wo = off; off += d * (size_t)m.q_dim;
+        o.ffn_norm = off; off += d;
+        o.wgu = off; off += 2 * F * d;
+        o.wdown = off; off += d * F;
+    }
+    m.off_final_norm = off; off += d;
+    m.off_head = off;
+    if (s.head_kind == RSD_HEAD_LM) off += (size_t)s.vocab * d;
+    else { off += d; m.off_br = off; off += 8; }
+    m.n_elts = off;
+    if (!w.blob || w.nbytes < off * m.esz)
+        return fail(c, RSD_EINVAL, "model %d: weight blob holds %llu bytes, %llu needed", which,
+                    (unsigned long long)w.nbytes, (unsigned long long)(off * m.esz));
+    if (reinterpret_cast<uintptr_t>(w.blob) % 16) return fail(c, RSD_EINVAL, "model %d: blob not 16-byte aligned", which);
+    m.blob = static_cast<const char*>(w.blob);
+    return RSD_OK;
+}
+
+template <typename WT> const WT* wptr(const Model& m, size_t off) { return reinterpret_cast<const WT*>(m.blob) + off; }
+
+int setup_kv(rsd_ctx* c, Model& m, int which) {
+    const int B = c->B;
+    m.max_pages = ceil_div(c->p.max_ctx, RSD_PAGE);
+    m.page_elts = (size_t)2 * m.s.n_kv_heads * RSD_PAGE * m.hd;
+    const size_t page_bytes = m.page_elts * m.esz * m.s.n_layers;
+    size_t pages = (size_t)B * m.max_pages;
+    if (c->p.kv_pool_bytes[which]) pages = std::min<size_t>(pages, c->p.kv_pool_bytes[which] / page_bytes);
+    if (pages < 1) return fail(c, RSD_EINVAL, "model %d: KV pool smaller than one page", which);
+    m.pool_pages = (int)pages;
+    HIPCHK(c, hipMalloc(reinterpret_cast<void**>(&m.pool), pages * page_bytes));
+    m.free_list.resize(pages);
+    for (size_t i = 0; i < pages; ++i) m.free_list[i] = (int)(pages - 1 - i);   // pop_back hands out 0,1,2,...
+    HIPCHK(c, pin_alloc(&m.bt_host, (size_t)B * m.max_pages));
+    HIPCHK(c, dev_alloc(&m.bt_dev, (size_t)B * m.max_pages));
+    std::fill(m.bt_host, m.bt_host + (size_t)B * m.max_pages, -1);
+    m.n_pages.assign(B, 0);
+    m.bt_dirty = true;
+    // rotary table in fp64 on the host, rounded once to fp32
+    const int half = m.hd / 2;
+    std::vector<float2> tab((size_t)c->p.max_ctx * half);
+    for (int i = 0; i < half; ++i) {
+        const double inv = std::pow((double)m.s.rope_theta, -2.0 * i / m.hd);
+        for (int pos = 0; pos < c->p.max_ctx; ++pos) {
+            const double a = pos * inv;
+            tab[(size_t)pos * half + i] = make_float2((float)std::cos(a), (float)std::sin(a));
+        }
+    }
+    HIPCHK(c, dev_alloc(&m.rope, tab.size()));
+    HIPCHK(c, hipMemcpy(m.rope, tab.data(), tab.size() * sizeof(float2), hipMemcpyHostToDevice));
+    // splits of the decode attention: enough blocks to occupy the chip, at least 4 pages each
+    int s = 256 / std::max(1, B * m.s.n_kv_heads);
+    s = std::min(s, std::min(32, ceil_div(m.max_pages, 4)));
+    m.splits = std::max(1, s);
+    return RSD_OK;
+}
+
+bool ensure_pages(Model& m, int b, int need) {
+    while (m.n_pages[b] < need) {
+        if (m.free_list.empty()) return false;
+        const int pg = m.free_list.back();
+        m.free_list.pop_back();
+        m.bt_host[(size_t)b * m.max_pages + m.n_pages[b]++] = pg;
+        m.bt_dirty = true;
+    }
+    return true;
+}
+void trim_pages(Model& m, int b, int keep) {
+    while (m.n_pages[b] > keep) {
+        int& e = m.bt_host[(size_t)b * m.max_pages + --m.n_pages[b]];
+        m.free_list.push_back(e);
+        e = -1;
+        m.bt_dirty = true;
+    }
+}
+int upload_tables(rsd_ctx* c, Model& m) {
+    if (!m.bt_dirty) return RSD_OK;
+    HIPCHK(c, hipMemcpyAsync(m.bt_dev, m.bt_host, (size_t)c->B * m.max_pages * sizeof(int), hipMemcpyHostToDevice, c->st));
+    m.bt_dirty = false;
+    return RSD_OK;
+}
+
+int push_state(rsd_ctx* c) {
+    HIPCHK(c, hipMemcpyAsync(c->sb_dev, c->sb, c->sb_ints * sizeof(int), hipMemcpyHostToDevice, c->st));
+    return RSD_OK;
+}
+int pull_state(rsd_ctx* c) {
+    HIPCHK(c, hipMemcpyAsync(c->sb, c->sb_dev, c->sb_ints * sizeof(int), hipMemcpyDeviceToHost, c->st));
+    HIPCHK(c, hipStreamSynchronize(c->st));
+    return RSD_OK;
+}
+
+// ------------------------------------------------------------------ forward passes
+template <typename KT, int HD>
+void launch_attn_g(rsd_ctx* c, const Model& m, int l, int M, const RowMap& rm, int S) {
+    const KT* pool_l = reinterpret_cast<const KT*>(m.pool) + (size_t)l * m.pool_pages * m.page_elts;
+    const float scale = 1.0f / std::sqrt((float)HD);
+    const dim3 grid(M, m.s.n_kv_heads, S), block(256);
+#define RSD_ATTN_CASE(GG)                                                                                   \
+    case GG:                                                                                                \
+        hipLaunchKernelGGL((attn_rows_kernel<KT, HD, GG>), grid, block, 0, c->st, c->qkv, m.n_qkv, pool_l,  \
+                           m.bt_dev, m.max_pages, rm, m.s.n_heads, m.s.n_kv_heads, S, scale, c->att,        \
+                           m.q_dim, c->part_acc, c->part_ml);                                               \
+        break;
+    switch (m.G) {
+        RSD_ATTN_CASE(1) RSD_ATTN_CASE(2) RSD_ATTN_CASE(4) RSD_ATTN_CASE(6) RSD_ATTN_CASE(7) RSD_ATTN_CASE(8)
+    }
+#undef RSD_ATTN_CASE
+    if (S > 1)
+        hipLaunchKernelGGL((attn_combine_kernel<HD>), dim3(M, m.s.n_heads), dim3(HD), 0, c->st, c->part_acc,
+                           c->part_ml, rm, m.s.n_heads, S, c->att, m.q_dim);
+}
+
+template <typename WT>
+void run_layers(rsd_ctx* c, Model& m, int M, const RowMap& rm, bool decode) {
+    hipStream_t st = c->st;
+    const int d = m.s.d_model, F = m.s.d_ffn;
+    const float eps = m.s.rms_eps;
+    hipLaunchKernelGGL((embed_kernel<WT>), dim3(M), dim3(256), 0, st, wptr<WT>(m, m.off_embed), d, c->ds.tokens,
+                       c->p.max_ctx, rm, c->h);
+    const int S = decode ? m.splits : 1;
+    const bool fused = M <= 8;   // few rows: norm / SwiGLU / residual folded into the weight-streaming kernels
+    for (int l = 0; l < m.s.n_layers; ++l) {
+        const LayerOff& o = m.layers[l];
+        if (fused) {
+            gemv_launch<WT>(st, PRO_NORM, EPI_STORE, wptr<WT>(m, o.wqkv), m.n_qkv, d, c->h, d,
+                            wptr<WT>(m, o.attn_norm), eps, c->qkv, m.n_qkv, M);
+        } else {
+            hipLaunchKernelGGL((rmsnorm_kernel<WT>), dim3(M), dim3(256), 0, st, c->h, d, wptr<WT>(m, o.attn_norm), eps, c->xn);
+            gemm_launch(st, EPI_STORE, wptr<WT>(m, o.wqkv), m.n_qkv, d, c->xn, d, c->qkv, m.n_qkv, M);
+        }
+        WT* pool_l = reinterpret_cast<WT*>(m.pool) + (size_t)l * m.pool_pages * m.page_elts;
+        if (m.hd == 128) {
+            hipLaunchKernelGGL((rope_kv_kernel<WT, 128>), dim3(M), dim3(256), 0, st, c->qkv, m.n_qkv, pool_l, m.bt_dev,
+                               m.max_pages, rm, m.rope, m.s.n_heads, m.s.n_kv_heads);
+            launch_attn_g<WT, 128>(c, m, l, M, rm, S);
+        } else {
+            hipLaunchKernelGGL((rope_kv_kernel<WT, 32>), dim3(M), dim3(256), 0, st, c->qkv, m.n_qkv, pool_l, m.bt_dev,
+                               m.max_pages, rm, m.rope, m.s.n_heads, m.s.n_kv_heads);
+            launch_attn_g<WT, 32>(c, m, l, M, rm, S);
+        }
+        if (fused) {
+            gemv_launch<WT>(st, PRO_NONE, EPI_RESID, wptr<WT>(m, o.wo), d, m.q_dim, c->att, m.q_dim,
+                            (const WT*)nullptr, 0.f, c->h, d, M);
+            gemv_launch<WT>(st, PRO_NORM, EPI_STORE, wptr<WT>(m, o.wgu), 2 * F, d, c->h, d,
+                            wptr<WT>(m, o.ffn_norm), eps, c->gu, 2 * F, M);
+            gemv_launch<WT>(st, PRO_SWIGLU, EPI_RESID, wptr<WT>(m, o.wdown), d, F, c->gu, 2 * F,
+                            (const WT*)nullptr, 0.f, c->h, d, M);
+        } else {
+            gemm_launch(st, EPI_RESID, wptr<WT>(m, o.wo), d, m.q_dim, c->att, m.q_dim, c->h, d, M);
+            hipLaunchKernelGGL((rmsnorm_kernel<WT>), dim3(M), dim3(256), 0, st, c->h, d, wptr<WT>(m, o.ffn_norm), eps, c->xn);
+            gemm_launch(st, EPI_STORE, wptr<WT>(m, o.wgu), 2 * F, d, c->xn, d, c->gu, 2 * F, M);
+            const size_t total = (size_t)M * F;
+            hipLaunchKernelGGL(swiglu_kernel, dim3((unsigned)((total / 4 + 255) / 256)), dim3(256), 0, st, c->gu, F, c->act, total);
+            gemm_launch(st, EPI_RESID, wptr<WT>(m, o.wdown), d, F, c->act, F, c->h, d, M);
+        }
+    }
+}
+
+// Vocabulary logits of M hidden rows X[M][d] -> Y[M][ldy]
+template <typename WT>
+void lm_head(rsd_ctx* c, Model& m, const float* X, int M, float* Y, int ldy) {
+    const int d = m.s.d_model, V = m.s.vocab;
+    if (M <= 8) {
+        gemv_launch<WT>(c->st, PRO_NORM, EPI_STORE, wptr<WT>(m, m.off_head), V, d, X, d, wptr<WT>(m, m.off_final_norm),
+                        m.s.rms_eps, Y, ldy, M);
+    } else {
+        for (int r0 = 0; r0 < M; r0 += kMaxRows) {
+            const int mm = std::min(kMaxRows, M - r0);
+            hipLaunchKernelGGL((rmsnorm_kernel<WT>), dim3(mm), dim3(256), 0, c->st, X + (size_t)r0 * d, d,
+                               wptr<WT>(m, m.off_final_norm), m.s.rms_eps, c->xn);
+            gemm_launch(c->st, EPI_STORE, wptr<WT>(m, m.off_head), V, d, c->xn, d, Y + (size_t)r0 * ldy, ldy, mm);
+        }
+    }
+}
+
+template <typename WT>
+void reward_rows(rsd_ctx* c, Model& m, const float* H, int n, const int* rows, float* out) {
+    hipLaunchKernelGGL((reward_head_kernel<WT>), dim3(n), dim3(256), 0, c->st, H, m.s.d_model, rows,
+                       wptr<WT>(m, m.off_final_norm), m.s.rms_eps, wptr<WT>(m, m.off_head), wptr<WT>(m, m.off_br), out);
+}
+
+void sample_rows(rsd_ctx* c, const float* logits, int ld, int V, const float* u, const int* u_index, int u_stride,
+                 float temperature, float top_p, int sep_id, float sep_bias, const int* active, int n, int* out) {
+    SampleArgs a{logits, ld, V, u, u_index, u_stride, temperature, top_p, sep_id, sep_bias, active, out};
+    hipLaunchKernelGGL(sample_kernel, dim3(n), dim3(1024), 0, c->st, a);
+}
+
+RowMap decode_map(rsd_ctx* c, int which) {
+    return RowMap{nullptr, nullptr, c->ds.kv_len + (size_t)which * c->B, c->ds.active};
+}
+
+// One single-token iteration of an LM model over all sequences: forward, head, sample, append.
+template <typename WT>
+void decode_iter(rsd_ctx* c, int which, const float* u, const int* forced) {
+    Model& m = c->m[which];
+    run_layers<WT>(c, m, c->B, decode_map(c, which), true);
+    lm_head<WT>(c, m, c->h, c->B, c->logits, m.s.vocab);
+    sample_rows(c, c->logits, m.s.vocab, m.s.vocab, u, c->ds.ctx_len, c->p.max_ctx, c->p.temperature, c->p.top_p,
+                c->p.sep_id, c->p.sep_logit_bias, c->ds.active, c->B, c->chosen);
+    hipLaunchKernelGGL(append_kernel, dim3(ceil_div(c->B, 64)), dim3(64), 0, c->st, c->ds, c->B, c->p.max_ctx, which,
+                       c->chosen, forced, c->p.sep_id, c->p.eos_id, c->p.step_cap);
+}
+
+// Chunked prefill of `pieces` (per sequence consecutive, ascending) through model `which`.
+// after_pass(first_row_of_piece[], pieces_in_pass, M) runs after the layers of every pass.
+template <typename WT, typename AfterPass>
+int prefill(rsd_ctx* c, int which, std::vector<Piece> pieces, AfterPass after_pass) {
+    Model& m = c->m[which];
+    size_t i = 0;
+    std::vector<Piece> pass;
+    std::vector<int> first_row;
+    while (i < pieces.size()) {
+        pass.clear();
+        first_row.clear();
+        int M = 0;
+        HIPCHK(c, hipStreamSynchronize(c->st));      // staging buffers of the previous pass are free again
+        std::fill(c->last_row_h, c->last_row_h + c->B, -1);
+        while (i < pieces.size() && M < kMaxRows) {
+            Piece pc = pieces[i];
+            const int room = kMaxRows - M;
+            Piece take = pc;
+            if (pc.end - pc.start > room) take.end = pc.start + room;
+            first_row.push_back(M);
+            pass.push_back(take);
+            for (int p = take.start; p < take.end; ++p, ++M) { c->row_seq_h[M] = take.b; c->row_pos_h[M] = p; }
+            // "last row" of a sequence: the final position of its final piece
+            const bool final_piece = take.end == pc.end && (i + 1 == pieces.size() || pieces[i + 1].b != pc.b);
+            if (final_piece) c->last_row_h[take.b] = M - 1;
+            if (take.end < pc.end) { pieces[i].start = take.end; break; }
+            ++i;
+        }
+        HIPCHK(c, hipMemcpyAsync(c->row_seq_dev, c->row_seq_h, M * sizeof(int), hipMemcpyHostToDevice, c->st));
+        HIPCHK(c, hipMemcpyAsync(c->row_pos_dev, c->row_pos_h, M * sizeof(int), hipMemcpyHostToDevice, c->st));
+        HIPCHK(c, hipMemcpyAsync(c->last_row_dev, c->last_row_h, c->B * sizeof(int), hipMemcpyHostToDevice, c->st));
+        RowMap rm{c->row_seq_dev, c->row_pos_dev, nullptr, nullptr};
+        run_layers<WT>(c, m, M, rm, false);
+        const int rc = after_pass(pass, first_row, M);
+        if (rc != RSD_OK) return rc;
+    }
+    HIPCHK(c, hipGetLastError());
+    return RSD_OK;
+}
+
+// One stage of token generation (a reasoning step) with an LM model on the
+// currently active sequences.  The first iteration feeds whatever the model
+// has not seen yet (one token, or a catch-up chunk), the rest one token each.
+template <typename WT>
+int gen_stage(rsd_ctx* c, int which, const float* u, const int* forced) {
+    const int B = c->B;
+    Model& m = c->m[which];
+    std::vector<Piece> pieces;
+    bool all_single = true;
+    int n_act = 0;
+    for (int b = 0; b < B; ++b)
+        if (c->active()[b]) {
+            ++n_act;
+            const int s = c->kv_len(which)[b], e = c->ctx_len()[b];
+            if (e - s != 1) all_single = false;
+            pieces.push_back(Piece{b, s, e});
+        }
+    if (!n_act) return RSD_OK;
+    int iters = 0;
+    if (!all_single) {
+        int rc = prefill<WT>(c, which, pieces, [&](const std::vector<Piece>&, const std::vector<int>&, int) {
+            hipLaunchKernelGGL(gather_rows_kernel, dim3(B), dim3(256), 0, c->st, c->h, c->last_row_dev, m.s.d_model, c->hl);
+            return RSD_OK;
+        });
+        if (rc != RSD_OK) return rc;
+        lm_head<WT>(c, m, c->hl, B, c->logits, m.s.vocab);
+        sample_rows(c, c->logits, m.s.vocab, m.s.vocab, u, c->ds.ctx_len, c->p.max_ctx, c->p.temperature, c->p.top_p,
+                    c->p.sep_id, c->p.sep_logit_bias, c->ds.active, B, c->chosen);
+        hipLaunchKernelGGL(append_kernel, dim3(ceil_div(B, 64)), dim3(64), 0, c->st, c->ds, B, c->p.max_ctx, which,
+                           c->chosen, forced, c->p.sep_id, c->p.eos_id, c->p.step_cap);
+        iters = 1;
+    }
+    while (iters < c->p.step_cap) {
+        decode_iter<WT>(c, which, u, forced);
+        ++iters;
+        if (iters % kPoll == 0 || iters == c->p.step_cap) {
+            HIPCHK(c, hipMemcpyAsync(c->poll_h, c->ds.n_active, sizeof(int), hipMemcpyDeviceToHost, c->st));
+            HIPCHK(c, hipStreamSynchronize(c->st));
+            if (*c->poll_h <= 0) break;
+        }
+    }
+    HIPCHK(c, hipGetLastError());
+    return RSD_OK;
+}
+
+int gen_stage_any(rsd_ctx* c, int which, const float* u, const int* forced) {
+    return c->m[which].s.dtype == RSD_F32 ? gen_stage<float>(c, which, u, forced) : gen_stage<bf16_t>(c, which, u, forced);
+}
+
+// tokens[b][ctx_pre[b] + j] -> dst[b][j], j < step_cap
+__global__ void extract_step_kernel(const int* tokens, const int* ctx_pre, const int* ctx_len, int max_ctx, int cap, int* dst) {
+    const int b = blockIdx.x;
+    for (int j = threadIdx.x; j < cap; j += blockDim.x) {
+        const int p = ctx_pre[b] + j;
+        dst[b * cap + j] = (p < ctx_len[b]) ? tokens[(size_t)b * max_ctx + p] : -1;
+    }
+}
+
+int fetch_step_tokens(rsd_ctx* c) {
+    hipLaunchKernelGGL(extract_step_kernel, dim3(c->B), dim3(64), 0, c->st, c->ds.tokens, c->ds.ctx_pre, c->ds.ctx_len,
+                       c->p.max_ctx, c->p.step_cap, c->steptok_dev);
+    HIPCHK(c, hipMemcpyAsync(c->steptok_h, c->steptok_dev, (size_t)c->B * c->p.step_cap * sizeof(int), hipMemcpyDeviceToHost, c->st));
+    return RSD_OK;
+}
+
+double now_ms() {
+    return std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now().time_since_epoch()).count();
+}
+
+void reset_sequences(rsd_ctx* c) {
+    for (int i = 0; i < 3; ++i)
+        for (int b = 0; b < c->B; ++b) trim_pages(c->m[i], b, 0);
+    std::fill(c->sb, c->sb + c->sb_ints, 0);
+    c->steps_done = 0;
+}
+
+}  // namespace
+
+// =========================================================================== C ABI
+extern "C" {
+
+const char* rsd_last_error(const rsd_ctx* c) { return c ? c->err.c_str() : "null context"; }
+
+void rsd_destroy(rsd_ctx* c) {
+    if (!c) return;
+    (void)hipStreamSynchronize(c->st);
+    for (auto& m : c->m) {
+        (void)hipFree(m.pool); (void)hipFree(m.bt_dev); (void)hipFree(m.rope);
+        if (m.bt_host) (void)hipHostFree(m.bt_host);
+    }
+    void* dev[] = {c->sb_dev, c->ds.tokens, c->ds.sampled[0], c->ds.sampled[1], c->h, c->xn, c->qkv, c->att, c->gu, c->act,
+                   c->part_acc, c->part_ml, c->hl, c->xl, c->logits, c->tmp_reward, c->chosen, c->steptok_dev,
+                   c->row_seq_dev, c->row_pos_dev, c->last_row_dev};
+    for (void* p : dev) if (p) (void)hipFree(p);
+    void* pin[] = {c->sb, c->row_seq_h, c->row_pos_h, c->last_row_h, c->steptok_h, c->poll_h};
+    for (void* p : pin) if (p) (void)hipHostFree(p);
+    delete c;
+}
+
+int rsd_init(rsd_ctx** out, const rsd_model_shape shape[3], const rsd_weights w[3], const rsd_params* p, int32_t batch,
+             void* hip_stream) {
+    if (!out) return RSD_EINVAL;
+    *out = nullptr;
+    rsd_ctx* c = new rsd_ctx();
+    *out = c;   // handed back even on failure so that the caller can read the error, then destroy
+    if (!shape || !w || !p) return fail(c, RSD_EINVAL, "null argument");
+    c->p = *p;
+    c->B = batch;
+    c->st = static_cast<hipStream_t>(hip_stream);
+    if (batch < 1 || batch > 4096) return fail(c, RSD_EINVAL, "batch %d out of range", batch);
+    if (p->page_tokens != RSD_PAGE) return fail(c, RSD_EINVAL, "page_tokens must be %d", RSD_PAGE);
+    if (p->step_cap < 1 || p->max_steps < 1 || p->max_ctx < 2) return fail(c, RSD_EINVAL, "bad step_cap/max_steps/max_ctx");
+    if (p->temperature < 0.f || p->top_p < 0.f || p->top_p > 1.f) return fail(c, RSD_EINVAL, "bad temperature/top_p");
+    if (p->omega_kind < 0 || p->omega_kind > 4) return fail(c, RSD_EINVAL, "bad omega_kind");
+    for (int i = 0; i < 3; ++i) {
+        int rc = setup_model(c, c->m[i], shape[i], w[i], i);
+        if (rc) return rc;
+    }
+    if (shape[0].vocab != shape[1].vocab || shape[0].vocab != shape[2].vocab)
+        return fail(c, RSD_EINVAL, "the three models must share one vocabulary");
+    if (p->sep_id < 0 || p->sep_id >= shape[0].vocab || p->eos_id >= shape[0].vocab)
+        return fail(c, RSD_EINVAL, "sep_id/eos_id outside the vocabulary");
+    for (int i = 0; i < 3; ++i) {
+        int rc = setup_kv(c, c->m[i], i);
+        if (rc) return rc;
+    }
+    const int B = batch;
+    const size_t mc = p->max_ctx;
+    c->sb_ints = (size_t)12 * B + 4;
+    HIPCHK(c, dev_alloc(&c->sb_dev, c->sb_ints));
+    HIPCHK(c, pin_alloc(&c->sb, c->sb_ints));
+    std::fill(c->sb, c->sb + c->sb_ints, 0);
+    HIPCHK(c, dev_alloc(&c->ds.tokens, B * mc));
+    HIPCHK(c, dev_alloc(&c->ds.sampled[0], B * mc));
+    HIPCHK(c, dev_alloc(&c->ds.sampled[1], B * mc));
+    c->ds.ctx_len = c->sb_dev;
+    c->ds.kv_len = c->sb_dev + B;
+    c->ds.active = c->sb_dev + 4 * B;
+    c->ds.step_len = c->sb_dev + 5 * B;
+    c->ds.finished = c->sb_dev + 6 * B;
+    c->ds.ctx_pre = c->sb_dev + 7 * B;
+    c->ds.accepted = c->sb_dev + 8 * B;
+    c->ds.own_accept = c->sb_dev + 9 * B;
+    c->ds.reward = reinterpret_cast<float*>(c->sb_dev + 10 * B);
+    c->in_step_dev = c->sb_dev + 11 * B;
+    c->ds.n_active = c->sb_dev + 12 * B;
+    // workspaces sized for the widest model
+    int d = 0, nq = 0, qd = 0, F = 0, V = 0, HS = 0;
+    for (auto& m : c->m) {
+        d = std::max(d, m.s.d_model); nq = std::max(nq, m.n_qkv); qd = std::max(qd, m.q_dim);
+        F = std::max(F, m.s.d_ffn); V = std::max(V, m.s.vocab);
+        HS = std::max(HS, m.s.n_heads * m.splits * m.hd);
+    }
+    const size_t R = std::max(kMaxRows, B);
+    c->ws_rows = (int)R;
+    HIPCHK(c, dev_alloc(&c->h, R * d));
+    HIPCHK(c, dev_alloc(&c->xn, R * d));
+    HIPCHK(c, dev_alloc(&c->qkv, R * nq));
+    HIPCHK(c, dev_alloc(&c->att, R * qd));
+    HIPCHK(c, dev_alloc(&c->gu, R * 2 * F));
+    HIPCHK(c, dev_alloc(&c->act, R * F));
+    HIPCHK(c, dev_alloc(&c->part_acc, (size_t)B * HS));
+    HIPCHK(c, dev_alloc(&c->part_ml, (size_t)B * HS));
+    HIPCHK(c, dev_alloc(&c->hl, (size_t)B * d));
+    HIPCHK(c, dev_alloc(&c->xl, (size_t)B * d));
+    HIPCHK(c, dev_alloc(&c->logits, (size_t)B * V));
+    HIPCHK(c, dev_alloc(&c->tmp_reward, R));
+    HIPCHK(c, dev_alloc(&c->chosen, (size_t)B));
+    HIPCHK(c, dev_alloc(&c->steptok_dev, (size_t)B * p->step_cap));
+    HIPCHK(c, dev_alloc(&c->row_seq_dev, R));
+    HIPCHK(c, dev_alloc(&c->row_pos_dev, R));
+    HIPCHK(c, dev_alloc(&c->last_row_dev, (size_t)B));
+    HIPCHK(c, pin_alloc(&c->row_seq_h, R));
+    HIPCHK(c, pin_alloc(&c->row_pos_h, R));
+    HIPCHK(c, pin_alloc(&c->last_row_h, (size_t)B));
+    HIPCHK(c, pin_alloc(&c->steptok_h, (size_t)B * p->step_cap));
+    HIPCHK(c, pin_alloc(&c->poll_h, 4));
+    HIPCHK(c, hipMemsetAsync(c->h, 0, R * d * sizeof(float), c->st));
+    HIPCHK(c, hipMemsetAsync(c->hl, 0, (size_t)B * d * sizeof(float), c->st));
+    HIPCHK(c, hipMemsetAsync(c->att, 0, R * qd * sizeof(float), c->st));
+    HIPCHK(c, hipMemsetAsync(c->gu, 0, R * 2 * F * sizeof(float), c->st));
+    HIPCHK(c, hipMemsetAsync(c->logits, 0, (size_t)B * V * sizeof(float), c->st));
+    HIPCHK(c, hipStreamSynchronize(c->st));
+    c->prompt_len.assign(B, 0);
+    return RSD_OK;
+}
+
+int rsd_set_prompts(rsd_ctx* c, const int32_t* tokens_dev, const int32_t* prompt_len_host) {
+    if (!c || !tokens_dev || !prompt_len_host) return fail(c, RSD_EINVAL, "null argument");
+    const int B = c->B;
+    for (int b = 0; b < B; ++b)
+        if (prompt_len_host[b] < 1 || prompt_len_host[b] > c->p.max_ctx)
+            return fail(c, RSD_EINVAL, "prompt_len[%d] = %d outside [1, max_ctx]", b, prompt_len_host[b]);
+    HIPCHK(c, hipStreamSynchronize(c->st));
+    reset_sequences(c);
+    const size_t n = (size_t)B * c->p.max_ctx;
+    HIPCHK(c, hipMemcpyAsync(c->ds.tokens, tokens_dev, n * sizeof(int), hipMemcpyDeviceToDevice, c->st));
+    for (int s = 0; s < 2; ++s)
+        hipLaunchKernelGGL(fill_int_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, c->st, c->ds.sampled[s], -1, n);
+    for (int b = 0; b < B; ++b) {
+        c->prompt_len[b] = prompt_len_host[b];
+        c->ctx_len()[b] = prompt_len_host[b];
+        c->finished()[b] = prompt_len_host[b] >= c->p.max_ctx ? RSD_FIN_MAX_CTX : RSD_RUNNING;
+    }
+    int rc = push_state(c);
+    if (rc) return rc;
+    HIPCHK(c, hipStreamSynchronize(c->st));
+    c->have_prompts = true;
+    return RSD_OK;
+}
+
+int rsd_set_uniforms(rsd_ctx* c, const float* u_draft_dev, const float* u_target_dev, const float* u_gate_dev) {
+    if (!c) return RSD_EINVAL;
+    c->u_draft = u_draft_dev; c->u_target = u_target_dev; c->u_gate = u_gate_dev;
+    return RSD_OK;
+}
+
+int rsd_set_criterion(rsd_ctx* c, float delta, int32_t omega_kind, float omega_a) {
+    if (!c) return RSD_EINVAL;
+    if (omega_kind < 0 || omega_kind > 4) return fail(c, RSD_EINVAL, "bad omega_kind");
+    c->p.delta = delta; c->p.omega_kind = omega_kind; c->p.omega_a = omega_a;
+    return RSD_OK;
+}
+
+int rsd_set_teacher(rsd_ctx* c, const int32_t* forced_draft_dev, const int32_t* forced_target_dev,
+                    const int32_t* forced_accept_dev) {
+    if (!c) return RSD_EINVAL;
+    c->forced_draft = forced_draft_dev; c->forced_target = forced_target_dev; c->forced_accept = forced_accept_dev;
+    return RSD_OK;
+}
+
+int rsd_step(rsd_ctx* c, rsd_step_out* out) {
+    if (!c) return RSD_EINVAL;
+    if (!c->have_prompts) return fail(c, RSD_ESTATE, "no prompts set");
+    const int B = c->B;
+    const rsd_params& P = c->p;
+    if (P.temperature > 0.f && (!c->u_draft || !c->u_target)) return fail(c, RSD_ESTATE, "sampling needs uniforms");
+    if (P.omega_kind != RSD_OMEGA_BINARY && !c->u_gate) return fail(c, RSD_ESTATE, "this omega needs u_gate");
+    int n_in = 0;
+    for (int b = 0; b < B; ++b) n_in += c->finished()[b] == RSD_RUNNING;
+    if (!n_in) return fail(c, RSD_ESTATE, "every sequence has finished");
+
+    // ---- set-up: mark the sequences taking part, reserve pages for draft and reward model
+    std::vector<int> kv_save(c->kv_len(0), c->kv_len(0) + 3 * B);
+    auto trim_all = [&]() {
+        for (int i = 0; i < 3; ++i)
+            for (int b = 0; b < B; ++b) trim_pages(c->m[i], b, ceil_div(c->kv_len(i)[b], RSD_PAGE));
+    };
+    for (int b = 0; b < B; ++b) {
+        const int in = c->finished()[b] == RSD_RUNNING;
+        c->in_step()[b] = in;
+        c->active()[b] = in;
+        c->step_len()[b] = 0;
+        c->ctx_pre()[b] = c->ctx_len()[b];
+        c->accepted()[b] = 0;
+        c->own_accept()[b] = 0;
+        c->reward()[b] = 0.f;
+    }
+    *c->n_active() = n_in;
+    for (int b = 0; b < B; ++b)
+        if (c->in_step()[b]) {
+            const int need = ceil_div(std::min(c->ctx_pre()[b] + P.step_cap, P.max_ctx), RSD_PAGE);
+            if (!ensure_pages(c->m[RSD_DRAFT], b, need) || !ensure_pages(c->m[RSD_PRM], b, need)) {
+                trim_all();
+                return fail(c, RSD_ENOMEM, "KV pool exhausted reserving the draft step of sequence %d", b);
+            }
+        }
+    int rc;
+    if ((rc = push_state(c))) return rc;
+    if ((rc = upload_tables(c, c->m[RSD_DRAFT]))) return rc;
+    if ((rc = upload_tables(c, c->m[RSD_PRM]))) return rc;
+
+    // ---- draft step  (Algorithm 1: "Generate draft step")
+    double t0 = now_ms();
+    if ((rc = gen_stage_any(c, RSD_DRAFT, c->u_draft, c->forced_draft))) return rc;
+    if ((rc = fetch_step_tokens(c))) return rc;
+    if ((rc = pull_state(c))) return rc;
+    double t1 = now_ms();
+    c->stage_ms[0] += t1 - t0;
+    if (out) {
+        for (int b = 0; b < B; ++b) {
+            const int n = c->in_step()[b] ? c->ctx_len()[b] - c->ctx_pre()[b] : 0;
+            if (out->draft_len) out->draft_len[b] = n;
+            if (out->draft_tokens)
+                std::memcpy(out->draft_tokens + (size_t)b * P.step_cap, c->steptok_h + (size_t)b * P.step_cap, P.step_cap * sizeof(int));
+        }
+    }
+    std::vector<int> last_tok(B, -1);
+    for (int b = 0; b < B; ++b)
+        if (c->in_step()[b]) last_tok[b] = c->steptok_h[(size_t)b * P.step_cap + (c->ctx_len()[b] - c->ctx_pre()[b] - 1)];
+
+    // ---- reward of the draft step  ("Compute reward")
+    {
+        std::vector<Piece> pieces;
+        for (int b = 0; b < B; ++b)
+            if (c->in_step()[b]) {
+                pieces.push_back(Piece{b, c->kv_len(RSD_PRM)[b], c->ctx_len()[b]});
+                c->kv_len(RSD_PRM)[b] = c->ctx_len()[b];
+            }
+        if ((rc = push_state(c))) return rc;
+        Model& pm = c->m[RSD_PRM];
+        auto after = [&](const std::vector<Piece>&, const std::vector<int>&, int) {
+            if (pm.s.dtype == RSD_F32) reward_rows<float>(c, pm, c->h, B, c->last_row_dev, c->ds.reward);
+            else reward_rows<bf16_t>(c, pm, c->h, B, c->last_row_dev, c->ds.reward);
+            return RSD_OK;
+        };
+        rc = pm.s.dtype == RSD_F32 ? prefill<float>(c, RSD_PRM, pieces, after) : prefill<bf16_t>(c, RSD_PRM, pieces, after);
+        if (rc) return rc;
+    }
+    HIPCHK(c, hipStreamSynchronize(c->st));
+    double t2 = now_ms();
+    c->stage_ms[1] += t2 - t1;
+
+    // ---- acceptance criterion and rollback  (Algorithm 2)
+    hipLaunchKernelGGL(gate_kernel, dim3(ceil_div(B, 64)), dim3(64), 0, c->st, c->ds, B, P.delta, P.omega_kind, P.omega_a,
+                       c->u_gate, P.max_steps, c->steps_done, c->forced_accept, c->in_step_dev);
+    if ((rc = pull_state(c))) return rc;
+    double t3 = now_ms();
+    c->stage_ms[2] += t3 - t2;
+    if (out) {
+        for (int b = 0; b < B; ++b) {
+            if (out->reward) out->reward[b] = c->reward()[b];
+            if (out->accepted) out->accepted[b] = c->accepted()[b];
+            if (out->own_accept) out->own_accept[b] = c->own_accept()[b];
+        }
+    }
+
+    // ---- target step for the rejected sequences  ("Generate a target step")
+    int n_rej = 0;
+    for (int b = 0; b < B; ++b) n_rej += c->in_step()[b] && !c->accepted()[b];
+    if (n_rej) {
+        bool ok = true;
+        for (int b = 0; b < B && ok; ++b)
+            if (c->in_step()[b] && !c->accepted()[b]) {
+                const int need = ceil_div(std::min(c->ctx_pre()[b] + P.step_cap, P.max_ctx), RSD_PAGE);
+                ok = ensure_pages(c->m[RSD_TARGET], b, need);
+            }
+        if (!ok) {
+            // undo the whole step: every sequence back to its pre-step context
+            for (int b = 0; b < B; ++b) {
+                if (c->in_step()[b]) c->ctx_len()[b] = c->ctx_pre()[b];
+                c->active()[b] = 0;
+            }
+            std::copy(kv_save.begin(), kv_save.end(), c->kv_len(0));
+            trim_all();
+            if ((rc = push_state(c))) return rc;
+            HIPCHK(c, hipStreamSynchronize(c->st));
+            return fail(c, RSD_ENOMEM, "KV pool exhausted reserving the target step");
+        }
+        for (int b = 0; b < B; ++b) c->step_len()[b] = 0;
+        *c->n_active() = n_rej;
+        if ((rc = push_state(c))) return rc;
+        if ((rc = upload_tables(c, c->m[RSD_TARGET]))) return rc;
+        if ((rc = gen_stage_any(c, RSD_TARGET, c->u_target, c->forced_target))) return rc;
+        if ((rc = fetch_step_tokens(c))) return rc;
+        if ((rc = pull_state(c))) return rc;
+        for (int b = 0; b < B; ++b)
+            if (c->in_step()[b] && !c->accepted()[b])
+                last_tok[b] = c->steptok_h[(size_t)b * P.step_cap + (c->ctx_len()[b] - c->ctx_pre()[b] - 1)];
+    }
+    double t4 = now_ms();
+    c->stage_ms[3] += t4 - t3;
+
+    // ---- termination test and record
+    c->steps_done += 1;
+    for (int b = 0; b < B; ++b) {
+        if (!c->in_step()[b]) {
+            if (out && out->final_len) out->final_len[b] = 0;
+            if (out && out->finished) out->finished[b] = c->finished()[b];
+            if (out && out->final_tokens) std::fill(out->final_tokens + (size_t)b * P.step_cap, out->final_tokens + (size_t)(b + 1) * P.step_cap, -1);
+            continue;
+        }
+        const int n = c->ctx_len()[b] - c->ctx_pre()[b];
+        if (P.eos_id >= 0 && last_tok[b] == P.eos_id) c->finished()[b] = RSD_FIN_EOS;
+        else if (c->ctx_len()[b] >= P.max_ctx) c->finished()[b] = RSD_FIN_MAX_CTX;
+        else if (c->steps_done >= P.max_steps) c->finished()[b] = RSD_FIN_MAX_STEPS;
+        if (out) {
+            if (out->final_len) out->final_len[b] = n;
+            if (out->finished) out->finished[b] = c->finished()[b];
+            if (out->final_tokens) {
+                // accepted: the draft step is the committed one and steptok still holds it
+                std::memcpy(out->final_tokens + (size_t)b * P.step_cap, c->steptok_h + (size_t)b * P.step_cap, P.step_cap * sizeof(int));
+            }
+        }
+    }
+    trim_all();
+    return RSD_OK;
+}
+
+int rsd_generate(rsd_ctx* c, int32_t max_steps, rsd_gen_out* out) {
+    if (!c) return RSD_EINVAL;
+    if (!c->have_prompts) return fail(c, RSD_ESTATE, "no prompts set");
+    const int B = c->B;
+    const int limit = max_steps > 0 ? std::min(max_steps, c->p.max_steps) : c->p.max_steps;
+    std::vector<int> dl(B), fl(B), acc(B);
+    rsd_step_out so{};
+    so.draft_len = dl.data(); so.final_len = fl.data(); so.accepted = acc.data();
+    rsd_gen_out g{};
+    if (out) { g.tokens = out->tokens; g.ctx_len = out->ctx_len; g.finished = out->finished; }
+    while (c->steps_done < limit) {
+        bool any = false;
+        for (int b = 0; b < B; ++b) any |= c->finished()[b] == RSD_RUNNING;
+        if (!any) break;
+        std::vector<int> was(B);
+        for (int b = 0; b < B; ++b) was[b] = c->finished()[b] == RSD_RUNNING;
+        int rc = rsd_step(c, &so);
+        if (rc) { if (out) *out = g; return rc; }
+        g.steps_run += 1;
+        for (int b = 0; b < B; ++b)
+            if (was[b]) {
+                g.n_draft += dl[b];
+                if (acc[b]) g.n_accept += 1; else { g.n_reject += 1; g.n_target += fl[b]; }
+            }
+    }
+    for (int b = 0; b < B; ++b) g.n_committed += c->ctx_len()[b] - c->prompt_len[b];
+    if (g.ctx_len) std::memcpy(g.ctx_len, c->ctx_len(), B * sizeof(int));
+    if (g.finished) std::memcpy(g.finished, c->finished(), B * sizeof(int));
+    if (g.tokens) {
+        HIPCHK(c, hipMemcpyAsync(g.tokens, c->ds.tokens, (size_t)B * c->p.max_ctx * sizeof(int), hipMemcpyDeviceToHost, c->st));
+        HIPCHK(c, hipStreamSynchronize(c->st));
+    }
+    if (out) *out = g;
+    return RSD_OK;
+}
+
+int rsd_export_state(rsd_ctx* c, int32_t* ctx_len, int32_t* kv_len, int32_t* n_pages, int32_t* tokens) {
+    if (!c) return RSD_EINVAL;
+    const int B = c->B;
+    if (ctx_len) std::memcpy(ctx_len, c->ctx_len(), B * sizeof(int));
+    if (kv_len) std::memcpy(kv_len, c->kv_len(0), 3 * B * sizeof(int));
+    if (n_pages)
+        for (int i = 0; i < 3; ++i)
+            for (int b = 0; b < B; ++b) n_pages[i * B + b] = c->m[i].n_pages[b];
+    if (tokens) {
+        HIPCHK(c, hipMemcpyAsync(tokens, c->ds.tokens, (size_t)B * c->p.max_ctx * sizeof(int), hipMemcpyDeviceToHost, c->st));
+        HIPCHK(c, hipStreamSynchronize(c->st));
+    }
+    return RSD_OK;
+}
+
+int rsd_export_pages(rsd_ctx* c, int32_t model, int32_t* block_table, int32_t* max_pages, int32_t* pool_pages,
+                     int32_t* free_pages) {
+    if (!c || model < 0 || model > 2) return fail(c, RSD_EINVAL, "bad model index");
+    Model& m = c->m[model];
+    if (block_table) std::memcpy(block_table, m.bt_host, (size_t)c->B * m.max_pages * sizeof(int));
+    if (max_pages) *max_pages = m.max_pages;
+    if (pool_pages) *pool_pages = m.pool_pages;
+    if (free_pages) *free_pages = (int)m.free_list.size();
+    return RSD_OK;
+}
+
+int rsd_export_sampled(rsd_ctx* c, int32_t* sampled_draft, int32_t* sampled_target) {
+    if (!c) return RSD_EINVAL;
+    const size_t n = (size_t)c->B * c->p.max_ctx * sizeof(int);
+    if (sampled_draft) HIPCHK(c, hipMemcpyAsync(sampled_draft, c->ds.sampled[0], n, hipMemcpyDeviceToHost, c->st));
+    if (sampled_target) HIPCHK(c, hipMemcpyAsync(sampled_target, c->ds.sampled[1], n, hipMemcpyDeviceToHost, c->st));
+    HIPCHK(c, hipStreamSynchronize(c->st));
+    return RSD_OK;
+}
+
+int rsd_stage_ms(rsd_ctx* c, double ms[4], int32_t reset) {
+    if (!c || !ms) return RSD_EINVAL;
+    for (int i = 0; i < 4; ++i) { ms[i] = c->stage_ms[i]; if (reset) c->stage_ms[i] = 0; }
+    return RSD_OK;
+}
+
+int rsd_sample(rsd_ctx* c, const float* logits_dev, const float* u_dev, int32_t n, int32_t vocab, float temperature,
+               float top_p, int32_t* out_dev) {
+    if (!c || !logits_dev || !out_dev || n < 1 || vocab < 1) return fail(c, RSD_EINVAL, "bad argument");
+    if (temperature > 0.f && !u_dev) return fail(c, RSD_EINVAL, "sampling needs uniforms");
+    if (temperature < 0.f || top_p < 0.f || top_p > 1.f) return fail(c, RSD_EINVAL, "bad temperature/top_p");
+    sample_rows(c, logits_dev, vocab, vocab, u_dev, nullptr, 1, temperature, top_p, -1, 0.f, nullptr, n, out_dev);
+    HIPCHK(c, hipGetLastError());
+    HIPCHK(c, hipStreamSynchronize(c->st));
+    return RSD_OK;
+}
+
+}  // extern "C"
+
+// --------------------------------------------------------------------------- rsd_forward
+namespace {
+
+template <typename WT>
+int forward_impl(rsd_ctx* c, int which, const int32_t* tokens_host, const int32_t* lens, int T, int chunk, float* out) {
+    const int B = c->B;
+    Model& m = c->m[which];
+    const bool lm = m.s.head_kind == RSD_HEAD_LM;
+    const int V = m.s.vocab;
+    HIPCHK(c, hipStreamSynchronize(c->st));
+    reset_sequences(c);
+    c->have_prompts = false;
+    int maxlen = 0;
+    for (int b = 0; b < B; ++b) {
+        if (lens[b] < 0 || lens[b] > T) return fail(c, RSD_EINVAL, "lens[%d] out of range", b);
+        maxlen = std::max(maxlen, lens[b]);
+        if (!ensure_pages(m, b, ceil_div(lens[b], RSD_PAGE))) return fail(c, RSD_ENOMEM, "KV pool too small for rsd_forward");
+        c->ctx_len()[b] = lens[b];
+    }
+    int rc;
+    if ((rc = upload_tables(c, m))) return rc;
+    HIPCHK(c, hipMemcpy2DAsync(c->ds.tokens, (size_t)c->p.max_ctx * sizeof(int), tokens_host, (size_t)T * sizeof(int),
+                               (size_t)T * sizeof(int), B, hipMemcpyHostToDevice, c->st));
+    if (chunk <= 1) {
+        for (int t = 0; t < maxlen; ++t) {
+            for (int b = 0; b < B; ++b) { c->active()[b] = t < lens[b]; c->kv_len(which)[b] = t; }
+            if ((rc = push_state(c))) return rc;
+            run_layers<WT>(c, m, B, decode_map(c, which), true);
+            if (lm) lm_head<WT>(c, m, c->h, B, c->logits, V);
+            else reward_rows<WT>(c, m, c->h, B, nullptr, c->tmp_reward);
+            for (int b = 0; b < B; ++b)
+                if (t < lens[b]) {
+                    if (lm) HIPCHK(c, hipMemcpyAsync(out + ((size_t)b * T + t) * V, c->logits + (size_t)b * V, (size_t)V * sizeof(float), hipMemcpyDeviceToDevice, c->st));
+                    else HIPCHK(c, hipMemcpyAsync(out + (size_t)b * T + t, c->tmp_reward + b, sizeof(float), hipMemcpyDeviceToDevice, c->st));
+                }
+            HIPCHK(c, hipStreamSynchronize(c->st));   // the mirror is rewritten next iteration
+        }
+    } else {
+        for (int s0 = 0; s0 < maxlen; s0 += chunk) {
+            std::vector<Piece> pieces;
+            for (int b = 0; b < B; ++b)
+                if (s0 < lens[b]) pieces.push_back(Piece{b, s0, std::min(lens[b], s0 + chunk)});
+            auto after = [&](const std::vector<Piece>& pass, const std::vector<int>& first, int M) {
+                if (!lm) reward_rows<WT>(c, m, c->h, M, nullptr, c->tmp_reward);
+                for (size_t i = 0; i < pass.size(); ++i) {
+                    const Piece& pc = pass[i];
+                    const int n = pc.end - pc.start;
+                    if (lm) lm_head<WT>(c, m, c->h + (size_t)first[i] * m.s.d_model, n, out + ((size_t)pc.b * T + pc.start) * V, V);
+                    else HIPCHK(c, hipMemcpyAsync(out + (size_t)pc.b * T + pc.start, c->tmp_reward + first[i], n * sizeof(float), hipMemcpyDeviceToDevice, c->st));
+                }
+                return RSD_OK;
+            };
+            if ((rc = prefill<WT>(c, which, pieces, after))) return rc;
+        }
+    }
+    HIPCHK(c, hipGetLastError());
+    HIPCHK(c, hipStreamSynchronize(c->st));
+    reset_sequences(c);
+    return RSD_OK;
+}
+
+}  // namespace
+
+extern "C" int rsd_forward(rsd_ctx* c, int32_t model, const int32_t* tokens_host, const int32_t* lens_host, int32_t T,
+                           int32_t chunk, float* out_dev) {
+    if (!c || model < 0 || model > 2 || !tokens_host || !lens_host || !out_dev) return fail(c, RSD_EINVAL, "bad argument");
+    if (T < 1 || T > c->p.max_ctx) return fail(c, RSD_EINVAL, "T outside [1, max_ctx]");
+    return c->m[model].s.dtype == RSD_F32 ? forward_impl<float>(c, model, tokens_host, lens_host, T, chunk, out_dev)
+                                           : forward_impl<bf16_t>(c, model, tokens_host, lens_host, T, chunk, out_dev);
+}

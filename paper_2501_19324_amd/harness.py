@@ -1,0 +1,41 @@
+"""Set a workload from :mod:`rsd_inputs` up on the GPU: weights generated on
+the device, prompts and uniforms uploaded, context created.  Plumbing only."""
+from __future__ import annotations
+
+import numpy as np
+
+from rsd_inputs import Workload, model_blob_torch, prompt_lengths, prompt_tokens, uniforms
+
+from . import binding as R
+
+
+class Session:
+    """A context plus the device buffers it borrows."""
+
+    def __init__(self, w: Workload, delta=None, weights=None, use_graphs: int = 1, kv_pool_bytes=(0, 0, 0),
+                 omega_kind=None, omega_a=None):
+        import torch
+
+        self.w = w
+        dev = torch.device("cuda:0")
+        self.weights = weights if weights is not None else [model_blob_torch(w.seed, i, s, dev) for i, s in enumerate(w.shapes)]
+        self.ctx = R.rsd_init(w.shapes, self.weights, batch=w.batch, delta=w.delta if delta is None else delta,
+                              sep_id=w.sep_id, step_cap=w.step_cap, max_steps=w.max_steps, max_ctx=w.max_ctx,
+                              eos_id=w.eos_id, temperature=w.temperature, top_p=w.top_p,
+                              sep_logit_bias=w.sep_logit_bias,
+                              omega_kind=w.omega_kind if omega_kind is None else omega_kind,
+                              omega_a=w.omega_a if omega_a is None else omega_a,
+                              kv_pool_bytes=kv_pool_bytes, use_graphs=use_graphs)
+        self.prompt_len = prompt_lengths(w)
+        self.tokens_host = prompt_tokens(w)
+        self.tokens = torch.from_numpy(self.tokens_host).to(dev)
+        self.u_host = {k: uniforms(w, k, n) for k, n in (("U_DRAFT", w.max_ctx), ("U_TARGET", w.max_ctx), ("U_GATE", w.max_steps))}
+        self.u = {k: torch.from_numpy(v).to(dev) for k, v in self.u_host.items()}
+        R.rsd_set_uniforms(self.ctx, self.u["U_DRAFT"], self.u["U_TARGET"], self.u["U_GATE"])
+        self.reset()
+
+    def reset(self):
+        R.rsd_set_prompts(self.ctx, self.tokens, self.prompt_len)
+
+    def close(self):
+        R.rsd_destroy(self.ctx)
