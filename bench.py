@@ -1,0 +1,144 @@
+#!/usr/bin/env python3
+"""Benchmark of the RSD hot path on one MI355X.
+
+A "step" is one full pass of Algorithm 1 over one batch of synthetic prompts:
+every reasoning step runs draft decode, reward-model scoring, the delta gate
+with rollback and target regeneration, until max_steps.  The default workload
+is configuration 1 (bf16, batch 1, 1.5B draft / 7B target / 1.5B reward model,
+256-token prompt, 16 steps of <= 64 tokens, top-p 0.95 at T = 0.7, delta 0.7).
+Prints one JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0       # MI355X HBM3E, published
+PROBE_OPS = {"qkv": 0, "o": 1, "gate_up": 2, "down": 3, "head": 4}
+
+
+def cpu_baseline(w, budget_s=20.0):
+    """The fp64 CPU checker timed on a bounded sample of the same workload:
+    the three models at full width and vocabulary but 2 layers each, first
+    reasoning step capped at 4 tokens (the full-depth models need > 100 GB as
+    fp64 and minutes per token)."""
+    import numpy as np
+    import torch
+    from dataclasses import replace
+    from rsd_inputs import workload, model_weights_np, prompt_tokens, prompt_lengths, uniforms
+    from oracle import rsd_oracle as O
+
+    layers = 2
+    ws = workload(w.name, n_layers=layers, batch=1, step_cap=4, max_steps=1)
+    cores = min(16, os.cpu_count() or 1)
+    models = [O.OracleModel(s, model_weights_np(ws.seed, i, s, threads=cores)) for i, s in enumerate(ws.shapes)]
+    toks, lens = prompt_tokens(ws), prompt_lengths(ws)
+    P = O.Params(delta=ws.delta, sep_id=ws.sep_id, step_cap=ws.step_cap, max_steps=1, max_ctx=ws.max_ctx,
+                 temperature=float(np.float32(ws.temperature)), top_p=float(np.float32(ws.top_p)))
+    t0 = time.time()
+    out = O.generate_sequence(models[0], models[1], models[2], toks[0, :lens[0]],
+                              uniforms(ws, "U_DRAFT", ws.max_ctx)[0], uniforms(ws, "U_TARGET", ws.max_ctx)[0],
+                              uniforms(ws, "U_GATE", 1)[0], P)
+    dt = time.time() - t0
+    n = len(out["tokens"]) - int(lens[0])
+    return {"value": n / dt, "unit": "tokens/s", "cores": int(torch.get_num_threads()), "kind": "oracle",
+            "sample": f"{ws.name} shapes at full width and vocabulary, {layers} of {w.draft.n_layers} layers per model, "
+                      f"1 sequence, prompt {int(lens[0])} tokens + first reasoning step of {n} tokens "
+                      f"(prompt prefill of all touched models included), {dt:.1f} s; at full depth the rate is "
+                      f"roughly {w.draft.n_layers // layers}x lower"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="cfg1")
+    ap.add_argument("--delta", type=float, default=None)
+    ap.add_argument("--layers", type=int, default=None, help="reduce depth (debugging only; invalid as a result)")
+    ap.add_argument("--probe", default="gate_up", choices=sorted(PROBE_OPS))
+    ap.add_argument("--probe-model", type=int, default=1)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-graphs", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (sequences are independent; more GPUs would shard the "
+              "batch with no communication); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from rsd_inputs import workload
+    from paper_2501_19324_amd import binding as R
+    from paper_2501_19324_amd.harness import Session
+
+    kw = {}
+    if args.layers:
+        kw["n_layers"] = args.layers
+    w = workload(args.workload, **kw)
+    delta = w.delta if args.delta is None else args.delta
+    t_setup = time.time()
+    s = Session(w, delta=delta, use_graphs=0 if args.no_graphs else 1)
+    torch.cuda.synchronize()
+    t_setup = time.time() - t_setup
+
+    def one_pass():
+        s.reset()
+        return R.rsd_generate(s.ctx, want_tokens=False)
+
+    for _ in range(args.warmup):
+        one_pass()
+    R.rsd_stage_ms(s.ctx, reset=True)
+    R.rsd_probe_start(s.ctx, args.probe_model, PROBE_OPS[args.probe], 8192, 4)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    tokens = drafted = targeted = acc = rej = 0
+    for _ in range(args.steps):
+        g = one_pass()
+        tokens += g["n_committed"]; drafted += g["n_draft"]; targeted += g["n_target"]
+        acc += g["n_accept"]; rej += g["n_reject"]
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    probe = R.rsd_probe_read(s.ctx)
+    stage = R.rsd_stage_ms(s.ctx)
+
+    roof = None
+    if probe["n"] > 0:
+        avg_s = probe["total_ms"] / probe["n"] * 1e-3
+        gbs = probe["bytes_per_launch"] / avg_s / 1e9
+        roof = {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None,
+                "kernel": f"gemv_kernel ({args.probe} projection of model {args.probe_model}, single-token decode)",
+                "bytes_per_launch": probe["bytes_per_launch"], "avg_launch_us": round(avg_s * 1e6, 2),
+                "launches_timed": probe["n"]}
+    # decode-stage view of the same roofline: bytes every sampled token has to read
+    dec_bytes = drafted * w.draft.decode_weight_bytes() + targeted * w.target.decode_weight_bytes()
+    dec_s = (stage[0] + stage[3]) * 1e-3
+    line = {
+        "metric": "generated tokens/s (1 GPU) per delta",
+        "value": round(tokens / dt, 2), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(dt / args.steps * 1e3, 2), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": w.draft.dtype, "data": "synthetic",
+        "config": {"workload": f"{w.name}: batch {w.batch}, draft {w.draft.n_layers}L-d{w.draft.d_model}, target "
+                               f"{w.target.n_layers}L-d{w.target.d_model}, PRM {w.prm.n_layers}L-d{w.prm.d_model}, "
+                               f"vocab {w.draft.vocab}, prompts {w.prompt_len_min}-{w.prompt_len_max}, "
+                               f"{w.max_steps} steps x <= {w.step_cap} tokens, T={w.temperature}, top_p={w.top_p}",
+                   "delta": delta, "committed_tokens_per_pass": tokens // max(args.steps, 1),
+                   "accept_rate": round(acc / max(acc + rej, 1), 4), "draft_tokens": drafted, "target_tokens": targeted,
+                   "stage_ms_per_pass": {k: round(v / args.steps, 2) for k, v in zip(("draft", "prm", "gate", "target"), stage)},
+                   "decode_weight_stream_GBs": round(dec_bytes / dec_s / 1e9, 1) if dec_s > 0 else None,
+                   "setup_s": round(t_setup, 1)},
+        "roofline": roof,
+    }
+    s.close()
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(w)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

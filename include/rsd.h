@@ -167,15 +167,16 @@ int rsd_export_pages(rsd_ctx *c, int32_t model, int32_t *block_table, int32_t *m
                      int32_t *pool_pages, int32_t *free_pages);
 
 /* Teacher forcing for parity tests, BORROWED dev arrays (NULL switches a part
- * off): forced_draft / forced_target [B][max_ctx]: when >= 0, the token
- * appended at that position by that model is the forced one (the model's own
- * choice is still recorded, see rsd_export_sampled); forced_accept
- * [B][max_steps]: when >= 0, the decision applied at that step. */
+ * off): forced_draft / forced_target [B][max_steps][step_cap]: when entry
+ * [b][i][j] is >= 0, the j-th token that model appends in step i of sequence b
+ * is the forced one (the model's own choice is still recorded, see
+ * rsd_export_sampled); forced_accept [B][max_steps]: when >= 0, the decision
+ * applied at that step. */
 int rsd_set_teacher(rsd_ctx *c, const int32_t *forced_draft_dev, const int32_t *forced_target_dev,
                     const int32_t *forced_accept_dev);
 
-/* The tokens each model's sampler chose, by absolute position: HOST
- * [B][max_ctx] each, -1 where the model sampled nothing. */
+/* The tokens each model's sampler chose: HOST [B][max_steps][step_cap] each,
+ * -1 where the model sampled nothing. */
 int rsd_export_sampled(rsd_ctx *c, int32_t *sampled_draft, int32_t *sampled_target);
 
 /* Teacher-forced evaluation of one model for parity tests.  tokens is host
@@ -199,6 +200,16 @@ int rsd_sample(rsd_ctx *c, const float *logits_dev, const float *u_dev, int32_t 
  * stages): ms[0] draft, ms[1] reward model, ms[2] criterion + rollback,
  * ms[3] target.  reset != 0 clears them after reading. */
 int rsd_stage_ms(rsd_ctx *c, double ms[4], int32_t reset);
+
+/* Kernel timing probe for roofline reports.  While armed, every `stride`-th
+ * launch of one weight-streaming projection (op: 0 qkv, 1 attention output,
+ * 2 gate+up, 3 down, 4 output head) in `model`'s single-token decode path is
+ * bracketed by a pair of HIP events on the context's stream, up to
+ * max_samples pairs.  rsd_probe_read synchronises, returns the number of
+ * timed launches, their summed duration and the algorithmic bytes one such
+ * launch moves (weights once + activations in and out), and disarms. */
+int rsd_probe_start(rsd_ctx *c, int32_t model, int32_t op, int32_t max_samples, int32_t stride);
+int rsd_probe_read(rsd_ctx *c, int64_t *n_samples, double *total_ms, int64_t *bytes_per_launch);
 
 const char *rsd_last_error(const rsd_ctx *c);
 void rsd_destroy(rsd_ctx *c);

@@ -118,15 +118,33 @@ def gqa_attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, q_pos: np.ndarray
     return out
 
 
+def round_to_bf16(x: np.ndarray) -> np.ndarray:
+    """Nearest bf16 value (8-bit significand, ties to even) of each fp64 entry,
+    returned as fp64.  One rounding, straight from the fp64 bits; inputs are
+    finite and within the normal range of bf16."""
+    b = np.ascontiguousarray(x, dtype=F64).view(np.uint64)
+    lsb = (b >> np.uint64(45)) & np.uint64(1)
+    r = (b + np.uint64((1 << 44) - 1) + lsb) & ~np.uint64((1 << 45) - 1)
+    return r.view(F64)
+
+
 class KVCache:
     """Dense per-layer key/value store of one (model, sequence).  ``length`` is
-    the number of leading positions held; truncation just lowers it."""
+    the number of leading positions held; truncation just lowers it.
 
-    def __init__(self, shape, capacity: int):
+    ``kv_dtype`` states how entries are stored: "exact" keeps the fp64 values;
+    "bf16" rounds every (rotated) key and every value to bf16 as it is written,
+    which is the storage format the workload definition fixes for the bf16
+    models' caches (a quantisation step of the method as specified, not a
+    shortcut of this checker: all arithmetic on the stored values stays fp64)."""
+
+    def __init__(self, shape, capacity: int, kv_dtype: str = "exact"):
+        assert kv_dtype in ("exact", "bf16")
         L, Hkv, hd = shape.n_layers, shape.n_kv_heads, shape.head_dim
         self.k = np.zeros((L, capacity, Hkv, hd), dtype=F64)
         self.v = np.zeros((L, capacity, Hkv, hd), dtype=F64)
         self.length = 0
+        self.kv_dtype = kv_dtype
 
     def truncate(self, n: int) -> None:
         assert 0 <= n <= self.length
@@ -150,6 +168,8 @@ def forward_chunk(m: OracleModel, kv: KVCache, tokens: Sequence[int]) -> np.ndar
         v = (a @ m.mat(p + "wv").T).reshape(T, Hkv, hd)
         q = rope(q, pos, s.rope_theta)
         k = rope(k, pos, s.rope_theta)
+        if kv.kv_dtype == "bf16":
+            k, v = round_to_bf16(k), round_to_bf16(v)
         kv.k[l, p0:p0 + T] = k
         kv.v[l, p0:p0 + T] = v
         o = gqa_attention(q, kv.k[l, :p0 + T], kv.v[l, :p0 + T], pos)
@@ -162,10 +182,10 @@ def forward_chunk(m: OracleModel, kv: KVCache, tokens: Sequence[int]) -> np.ndar
     return rmsnorm(h, m.mat("final_norm"), s.rms_eps)
 
 
-def forward_full(m: OracleModel, tokens: Sequence[int]) -> np.ndarray:
+def forward_full(m: OracleModel, tokens: Sequence[int], kv_dtype: str = "exact") -> np.ndarray:
     """Plain causal forward over the whole sequence with no cache kept:
     final-norm hidden states [len(tokens), d]."""
-    return forward_chunk(m, KVCache(m.s, len(tokens)), tokens)
+    return forward_chunk(m, KVCache(m.s, len(tokens), kv_dtype), tokens)
 
 
 def lm_logits(m: OracleModel, y: np.ndarray) -> np.ndarray:
@@ -256,6 +276,7 @@ class Params:
     omega_kind: int = OMEGA_BINARY
     omega_a: float = 0.0
     page_tokens: int = 16
+    kv_dtype: str = "exact"      # "bf16": keys and values are stored rounded to bf16 (see KVCache)
 
 
 class _Runner:
@@ -263,10 +284,11 @@ class _Runner:
     the tokens it has not seen (kv_len tracks how many it holds), or - with
     ``use_cache=False`` - recomputes the whole prefix every time."""
 
-    def __init__(self, model: OracleModel, max_ctx: int, use_cache: bool):
+    def __init__(self, model: OracleModel, max_ctx: int, use_cache: bool, kv_dtype: str = "exact"):
         self.m = model
         self.use_cache = use_cache
-        self.kv = KVCache(model.s, max_ctx) if use_cache else None
+        self.kv_dtype = kv_dtype
+        self.kv = KVCache(model.s, max_ctx, kv_dtype) if use_cache else None
         self.kv_len = 0
 
     def last_hidden(self, tokens: Sequence[int]) -> np.ndarray:
@@ -277,7 +299,7 @@ class _Runner:
             assert self.kv.length == self.kv_len < n
             y = forward_chunk(self.m, self.kv, tokens[self.kv_len:n])[-1]
         else:
-            y = forward_full(self.m, tokens)[-1]
+            y = forward_full(self.m, tokens, self.kv_dtype)[-1]
         self.kv_len = n
         return y
 
@@ -288,18 +310,22 @@ class _Runner:
                 self.kv.truncate(n)
 
 
-def gen_step(run: _Runner, tokens: List[int], u_row: np.ndarray, P: Params):
+def gen_step(run: _Runner, tokens: List[int], u_row: np.ndarray, P: Params, margins: Optional[list] = None):
     """Generate one reasoning step with ``run``'s model, appending to
     ``tokens`` in place: sample until the separator or EOS has been appended,
     or the step holds step_cap tokens, or the context is full.  The uniform
     for the token placed at absolute position i is u_row[i].  Returns the
-    step's tokens."""
+    step's tokens.  ``margins``, when given, collects the top-2 logit gap at
+    every sampled position (used by parity tests to excuse near-ties)."""
     start = len(tokens)
     while True:
         y = run.last_hidden(tokens)
         lg = lm_logits(run.m, y).copy()
         lg[P.sep_id] += P.sep_logit_bias
         t = sample(lg, float(u_row[len(tokens)]), P.temperature, P.top_p)
+        if margins is not None:                     # diagnostic only: gap between the two largest logits
+            top2 = np.partition(lg, -2)[-2:]
+            margins.append(float(top2[1] - top2[0]))
         tokens.append(t)
         n = len(tokens) - start
         if t == P.sep_id or t == P.eos_id or n >= P.step_cap or len(tokens) >= P.max_ctx:
@@ -317,9 +343,9 @@ def generate_sequence(draft: OracleModel, target: OracleModel, prm: OracleModel,
     only ever fed when a rejection needs it)."""
     delta = float(np.float32(P.delta))       # the threshold is an fp32 argument
     tokens = [int(t) for t in prompt]
-    rd = _Runner(draft, P.max_ctx, use_cache)
-    rt = _Runner(target, P.max_ctx, use_cache)
-    rp = _Runner(prm, P.max_ctx, use_cache)
+    rd = _Runner(draft, P.max_ctx, use_cache, P.kv_dtype)
+    rt = _Runner(target, P.max_ctx, use_cache, P.kv_dtype)
+    rp = _Runner(prm, P.max_ctx, use_cache, P.kv_dtype)
     records = []
     reason = RUNNING
     n_steps = P.max_steps if max_steps is None else max_steps
@@ -329,16 +355,17 @@ def generate_sequence(draft: OracleModel, target: OracleModel, prm: OracleModel,
         if reason != RUNNING:
             break
         ctx_pre = len(tokens)
-        draft_step = gen_step(rd, tokens, u_draft, P)
+        dm, fm = [], []
+        draft_step = gen_step(rd, tokens, u_draft, P, dm)
         r = reward(prm, rp.last_hidden(tokens))
         ok = accept(r, P.omega_kind, delta, P.omega_a, float(u_gate[i]))
         if ok:
-            final = draft_step
+            final, fm = draft_step, dm
         else:
             del tokens[ctx_pre:]
             rd.truncate(ctx_pre)
             rp.truncate(ctx_pre)
-            final = gen_step(rt, tokens, u_target, P)
+            final = gen_step(rt, tokens, u_target, P, fm)
         if P.eos_id >= 0 and P.eos_id in final:
             reason = FIN_EOS
         elif len(tokens) >= P.max_ctx:
@@ -349,6 +376,7 @@ def generate_sequence(draft: OracleModel, target: OracleModel, prm: OracleModel,
         records.append(dict(step=i, ctx_pre=ctx_pre, draft_tokens=list(draft_step), reward=r,
                             accepted=bool(ok), final_tokens=list(final), ctx_len=len(tokens),
                             kv_len=kv, n_pages=[-(-n // P.page_tokens) for n in kv],
+                            draft_margins=dm, final_margins=fm,
                             finished=reason))
     return dict(tokens=tokens, prompt_len=len(prompt), records=records, finished=reason,
                 kv_len=[rd.kv_len, rt.kv_len, rp.kv_len])

@@ -17,14 +17,15 @@ __all__ = ["RSD_OK", "RSD_EINVAL", "RSD_ENOMEM", "RSD_ESTATE", "RSD_EHIP", "RSD_
            "RsdError", "Context", "load_library", "rsd_init", "rsd_set_prompts", "rsd_set_uniforms",
            "rsd_set_criterion", "rsd_step", "rsd_generate", "rsd_export_state", "rsd_export_pages",
            "rsd_set_teacher", "rsd_export_sampled", "rsd_forward", "rsd_sample", "rsd_stage_ms", "rsd_destroy",
+           "rsd_probe_start", "rsd_probe_read",
            "EXPORTED_SYMBOLS"]
 
 RSD_OK, RSD_EINVAL, RSD_ENOMEM, RSD_ESTATE, RSD_EHIP = 0, -1, -2, -3, -4
 RSD_DRAFT, RSD_TARGET, RSD_PRM = 0, 1, 2
 EXPORTED_SYMBOLS = ["rsd_init", "rsd_set_prompts", "rsd_set_uniforms", "rsd_set_criterion", "rsd_step",
                     "rsd_generate", "rsd_export_state", "rsd_export_pages", "rsd_set_teacher",
-                    "rsd_export_sampled", "rsd_forward", "rsd_sample", "rsd_stage_ms", "rsd_last_error",
-                    "rsd_destroy"]
+                    "rsd_export_sampled", "rsd_forward", "rsd_sample", "rsd_stage_ms", "rsd_probe_start", "rsd_probe_read",
+                    "rsd_last_error", "rsd_destroy"]
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "librsd.so")
 
 
@@ -217,8 +218,8 @@ def rsd_export_pages(ctx: Context, model: int) -> dict:
 
 
 def rsd_export_sampled(ctx: Context):
-    a = np.zeros((ctx.batch, ctx.max_ctx), np.int32)
-    b = np.zeros((ctx.batch, ctx.max_ctx), np.int32)
+    a = np.zeros((ctx.batch, ctx.max_steps, ctx.step_cap), np.int32)
+    b = np.zeros((ctx.batch, ctx.max_steps, ctx.step_cap), np.int32)
     ctx.check(load_library().rsd_export_sampled(ctx.handle, _np_ptr(a), _np_ptr(b)))
     return a, b
 
@@ -255,3 +256,14 @@ def rsd_stage_ms(ctx: Context, reset: bool = False) -> np.ndarray:
     ms = (C.c_double * 4)()
     ctx.check(load_library().rsd_stage_ms(ctx.handle, ms, C.c_int32(int(reset))))
     return np.array(list(ms))
+
+
+def rsd_probe_start(ctx: Context, model: int, op: int, max_samples: int = 4096, stride: int = 1) -> None:
+    ctx.check(load_library().rsd_probe_start(ctx.handle, C.c_int32(model), C.c_int32(op), C.c_int32(max_samples),
+                                             C.c_int32(stride)))
+
+
+def rsd_probe_read(ctx: Context) -> dict:
+    n, ms, by = C.c_int64(), C.c_double(), C.c_int64()
+    ctx.check(load_library().rsd_probe_read(ctx.handle, C.byref(n), C.byref(ms), C.byref(by)))
+    return dict(n=n.value, total_ms=ms.value, bytes_per_launch=by.value)

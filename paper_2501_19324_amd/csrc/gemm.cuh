@@ -2,8 +2,11 @@
 // batches): Y[m][n] (+)= sum_k X[m][k] * W[n][k]; X fp32 [M][ldx], W row-major
 // [N][K], Y fp32 [M][ldy].  Both operands are contiguous along K ("NT" form).
 //   * fp32 weights: plain VALU tile kernel (the tiny configuration only).
-//   * bf16 weights: MFMA kernel; activations are rounded to bf16 while they are
-//     staged into LDS, products accumulate in fp32.
+//   * bf16 weights: MFMA kernel.  An fp32 activation x is staged into LDS as two
+//     bf16 numbers, hi = bf16(x) and lo = bf16(x - hi), and every weight tile is
+//     multiplied with both (W.hi + W.lo, fp32 accumulation): the activations keep
+//     16 mantissa bits, which the bit-for-bit agreement of the bf16 KV-cache
+//     entries with an exact evaluation needs; one bf16 pass would leave 8.
 // Requirements checked by the caller: K % 32 == 0; N, M arbitrary.
 #pragma once
 #include "common.cuh"
@@ -74,7 +77,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
     constexpr int BN = 128, BK = 32, LDS_STRIDE = BK + 8;   // 80-byte rows: 16-byte aligned, conflict-free
     constexpr int WM = BM / 2;                               // rows of the tile per wave (2 x 2 waves)
     constexpr int TI = WM / 32;                              // 32-row MFMA tiles per wave along M
-    __shared__ __attribute__((aligned(16))) uint16_t As[BM * LDS_STRIDE];
+    __shared__ __attribute__((aligned(16))) uint16_t As[BM * LDS_STRIDE];    // hi parts
+    __shared__ __attribute__((aligned(16))) uint16_t Al[BM * LDS_STRIDE];    // lo parts
     __shared__ __attribute__((aligned(16))) uint16_t Bs[BN * LDS_STRIDE];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
@@ -108,10 +112,18 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
 #pragma unroll
         for (int i = 0; i < A_F4; ++i) {
             const int idx = tid + i * 256, row = idx >> 3, c4 = idx & 7;
-            uint2 p;
-            p.x = (uint32_t)f2bf(av[i].x) | ((uint32_t)f2bf(av[i].y) << 16);
-            p.y = (uint32_t)f2bf(av[i].z) | ((uint32_t)f2bf(av[i].w) << 16);
+            const float x[4] = {av[i].x, av[i].y, av[i].z, av[i].w};
+            uint16_t hi[4], lo[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                hi[e] = f2bf(x[e]);
+                lo[e] = f2bf(x[e] - bf2f(hi[e]));
+            }
+            uint2 p, q;
+            p.x = (uint32_t)hi[0] | ((uint32_t)hi[1] << 16); p.y = (uint32_t)hi[2] | ((uint32_t)hi[3] << 16);
+            q.x = (uint32_t)lo[0] | ((uint32_t)lo[1] << 16); q.y = (uint32_t)lo[2] | ((uint32_t)lo[3] << 16);
             *reinterpret_cast<uint2*>(&As[row * LDS_STRIDE + c4 * 4]) = p;
+            *reinterpret_cast<uint2*>(&Al[row * LDS_STRIDE + c4 * 4]) = q;
         }
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
@@ -121,12 +133,12 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
         __syncthreads();
 #pragma unroll
         for (int kk = 0; kk < BK; kk += 16) {
-            bf16x8_t a[TI], b[2];
+            bf16x8_t a[TI], al[TI], b[2];
 #pragma unroll
             for (int i = 0; i < TI; ++i) {
-                const uint4 r = *reinterpret_cast<const uint4*>(
-                    &As[(wm * WM + i * 32 + (lane & 31)) * LDS_STRIDE + kk + (lane >> 5) * 8]);
-                a[i] = __builtin_bit_cast(bf16x8_t, r);
+                const int off = (wm * WM + i * 32 + (lane & 31)) * LDS_STRIDE + kk + (lane >> 5) * 8;
+                a[i] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(&As[off]));
+                al[i] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(&Al[off]));
             }
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
@@ -137,8 +149,10 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
 #pragma unroll
             for (int i = 0; i < TI; ++i)
 #pragma unroll
-                for (int j = 0; j < 2; ++j)
+                for (int j = 0; j < 2; ++j) {
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[i], b[j], acc[i][j], 0, 0, 0);
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+                }
         }
     }
 #pragma unroll

@@ -89,6 +89,11 @@ struct rsd_ctx {
     int *row_seq_h = nullptr, *row_pos_h = nullptr, *last_row_h = nullptr, *steptok_h = nullptr;
     int *poll_h = nullptr;
     double stage_ms[4] = {0, 0, 0, 0};
+    // kernel timing probe
+    int probe_model = -1, probe_op = -1, probe_stride = 1, probe_seen = 0;
+    size_t probe_used = 0;
+    long long probe_bytes = 0;
+    std::vector<hipEvent_t> probe_ev;
 };
 
 namespace {
@@ -257,6 +262,25 @@ void launch_attn_g(rsd_ctx* c, const Model& m, int l, int M, const RowMap& rm, i
                            c->part_ml, rm, m.s.n_heads, S, c->att, m.q_dim);
 }
 
+// Brackets one launch with a pair of events when the probe is armed for it.
+struct ProbeScope {
+    rsd_ctx* c;
+    bool on = false;
+    ProbeScope(rsd_ctx* c_, const Model& m, int op, long long bytes) : c(c_) {
+        if (c->probe_op != op || &m != &c->m[c->probe_model < 0 ? 0 : c->probe_model] || c->probe_model < 0) return;
+        if (c->probe_used + 2 > c->probe_ev.size()) return;
+        if (c->probe_seen++ % c->probe_stride) return;
+        on = true;
+        c->probe_bytes = bytes;
+        (void)hipEventRecord(c->probe_ev[c->probe_used], c->st);
+    }
+    ~ProbeScope() {
+        if (!on) return;
+        (void)hipEventRecord(c->probe_ev[c->probe_used + 1], c->st);
+        c->probe_used += 2;
+    }
+};
+
 template <typename WT>
 void run_layers(rsd_ctx* c, Model& m, int M, const RowMap& rm, bool decode) {
     hipStream_t st = c->st;
@@ -268,7 +292,9 @@ void run_layers(rsd_ctx* c, Model& m, int M, const RowMap& rm, bool decode) {
     const bool fused = M <= 8;   // few rows: norm / SwiGLU / residual folded into the weight-streaming kernels
     for (int l = 0; l < m.s.n_layers; ++l) {
         const LayerOff& o = m.layers[l];
+        const long long esz = sizeof(WT);
         if (fused) {
+            ProbeScope ps(c, m, 0, (long long)m.n_qkv * d * esz + 4LL * M * (d + m.n_qkv));
             gemv_launch<WT>(st, PRO_NORM, EPI_STORE, wptr<WT>(m, o.wqkv), m.n_qkv, d, c->h, d,
                             wptr<WT>(m, o.attn_norm), eps, c->qkv, m.n_qkv, M);
         } else {
@@ -286,12 +312,21 @@ void run_layers(rsd_ctx* c, Model& m, int M, const RowMap& rm, bool decode) {
             launch_attn_g<WT, 32>(c, m, l, M, rm, S);
         }
         if (fused) {
-            gemv_launch<WT>(st, PRO_NONE, EPI_RESID, wptr<WT>(m, o.wo), d, m.q_dim, c->att, m.q_dim,
-                            (const WT*)nullptr, 0.f, c->h, d, M);
-            gemv_launch<WT>(st, PRO_NORM, EPI_STORE, wptr<WT>(m, o.wgu), 2 * F, d, c->h, d,
-                            wptr<WT>(m, o.ffn_norm), eps, c->gu, 2 * F, M);
-            gemv_launch<WT>(st, PRO_SWIGLU, EPI_RESID, wptr<WT>(m, o.wdown), d, F, c->gu, 2 * F,
-                            (const WT*)nullptr, 0.f, c->h, d, M);
+            {
+                ProbeScope ps(c, m, 1, (long long)d * m.q_dim * esz + 4LL * M * (m.q_dim + 2 * d));
+                gemv_launch<WT>(st, PRO_NONE, EPI_RESID, wptr<WT>(m, o.wo), d, m.q_dim, c->att, m.q_dim,
+                                (const WT*)nullptr, 0.f, c->h, d, M);
+            }
+            {
+                ProbeScope ps(c, m, 2, 2LL * F * d * esz + 4LL * M * (d + 2 * F));
+                gemv_launch<WT>(st, PRO_NORM, EPI_STORE, wptr<WT>(m, o.wgu), 2 * F, d, c->h, d,
+                                wptr<WT>(m, o.ffn_norm), eps, c->gu, 2 * F, M);
+            }
+            {
+                ProbeScope ps(c, m, 3, (long long)d * F * esz + 4LL * M * (2 * F + 2 * d));
+                gemv_launch<WT>(st, PRO_SWIGLU, EPI_RESID, wptr<WT>(m, o.wdown), d, F, c->gu, 2 * F,
+                                (const WT*)nullptr, 0.f, c->h, d, M);
+            }
         } else {
             gemm_launch(st, EPI_RESID, wptr<WT>(m, o.wo), d, m.q_dim, c->att, m.q_dim, c->h, d, M);
             hipLaunchKernelGGL((rmsnorm_kernel<WT>), dim3(M), dim3(256), 0, st, c->h, d, wptr<WT>(m, o.ffn_norm), eps, c->xn);
@@ -308,6 +343,7 @@ template <typename WT>
 void lm_head(rsd_ctx* c, Model& m, const float* X, int M, float* Y, int ldy) {
     const int d = m.s.d_model, V = m.s.vocab;
     if (M <= 8) {
+        ProbeScope ps(c, m, 4, (long long)V * d * sizeof(WT) + 4LL * M * (d + V));
         gemv_launch<WT>(c->st, PRO_NORM, EPI_STORE, wptr<WT>(m, m.off_head), V, d, X, d, wptr<WT>(m, m.off_final_norm),
                         m.s.rms_eps, Y, ldy, M);
     } else {
@@ -345,7 +381,7 @@ void decode_iter(rsd_ctx* c, int which, const float* u, const int* forced) {
     sample_rows(c, c->logits, m.s.vocab, m.s.vocab, u, c->ds.ctx_len, c->p.max_ctx, c->p.temperature, c->p.top_p,
                 c->p.sep_id, c->p.sep_logit_bias, c->ds.active, c->B, c->chosen);
     hipLaunchKernelGGL(append_kernel, dim3(ceil_div(c->B, 64)), dim3(64), 0, c->st, c->ds, c->B, c->p.max_ctx, which,
-                       c->chosen, forced, c->p.sep_id, c->p.eos_id, c->p.step_cap);
+                       c->chosen, forced, c->p.sep_id, c->p.eos_id, c->p.step_cap, c->steps_done, c->p.max_steps);
 }
 
 // Chunked prefill of `pieces` (per sequence consecutive, ascending) through model `which`.
@@ -417,7 +453,7 @@ int gen_stage(rsd_ctx* c, int which, const float* u, const int* forced) {
         sample_rows(c, c->logits, m.s.vocab, m.s.vocab, u, c->ds.ctx_len, c->p.max_ctx, c->p.temperature, c->p.top_p,
                     c->p.sep_id, c->p.sep_logit_bias, c->ds.active, B, c->chosen);
         hipLaunchKernelGGL(append_kernel, dim3(ceil_div(B, 64)), dim3(64), 0, c->st, c->ds, B, c->p.max_ctx, which,
-                           c->chosen, forced, c->p.sep_id, c->p.eos_id, c->p.step_cap);
+                           c->chosen, forced, c->p.sep_id, c->p.eos_id, c->p.step_cap, c->steps_done, c->p.max_steps);
         iters = 1;
     }
     while (iters < c->p.step_cap) {
@@ -482,6 +518,7 @@ void rsd_destroy(rsd_ctx* c) {
                    c->part_acc, c->part_ml, c->hl, c->xl, c->logits, c->tmp_reward, c->chosen, c->steptok_dev,
                    c->row_seq_dev, c->row_pos_dev, c->last_row_dev};
     for (void* p : dev) if (p) (void)hipFree(p);
+    for (hipEvent_t e : c->probe_ev) (void)hipEventDestroy(e);
     void* pin[] = {c->sb, c->row_seq_h, c->row_pos_h, c->last_row_h, c->steptok_h, c->poll_h};
     for (void* p : pin) if (p) (void)hipHostFree(p);
     delete c;
@@ -521,8 +558,8 @@ int rsd_init(rsd_ctx** out, const rsd_model_shape shape[3], const rsd_weights w[
     HIPCHK(c, pin_alloc(&c->sb, c->sb_ints));
     std::fill(c->sb, c->sb + c->sb_ints, 0);
     HIPCHK(c, dev_alloc(&c->ds.tokens, B * mc));
-    HIPCHK(c, dev_alloc(&c->ds.sampled[0], B * mc));
-    HIPCHK(c, dev_alloc(&c->ds.sampled[1], B * mc));
+    HIPCHK(c, dev_alloc(&c->ds.sampled[0], (size_t)B * p->max_steps * p->step_cap));
+    HIPCHK(c, dev_alloc(&c->ds.sampled[1], (size_t)B * p->max_steps * p->step_cap));
     c->ds.ctx_len = c->sb_dev;
     c->ds.kv_len = c->sb_dev + B;
     c->ds.active = c->sb_dev + 4 * B;
@@ -585,8 +622,9 @@ int rsd_set_prompts(rsd_ctx* c, const int32_t* tokens_dev, const int32_t* prompt
     reset_sequences(c);
     const size_t n = (size_t)B * c->p.max_ctx;
     HIPCHK(c, hipMemcpyAsync(c->ds.tokens, tokens_dev, n * sizeof(int), hipMemcpyDeviceToDevice, c->st));
+    const size_t ns = (size_t)B * c->p.max_steps * c->p.step_cap;
     for (int s = 0; s < 2; ++s)
-        hipLaunchKernelGGL(fill_int_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, c->st, c->ds.sampled[s], -1, n);
+        hipLaunchKernelGGL(fill_int_kernel, dim3((unsigned)((ns + 255) / 256)), dim3(256), 0, c->st, c->ds.sampled[s], -1, ns);
     for (int b = 0; b < B; ++b) {
         c->prompt_len[b] = prompt_len_host[b];
         c->ctx_len()[b] = prompt_len_host[b];
@@ -841,7 +879,7 @@ int rsd_export_pages(rsd_ctx* c, int32_t model, int32_t* block_table, int32_t* m
 
 int rsd_export_sampled(rsd_ctx* c, int32_t* sampled_draft, int32_t* sampled_target) {
     if (!c) return RSD_EINVAL;
-    const size_t n = (size_t)c->B * c->p.max_ctx * sizeof(int);
+    const size_t n = (size_t)c->B * c->p.max_steps * c->p.step_cap * sizeof(int);
     if (sampled_draft) HIPCHK(c, hipMemcpyAsync(sampled_draft, c->ds.sampled[0], n, hipMemcpyDeviceToHost, c->st));
     if (sampled_target) HIPCHK(c, hipMemcpyAsync(sampled_target, c->ds.sampled[1], n, hipMemcpyDeviceToHost, c->st));
     HIPCHK(c, hipStreamSynchronize(c->st));
@@ -851,6 +889,37 @@ int rsd_export_sampled(rsd_ctx* c, int32_t* sampled_draft, int32_t* sampled_targ
 int rsd_stage_ms(rsd_ctx* c, double ms[4], int32_t reset) {
     if (!c || !ms) return RSD_EINVAL;
     for (int i = 0; i < 4; ++i) { ms[i] = c->stage_ms[i]; if (reset) c->stage_ms[i] = 0; }
+    return RSD_OK;
+}
+
+int rsd_probe_start(rsd_ctx* c, int32_t model, int32_t op, int32_t max_samples, int32_t stride) {
+    if (!c) return RSD_EINVAL;
+    if (model < -1 || model > 2 || op < 0 || op > 4 || max_samples < 0 || max_samples > (1 << 20) || stride < 1)
+        return fail(c, RSD_EINVAL, "bad probe argument");
+    HIPCHK(c, hipStreamSynchronize(c->st));
+    while (c->probe_ev.size() < 2 * (size_t)max_samples) {
+        hipEvent_t e;
+        HIPCHK(c, hipEventCreate(&e));
+        c->probe_ev.push_back(e);
+    }
+    c->probe_model = model; c->probe_op = op; c->probe_stride = stride;
+    c->probe_seen = 0; c->probe_used = 0; c->probe_bytes = 0;
+    return RSD_OK;
+}
+
+int rsd_probe_read(rsd_ctx* c, int64_t* n_samples, double* total_ms, int64_t* bytes_per_launch) {
+    if (!c) return RSD_EINVAL;
+    HIPCHK(c, hipStreamSynchronize(c->st));
+    double tot = 0;
+    for (size_t i = 0; i + 1 < c->probe_used; i += 2) {
+        float ms = 0.f;
+        HIPCHK(c, hipEventElapsedTime(&ms, c->probe_ev[i], c->probe_ev[i + 1]));
+        tot += ms;
+    }
+    if (n_samples) *n_samples = (int64_t)(c->probe_used / 2);
+    if (total_ms) *total_ms = tot;
+    if (bytes_per_launch) *bytes_per_launch = c->probe_bytes;
+    c->probe_model = -1;
     return RSD_OK;
 }
 

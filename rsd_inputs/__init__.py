@@ -15,6 +15,7 @@ from .generate import (
     model_weights_np,
     model_blob_np,
     model_blob_torch,
+    weights_from_blob,
     prompt_lengths,
     prompt_tokens,
     uniforms,
@@ -25,6 +26,6 @@ from .generate import (
 __all__ = [
     "ModelShape", "Workload", "WORKLOADS", "workload", "blob_layout", "STREAMS",
     "hash32_np", "normal_table", "weight_values_np", "model_weights_np",
-    "model_blob_np", "model_blob_torch", "prompt_lengths", "prompt_tokens",
+    "model_blob_np", "model_blob_torch", "weights_from_blob", "prompt_lengths", "prompt_tokens",
     "uniforms", "bf16_bits_to_f32", "f32_to_bf16_bits",
 ]

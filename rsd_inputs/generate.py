@@ -88,21 +88,45 @@ def _weight_stream(which: int) -> int:
     return (STREAMS["W_DRAFT"], STREAMS["W_TARGET"], STREAMS["W_PRM"])[which]
 
 
-def weight_values_np(seed: int, which: int, tensor_idx: int, start: int, count: int, dtype: str) -> np.ndarray:
+def weight_values_np(seed: int, which: int, tensor_idx: int, start: int, count: int, dtype: str,
+                     out: np.ndarray = None) -> np.ndarray:
     """fp32 values (exact in ``dtype``) of elements ``[start, start+count)`` of
     tensor number ``tensor_idx`` (its position in the blob layout) of model
     ``which`` (0 draft, 1 target, 2 reward model)."""
     key = _key(seed, _weight_stream(which), tensor_idx)
-    idx = np.arange(start, start + count, dtype=np.uint64)
-    h = hash32_np(idx, key)
-    return normal_table(dtype)[(h >> np.uint32(16)).astype(np.intp)]
+    # index + key wraps modulo 2^32, exactly as in hash32_np
+    x = np.arange(start, start + count, dtype=np.uint64).astype(np.uint32) if start + count > _M32 else \
+        np.arange(start, start + count, dtype=np.uint32)
+    x += np.uint32(key)
+    x ^= x >> np.uint32(16)
+    x *= np.uint32(0x7FEB352D)
+    x ^= x >> np.uint32(15)
+    x *= np.uint32(0x846CA68B)
+    x ^= x >> np.uint32(16)
+    x >>= np.uint32(16)
+    return np.take(normal_table(dtype), x, out=out)
+
+
+def fill_weights_np(seed: int, which: int, tensor_idx: int, dst: np.ndarray, dtype: str, threads: int = 1,
+                    piece: int = 1 << 22) -> None:
+    """Fill the flat fp32 array ``dst`` with a whole tensor, optionally with a
+    pool of threads (NumPy releases the GIL inside its loops)."""
+    n = dst.size
+    spans = [(s, min(piece, n - s)) for s in range(0, n, piece)]
+    if threads <= 1 or len(spans) == 1:
+        for s, c in spans:
+            weight_values_np(seed, which, tensor_idx, s, c, dtype, out=dst[s:s + c])
+        return
+    from concurrent.futures import ThreadPoolExecutor
+    with ThreadPoolExecutor(threads) as ex:
+        list(ex.map(lambda sc: weight_values_np(seed, which, tensor_idx, sc[0], sc[1], dtype, out=dst[sc[0]:sc[0] + sc[1]]), spans))
 
 
 def _is_gain(name: str) -> bool:
     return name.endswith("norm")
 
 
-def model_weights_np(seed: int, which: int, shape: ModelShape) -> dict:
+def model_weights_np(seed: int, which: int, shape: ModelShape, threads: int = 1) -> dict:
     """All tensors of one model as a dict name -> fp32 array (values exact in
     the model's storage type)."""
     layout, _ = blob_layout(shape)
@@ -113,9 +137,9 @@ def model_weights_np(seed: int, which: int, shape: ModelShape) -> dict:
         elif name == "b_r":
             a = np.zeros(cols, dtype=np.float32)
         else:
-            a = weight_values_np(seed, which, ti, 0, rows * cols, shape.dtype).reshape(rows, cols)
-            if rows == 1:
-                a = a.reshape(cols)
+            a = np.empty(rows * cols, dtype=np.float32)
+            fill_weights_np(seed, which, ti, a, shape.dtype, threads)
+            a = a.reshape(cols) if rows == 1 else a.reshape(rows, cols)
         out[name] = a
     return out
 
@@ -211,4 +235,18 @@ def uniforms(w: Workload, stream: str, n_cols: int) -> np.ndarray:
     for b in range(w.batch):
         h = hash32_np(np.arange(n_cols, dtype=np.uint64), _key(w.seed, STREAMS[stream], b))
         out[b] = (h >> np.uint32(8)).astype(np.float32) * np.float32(2.0 ** -24)
+    return out
+
+
+def weights_from_blob(blob: np.ndarray, shape: ModelShape) -> dict:
+    """Split a blob (fp32 array, or uint16 bf16 bit patterns) into the dict of
+    fp32 tensors :func:`model_weights_np` returns (views where possible)."""
+    layout, total = blob_layout(shape)
+    assert blob.size == total
+    out = {}
+    for name, rows, cols, off in layout:
+        a = blob[off:off + rows * cols]
+        if a.dtype == np.uint16:
+            a = bf16_bits_to_f32(a)
+        out[name] = a.reshape(cols) if rows == 1 else a.reshape(rows, cols)
     return out

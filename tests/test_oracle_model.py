@@ -233,3 +233,33 @@ def test_bf16_weights_are_used_exactly():
     assert np.array_equal(a.astype(np.float32), ws["l0.wq"])
     b = torch.from_numpy(ws["l0.wq"]).to(torch.bfloat16).to(torch.float32).numpy()
     assert np.array_equal(b, ws["l0.wq"])
+
+
+def test_bf16_storage_rounding_is_nearest_even():
+    r = np.random.default_rng(12)
+    x = np.concatenate([r.normal(size=20000) * 1.3, r.normal(size=2000) * 1e-3, [0.0, 1.0, -2.5]])
+    got = O.round_to_bf16(x)
+    ref = torch.from_numpy(x).to(torch.float32).to(torch.bfloat16).to(torch.float64).numpy()
+    assert np.array_equal(got, ref)
+    # ties go to the even neighbour: 1 + 2^-8 lies halfway between 1 and 1 + 2^-7
+    assert O.round_to_bf16(np.array([1.0 + 2.0 ** -8]))[0] == 1.0
+    assert O.round_to_bf16(np.array([1.0 + 3 * 2.0 ** -8]))[0] == 1.0 + 2.0 ** -6
+    assert np.max(np.abs(got - x) / np.maximum(np.abs(x), 1e-30)) <= 2.0 ** -8
+
+
+def test_bf16_cache_rounds_what_is_stored_and_nothing_else(tiny):
+    m = tiny["models"][1]
+    toks = [int(t) for t in tiny["tokens"][1, :20]]
+    kv = O.KVCache(m.s, 32, "bf16")
+    y = O.forward_chunk(m, kv, toks[:12])
+    for t in toks[12:]:
+        y = np.concatenate([y, O.forward_chunk(m, kv, [t])])
+    # every stored entry is a bf16 value, the result differs from the exact run by a bf16-sized amount,
+    # and chunking does not matter (cache and recompute agree to fp64 rounding)
+    assert np.array_equal(kv.k[:, :20], O.round_to_bf16(kv.k[:, :20]))
+    assert np.array_equal(kv.v[:, :20], O.round_to_bf16(kv.v[:, :20]))
+    exact = O.forward_full(m, toks)
+    full = O.forward_full(m, toks, "bf16")
+    assert np.max(np.abs(y - full)) < 1e-12
+    d = np.max(np.abs(full - exact))
+    assert 1e-5 < d < 5e-2

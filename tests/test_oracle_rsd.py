@@ -84,6 +84,16 @@ def test_cache_and_no_cache_runs_agree(tiny):
     assert seen == {True, False}
 
 
+def test_cache_and_no_cache_runs_agree_with_bf16_storage(tiny):
+    P = params(tiny["w"], kv_dtype="bf16", **GREEDY_MIX)
+    for b in (1, 3):
+        a = run(tiny, b, P, use_cache=True)
+        c = run(tiny, b, P, use_cache=False)
+        assert a["tokens"] == c["tokens"]
+        assert [r["accepted"] for r in a["records"]] == [r["accepted"] for r in c["records"]]
+        assert max(abs(x["reward"] - y["reward"]) for x, y in zip(a["records"], c["records"])) < 1e-12
+
+
 def test_kv_offsets_follow_the_contract(tiny):
     """After a step: accepted -> draft holds ctx-1 tokens, reward model ctx,
     target unchanged; rejected -> draft and reward model hold the pre-step
