@@ -64,6 +64,7 @@ def main():
     ap.add_argument("--probe-model", type=int, default=1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graphs", action="store_true")
+    ap.add_argument("--ops", action="store_true", help="extra passes after the timed region: per-projection table")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (sequences are independent; more GPUs would shard the "
@@ -134,6 +135,18 @@ def main():
                    "setup_s": round(t_setup, 1)},
         "roofline": roof,
     }
+    if args.ops:
+        table = {}
+        for model, shape in ((0, w.draft), (1, w.target)):
+            for name, op in PROBE_OPS.items():
+                R.rsd_probe_start(s.ctx, model, op, 4096, 1)
+                one_pass()
+                p = R.rsd_probe_read(s.ctx)
+                if p["n"]:
+                    us = p["total_ms"] / p["n"] * 1e3
+                    table[f"m{model}.{name}"] = {"us": round(us, 2), "MB": round(p["bytes_per_launch"] / 1e6, 2),
+                                                 "GBs": round(p["bytes_per_launch"] / us / 1e3, 1), "n": p["n"]}
+        line["config"]["ops"] = table
     s.close()
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(w)

@@ -10,6 +10,27 @@
 
 #define RSD_PAGE 16
 
+// bf16 caches keep the values of a page transposed, [head_dim][16 tokens], so that
+// the token axis (the contraction axis of P.V) is contiguous for the MFMA
+// operands; fp32 caches (tiny configuration, VALU kernels only) keep [16][head_dim].
+template <typename KT> struct KvTraits { static constexpr bool v_transposed = false; };
+template <> struct KvTraits<bf16_t> { static constexpr bool v_transposed = true; };
+
+// 8 consecutive head-dim elements [e0, e0+8) of token `slot` from one head's value page
+template <typename KT, int HD>
+__device__ __forceinline__ void load_v8(const KT* __restrict__ vhead, int slot, int e0, float o[8]) {
+    if (KvTraits<KT>::v_transposed) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] = ld1(vhead + (e0 + e) * RSD_PAGE + slot);
+    } else {
+        load8(vhead + slot * HD + e0, o);
+    }
+}
+template <typename KT, int HD>
+__device__ __forceinline__ KT* v_addr(KT* vhead, int slot, int e) {
+    return KvTraits<KT>::v_transposed ? vhead + e * RSD_PAGE + slot : vhead + slot * HD + e;
+}
+
 // One block per (row, kv head, split).  The G query heads of the group share
 // every key/value load.  A "lane group" of HD/8 lanes covers one token (16
 // bytes of bf16 per lane); each lane group runs its own online softmax over
@@ -65,7 +86,7 @@ __global__ __launch_bounds__(256) void attn_rows_kernel(const float* __restrict_
             const int t = pg * RSD_PAGE + slot;
             float kx[8], vx[8];
             load8(kbase + slot * HD + part * 8, kx);
-            load8(vbase + slot * HD + part * 8, vx);
+            load_v8<KT, HD>(vbase, slot, part * 8, vx);
             float s[G];
 #pragma unroll
             for (int g = 0; g < G; ++g) {
@@ -80,8 +101,8 @@ __global__ __launch_bounds__(256) void attn_rows_kernel(const float* __restrict_
 #pragma unroll
                 for (int g = 0; g < G; ++g) {
                     const float mn = fmaxf(mx[g], s[g]);
-                    const float corr = expf(mx[g] - mn);      // exp(-inf) = 0 on the first token
-                    const float p = expf(s[g] - mn);
+                    const float corr = __expf(mx[g] - mn);      // exp(-inf) = 0 on the first token
+                    const float p = __expf(s[g] - mn);
                     l[g] = l[g] * corr + p;
 #pragma unroll
                     for (int e = 0; e < 8; ++e) acc[g][e] = acc[g][e] * corr + p * vx[e];
@@ -99,8 +120,8 @@ __global__ __launch_bounds__(256) void attn_rows_kernel(const float* __restrict_
             const float mo = __shfl_xor(mx[g], off, RSD_WAVE);
             const float lo = __shfl_xor(l[g], off, RSD_WAVE);
             const float mn = fmaxf(mx[g], mo);
-            const float ca = (mx[g] == -INFINITY) ? 0.0f : expf(mx[g] - mn);
-            const float cb = (mo == -INFINITY) ? 0.0f : expf(mo - mn);
+            const float ca = (mx[g] == -INFINITY) ? 0.0f : __expf(mx[g] - mn);
+            const float cb = (mo == -INFINITY) ? 0.0f : __expf(mo - mn);
             l[g] = l[g] * ca + lo * cb;
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
@@ -129,7 +150,7 @@ __global__ __launch_bounds__(256) void attn_rows_kernel(const float* __restrict_
         float a = 0.0f, ll = 0.0f;
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
-            const float c = (s_m[w][g] == -INFINITY) ? 0.0f : expf(s_m[w][g] - mn);
+            const float c = (s_m[w][g] == -INFINITY) ? 0.0f : __expf(s_m[w][g] - mn);
             a += s_acc[w][g][e] * c;
             ll += s_l[w][g] * c;
         }
@@ -157,7 +178,7 @@ __global__ void attn_combine_kernel(const float* __restrict__ part_acc, const fl
     float a = 0.0f, ll = 0.0f;
     for (int s = 0; s < S; ++s) {
         const float m = part_ml[(base + s) * 2];
-        const float c = (m == -INFINITY) ? 0.0f : expf(m - mn);
+        const float c = (m == -INFINITY) ? 0.0f : __expf(m - mn);
         a += part_acc[(base + s) * HD + e] * c;
         ll += part_ml[(base + s) * 2 + 1] * c;
     }
@@ -182,7 +203,7 @@ __global__ __launch_bounds__(256) void rope_kv_kernel(float* __restrict__ qkv, i
     const int page = block_table[(size_t)seq * max_pages + pos / RSD_PAGE], slot = pos % RSD_PAGE;
     const size_t page_elts = (size_t)2 * Hkv * RSD_PAGE * HD;
     KT* kdst = pool_layer + (size_t)page * page_elts + (size_t)slot * HD;
-    KT* vdst = kdst + (size_t)Hkv * RSD_PAGE * HD;
+    KT* vpage = pool_layer + (size_t)page * page_elts + (size_t)Hkv * RSD_PAGE * HD;
     const int nq = H * HALF, nk = Hkv * HALF, nv = Hkv * HD;
     for (int idx = threadIdx.x; idx < nq + nk + nv; idx += 256) {
         if (idx < nq + nk) {
@@ -198,7 +219,497 @@ __global__ __launch_bounds__(256) void rope_kv_kernel(float* __restrict__ qkv, i
             }
         } else {
             const int j = idx - nq - nk, hk = j / HD, e = j - hk * HD;
-            st1(vdst + (size_t)hk * RSD_PAGE * HD + e, row[(H + Hkv) * HD + j]);
+            st1(v_addr<KT, HD>(vpage + (size_t)hk * RSD_PAGE * HD, slot, e), row[(H + Hkv) * HD + j]);
         }
     }
+}
+
+// ---------------------------------------------------------------------------
+// Single-token decode: rotary embedding, cache write and attention in one
+// launch.  grid = (sequences, kv heads, S).  Every block rotates the group's
+// queries itself; the cached positions 0..pos-1 are cut into S page ranges, one
+// per block, and the new token (position pos) is added by the block of the
+// last range straight from registers, after rounding its key and value to the
+// cache's storage type, and written to the cache by that block.  With S > 1
+// each block leaves a partial (max, sum, accumulator); the block that draws
+// the last ticket of its (sequence, kv head) merges them and resets the ticket.
+template <typename KT> __device__ __forceinline__ float round_store(float v);
+template <> __device__ __forceinline__ float round_store<float>(float v) { return v; }
+template <> __device__ __forceinline__ float round_store<bf16_t>(float v) { return bf2f(f2bf(v)); }
+
+__device__ __forceinline__ void store8(float* p, const float v[8]) {
+    *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+    *reinterpret_cast<float4*>(p + 4) = make_float4(v[4], v[5], v[6], v[7]);
+}
+__device__ __forceinline__ void store8(bf16_t* p, const float v[8]) {
+    uint4 r;
+    r.x = (uint32_t)f2bf(v[0]) | ((uint32_t)f2bf(v[1]) << 16);
+    r.y = (uint32_t)f2bf(v[2]) | ((uint32_t)f2bf(v[3]) << 16);
+    r.z = (uint32_t)f2bf(v[4]) | ((uint32_t)f2bf(v[5]) << 16);
+    r.w = (uint32_t)f2bf(v[6]) | ((uint32_t)f2bf(v[7]) << 16);
+    *reinterpret_cast<uint4*>(p) = r;
+}
+
+// rotate the 8 elements [e0, e0+8) of one head vector `src` (fp32, HD long)
+template <int HD>
+__device__ __forceinline__ void rope8(const float* __restrict__ src, const float2* __restrict__ cs, int e0, float o[8]) {
+    constexpr int HALF = HD / 2;
+    float own[8], oth[8];
+    load8(src + e0, own);
+    const bool first = e0 < HALF;
+    load8(src + (first ? e0 + HALF : e0 - HALF), oth);
+    const int i0 = first ? e0 : e0 - HALF;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const float2 c = cs[i0 + e];
+        o[e] = first ? (own[e] * c.x - oth[e] * c.y) : (own[e] * c.x + oth[e] * c.y);
+    }
+}
+
+template <typename KT, int HD, int G>
+__global__ __launch_bounds__(256) void attn_decode_kernel(const float* __restrict__ qkv, int ldq,
+                                                          KT* __restrict__ pool_layer,
+                                                          const int* __restrict__ block_table, int max_pages,
+                                                          const int* __restrict__ kv_len,
+                                                          const int* __restrict__ active,
+                                                          const float2* __restrict__ rope, int H, int Hkv, int S,
+                                                          float scale, float* __restrict__ out, int ldo,
+                                                          float* part_acc, float* part_ml, int* tickets) {
+    constexpr int LPT = HD / 8, TPW = 64 / LPT;
+    constexpr int ITERS = RSD_PAGE / TPW > 0 ? RSD_PAGE / TPW : 1;
+    const int r = blockIdx.x, hk = blockIdx.y, sp = blockIdx.z;
+    if (!active[r]) return;
+    const int pos = kv_len[r];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int part = lane % LPT, tsub = lane / LPT;
+    const float* row = qkv + (size_t)r * ldq;
+    const float2* cs = rope + (size_t)pos * (HD / 2);
+
+    float q[G][8];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        rope8<HD>(row + (hk * G + g) * HD, cs, part * 8, q[g]);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) q[g][e] *= scale;
+    }
+    float mx[G], l[G], acc[G][8];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        mx[g] = -INFINITY; l[g] = 0.0f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[g][e] = 0.0f;
+    }
+    auto absorb = [&](const float kx[8], const float vx[8], bool valid) {
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            float d = 0.0f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) d += q[g][e] * kx[e];
+#pragma unroll
+            for (int off = 1; off < LPT; off <<= 1) d += __shfl_xor(d, off, RSD_WAVE);
+            if (valid) {
+                const float mn = fmaxf(mx[g], d);
+                const float corr = __expf(mx[g] - mn);
+                const float p = __expf(d - mn);
+                l[g] = l[g] * corr + p;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc[g][e] = acc[g][e] * corr + p * vx[e];
+                mx[g] = mn;
+            }
+        }
+    };
+
+    const int n_pages = (pos + RSD_PAGE - 1) / RSD_PAGE;      // pages holding cached positions 0..pos-1
+    const int pps = (n_pages + S - 1) / S;
+    const int p_begin = sp * pps, p_end = min(n_pages, p_begin + pps);
+    const int* bt = block_table + (size_t)r * max_pages;
+    const size_t page_elts = (size_t)2 * Hkv * RSD_PAGE * HD;
+    const size_t head_off = (size_t)hk * RSD_PAGE * HD, v_off = (size_t)Hkv * RSD_PAGE * HD;
+
+    for (int pg = p_begin + wave; pg < p_end; pg += 4) {
+        const KT* kbase = pool_layer + (size_t)bt[pg] * page_elts + head_off;
+        float kx[ITERS][8], vx[ITERS][8];
+#pragma unroll
+        for (int it = 0; it < ITERS; ++it) {
+            const int slot = it * TPW + tsub;
+            load8(kbase + slot * HD + part * 8, kx[it]);
+            load_v8<KT, HD>(kbase + v_off, slot, part * 8, vx[it]);
+        }
+#pragma unroll
+        for (int it = 0; it < ITERS; ++it) absorb(kx[it], vx[it], pg * RSD_PAGE + it * TPW + tsub < pos);
+    }
+    if (sp == S - 1 && wave == 0) {
+        // the new token: rotate its key, round key and value as the cache stores them, write, attend
+        float kn[8], vn[8];
+        rope8<HD>(row + (H + hk) * HD, cs, part * 8, kn);
+        load8(row + (H + Hkv + hk) * HD + part * 8, vn);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { kn[e] = round_store<KT>(kn[e]); vn[e] = round_store<KT>(vn[e]); }
+        if (tsub == 0) {
+            KT* khead = pool_layer + (size_t)bt[pos / RSD_PAGE] * page_elts + head_off;
+            store8(khead + (size_t)(pos % RSD_PAGE) * HD + part * 8, kn);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) st1(v_addr<KT, HD>(khead + v_off, pos % RSD_PAGE, part * 8 + e), vn[e]);
+        }
+        absorb(kn, vn, tsub == 0);
+    }
+
+#pragma unroll
+    for (int off = LPT; off < 64; off <<= 1) {
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            const float mo = __shfl_xor(mx[g], off, RSD_WAVE);
+            const float lo = __shfl_xor(l[g], off, RSD_WAVE);
+            const float mn = fmaxf(mx[g], mo);
+            const float ca = (mx[g] == -INFINITY) ? 0.0f : __expf(mx[g] - mn);
+            const float cb = (mo == -INFINITY) ? 0.0f : __expf(mo - mn);
+            l[g] = l[g] * ca + lo * cb;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float ao = __shfl_xor(acc[g][e], off, RSD_WAVE);
+                acc[g][e] = acc[g][e] * ca + ao * cb;
+            }
+            mx[g] = mn;
+        }
+    }
+    __shared__ float s_acc[4][G][HD];
+    __shared__ float s_m[4][G], s_l[4][G];
+    __shared__ int s_last;
+    if (lane < LPT) {
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) s_acc[wave][g][part * 8 + e] = acc[g][e];
+            if (lane == 0) { s_m[wave][g] = mx[g]; s_l[wave][g] = l[g]; }
+        }
+    }
+    __syncthreads();
+    for (int idx = tid; idx < G * HD; idx += 256) {
+        const int g = idx / HD, e = idx - g * HD;
+        const float mn = fmaxf(fmaxf(s_m[0][g], s_m[1][g]), fmaxf(s_m[2][g], s_m[3][g]));
+        float a = 0.0f, ll = 0.0f;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            const float c = (s_m[w][g] == -INFINITY) ? 0.0f : __expf(s_m[w][g] - mn);
+            a += s_acc[w][g][e] * c;
+            ll += s_l[w][g] * c;
+        }
+        const int h = hk * G + g;
+        if (S == 1) {
+            out[(size_t)r * ldo + h * HD + e] = a / ll;
+        } else {
+            const size_t pi = ((size_t)r * H + h) * S + sp;
+            part_acc[pi * HD + e] = a;
+            if (e == 0) { part_ml[pi * 2] = mn; part_ml[pi * 2 + 1] = ll; }
+        }
+    }
+    if (S == 1) return;
+    __threadfence();
+    __syncthreads();
+    if (tid == 0) s_last = (atomicAdd(&tickets[r * Hkv + hk], 1) == S - 1);
+    __syncthreads();
+    if (!s_last) return;
+    __threadfence();
+    // partials of other blocks: device-scope loads (they bypass this unit's L1), all independent of one another
+    auto ld = [](const float* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); };
+    __shared__ float s_c[G][32];       // S <= 32: weight exp(m_s - max) of every split
+    __shared__ float s_den[G];
+    for (int idx = tid; idx < G * 32; idx += 256) {
+        const int g = idx >> 5, sl = idx & 31;
+        if (sl < S) s_c[g][sl] = ld(&part_ml[(((size_t)r * H + hk * G + g) * S + sl) * 2]);
+    }
+    __syncthreads();
+    if (tid < G) {
+        const int g = tid;
+        float mn = -INFINITY;
+        for (int sl = 0; sl < S; ++sl) mn = fmaxf(mn, s_c[g][sl]);
+        float den = 0.0f;
+        for (int sl = 0; sl < S; ++sl) {
+            const float m = s_c[g][sl];
+            const float cc = (m == -INFINITY) ? 0.0f : __expf(m - mn);
+            den += ld(&part_ml[(((size_t)r * H + hk * G + g) * S + sl) * 2 + 1]) * cc;
+            s_c[g][sl] = cc;
+        }
+        s_den[g] = den;
+    }
+    __syncthreads();
+    for (int idx = tid; idx < G * HD; idx += 256) {
+        const int g = idx / HD, e = idx - g * HD;
+        const size_t base = ((size_t)r * H + hk * G + g) * S;
+        float a = 0.0f;
+        for (int sl = 0; sl < S; ++sl) a += ld(&part_acc[(base + sl) * HD + e]) * s_c[g][sl];
+        out[(size_t)r * ldo + (hk * G + g) * HD + e] = a / s_den[g];
+    }
+    if (tid == 0) tickets[r * Hkv + hk] = 0;
+}
+
+// ---------------------------------------------------------------------------
+// MFMA single-token decode attention for bf16 caches, head_dim 128.
+//
+// One block per (sequence, kv head, split); each of its NW waves takes pages
+// round-robin.  Per page (16 tokens) and wave:
+//   S^T[token][head] = K . Q^T      v_mfma_f32_16x16x32_bf16, 4 steps over head_dim;
+//                                   K straight from HBM (64 contiguous bytes per lane),
+//                                   Q^T of the group's G heads padded to 16 columns
+//   online softmax per head (column), in the accumulator layout
+//   O[head][col]   += P . V         v_mfma_f32_16x16x16bf16_1k, 8 column blocks; the
+//                                   softmax output already sits in the A-operand layout,
+//                                   V^T pages give 8 contiguous bytes per lane
+// The fp32 operands (rotated, scaled q and the probabilities) enter as hi + lo
+// bf16 pairs, two MFMAs each, so they keep 16 significant bits; K and V are
+// bf16 in the cache and enter exactly.  The new token is added from registers
+// by wave 0 of the last split, which also writes it to the cache.
+typedef __attribute__((ext_vector_type(8))) __bf16 abf16x8_t;
+typedef __attribute__((ext_vector_type(4))) short as16x4_t;
+typedef __attribute__((ext_vector_type(4))) float af32x4_t;
+
+__device__ __forceinline__ void split_hi_lo8(const float x[8], abf16x8_t& hi, abf16x8_t& lo) {
+    uint32_t h[4], l[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const uint16_t h0 = f2bf(x[2 * e]), h1 = f2bf(x[2 * e + 1]);
+        const uint16_t l0 = f2bf(x[2 * e] - bf2f(h0)), l1 = f2bf(x[2 * e + 1] - bf2f(h1));
+        h[e] = (uint32_t)h0 | ((uint32_t)h1 << 16);
+        l[e] = (uint32_t)l0 | ((uint32_t)l1 << 16);
+    }
+    hi = __builtin_bit_cast(abf16x8_t, make_uint4(h[0], h[1], h[2], h[3]));
+    lo = __builtin_bit_cast(abf16x8_t, make_uint4(l[0], l[1], l[2], l[3]));
+}
+
+template <int G, int NW>
+__global__ __launch_bounds__(NW * 64) void attn_decode_mfma_kernel(const float* __restrict__ qkv, int ldq,
+                                                                   bf16_t* __restrict__ pool_layer,
+                                                                   const int* __restrict__ block_table, int max_pages,
+                                                                   const int* __restrict__ kv_len,
+                                                                   const int* __restrict__ active,
+                                                                   const float2* __restrict__ rope, int H, int Hkv,
+                                                                   int S, float scale, float* __restrict__ out, int ldo,
+                                                                   float* part_acc, float* part_ml, int* tickets) {
+    constexpr int HD = 128;
+    const int r = blockIdx.x, hk = blockIdx.y, sp = blockIdx.z;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    // independent loads issued together.  With one split the pages of this wave are wave, wave + NW, ...
+    // whatever the position turns out to be, so their table entries (lane i holds the i-th) can be
+    // requested before the position is known; entries beyond the sequence are never used.
+    const int is_active = active[r];
+    const int pos = kv_len[r];
+    int bt_mine = -1;
+    if (S == 1 && wave + lane * NW < max_pages) bt_mine = block_table[(size_t)r * max_pages + wave + lane * NW];
+    if (!is_active) return;
+    const int l16 = lane & 15, c = lane >> 4;
+    const float* row = qkv + (size_t)r * ldq;
+    const float2* cs = rope + (size_t)pos * (HD / 2);
+
+    const int n_pages = (pos + RSD_PAGE - 1) / RSD_PAGE;      // pages holding cached positions 0..pos-1
+    const int pps = (n_pages + S - 1) / S;
+    const int p_begin = sp * pps, p_end = min(n_pages, p_begin + pps);
+    const int* bt = block_table + (size_t)r * max_pages;
+    const size_t page_elts = (size_t)2 * Hkv * RSD_PAGE * HD;
+    const size_t head_off = (size_t)hk * RSD_PAGE * HD, v_off = (size_t)Hkv * RSD_PAGE * HD;
+
+    // operands of one page: K chunk j of token l16 = K[l16][c*32 + j*8 ..+8]; V block nb = V^T[nb*16 + l16][c*4 ..+4]
+    uint4 kc[4], kn[4];
+    uint2 vc[8], vn[8];
+    auto fetch_phys = [&](int phys, uint4 k[4], uint2 v[8]) {
+        const bf16_t* kb = pool_layer + (size_t)phys * page_elts + head_off;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) k[j] = *reinterpret_cast<const uint4*>(kb + l16 * HD + c * 32 + j * 8);
+#pragma unroll
+        for (int nb = 0; nb < 8; ++nb) v[nb] = *reinterpret_cast<const uint2*>(kb + v_off + (nb * 16 + l16) * RSD_PAGE + c * 4);
+    };
+    if (S > 1 && p_begin + wave + lane * NW < p_end) bt_mine = bt[p_begin + wave + lane * NW];
+    // i-th page of this wave (i < 64: a block never holds more than 64 * NW pages)
+    auto fetch = [&](int i, uint4 k[4], uint2 v[8]) { fetch_phys(__shfl(bt_mine, i, RSD_WAVE), k, v); };
+    uint4 k2[4], k3[4];
+    uint2 v2[8], v3[8];          // three pages in flight ahead of the one being used
+    int pg = p_begin + wave, it = 0;
+    if (pg < p_end) fetch(0, kc, vc);
+    if (pg + NW < p_end) fetch(1, kn, vn);
+    if (pg + 2 * NW < p_end) fetch(2, k2, v2);
+
+    // Q^T operand: column l16 = head, k-group c
+    abf16x8_t qh[4], ql[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        float qv[8];
+        if (l16 < G) {
+            rope8<HD>(row + (hk * G + l16) * HD, cs, c * 32 + j * 8, qv);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) qv[e] *= scale;
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) qv[e] = 0.0f;
+        }
+        split_hi_lo8(qv, qh[j], ql[j]);
+    }
+
+    // the new token as a pseudo page whose only valid token is row 0 (wave 0 of the last split):
+    // rotate its key, round key and value to bf16 as the cache stores them, write them to the cache.
+    // Done before the page loop so that its loads overlap the first page fetches.
+    const bool owns_new = (sp == S - 1 && wave == 0);
+    uint4 k1[4];
+    uint2 v1[8];
+    if (owns_new) {
+        bf16_t* kb = pool_layer + (size_t)bt[pos / RSD_PAGE] * page_elts + head_off;
+        const int slot = pos % RSD_PAGE;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            float kv[8];
+            rope8<HD>(row + (H + hk) * HD, cs, c * 32 + j * 8, kv);
+            uint4 pk;
+            pk.x = (uint32_t)f2bf(kv[0]) | ((uint32_t)f2bf(kv[1]) << 16);
+            pk.y = (uint32_t)f2bf(kv[2]) | ((uint32_t)f2bf(kv[3]) << 16);
+            pk.z = (uint32_t)f2bf(kv[4]) | ((uint32_t)f2bf(kv[5]) << 16);
+            pk.w = (uint32_t)f2bf(kv[6]) | ((uint32_t)f2bf(kv[7]) << 16);
+            if (l16 == 0) *reinterpret_cast<uint4*>(kb + (size_t)slot * HD + c * 32 + j * 8) = pk;
+            k1[j] = (l16 == 0) ? pk : make_uint4(0u, 0u, 0u, 0u);
+        }
+#pragma unroll
+        for (int nb = 0; nb < 8; ++nb) {
+            const uint16_t vb = f2bf(row[(H + Hkv + hk) * HD + nb * 16 + l16]);
+            if (c == 0) kb[v_off + (size_t)(nb * 16 + l16) * RSD_PAGE + slot].v = vb;
+            v1[nb] = make_uint2(c == 0 ? (uint32_t)vb : 0u, 0u);
+        }
+    }
+
+    float m_run = -INFINITY, l_run = 0.0f;                 // of head l16 (replicated over the 4 lanes sharing it)
+    af32x4_t o[8];                                          // o[nb][i] = O[head c*4+i][nb*16 + l16]
+#pragma unroll
+    for (int nb = 0; nb < 8; ++nb) o[nb] = af32x4_t{0.f, 0.f, 0.f, 0.f};
+
+    // one page: tokens c*4+i of it are valid iff (vmask >> i) & 1
+    auto process = [&](const uint4 k[4], const uint2 v[8], int vmask) {
+        af32x4_t s = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const abf16x8_t ka = __builtin_bit_cast(abf16x8_t, k[j]);
+            s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, ql[j], s, 0, 0, 0);
+            s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, qh[j], s, 0, 0, 0);
+        }
+        float mloc = -INFINITY;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) if ((vmask >> i) & 1) mloc = fmaxf(mloc, s[i]);
+        mloc = fmaxf(mloc, __shfl_xor(mloc, 16, RSD_WAVE));
+        mloc = fmaxf(mloc, __shfl_xor(mloc, 32, RSD_WAVE));
+        const float m_new = fmaxf(m_run, mloc);
+        const float corr = (m_run == -INFINITY) ? 0.0f : __expf(m_run - m_new);
+        float p[4], lsum = 0.0f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            p[i] = (((vmask >> i) & 1) && m_new > -INFINITY) ? __expf(s[i] - m_new) : 0.0f;
+            lsum += p[i];
+        }
+        lsum += __shfl_xor(lsum, 16, RSD_WAVE);
+        lsum += __shfl_xor(lsum, 32, RSD_WAVE);
+        l_run = l_run * corr + lsum;
+        m_run = m_new;
+        // P as A operand (row = head l16, k = token c*4+i): hi and lo halves
+        uint16_t ph[4], pl[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { ph[i] = f2bf(p[i]); pl[i] = f2bf(p[i] - bf2f(ph[i])); }
+        const as16x4_t pa = __builtin_bit_cast(as16x4_t, make_uint2((uint32_t)ph[0] | ((uint32_t)ph[1] << 16), (uint32_t)ph[2] | ((uint32_t)ph[3] << 16)));
+        const as16x4_t pb = __builtin_bit_cast(as16x4_t, make_uint2((uint32_t)pl[0] | ((uint32_t)pl[1] << 16), (uint32_t)pl[2] | ((uint32_t)pl[3] << 16)));
+        // the accumulator rows of this lane are heads c*4+i: fetch their correction factors
+        float cr[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) cr[i] = __shfl(corr, c * 4 + i, RSD_WAVE);
+        // slots past the sequence hold whatever the pool held: zero them (0 * NaN would poison the sum)
+        const uint32_t mk0 = ((vmask & 1) ? 0xFFFFu : 0u) | ((vmask & 2) ? 0xFFFF0000u : 0u);
+        const uint32_t mk1 = ((vmask & 4) ? 0xFFFFu : 0u) | ((vmask & 8) ? 0xFFFF0000u : 0u);
+#pragma unroll
+        for (int nb = 0; nb < 8; ++nb) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) o[nb][i] *= cr[i];
+            const as16x4_t vb = __builtin_bit_cast(as16x4_t, make_uint2(v[nb].x & mk0, v[nb].y & mk1));
+            o[nb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pb, vb, o[nb], 0, 0, 0);
+            o[nb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pa, vb, o[nb], 0, 0, 0);
+        }
+    };
+
+    while (pg < p_end) {
+        // the next two pages are in registers or on their way; start the third before using this one
+        if (pg + 3 * NW < p_end) fetch(it + 3, k3, v3);
+        int vmask = 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) vmask |= (pg * RSD_PAGE + c * 4 + i < pos) ? (1 << i) : 0;
+        process(kc, vc, vmask);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { kc[j] = kn[j]; kn[j] = k2[j]; k2[j] = k3[j]; }
+#pragma unroll
+        for (int nb = 0; nb < 8; ++nb) { vc[nb] = vn[nb]; vn[nb] = v2[nb]; v2[nb] = v3[nb]; }
+        pg += NW;
+        ++it;
+    }
+
+    if (owns_new) process(k1, v1, c == 0 ? 1 : 0);
+
+    // ---- merge the waves of the block through LDS
+    __shared__ float s_o[NW][G][HD];
+    __shared__ float s_m[NW][16], s_l[NW][16];
+    __shared__ int s_last;
+    if (c == 0) { s_m[wave][l16] = m_run; s_l[wave][l16] = l_run; }
+#pragma unroll
+    for (int nb = 0; nb < 8; ++nb)
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if (c * 4 + i < G) s_o[wave][c * 4 + i][nb * 16 + l16] = o[nb][i];
+    __syncthreads();
+    for (int idx = tid; idx < G * HD; idx += NW * 64) {
+        const int g = idx / HD, e = idx - g * HD;
+        float mn = -INFINITY;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) mn = fmaxf(mn, s_m[w][g]);
+        float a = 0.0f, ll = 0.0f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+            const float cc = (s_m[w][g] == -INFINITY) ? 0.0f : __expf(s_m[w][g] - mn);
+            a += s_o[w][g][e] * cc;
+            ll += s_l[w][g] * cc;
+        }
+        const int h = hk * G + g;
+        if (S == 1) {
+            out[(size_t)r * ldo + h * HD + e] = a / ll;
+        } else {
+            const size_t pi = ((size_t)r * H + h) * S + sp;
+            part_acc[pi * HD + e] = a;
+            if (e == 0) { part_ml[pi * 2] = mn; part_ml[pi * 2 + 1] = ll; }
+        }
+    }
+    if (S == 1) return;
+    __threadfence();
+    __syncthreads();
+    if (tid == 0) s_last = (atomicAdd(&tickets[r * Hkv + hk], 1) == S - 1);
+    __syncthreads();
+    if (!s_last) return;
+    __threadfence();
+    auto ld = [](const float* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); };
+    __shared__ float s_c[G][64];       // S <= 64: weight exp(m_s - max) of every split
+    __shared__ float s_den[G];
+    for (int idx = tid; idx < G * 64; idx += NW * 64) {
+        const int g = idx >> 6, sl = idx & 63;
+        if (sl < S) s_c[g][sl] = ld(&part_ml[(((size_t)r * H + hk * G + g) * S + sl) * 2]);
+    }
+    __syncthreads();
+    if (tid < G) {
+        const int g = tid;
+        float mn = -INFINITY;
+        for (int sl = 0; sl < S; ++sl) mn = fmaxf(mn, s_c[g][sl]);
+        float den = 0.0f;
+        for (int sl = 0; sl < S; ++sl) {
+            const float m = s_c[g][sl];
+            const float cc = (m == -INFINITY) ? 0.0f : __expf(m - mn);
+            den += ld(&part_ml[(((size_t)r * H + hk * G + g) * S + sl) * 2 + 1]) * cc;
+            s_c[g][sl] = cc;
+        }
+        s_den[g] = den;
+    }
+    __syncthreads();
+    for (int idx = tid; idx < G * HD; idx += NW * 64) {
+        const int g = idx / HD, e = idx - g * HD;
+        const size_t base = ((size_t)r * H + hk * G + g) * S;
+        float a = 0.0f;
+        for (int sl = 0; sl < S; ++sl) a += ld(&part_acc[(base + sl) * HD + e]) * s_c[g][sl];
+        out[(size_t)r * ldo + (hk * G + g) * HD + e] = a / s_den[g];
+    }
+    if (tid == 0) tickets[r * Hkv + hk] = 0;
 }

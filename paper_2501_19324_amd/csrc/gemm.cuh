@@ -66,36 +66,43 @@ __global__ __launch_bounds__(256) void sgemm_nt_kernel(const float* __restrict__
 }
 
 // ---------------------------------------------------------------- bf16 MFMA
-// Block tile BM x 128 (BM = 64 or 128), K step 32, 256 threads = 4 waves.
+// Block tile BM x BN (64 or 128 each), K step 32, 256 threads = 2 x 2 waves.
 // v_mfma_f32_32x32x16_bf16: per lane 8 consecutive-k bf16 of row (lane % 32) at
 // k offset 8 * (lane / 32) for each operand; the 16 results of a lane sit at
 // rows 8 * (v / 4) + 4 * (lane / 32) + v % 4, column lane % 32.
-template <int BM, int EPI>
+// blockIdx.z cuts K into gridDim.z slices (few-row GEMMs stream the weights and
+// need more blocks than output tiles); with slices the tile is stored to
+// part[z][M][N] and splitk_reduce_kernel adds the slices in a fixed order.
+template <int BM, int BN, int EPI>
 __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict__ W, int N, int K,
                                                         const float* __restrict__ X, int ldx,
-                                                        float* __restrict__ Y, int ldy, int M) {
-    constexpr int BN = 128, BK = 32, LDS_STRIDE = BK + 8;   // 80-byte rows: 16-byte aligned, conflict-free
-    constexpr int WM = BM / 2;                               // rows of the tile per wave (2 x 2 waves)
-    constexpr int TI = WM / 32;                              // 32-row MFMA tiles per wave along M
+                                                        float* __restrict__ Y, int ldy, int M,
+                                                        float* __restrict__ part) {
+    constexpr int BK = 32, LDS_STRIDE = BK + 8;             // 80-byte rows: 16-byte aligned, conflict-free
+    constexpr int WM = BM / 2, WN = BN / 2;                  // tile of one wave
+    constexpr int TI = WM / 32, TJ = WN / 32;                // 32x32 MFMA tiles per wave
     __shared__ __attribute__((aligned(16))) uint16_t As[BM * LDS_STRIDE];    // hi parts
     __shared__ __attribute__((aligned(16))) uint16_t Al[BM * LDS_STRIDE];    // lo parts
     __shared__ __attribute__((aligned(16))) uint16_t Bs[BN * LDS_STRIDE];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+    const int ksl = ((K / BK + gridDim.z - 1) / gridDim.z) * BK;             // K slice of this block
+    const int k_begin = blockIdx.z * ksl, k_end = min(K, k_begin + ksl);
 
-    f32x16_t acc[TI][2];
+    f32x16_t acc[TI][TJ];
 #pragma unroll
     for (int i = 0; i < TI; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < TJ; ++j)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
     constexpr int A_F4 = BM * BK / 4 / 256;   // float4 loads of X per thread (2 or 4)
-    for (int k0 = 0; k0 < K; k0 += BK) {
+    constexpr int B_U4 = BN * BK / 8 / 256;   // uint4 loads of W per thread (1 or 2)
+    for (int k0 = k_begin; k0 < k_end; k0 += BK) {
         float4 av[A_F4];
-        uint4 bv[2];
+        uint4 bv[B_U4];
 #pragma unroll
         for (int i = 0; i < A_F4; ++i) {
             const int idx = tid + i * 256, row = idx >> 3, c4 = idx & 7;
@@ -103,7 +110,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
             if (m0 + row < M) av[i] = *reinterpret_cast<const float4*>(X + (size_t)(m0 + row) * ldx + k0 + c4 * 4);
         }
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
+        for (int i = 0; i < B_U4; ++i) {
             const int idx = tid + i * 256, row = idx >> 2, c8 = idx & 3;
             bv[i] = make_uint4(0u, 0u, 0u, 0u);
             if (n0 + row < N) bv[i] = *reinterpret_cast<const uint4*>(W + (size_t)(n0 + row) * K + k0 + c8 * 8);
@@ -126,14 +133,14 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
             *reinterpret_cast<uint2*>(&Al[row * LDS_STRIDE + c4 * 4]) = q;
         }
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
+        for (int i = 0; i < B_U4; ++i) {
             const int idx = tid + i * 256, row = idx >> 2, c8 = idx & 3;
             *reinterpret_cast<uint4*>(&Bs[row * LDS_STRIDE + c8 * 8]) = bv[i];
         }
         __syncthreads();
 #pragma unroll
         for (int kk = 0; kk < BK; kk += 16) {
-            bf16x8_t a[TI], al[TI], b[2];
+            bf16x8_t a[TI], al[TI], b[TJ];
 #pragma unroll
             for (int i = 0; i < TI; ++i) {
                 const int off = (wm * WM + i * 32 + (lane & 31)) * LDS_STRIDE + kk + (lane >> 5) * 8;
@@ -141,56 +148,98 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
                 al[i] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(&Al[off]));
             }
 #pragma unroll
-            for (int j = 0; j < 2; ++j) {
+            for (int j = 0; j < TJ; ++j) {
                 const uint4 r = *reinterpret_cast<const uint4*>(
-                    &Bs[(wn * 64 + j * 32 + (lane & 31)) * LDS_STRIDE + kk + (lane >> 5) * 8]);
+                    &Bs[(wn * WN + j * 32 + (lane & 31)) * LDS_STRIDE + kk + (lane >> 5) * 8]);
                 b[j] = __builtin_bit_cast(bf16x8_t, r);
             }
 #pragma unroll
             for (int i = 0; i < TI; ++i)
 #pragma unroll
-                for (int j = 0; j < 2; ++j) {
+                for (int j = 0; j < TJ; ++j) {
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[i], b[j], acc[i][j], 0, 0, 0);
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
                 }
         }
     }
+    const bool sliced = gridDim.z > 1;
 #pragma unroll
     for (int i = 0; i < TI; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const int n = n0 + wn * 64 + j * 32 + (lane & 31);
+        for (int j = 0; j < TJ; ++j) {
+            const int n = n0 + wn * WN + j * 32 + (lane & 31);
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int m = m0 + wm * WM + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
                 if (m < M && n < N) {
-                    float* yp = Y + (size_t)m * ldy + n;
-                    *yp = (EPI == EPI_RESID) ? (*yp + acc[i][j][v]) : acc[i][j][v];
+                    if (sliced) {
+                        part[((size_t)blockIdx.z * M + m) * N + n] = acc[i][j][v];
+                    } else {
+                        float* yp = Y + (size_t)m * ldy + n;
+                        *yp = (EPI == EPI_RESID) ? (*yp + acc[i][j][v]) : acc[i][j][v];
+                    }
                 }
             }
         }
 }
 
+// Y[m][n] (+)= sum_z part[z][m][n], slices added in ascending z
+template <int EPI>
+__global__ void splitk_reduce_kernel(const float* __restrict__ part, int KS, int M, int N, float* __restrict__ Y, int ldy) {
+    const size_t i = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
+    if (i >= (size_t)M * N) return;
+    const size_t m = i / N, n = i - m * N;           // N is a multiple of 4
+    float4 a = *reinterpret_cast<const float4*>(part + i);
+    for (int z = 1; z < KS; ++z) {
+        const float4 b = *reinterpret_cast<const float4*>(part + (size_t)z * M * N + i);
+        a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
+    }
+    float4* yp = reinterpret_cast<float4*>(Y + m * ldy + n);
+    if (EPI == EPI_RESID) { const float4 y = *yp; a.x += y.x; a.y += y.y; a.z += y.z; a.w += y.w; }
+    *yp = a;
+}
+
 // ---------------------------------------------------------------- dispatch
 static void gemm_launch(hipStream_t st, int epi, const float* W, int N, int K, const float* X, int ldx,
-                        float* Y, int ldy, int M) {
+                        float* Y, int ldy, int M, float* part, size_t part_floats) {
+    (void)part; (void)part_floats;
     if (M <= 8) { gemv_launch<float>(st, PRO_NONE, epi, W, N, K, X, ldx, nullptr, 0.f, Y, ldy, M); return; }
     const dim3 grid((N + 63) / 64, (M + 63) / 64), block(256);
     if (epi == EPI_RESID) hipLaunchKernelGGL((sgemm_nt_kernel<EPI_RESID>), grid, block, 0, st, W, N, K, X, ldx, Y, ldy, M);
     else                  hipLaunchKernelGGL((sgemm_nt_kernel<EPI_STORE>), grid, block, 0, st, W, N, K, X, ldx, Y, ldy, M);
 }
 
+template <int BM, int BN>
+static void gemm_bf16_launch(hipStream_t st, int epi, const bf16_t* W, int N, int K, const float* X, int ldx,
+                             float* Y, int ldy, int M, float* part, int KS) {
+    const dim3 grid((N + BN - 1) / BN, (M + BM - 1) / BM, KS), block(256);
+    if (epi == EPI_RESID) hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, EPI_RESID>), grid, block, 0, st, W, N, K, X, ldx, Y, ldy, M, part);
+    else                  hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, EPI_STORE>), grid, block, 0, st, W, N, K, X, ldx, Y, ldy, M, part);
+    if (KS > 1) {
+        const unsigned nb = (unsigned)(((size_t)M * N / 4 + 255) / 256);
+        if (epi == EPI_RESID) hipLaunchKernelGGL((splitk_reduce_kernel<EPI_RESID>), dim3(nb), block, 0, st, part, KS, M, N, Y, ldy);
+        else                  hipLaunchKernelGGL((splitk_reduce_kernel<EPI_STORE>), dim3(nb), block, 0, st, part, KS, M, N, Y, ldy);
+    }
+}
+
 static void gemm_launch(hipStream_t st, int epi, const bf16_t* W, int N, int K, const float* X, int ldx,
-                        float* Y, int ldy, int M) {
+                        float* Y, int ldy, int M, float* part, size_t part_floats) {
     if (M <= 8) { gemv_launch<bf16_t>(st, PRO_NONE, epi, W, N, K, X, ldx, nullptr, 0.f, Y, ldy, M); return; }
-    const dim3 block(256);
-    if (M <= 64) {
-        const dim3 grid((N + 127) / 128, (M + 63) / 64);
-        if (epi == EPI_RESID) hipLaunchKernelGGL((gemm_bf16_kernel<64, EPI_RESID>), grid, block, 0, st, W, N, K, X, ldx, Y, ldy, M);
-        else                  hipLaunchKernelGGL((gemm_bf16_kernel<64, EPI_STORE>), grid, block, 0, st, W, N, K, X, ldx, Y, ldy, M);
+    // Tiles: 64 rows of activations when there are few; narrow weight tiles and K slices until
+    // about two blocks per compute unit exist (these shapes are bound by streaming W once).
+    const int bm = M <= 64 ? 64 : 128;
+    const int tm = (M + bm - 1) / bm;
+    int bn = 128;
+    if (((N + 127) / 128) * tm < 512) bn = 64;
+    const int tiles = ((N + bn - 1) / bn) * tm;
+    int ks = 1;
+    while (ks < 16 && tiles * ks < 512 && K / (ks * 2) >= 512 && (size_t)(ks * 2) * M * N <= part_floats) ks *= 2;
+    if (!part) ks = 1;
+    if (bm == 64) {
+        if (bn == 64) gemm_bf16_launch<64, 64>(st, epi, W, N, K, X, ldx, Y, ldy, M, part, ks);
+        else          gemm_bf16_launch<64, 128>(st, epi, W, N, K, X, ldx, Y, ldy, M, part, ks);
     } else {
-        const dim3 grid((N + 127) / 128, (M + 127) / 128);
-        if (epi == EPI_RESID) hipLaunchKernelGGL((gemm_bf16_kernel<128, EPI_RESID>), grid, block, 0, st, W, N, K, X, ldx, Y, ldy, M);
-        else                  hipLaunchKernelGGL((gemm_bf16_kernel<128, EPI_STORE>), grid, block, 0, st, W, N, K, X, ldx, Y, ldy, M);
+        if (bn == 64) gemm_bf16_launch<128, 64>(st, epi, W, N, K, X, ldx, Y, ldy, M, part, ks);
+        else          gemm_bf16_launch<128, 128>(st, epi, W, N, K, X, ldx, Y, ldy, M, part, ks);
     }
 }

@@ -7,10 +7,11 @@
 //   PRO_SWIGLU  x = silu(X[k]) * X[K + k]               (SwiGLU fused in)
 // and the result is either stored or added to Y (residual stream).
 #pragma once
+#include <algorithm>
 #include "common.cuh"
 
 enum { PRO_NONE = 0, PRO_NORM = 1, PRO_SWIGLU = 2 };
-enum { EPI_STORE = 0, EPI_RESID = 1 };
+enum { EPI_STORE = 0, EPI_RESID = 1, EPI_SWIGLU = 2 };
 
 // Block = 256 threads working on R consecutive rows of W.  The K axis is cut
 // in 16-byte (8 bf16) slots dealt round-robin to the threads, so one block
@@ -114,11 +115,194 @@ __global__ __launch_bounds__(256) void gemv_kernel(const WT* __restrict__ W, int
     }
 }
 
+// Raw 8-element weight loads (kept packed in registers until they are used).
+template <typename WT> struct Raw8;
+template <> struct Raw8<bf16_t> {
+    uint4 v;
+    __device__ __forceinline__ void load(const bf16_t* p) { v = *reinterpret_cast<const uint4*>(p); }
+    __device__ __forceinline__ void unpack(float o[8]) const { unpack8(v, o); }
+};
+template <> struct Raw8<float> {
+    float4 a, b;
+    __device__ __forceinline__ void load(const float* p) {
+        a = *reinterpret_cast<const float4*>(p); b = *reinterpret_cast<const float4*>(p + 4);
+    }
+    __device__ __forceinline__ void unpack(float o[8]) const {
+        o[0] = a.x; o[1] = a.y; o[2] = a.z; o[3] = a.w; o[4] = b.x; o[5] = b.y; o[6] = b.z; o[7] = b.w;
+    }
+};
+
+// Variant for activations that fit LDS whole (MT * K floats).  The block stages
+// (and transforms) x once.  Each WAVE then owns row groups (R rows, or R gate/up
+// row pairs) and walks them with its 64 lanes spread along K, 1 KiB per row and
+// step; sums are finished with wave shuffles, so the main loop has no block
+// barrier.  Weight loads run one step ahead of the arithmetic (also across the
+// boundary between row groups, and the very first ones are issued before the
+// prologue), which keeps 8..16 loads of 16 bytes per lane in flight.
+//   EPI_SWIGLU: W holds [gate ; up] (2N rows); row n of gate and row N + n of up
+//   are read together and silu(gate.x) * (up.x) is stored: N outputs.
+template <typename WT, int MT, int R, int U, int PRO, int EPI>
+__global__ __launch_bounds__(256) void gemv_full_kernel(const WT* __restrict__ W, int N, int K,
+                                                        const float* __restrict__ X, int ldx,
+                                                        const WT* __restrict__ gain, float eps,
+                                                        float* __restrict__ Y, int ldy, int M) {
+    constexpr int NA = (EPI == EPI_SWIGLU) ? 2 : 1;     // accumulator sets (gate and up)
+    constexpr int NR = NA * R;                          // weight rows streamed together
+    extern __shared__ float smem[];
+    float* xs = smem;                                   // [MT][K]
+    __shared__ float red4[4];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int slots = K >> 3, iters = (slots + 64 * U - 1) / (64 * U);    // a step covers U KiB of every row
+    const int n_groups = (N + R - 1) / R;
+    const int rg0 = blockIdx.x * 4 + wave, rg_stride = gridDim.x * 4;
+    const int my_groups = rg0 < n_groups ? (n_groups - rg0 + rg_stride - 1) / rg_stride : 0;
+    const int total = my_groups * iters;
+
+    auto fetch = [&](int g, int i, Raw8<WT> dst[U][NR]) {
+        const int n0 = (rg0 + g * rg_stride) * R;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int s = (i * U + u) * 64 + lane;
+            if (s < slots) {
+#pragma unroll
+                for (int a = 0; a < NA; ++a)
+#pragma unroll
+                    for (int r = 0; r < R; ++r)
+                        dst[u][a * R + r].load(W + ((size_t)a * N + min(n0 + r, N - 1)) * K + s * 8);
+            }
+        }
+    };
+    Raw8<WT> cur[U][NR], nxt[U][NR];
+    if (total > 0) fetch(0, 0, cur);
+
+    float rs[MT];
+#pragma unroll
+    for (int m = 0; m < MT; ++m) rs[m] = 1.0f;
+    if (PRO == PRO_NORM) {
+#pragma unroll
+        for (int m = 0; m < MT; ++m) {
+            float ss = 0.0f;
+            if (m < M)
+                for (int k = tid * 4; k < K; k += 1024) {
+                    const float4 v = *reinterpret_cast<const float4*>(X + (size_t)m * ldx + k);
+                    ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+                }
+            ss = block256_sum(ss, red4);
+            rs[m] = 1.0f / sqrtf(ss / (float)K + eps);
+        }
+    }
+    for (int idx = tid * 4; idx < MT * K; idx += 1024) {
+        const int m = idx / K, k = idx - m * K;
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (m < M) {
+            v = *reinterpret_cast<const float4*>(X + (size_t)m * ldx + k);
+            if (PRO == PRO_NORM) {
+                const WT* gp = gain + k;
+                v.x *= rs[m] * ld1(gp);     v.y *= rs[m] * ld1(gp + 1);
+                v.z *= rs[m] * ld1(gp + 2); v.w *= rs[m] * ld1(gp + 3);
+            }
+        }
+        *reinterpret_cast<float4*>(xs + idx) = v;
+    }
+    __syncthreads();
+
+    float acc[NA][MT][R];
+#pragma unroll
+    for (int a = 0; a < NA; ++a)
+#pragma unroll
+        for (int m = 0; m < MT; ++m)
+#pragma unroll
+            for (int r = 0; r < R; ++r) acc[a][m][r] = 0.0f;
+
+    int g = 0, i = 0;
+    for (int t = 0; t < total; ++t) {
+        int gn = g, in = i + 1;
+        if (in == iters) { in = 0; gn = g + 1; }
+        if (t + 1 < total) fetch(gn, in, nxt);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int s = (i * U + u) * 64 + lane;
+            if (s < slots) {
+                float w[NR][8];
+#pragma unroll
+                for (int q = 0; q < NR; ++q) cur[u][q].unpack(w[q]);
+#pragma unroll
+                for (int m = 0; m < MT; ++m) {
+                    const float4 xa = *reinterpret_cast<const float4*>(xs + (size_t)m * K + s * 8);
+                    const float4 xb = *reinterpret_cast<const float4*>(xs + (size_t)m * K + s * 8 + 4);
+#pragma unroll
+                    for (int a = 0; a < NA; ++a)
+#pragma unroll
+                        for (int r = 0; r < R; ++r) {
+                            const float* ww = w[a * R + r];
+                            acc[a][m][r] += xa.x * ww[0] + xa.y * ww[1] + xa.z * ww[2] + xa.w * ww[3]
+                                          + xb.x * ww[4] + xb.y * ww[5] + xb.z * ww[6] + xb.w * ww[7];
+                        }
+                }
+            }
+        }
+        if (i == iters - 1) {
+            const int n0 = (rg0 + g * rg_stride) * R;
+#pragma unroll
+            for (int m = 0; m < MT; ++m)
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    float v = wave_sum(acc[0][m][r]);
+                    float u = (EPI == EPI_SWIGLU) ? wave_sum(acc[NA - 1][m][r]) : 0.0f;
+                    acc[0][m][r] = 0.0f;
+                    acc[NA - 1][m][r] = 0.0f;
+                    if (lane == 0 && m < M && n0 + r < N) {
+                        float* yp = Y + (size_t)m * ldy + n0 + r;
+                        if (EPI == EPI_SWIGLU) *yp = v / (1.0f + expf(-v)) * u;
+                        else *yp = (EPI == EPI_RESID) ? (*yp + v) : v;
+                    }
+                }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int q = 0; q < NR; ++q) cur[u][q] = nxt[u][q];
+        g = gn; i = in;
+    }
+}
+
+constexpr size_t kGemvFullLds = 120 * 1024;      // most LDS the whole-activation variant may take
+
+// Whole-activation variant with R rows (or gate/up pairs) per wave and U KiB per row and step.
+template <typename WT, int MT, int R, int U>
+static bool gemv_launch_full(hipStream_t st, int pro, int epi, const WT* W, int N, int K, const float* X,
+                             int ldx, const WT* gain, float eps, float* Y, int ldy, int M) {
+    const size_t full = (size_t)MT * K * sizeof(float);
+    if (full > kGemvFullLds || pro == PRO_SWIGLU) return false;
+    // blocks resident at once: limited by LDS (160 KB per compute unit), at most 6 per unit
+    const int per_cu = (int)std::max<size_t>(1, std::min<size_t>(6, (160 * 1024) / (full + 64)));
+    const int n_groups = (N + R - 1) / R;
+    const dim3 grid(std::min((n_groups + 3) / 4, 256 * per_cu)), block(256);
+#define RSD_GEMVF_CASE(P, E)                                                                                 \
+    if (pro == P && epi == E) {                                                                              \
+        static bool raised = false;   /* one flag per kernel instance: dynamic LDS above 64 KB must be allowed */ \
+        if (!raised && full > 64 * 1024) {                                                                   \
+            (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemv_full_kernel<WT, MT, R, U, P, E>),   \
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)kGemvFullLds);        \
+            raised = true;                                                                                   \
+        }                                                                                                    \
+        hipLaunchKernelGGL((gemv_full_kernel<WT, MT, R, U, P, E>), grid, block, full, st, W, N, K, X, ldx,   \
+                           gain, eps, Y, ldy, M);                                                            \
+        return true;                                                                                         \
+    }
+    RSD_GEMVF_CASE(PRO_NONE, EPI_STORE)
+    RSD_GEMVF_CASE(PRO_NONE, EPI_RESID)
+    RSD_GEMVF_CASE(PRO_NORM, EPI_STORE)
+    RSD_GEMVF_CASE(PRO_NORM, EPI_SWIGLU)
+#undef RSD_GEMVF_CASE
+    return false;
+}
+
+// Fallback for activations too large for LDS: K is walked in chunks, one block per R rows.
 template <typename WT, int MT, int R>
-static void gemv_launch_mr(hipStream_t st, int pro, int epi, const WT* W, int N, int K, const float* X,
-                           int ldx, const WT* gain, float eps, float* Y, int ldy, int M) {
-    // LDS budget for the staged activations: 32 KB (48 KB when 8 rows are live)
-    int KC = (MT == 8 ? 1536 : 8192 / MT);
+static void gemv_launch_chunked(hipStream_t st, int pro, int epi, const WT* W, int N, int K, const float* X,
+                                int ldx, const WT* gain, float eps, float* Y, int ldy, int M) {
+    int KC = (MT == 8 ? 1536 : 8192 / MT);   // LDS budget for the staged activations: 32 KB (48 KB for 8 rows)
     if (KC > K) KC = K;
     const size_t smem = (size_t)(MT * KC + 4 * MT * R + 8) * sizeof(float);
     const dim3 grid((N + R - 1) / R), block(256);
@@ -135,20 +319,50 @@ static void gemv_launch_mr(hipStream_t st, int pro, int epi, const WT* W, int N,
 #undef RSD_GEMV_CASE
 }
 
-// M <= 8.  Rows per block: 4 when N is small (more blocks), 8 for long outputs.
+// True when gemv_launch can fuse SwiGLU into the gate/up kernel for this shape (then the
+// down projection reads the activated values with PRO_NONE).
+static bool gemv_can_fuse_swiglu(int M, int K) {
+    const int MT = M <= 1 ? 1 : M <= 2 ? 2 : M <= 4 ? 4 : 8;
+    return (size_t)MT * K * sizeof(float) <= kGemvFullLds;
+}
+
+template <typename WT, int MT>
+static void gemv_launch_mt(hipStream_t st, int pro, int epi, const WT* W, int N, int K, const float* X, int ldx,
+                           const WT* gain, float eps, float* Y, int ldy, int M) {
+    // rows per wave: as many as still leave every compute unit a couple of blocks; then enough
+    // KiB per row and step to keep about 8 loads per lane in flight
+    const int pairs = epi == EPI_SWIGLU ? 2 : 1;
+    const int steps = (K / 8 + 63) / 64;          // KiB per row
+    bool done = false;
+    if (MT == 1) {
+        int R = 8 / pairs;
+        while (R > 1 && (N / R) < 2048) R >>= 1;
+        int U = std::max(1, 8 / (R * pairs));
+        while (U > 1 && U > steps) U >>= 1;
+        if (pairs == 2) {
+            if (R >= 4) done = gemv_launch_full<WT, MT, 4, 1>(st, pro, epi, W, N, K, X, ldx, gain, eps, Y, ldy, M);
+            else if (R == 2) done = gemv_launch_full<WT, MT, 2, 2>(st, pro, epi, W, N, K, X, ldx, gain, eps, Y, ldy, M);
+            else done = gemv_launch_full<WT, MT, 1, 4>(st, pro, epi, W, N, K, X, ldx, gain, eps, Y, ldy, M);
+        } else if (R == 8) done = gemv_launch_full<WT, MT, 8, 1>(st, pro, epi, W, N, K, X, ldx, gain, eps, Y, ldy, M);
+        else if (R == 4) done = U >= 2 ? gemv_launch_full<WT, MT, 4, 2>(st, pro, epi, W, N, K, X, ldx, gain, eps, Y, ldy, M)
+                                       : gemv_launch_full<WT, MT, 4, 1>(st, pro, epi, W, N, K, X, ldx, gain, eps, Y, ldy, M);
+        else if (R == 2) done = U >= 4 ? gemv_launch_full<WT, MT, 2, 4>(st, pro, epi, W, N, K, X, ldx, gain, eps, Y, ldy, M)
+                                       : gemv_launch_full<WT, MT, 2, 2>(st, pro, epi, W, N, K, X, ldx, gain, eps, Y, ldy, M);
+        else done = U >= 8 ? gemv_launch_full<WT, MT, 1, 8>(st, pro, epi, W, N, K, X, ldx, gain, eps, Y, ldy, M)
+                           : gemv_launch_full<WT, MT, 1, 4>(st, pro, epi, W, N, K, X, ldx, gain, eps, Y, ldy, M);
+    } else {
+        if (pairs == 2) done = gemv_launch_full<WT, MT, 2, 1>(st, pro, epi, W, N, K, X, ldx, gain, eps, Y, ldy, M);
+        else done = gemv_launch_full<WT, MT, 4, 1>(st, pro, epi, W, N, K, X, ldx, gain, eps, Y, ldy, M);
+    }
+    if (!done) gemv_launch_chunked<WT, MT, 4>(st, pro, epi, W, N, K, X, ldx, gain, eps, Y, ldy, M);
+}
+
+// M <= 8
 template <typename WT>
 static void gemv_launch(hipStream_t st, int pro, int epi, const WT* W, int N, int K, const float* X, int ldx,
                         const WT* gain, float eps, float* Y, int ldy, int M) {
-    const bool wide = N >= 16384;
-    if (M <= 1) {
-        if (wide) gemv_launch_mr<WT, 1, 8>(st, pro, epi, W, N, K, X, ldx, gain, eps, Y, ldy, M);
-        else      gemv_launch_mr<WT, 1, 4>(st, pro, epi, W, N, K, X, ldx, gain, eps, Y, ldy, M);
-    } else if (M <= 2) {
-        if (wide) gemv_launch_mr<WT, 2, 8>(st, pro, epi, W, N, K, X, ldx, gain, eps, Y, ldy, M);
-        else      gemv_launch_mr<WT, 2, 4>(st, pro, epi, W, N, K, X, ldx, gain, eps, Y, ldy, M);
-    } else if (M <= 4) {
-        gemv_launch_mr<WT, 4, 4>(st, pro, epi, W, N, K, X, ldx, gain, eps, Y, ldy, M);
-    } else {
-        gemv_launch_mr<WT, 8, 4>(st, pro, epi, W, N, K, X, ldx, gain, eps, Y, ldy, M);
-    }
+    if (M <= 1) gemv_launch_mt<WT, 1>(st, pro, epi, W, N, K, X, ldx, gain, eps, Y, ldy, M);
+    else if (M <= 2) gemv_launch_mt<WT, 2>(st, pro, epi, W, N, K, X, ldx, gain, eps, Y, ldy, M);
+    else if (M <= 4) gemv_launch_mt<WT, 4>(st, pro, epi, W, N, K, X, ldx, gain, eps, Y, ldy, M);
+    else gemv_launch_mt<WT, 8>(st, pro, epi, W, N, K, X, ldx, gain, eps, Y, ldy, M);
 }

@@ -109,32 +109,6 @@ struct SeqState {
     int* sampled[2];    // [B][max_steps][step_cap] each: tokens chosen by the draft / target samplers
 };
 
-// After the sampler: append the new token of every active sequence and decide
-// whether its step goes on.  `model` is 0 (draft) or 1 (target).
-// The model's own choice is recorded at [b][step][j] (j = index inside the
-// step); a teacher array of the same shape may replace the appended token.
-__global__ void append_kernel(SeqState st, int B, int max_ctx, int model, const int* __restrict__ chosen,
-                              const int* __restrict__ forced, int sep_id, int eos_id, int step_cap,
-                              int step, int max_steps) {
-    const int b = blockIdx.x * blockDim.x + threadIdx.x;
-    if (b >= B || !st.active[b]) return;
-    const int pos = st.ctx_len[b];
-    const int own = chosen[b];
-    const size_t rec = ((size_t)b * max_steps + step) * step_cap + st.step_len[b];
-    st.sampled[model][rec] = own;
-    int tok = own;
-    if (forced) { const int f = forced[rec]; if (f >= 0) tok = f; }
-    st.tokens[(size_t)b * max_ctx + pos] = tok;
-    st.ctx_len[b] = pos + 1;
-    st.kv_len[model * B + b] = pos;          // every token before the new one has been fed
-    const int sl = st.step_len[b] + 1;
-    st.step_len[b] = sl;
-    if (tok == sep_id || tok == eos_id || sl >= step_cap || pos + 1 >= max_ctx) {
-        st.active[b] = 0;
-        atomicSub(st.n_active, 1);
-    }
-}
-
 // Acceptance criterion A_omega (Algorithm 2) on the rewards of the draft steps,
 // then the rollback of rejected sequences to their pre-step context.
 __global__ void gate_kernel(SeqState st, int B, float delta, int omega_kind, float omega_a,

@@ -83,6 +83,13 @@ struct rsd_ctx {
     int ws_rows = 0;
     float *h = nullptr, *xn = nullptr, *qkv = nullptr, *att = nullptr, *gu = nullptr, *act = nullptr;
     float *part_acc = nullptr, *part_ml = nullptr;
+    int* tickets = nullptr;
+    float* part_k = nullptr;         // K-slice partial sums of few-row GEMMs
+    size_t part_k_floats = 0;
+    // sampler workspace (per row: block maxima, histograms of the three radix levels, block masses, selections)
+    int smp_rows = 0;
+    float* smp_pmax = nullptr; int* smp_pidx = nullptr;
+    u64_t *smp_hist = nullptr, *smp_psum = nullptr, *smp_sel = nullptr;
     float *hl = nullptr, *xl = nullptr, *logits = nullptr, *tmp_reward = nullptr;
     int *chosen = nullptr, *steptok_dev = nullptr;
     int *row_seq_dev = nullptr, *row_pos_dev = nullptr, *last_row_dev = nullptr;
@@ -136,6 +143,7 @@ int setup_model(rsd_ctx* c, Model& m, const rsd_model_shape& s, const rsd_weight
         return fail(c, RSD_EINVAL, "model %d: query group of %d heads unsupported", which, m.G);
     if (s.d_model % 64 || s.d_ffn % 64) return fail(c, RSD_EINVAL, "model %d: d_model and d_ffn must be multiples of 64", which);
     if (s.dtype != RSD_F32 && s.dtype != RSD_BF16) return fail(c, RSD_EINVAL, "model %d: bad dtype", which);
+    if (s.dtype == RSD_BF16 && m.hd != 128) return fail(c, RSD_EINVAL, "model %d: bf16 models need head_dim 128", which);
     if (s.head_kind != (which == RSD_PRM ? RSD_HEAD_REWARD : RSD_HEAD_LM))
         return fail(c, RSD_EINVAL, "model %d: wrong head kind", which);
     m.esz = s.dtype == RSD_F32 ? 4 : 2;
@@ -203,6 +211,12 @@ int setup_kv(rsd_ctx* c, Model& m, int which) {
     int s = 256 / std::max(1, B * m.s.n_kv_heads);
     s = std::min(s, std::min(32, ceil_div(m.max_pages, 4)));
     m.splits = std::max(1, s);
+    if (m.s.dtype == RSD_BF16) {
+        // MFMA kernel: a page costs a wave well under a microsecond, so up to 2048 tokens stay one
+        // split of 8 waves (no partials to merge); beyond that, 4-wave blocks of at most 32 pages
+        if (m.max_pages <= 128) m.splits = 1;
+        else m.splits = std::min(64, std::max(ceil_div(m.max_pages, 32), std::min(16, 512 / std::max(1, B * m.s.n_kv_heads))));
+    }
     return RSD_OK;
 }
 
@@ -281,6 +295,50 @@ struct ProbeScope {
     }
 };
 
+template <typename KT, int HD>
+void launch_attn_decode(rsd_ctx* c, const Model& m, int l, int M, int which) {
+    KT* pool_l = reinterpret_cast<KT*>(m.pool) + (size_t)l * m.pool_pages * m.page_elts;
+    const float scale = 1.0f / std::sqrt((float)HD);
+    const int S = m.splits;
+    const dim3 grid(M, m.s.n_kv_heads, S), block(256);
+#define RSD_ATTN_CASE(GG)                                                                                     \
+    case GG:                                                                                                  \
+        hipLaunchKernelGGL((attn_decode_kernel<KT, HD, GG>), grid, block, 0, c->st, c->qkv, m.n_qkv, pool_l,  \
+                           m.bt_dev, m.max_pages, c->ds.kv_len + (size_t)which * c->B, c->ds.active, m.rope,  \
+                           m.s.n_heads, m.s.n_kv_heads, S, scale, c->att, m.q_dim, c->part_acc, c->part_ml,   \
+                           c->tickets);                                                                       \
+        break;
+    switch (m.G) {
+        RSD_ATTN_CASE(1) RSD_ATTN_CASE(2) RSD_ATTN_CASE(4) RSD_ATTN_CASE(6) RSD_ATTN_CASE(7) RSD_ATTN_CASE(8)
+    }
+#undef RSD_ATTN_CASE
+}
+
+// bf16 caches with head_dim 128: the MFMA kernel; 8 waves per block when the whole context is one split
+void launch_attn_decode_mfma(rsd_ctx* c, const Model& m, int l, int M, int which) {
+    bf16_t* pool_l = reinterpret_cast<bf16_t*>(m.pool) + (size_t)l * m.pool_pages * m.page_elts;
+    const float scale = 1.0f / std::sqrt(128.0f);
+    const int S = m.splits;
+    const dim3 grid(M, m.s.n_kv_heads, S);
+#define RSD_ATTN_CASE(GG)                                                                                          \
+    case GG:                                                                                                       \
+        if (S == 1)                                                                                                \
+            hipLaunchKernelGGL((attn_decode_mfma_kernel<GG, 8>), grid, dim3(512), 0, c->st, c->qkv, m.n_qkv, pool_l, \
+                               m.bt_dev, m.max_pages, c->ds.kv_len + (size_t)which * c->B, c->ds.active, m.rope,   \
+                               m.s.n_heads, m.s.n_kv_heads, S, scale, c->att, m.q_dim, c->part_acc, c->part_ml,    \
+                               c->tickets);                                                                        \
+        else                                                                                                       \
+            hipLaunchKernelGGL((attn_decode_mfma_kernel<GG, 4>), grid, dim3(256), 0, c->st, c->qkv, m.n_qkv, pool_l, \
+                               m.bt_dev, m.max_pages, c->ds.kv_len + (size_t)which * c->B, c->ds.active, m.rope,   \
+                               m.s.n_heads, m.s.n_kv_heads, S, scale, c->att, m.q_dim, c->part_acc, c->part_ml,    \
+                               c->tickets);                                                                        \
+        break;
+    switch (m.G) {
+        RSD_ATTN_CASE(1) RSD_ATTN_CASE(2) RSD_ATTN_CASE(4) RSD_ATTN_CASE(6) RSD_ATTN_CASE(7) RSD_ATTN_CASE(8)
+    }
+#undef RSD_ATTN_CASE
+}
+
 template <typename WT>
 void run_layers(rsd_ctx* c, Model& m, int M, const RowMap& rm, bool decode) {
     hipStream_t st = c->st;
@@ -299,10 +357,15 @@ void run_layers(rsd_ctx* c, Model& m, int M, const RowMap& rm, bool decode) {
                             wptr<WT>(m, o.attn_norm), eps, c->qkv, m.n_qkv, M);
         } else {
             hipLaunchKernelGGL((rmsnorm_kernel<WT>), dim3(M), dim3(256), 0, st, c->h, d, wptr<WT>(m, o.attn_norm), eps, c->xn);
-            gemm_launch(st, EPI_STORE, wptr<WT>(m, o.wqkv), m.n_qkv, d, c->xn, d, c->qkv, m.n_qkv, M);
+            gemm_launch(st, EPI_STORE, wptr<WT>(m, o.wqkv), m.n_qkv, d, c->xn, d, c->qkv, m.n_qkv, M, c->part_k, c->part_k_floats);
         }
         WT* pool_l = reinterpret_cast<WT*>(m.pool) + (size_t)l * m.pool_pages * m.page_elts;
-        if (m.hd == 128) {
+        if (decode) {
+            const int which = (int)(&m - &c->m[0]);
+            if (m.s.dtype == RSD_BF16) launch_attn_decode_mfma(c, m, l, M, which);
+            else if (m.hd == 128) launch_attn_decode<WT, 128>(c, m, l, M, which);
+            else launch_attn_decode<WT, 32>(c, m, l, M, which);
+        } else if (m.hd == 128) {
             hipLaunchKernelGGL((rope_kv_kernel<WT, 128>), dim3(M), dim3(256), 0, st, c->qkv, m.n_qkv, pool_l, m.bt_dev,
                                m.max_pages, rm, m.rope, m.s.n_heads, m.s.n_kv_heads);
             launch_attn_g<WT, 128>(c, m, l, M, rm, S);
@@ -317,23 +380,36 @@ void run_layers(rsd_ctx* c, Model& m, int M, const RowMap& rm, bool decode) {
                 gemv_launch<WT>(st, PRO_NONE, EPI_RESID, wptr<WT>(m, o.wo), d, m.q_dim, c->att, m.q_dim,
                                 (const WT*)nullptr, 0.f, c->h, d, M);
             }
-            {
-                ProbeScope ps(c, m, 2, 2LL * F * d * esz + 4LL * M * (d + 2 * F));
-                gemv_launch<WT>(st, PRO_NORM, EPI_STORE, wptr<WT>(m, o.wgu), 2 * F, d, c->h, d,
-                                wptr<WT>(m, o.ffn_norm), eps, c->gu, 2 * F, M);
-            }
-            {
-                ProbeScope ps(c, m, 3, (long long)d * F * esz + 4LL * M * (2 * F + 2 * d));
-                gemv_launch<WT>(st, PRO_SWIGLU, EPI_RESID, wptr<WT>(m, o.wdown), d, F, c->gu, 2 * F,
-                                (const WT*)nullptr, 0.f, c->h, d, M);
+            if (gemv_can_fuse_swiglu(M, d) && gemv_can_fuse_swiglu(M, F)) {
+                {
+                    ProbeScope ps(c, m, 2, 2LL * F * d * esz + 4LL * M * (d + F));
+                    gemv_launch<WT>(st, PRO_NORM, EPI_SWIGLU, wptr<WT>(m, o.wgu), F, d, c->h, d,
+                                    wptr<WT>(m, o.ffn_norm), eps, c->act, F, M);
+                }
+                {
+                    ProbeScope ps(c, m, 3, (long long)d * F * esz + 4LL * M * (F + 2 * d));
+                    gemv_launch<WT>(st, PRO_NONE, EPI_RESID, wptr<WT>(m, o.wdown), d, F, c->act, F,
+                                    (const WT*)nullptr, 0.f, c->h, d, M);
+                }
+            } else {
+                {
+                    ProbeScope ps(c, m, 2, 2LL * F * d * esz + 4LL * M * (d + 2 * F));
+                    gemv_launch<WT>(st, PRO_NORM, EPI_STORE, wptr<WT>(m, o.wgu), 2 * F, d, c->h, d,
+                                    wptr<WT>(m, o.ffn_norm), eps, c->gu, 2 * F, M);
+                }
+                {
+                    ProbeScope ps(c, m, 3, (long long)d * F * esz + 4LL * M * (2 * F + 2 * d));
+                    gemv_launch<WT>(st, PRO_SWIGLU, EPI_RESID, wptr<WT>(m, o.wdown), d, F, c->gu, 2 * F,
+                                    (const WT*)nullptr, 0.f, c->h, d, M);
+                }
             }
         } else {
-            gemm_launch(st, EPI_RESID, wptr<WT>(m, o.wo), d, m.q_dim, c->att, m.q_dim, c->h, d, M);
+            gemm_launch(st, EPI_RESID, wptr<WT>(m, o.wo), d, m.q_dim, c->att, m.q_dim, c->h, d, M, c->part_k, c->part_k_floats);
             hipLaunchKernelGGL((rmsnorm_kernel<WT>), dim3(M), dim3(256), 0, st, c->h, d, wptr<WT>(m, o.ffn_norm), eps, c->xn);
-            gemm_launch(st, EPI_STORE, wptr<WT>(m, o.wgu), 2 * F, d, c->xn, d, c->gu, 2 * F, M);
+            gemm_launch(st, EPI_STORE, wptr<WT>(m, o.wgu), 2 * F, d, c->xn, d, c->gu, 2 * F, M, c->part_k, c->part_k_floats);
             const size_t total = (size_t)M * F;
             hipLaunchKernelGGL(swiglu_kernel, dim3((unsigned)((total / 4 + 255) / 256)), dim3(256), 0, st, c->gu, F, c->act, total);
-            gemm_launch(st, EPI_RESID, wptr<WT>(m, o.wdown), d, F, c->act, F, c->h, d, M);
+            gemm_launch(st, EPI_RESID, wptr<WT>(m, o.wdown), d, F, c->act, F, c->h, d, M, c->part_k, c->part_k_floats);
         }
     }
 }
@@ -351,7 +427,7 @@ void lm_head(rsd_ctx* c, Model& m, const float* X, int M, float* Y, int ldy) {
             const int mm = std::min(kMaxRows, M - r0);
             hipLaunchKernelGGL((rmsnorm_kernel<WT>), dim3(mm), dim3(256), 0, c->st, X + (size_t)r0 * d, d,
                                wptr<WT>(m, m.off_final_norm), m.s.rms_eps, c->xn);
-            gemm_launch(c->st, EPI_STORE, wptr<WT>(m, m.off_head), V, d, c->xn, d, Y + (size_t)r0 * ldy, ldy, mm);
+            gemm_launch(c->st, EPI_STORE, wptr<WT>(m, m.off_head), V, d, c->xn, d, Y + (size_t)r0 * ldy, ldy, mm, c->part_k, c->part_k_floats);
         }
     }
 }
@@ -362,10 +438,26 @@ void reward_rows(rsd_ctx* c, Model& m, const float* H, int n, const int* rows, f
                        wptr<WT>(m, m.off_final_norm), m.s.rms_eps, wptr<WT>(m, m.off_head), wptr<WT>(m, m.off_br), out);
 }
 
+// Sample one token per row; with `ap` the chosen token is also appended to its sequence.
 void sample_rows(rsd_ctx* c, const float* logits, int ld, int V, const float* u, const int* u_index, int u_stride,
-                 float temperature, float top_p, int sep_id, float sep_bias, const int* active, int n, int* out) {
-    SampleArgs a{logits, ld, V, u, u_index, u_stride, temperature, top_p, sep_id, sep_bias, active, out};
-    hipLaunchKernelGGL(sample_kernel, dim3(n), dim3(1024), 0, c->st, a);
+                 float temperature, float top_p, int sep_id, float sep_bias, const int* active, int n, int* out,
+                 const AppendArgs& ap) {
+    for (int r0 = 0; r0 < n; r0 += c->smp_rows) {
+        const int rows = std::min(c->smp_rows, n - r0);
+        SampleArgs a{logits + (size_t)r0 * ld, ld, V, u ? u + (size_t)r0 * u_stride : nullptr,
+                     u_index ? u_index + r0 : nullptr, u_stride, temperature, top_p, sep_id, sep_bias,
+                     active ? active + r0 : nullptr, out ? out + r0 : nullptr,
+                     c->smp_pmax, c->smp_pidx, c->smp_hist, c->smp_psum, c->smp_sel};
+        sample_launch(c->st, a, ap, rows);
+    }
+}
+
+AppendArgs append_args(rsd_ctx* c, int which, const int* forced) {
+    AppendArgs ap{};
+    ap.enabled = 1; ap.st = c->ds; ap.B = c->B; ap.max_ctx = c->p.max_ctx; ap.model = which; ap.forced = forced;
+    ap.sep_id = c->p.sep_id; ap.eos_id = c->p.eos_id; ap.step_cap = c->p.step_cap; ap.step = c->steps_done;
+    ap.max_steps = c->p.max_steps;
+    return ap;
 }
 
 RowMap decode_map(rsd_ctx* c, int which) {
@@ -379,9 +471,7 @@ void decode_iter(rsd_ctx* c, int which, const float* u, const int* forced) {
     run_layers<WT>(c, m, c->B, decode_map(c, which), true);
     lm_head<WT>(c, m, c->h, c->B, c->logits, m.s.vocab);
     sample_rows(c, c->logits, m.s.vocab, m.s.vocab, u, c->ds.ctx_len, c->p.max_ctx, c->p.temperature, c->p.top_p,
-                c->p.sep_id, c->p.sep_logit_bias, c->ds.active, c->B, c->chosen);
-    hipLaunchKernelGGL(append_kernel, dim3(ceil_div(c->B, 64)), dim3(64), 0, c->st, c->ds, c->B, c->p.max_ctx, which,
-                       c->chosen, forced, c->p.sep_id, c->p.eos_id, c->p.step_cap, c->steps_done, c->p.max_steps);
+                c->p.sep_id, c->p.sep_logit_bias, c->ds.active, c->B, nullptr, append_args(c, which, forced));
 }
 
 // Chunked prefill of `pieces` (per sequence consecutive, ascending) through model `which`.
@@ -451,9 +541,7 @@ int gen_stage(rsd_ctx* c, int which, const float* u, const int* forced) {
         if (rc != RSD_OK) return rc;
         lm_head<WT>(c, m, c->hl, B, c->logits, m.s.vocab);
         sample_rows(c, c->logits, m.s.vocab, m.s.vocab, u, c->ds.ctx_len, c->p.max_ctx, c->p.temperature, c->p.top_p,
-                    c->p.sep_id, c->p.sep_logit_bias, c->ds.active, B, c->chosen);
-        hipLaunchKernelGGL(append_kernel, dim3(ceil_div(B, 64)), dim3(64), 0, c->st, c->ds, B, c->p.max_ctx, which,
-                           c->chosen, forced, c->p.sep_id, c->p.eos_id, c->p.step_cap, c->steps_done, c->p.max_steps);
+                    c->p.sep_id, c->p.sep_logit_bias, c->ds.active, B, nullptr, append_args(c, which, forced));
         iters = 1;
     }
     while (iters < c->p.step_cap) {
@@ -515,7 +603,7 @@ void rsd_destroy(rsd_ctx* c) {
         if (m.bt_host) (void)hipHostFree(m.bt_host);
     }
     void* dev[] = {c->sb_dev, c->ds.tokens, c->ds.sampled[0], c->ds.sampled[1], c->h, c->xn, c->qkv, c->att, c->gu, c->act,
-                   c->part_acc, c->part_ml, c->hl, c->xl, c->logits, c->tmp_reward, c->chosen, c->steptok_dev,
+                   c->part_acc, c->part_ml, c->part_k, c->tickets, c->smp_pmax, c->smp_pidx, c->smp_hist, c->smp_psum, c->smp_sel, c->hl, c->xl, c->logits, c->tmp_reward, c->chosen, c->steptok_dev,
                    c->row_seq_dev, c->row_pos_dev, c->last_row_dev};
     for (void* p : dev) if (p) (void)hipFree(p);
     for (hipEvent_t e : c->probe_ev) (void)hipEventDestroy(e);
@@ -588,6 +676,20 @@ int rsd_init(rsd_ctx** out, const rsd_model_shape shape[3], const rsd_weights w[
     HIPCHK(c, dev_alloc(&c->act, R * F));
     HIPCHK(c, dev_alloc(&c->part_acc, (size_t)B * HS));
     HIPCHK(c, dev_alloc(&c->part_ml, (size_t)B * HS));
+    int max_hkv = 1;
+    for (auto& m : c->m) max_hkv = std::max(max_hkv, m.s.n_kv_heads);
+    HIPCHK(c, dev_alloc(&c->tickets, (size_t)B * max_hkv));
+    HIPCHK(c, hipMemsetAsync(c->tickets, 0, (size_t)B * max_hkv * sizeof(int), c->st));
+    c->part_k_floats = (size_t)48 << 20;
+    HIPCHK(c, dev_alloc(&c->part_k, c->part_k_floats));
+    c->smp_rows = std::max(B, 64);
+    HIPCHK(c, dev_alloc(&c->smp_pmax, (size_t)c->smp_rows * SMP_NB));
+    HIPCHK(c, dev_alloc(&c->smp_pidx, (size_t)c->smp_rows * SMP_NB));
+    HIPCHK(c, dev_alloc(&c->smp_hist, (size_t)c->smp_rows * 3 * SMP_BINS));
+    HIPCHK(c, dev_alloc(&c->smp_psum, (size_t)c->smp_rows * SMP_NB));
+    HIPCHK(c, dev_alloc(&c->smp_sel, (size_t)c->smp_rows * 8));
+    HIPCHK(c, hipMemsetAsync(c->smp_hist, 0, (size_t)c->smp_rows * 3 * SMP_BINS * sizeof(u64_t), c->st));
+    HIPCHK(c, hipMemsetAsync(c->smp_sel, 0, (size_t)c->smp_rows * 8 * sizeof(u64_t), c->st));
     HIPCHK(c, dev_alloc(&c->hl, (size_t)B * d));
     HIPCHK(c, dev_alloc(&c->xl, (size_t)B * d));
     HIPCHK(c, dev_alloc(&c->logits, (size_t)B * V));
@@ -928,7 +1030,7 @@ int rsd_sample(rsd_ctx* c, const float* logits_dev, const float* u_dev, int32_t 
     if (!c || !logits_dev || !out_dev || n < 1 || vocab < 1) return fail(c, RSD_EINVAL, "bad argument");
     if (temperature > 0.f && !u_dev) return fail(c, RSD_EINVAL, "sampling needs uniforms");
     if (temperature < 0.f || top_p < 0.f || top_p > 1.f) return fail(c, RSD_EINVAL, "bad temperature/top_p");
-    sample_rows(c, logits_dev, vocab, vocab, u_dev, nullptr, 1, temperature, top_p, -1, 0.f, nullptr, n, out_dev);
+    sample_rows(c, logits_dev, vocab, vocab, u_dev, nullptr, 1, temperature, top_p, -1, 0.f, nullptr, n, out_dev, AppendArgs{});
     HIPCHK(c, hipGetLastError());
     HIPCHK(c, hipStreamSynchronize(c->st));
     return RSD_OK;

@@ -226,3 +226,26 @@ def test_full_vocabulary_head(gpu):
             err = float(np.max(np.abs(out[b, :lens[b]].cpu().numpy() - ref)))
             assert err < TOL, (chunk, b, err)
     s.close()
+
+
+def test_long_context_split_attention(gpu, mid_models):
+    """Contexts beyond 2048 tokens make the decode attention cut the cached
+    positions into several splits whose partial results are merged; ragged
+    lengths put the two sequences on different page counts."""
+    from oracle import rsd_oracle as O
+    R = gpu["R"]
+    w = mid_workload(2, prompt_len_min=2200, prompt_len_max=2300)
+    s = gpu["Session"](w)
+    rng = np.random.default_rng(77)
+    T = 2210
+    lens = np.array([T, 1333], np.int32)
+    toks = rng.integers(0, w.draft.vocab, size=(2, T)).astype(np.int32)
+    out = R.rsd_forward(s.ctx, 0, toks, lens, 1)
+    m = mid_models[0]
+    for b in range(2):
+        y = O.forward_full(m, [int(t) for t in toks[b, :lens[b]]], "bf16")
+        tail = slice(lens[b] - 48, lens[b])
+        ref = O.lm_logits(m, y[tail])
+        err = float(np.max(np.abs(out[b, tail].cpu().numpy() - ref)))
+        assert err < TOL, (b, err)
+    s.close()
