@@ -64,6 +64,7 @@ def main():
     ap.add_argument("--probe-model", type=int, default=1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graphs", action="store_true")
+    ap.add_argument("--max-steps", type=int, default=0, help="stop each pass after this many reasoning steps (debugging)")
     ap.add_argument("--ops", action="store_true", help="extra passes after the timed region: per-projection table")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -89,7 +90,7 @@ def main():
 
     def one_pass():
         s.reset()
-        return R.rsd_generate(s.ctx, want_tokens=False)
+        return R.rsd_generate(s.ctx, max_steps=args.max_steps, want_tokens=False)
 
     for _ in range(args.warmup):
         one_pass()

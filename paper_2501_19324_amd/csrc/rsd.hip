@@ -212,10 +212,16 @@ int setup_kv(rsd_ctx* c, Model& m, int which) {
     s = std::min(s, std::min(32, ceil_div(m.max_pages, 4)));
     m.splits = std::max(1, s);
     if (m.s.dtype == RSD_BF16) {
-        // MFMA kernel: a page costs a wave well under a microsecond, so up to 2048 tokens stay one
-        // split of 8 waves (no partials to merge); beyond that, 4-wave blocks of at most 32 pages
-        if (m.max_pages <= 128) m.splits = 1;
-        else m.splits = std::min(64, std::max(ceil_div(m.max_pages, 32), std::min(16, 512 / std::max(1, B * m.s.n_kv_heads))));
+        // MFMA kernel: a page costs a wave well under a microsecond.  A handful of (sequence, kv head)
+        // pairs with at most 2048 tokens stay one split of 8 waves (no partials to merge).  Otherwise
+        // 4-wave blocks: enough splits for about 384 blocks, none below 8 pages, none above 128 pages.
+        const int pairs = B * m.s.n_kv_heads;
+        if (m.max_pages <= 128 && pairs < 16) m.splits = 1;
+        else {
+            const int s_len = ceil_div(m.max_pages, 128);
+            const int s_par = std::min(ceil_div(384, pairs), ceil_div(m.max_pages, 8));
+            m.splits = std::min(64, std::max(s_len, s_par));
+        }
     }
     return RSD_OK;
 }
