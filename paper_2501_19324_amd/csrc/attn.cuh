@@ -713,3 +713,159 @@ __global__ __launch_bounds__(NW * 64) void attn_decode_mfma_kernel(const float* 
     }
     if (tid == 0) tickets[r * Hkv + hk] = 0;
 }
+
+// ---------------------------------------------------------------------------
+// MFMA chunked-prefill attention for bf16 caches, head_dim 128.
+//
+// Runs after rope_kv_kernel has rotated q in place and written the chunk's
+// keys/values to the cache.  One wave per work item = up to 4 consecutive rows
+// (query tokens) of one sequence and one kv head: two 16-column tiles, a
+// column being (row, head of the group); the wave walks every page up to the
+// last row's position once and feeds both tiles from the same K / V^T
+// registers.  Column (row, g) sees tokens <= position(row).  Same operand
+// layouts and hi + lo splitting as attn_decode_mfma_kernel.
+template <int G>
+__global__ __launch_bounds__(256) void attn_prefill_mfma_kernel(const float* __restrict__ qkv, int ldq,
+                                                                const bf16_t* __restrict__ pool_layer,
+                                                                const int* __restrict__ block_table, int max_pages,
+                                                                const int* __restrict__ row_seq,
+                                                                const int* __restrict__ row_pos,
+                                                                const int* __restrict__ item_row0,
+                                                                const int* __restrict__ item_n, int n_items,
+                                                                int H, int Hkv, float scale,
+                                                                float* __restrict__ out, int ldo) {
+    constexpr int HD = 128, NT = 2;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int item = blockIdx.x * 4 + wave, hk = blockIdx.y;
+    if (item >= n_items) return;
+    const int r0 = item_row0[item], n = item_n[item];
+    const int seq = row_seq[r0], p0 = row_pos[r0];
+    const int l16 = lane & 15, c = lane >> 4;
+    const int* bt = block_table + (size_t)seq * max_pages;
+    const size_t page_elts = (size_t)2 * Hkv * RSD_PAGE * HD;
+    const size_t head_off = (size_t)hk * RSD_PAGE * HD, v_off = (size_t)Hkv * RSD_PAGE * HD;
+    const int p_last = p0 + n - 1, n_pages = p_last / RSD_PAGE + 1;
+    int bt_mine = (lane < n_pages) ? bt[lane] : -1;        // refreshed every 64 pages
+
+    // column l16 of tile t: row r0 + 2t + l16 / 8, head l16 % 8
+    const int g_col = l16 & 7;
+    abf16x8_t qh[NT][4], ql[NT][4];
+    int pos_col[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        const int ri = 2 * t + (l16 >> 3);
+        const bool live = ri < n && g_col < G;
+        pos_col[t] = live ? p0 + ri : -1;                   // -1: the column sees no token
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            float qv[8];
+            if (live) {
+                load8(qkv + (size_t)(r0 + ri) * ldq + (hk * G + g_col) * HD + c * 32 + j * 8, qv);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) qv[e] *= scale;
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) qv[e] = 0.0f;
+            }
+            split_hi_lo8(qv, qh[t][j], ql[t][j]);
+        }
+    }
+    float m_run[NT], l_run[NT];
+    af32x4_t o[NT][8];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        m_run[t] = -INFINITY; l_run[t] = 0.0f;
+#pragma unroll
+        for (int nb = 0; nb < 8; ++nb) o[t][nb] = af32x4_t{0.f, 0.f, 0.f, 0.f};
+    }
+
+    uint4 kc[4], kn[4];
+    uint2 vc[8], vn[8];
+    auto fetch = [&](int pg, uint4 k[4], uint2 v[8]) {
+        const int phys = __shfl(bt_mine, pg & 63, RSD_WAVE);
+        const bf16_t* kb = pool_layer + (size_t)phys * page_elts + head_off;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) k[j] = *reinterpret_cast<const uint4*>(kb + l16 * HD + c * 32 + j * 8);
+#pragma unroll
+        for (int nb = 0; nb < 8; ++nb) v[nb] = *reinterpret_cast<const uint2*>(kb + v_off + (nb * 16 + l16) * RSD_PAGE + c * 4);
+    };
+    fetch(0, kc, vc);
+    for (int pg = 0; pg < n_pages; ++pg) {
+        if (pg + 1 < n_pages) {
+            if (((pg + 1) & 63) == 0) bt_mine = (pg + 1 + lane < n_pages) ? bt[pg + 1 + lane] : -1;
+            fetch(pg + 1, kn, vn);
+        }
+        // slots past the last row's position hold whatever the pool held: zero those values
+        int smask = 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) smask |= (pg * RSD_PAGE + c * 4 + i <= p_last) ? (1 << i) : 0;
+        const uint32_t mk0 = ((smask & 1) ? 0xFFFFu : 0u) | ((smask & 2) ? 0xFFFF0000u : 0u);
+        const uint32_t mk1 = ((smask & 4) ? 0xFFFFu : 0u) | ((smask & 8) ? 0xFFFF0000u : 0u);
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            af32x4_t s = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const abf16x8_t ka = __builtin_bit_cast(abf16x8_t, kc[j]);
+                s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, ql[t][j], s, 0, 0, 0);
+                s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, qh[t][j], s, 0, 0, 0);
+            }
+            int vmask = 0;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) vmask |= (pg * RSD_PAGE + c * 4 + i <= pos_col[t]) ? (1 << i) : 0;
+            float mloc = -INFINITY;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) if ((vmask >> i) & 1) mloc = fmaxf(mloc, s[i]);
+            mloc = fmaxf(mloc, __shfl_xor(mloc, 16, RSD_WAVE));
+            mloc = fmaxf(mloc, __shfl_xor(mloc, 32, RSD_WAVE));
+            const float m_new = fmaxf(m_run[t], mloc);
+            const float corr = (m_run[t] == -INFINITY) ? 0.0f : __expf(m_run[t] - m_new);
+            float p[4], lsum = 0.0f;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                p[i] = (((vmask >> i) & 1) && m_new > -INFINITY) ? __expf(s[i] - m_new) : 0.0f;
+                lsum += p[i];
+            }
+            lsum += __shfl_xor(lsum, 16, RSD_WAVE);
+            lsum += __shfl_xor(lsum, 32, RSD_WAVE);
+            l_run[t] = l_run[t] * corr + lsum;
+            m_run[t] = m_new;
+            uint16_t ph[4], pl[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { ph[i] = f2bf(p[i]); pl[i] = f2bf(p[i] - bf2f(ph[i])); }
+            const as16x4_t pa = __builtin_bit_cast(as16x4_t, make_uint2((uint32_t)ph[0] | ((uint32_t)ph[1] << 16), (uint32_t)ph[2] | ((uint32_t)ph[3] << 16)));
+            const as16x4_t pb = __builtin_bit_cast(as16x4_t, make_uint2((uint32_t)pl[0] | ((uint32_t)pl[1] << 16), (uint32_t)pl[2] | ((uint32_t)pl[3] << 16)));
+            float cr[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) cr[i] = __shfl(corr, c * 4 + i, RSD_WAVE);
+#pragma unroll
+            for (int nb = 0; nb < 8; ++nb) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) o[t][nb][i] *= cr[i];
+                const as16x4_t vb = __builtin_bit_cast(as16x4_t, make_uint2(vc[nb].x & mk0, vc[nb].y & mk1));
+                o[t][nb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pb, vb, o[t][nb], 0, 0, 0);
+                o[t][nb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pa, vb, o[t][nb], 0, 0, 0);
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) kc[j] = kn[j];
+#pragma unroll
+        for (int nb = 0; nb < 8; ++nb) vc[nb] = vn[nb];
+    }
+    // accumulator row c*4+i of tile t is column (row r0 + 2t + (c*4+i)/8, head (c*4+i)%8)
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int col = c * 4 + i;
+            const float den = __shfl(l_run[t], col, RSD_WAVE);
+            const int ri = 2 * t + (col >> 3), g = col & 7;
+            if (ri < n && g < G) {
+                float* dst = out + (size_t)(r0 + ri) * ldo + (hk * G + g) * HD + l16;
+                const float inv = 1.0f / den;
+#pragma unroll
+                for (int nb = 0; nb < 8; ++nb) dst[nb * 16] = o[t][nb][i] * inv;
+            }
+        }
+    }
+}

@@ -94,6 +94,9 @@ struct rsd_ctx {
     int *chosen = nullptr, *steptok_dev = nullptr;
     int *row_seq_dev = nullptr, *row_pos_dev = nullptr, *last_row_dev = nullptr;
     int *row_seq_h = nullptr, *row_pos_h = nullptr, *last_row_h = nullptr, *steptok_h = nullptr;
+    // chunked-prefill attention work items: first row and row count (<= 4 rows of one sequence)
+    int *item_row0_dev = nullptr, *item_n_dev = nullptr, *item_row0_h = nullptr, *item_n_h = nullptr;
+    int n_items = 0;
     int *poll_h = nullptr;
     double stage_ms[4] = {0, 0, 0, 0};
     // kernel timing probe
@@ -345,6 +348,23 @@ void launch_attn_decode_mfma(rsd_ctx* c, const Model& m, int l, int M, int which
 #undef RSD_ATTN_CASE
 }
 
+// chunked prefill over a bf16 cache: rows of the pass are described by the context's item arrays
+void launch_attn_prefill_mfma(rsd_ctx* c, const Model& m, int l, const RowMap& rm) {
+    const bf16_t* pool_l = reinterpret_cast<const bf16_t*>(m.pool) + (size_t)l * m.pool_pages * m.page_elts;
+    const float scale = 1.0f / std::sqrt(128.0f);
+    const dim3 grid(ceil_div(c->n_items, 4), m.s.n_kv_heads), block(256);
+#define RSD_ATTN_CASE(GG)                                                                                     \
+    case GG:                                                                                                  \
+        hipLaunchKernelGGL((attn_prefill_mfma_kernel<GG>), grid, block, 0, c->st, c->qkv, m.n_qkv, pool_l,    \
+                           m.bt_dev, m.max_pages, rm.row_seq, rm.row_pos, c->item_row0_dev, c->item_n_dev,    \
+                           c->n_items, m.s.n_heads, m.s.n_kv_heads, scale, c->att, m.q_dim);                  \
+        break;
+    switch (m.G) {
+        RSD_ATTN_CASE(1) RSD_ATTN_CASE(2) RSD_ATTN_CASE(4) RSD_ATTN_CASE(6) RSD_ATTN_CASE(7) RSD_ATTN_CASE(8)
+    }
+#undef RSD_ATTN_CASE
+}
+
 template <typename WT>
 void run_layers(rsd_ctx* c, Model& m, int M, const RowMap& rm, bool decode) {
     hipStream_t st = c->st;
@@ -374,7 +394,8 @@ void run_layers(rsd_ctx* c, Model& m, int M, const RowMap& rm, bool decode) {
         } else if (m.hd == 128) {
             hipLaunchKernelGGL((rope_kv_kernel<WT, 128>), dim3(M), dim3(256), 0, st, c->qkv, m.n_qkv, pool_l, m.bt_dev,
                                m.max_pages, rm, m.rope, m.s.n_heads, m.s.n_kv_heads);
-            launch_attn_g<WT, 128>(c, m, l, M, rm, S);
+            if (m.s.dtype == RSD_BF16) launch_attn_prefill_mfma(c, m, l, rm);
+            else launch_attn_g<WT, 128>(c, m, l, M, rm, S);
         } else {
             hipLaunchKernelGGL((rope_kv_kernel<WT, 32>), dim3(M), dim3(256), 0, st, c->qkv, m.n_qkv, pool_l, m.bt_dev,
                                m.max_pages, rm, m.rope, m.s.n_heads, m.s.n_kv_heads);
@@ -491,7 +512,7 @@ int prefill(rsd_ctx* c, int which, std::vector<Piece> pieces, AfterPass after_pa
     while (i < pieces.size()) {
         pass.clear();
         first_row.clear();
-        int M = 0;
+        int M = 0, n_items = 0;
         HIPCHK(c, hipStreamSynchronize(c->st));      // staging buffers of the previous pass are free again
         std::fill(c->last_row_h, c->last_row_h + c->B, -1);
         while (i < pieces.size() && M < kMaxRows) {
@@ -501,6 +522,10 @@ int prefill(rsd_ctx* c, int which, std::vector<Piece> pieces, AfterPass after_pa
             if (pc.end - pc.start > room) take.end = pc.start + room;
             first_row.push_back(M);
             pass.push_back(take);
+            for (int r = 0; r < take.end - take.start; r += 4) {
+                c->item_row0_h[n_items] = M + r;
+                c->item_n_h[n_items++] = std::min(4, take.end - take.start - r);
+            }
             for (int p = take.start; p < take.end; ++p, ++M) { c->row_seq_h[M] = take.b; c->row_pos_h[M] = p; }
             // "last row" of a sequence: the final position of its final piece
             const bool final_piece = take.end == pc.end && (i + 1 == pieces.size() || pieces[i + 1].b != pc.b);
@@ -511,6 +536,9 @@ int prefill(rsd_ctx* c, int which, std::vector<Piece> pieces, AfterPass after_pa
         HIPCHK(c, hipMemcpyAsync(c->row_seq_dev, c->row_seq_h, M * sizeof(int), hipMemcpyHostToDevice, c->st));
         HIPCHK(c, hipMemcpyAsync(c->row_pos_dev, c->row_pos_h, M * sizeof(int), hipMemcpyHostToDevice, c->st));
         HIPCHK(c, hipMemcpyAsync(c->last_row_dev, c->last_row_h, c->B * sizeof(int), hipMemcpyHostToDevice, c->st));
+        HIPCHK(c, hipMemcpyAsync(c->item_row0_dev, c->item_row0_h, n_items * sizeof(int), hipMemcpyHostToDevice, c->st));
+        HIPCHK(c, hipMemcpyAsync(c->item_n_dev, c->item_n_h, n_items * sizeof(int), hipMemcpyHostToDevice, c->st));
+        c->n_items = n_items;
         RowMap rm{c->row_seq_dev, c->row_pos_dev, nullptr, nullptr};
         run_layers<WT>(c, m, M, rm, false);
         const int rc = after_pass(pass, first_row, M);
@@ -610,10 +638,10 @@ void rsd_destroy(rsd_ctx* c) {
     }
     void* dev[] = {c->sb_dev, c->ds.tokens, c->ds.sampled[0], c->ds.sampled[1], c->h, c->xn, c->qkv, c->att, c->gu, c->act,
                    c->part_acc, c->part_ml, c->part_k, c->tickets, c->smp_pmax, c->smp_pidx, c->smp_hist, c->smp_psum, c->smp_sel, c->hl, c->xl, c->logits, c->tmp_reward, c->chosen, c->steptok_dev,
-                   c->row_seq_dev, c->row_pos_dev, c->last_row_dev};
+                   c->row_seq_dev, c->row_pos_dev, c->last_row_dev, c->item_row0_dev, c->item_n_dev};
     for (void* p : dev) if (p) (void)hipFree(p);
     for (hipEvent_t e : c->probe_ev) (void)hipEventDestroy(e);
-    void* pin[] = {c->sb, c->row_seq_h, c->row_pos_h, c->last_row_h, c->steptok_h, c->poll_h};
+    void* pin[] = {c->sb, c->item_row0_h, c->item_n_h, c->row_seq_h, c->row_pos_h, c->last_row_h, c->steptok_h, c->poll_h};
     for (void* p : pin) if (p) (void)hipHostFree(p);
     delete c;
 }
@@ -705,6 +733,10 @@ int rsd_init(rsd_ctx** out, const rsd_model_shape shape[3], const rsd_weights w[
     HIPCHK(c, dev_alloc(&c->row_seq_dev, R));
     HIPCHK(c, dev_alloc(&c->row_pos_dev, R));
     HIPCHK(c, dev_alloc(&c->last_row_dev, (size_t)B));
+    HIPCHK(c, dev_alloc(&c->item_row0_dev, R));
+    HIPCHK(c, dev_alloc(&c->item_n_dev, R));
+    HIPCHK(c, pin_alloc(&c->item_row0_h, R));
+    HIPCHK(c, pin_alloc(&c->item_n_h, R));
     HIPCHK(c, pin_alloc(&c->row_seq_h, R));
     HIPCHK(c, pin_alloc(&c->row_pos_h, R));
     HIPCHK(c, pin_alloc(&c->last_row_h, (size_t)B));
