@@ -231,8 +231,10 @@ __global__ __launch_bounds__(256) void rope_kv_kernel(float* __restrict__ qkv, i
 // per block, and the new token (position pos) is added by the block of the
 // last range straight from registers, after rounding its key and value to the
 // cache's storage type, and written to the cache by that block.  With S > 1
-// each block leaves a partial (max, sum, accumulator); the block that draws
-// the last ticket of its (sequence, kv head) merges them and resets the ticket.
+// each block leaves a partial (max, sum, accumulator) for attn_combine_kernel.
+// (Merging inside this kernel would need device-scope fences between blocks,
+// which on this multi-die part write back and invalidate L2 and cost far more
+// than a second launch.)
 template <typename KT> __device__ __forceinline__ float round_store(float v);
 template <> __device__ __forceinline__ float round_store<float>(float v) { return v; }
 template <> __device__ __forceinline__ float round_store<bf16_t>(float v) { return bf2f(f2bf(v)); }
@@ -274,7 +276,7 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(const float* __restric
                                                           const int* __restrict__ active,
                                                           const float2* __restrict__ rope, int H, int Hkv, int S,
                                                           float scale, float* __restrict__ out, int ldo,
-                                                          float* part_acc, float* part_ml, int* tickets) {
+                                                          float* __restrict__ part_acc, float* __restrict__ part_ml) {
     constexpr int LPT = HD / 8, TPW = 64 / LPT;
     constexpr int ITERS = RSD_PAGE / TPW > 0 ? RSD_PAGE / TPW : 1;
     const int r = blockIdx.x, hk = blockIdx.y, sp = blockIdx.z;
@@ -374,7 +376,6 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(const float* __restric
     }
     __shared__ float s_acc[4][G][HD];
     __shared__ float s_m[4][G], s_l[4][G];
-    __shared__ int s_last;
     if (lane < LPT) {
 #pragma unroll
         for (int g = 0; g < G; ++g) {
@@ -403,44 +404,6 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(const float* __restric
             if (e == 0) { part_ml[pi * 2] = mn; part_ml[pi * 2 + 1] = ll; }
         }
     }
-    if (S == 1) return;
-    __threadfence();
-    __syncthreads();
-    if (tid == 0) s_last = (atomicAdd(&tickets[r * Hkv + hk], 1) == S - 1);
-    __syncthreads();
-    if (!s_last) return;
-    __threadfence();
-    // partials of other blocks: device-scope loads (they bypass this unit's L1), all independent of one another
-    auto ld = [](const float* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); };
-    __shared__ float s_c[G][32];       // S <= 32: weight exp(m_s - max) of every split
-    __shared__ float s_den[G];
-    for (int idx = tid; idx < G * 32; idx += 256) {
-        const int g = idx >> 5, sl = idx & 31;
-        if (sl < S) s_c[g][sl] = ld(&part_ml[(((size_t)r * H + hk * G + g) * S + sl) * 2]);
-    }
-    __syncthreads();
-    if (tid < G) {
-        const int g = tid;
-        float mn = -INFINITY;
-        for (int sl = 0; sl < S; ++sl) mn = fmaxf(mn, s_c[g][sl]);
-        float den = 0.0f;
-        for (int sl = 0; sl < S; ++sl) {
-            const float m = s_c[g][sl];
-            const float cc = (m == -INFINITY) ? 0.0f : __expf(m - mn);
-            den += ld(&part_ml[(((size_t)r * H + hk * G + g) * S + sl) * 2 + 1]) * cc;
-            s_c[g][sl] = cc;
-        }
-        s_den[g] = den;
-    }
-    __syncthreads();
-    for (int idx = tid; idx < G * HD; idx += 256) {
-        const int g = idx / HD, e = idx - g * HD;
-        const size_t base = ((size_t)r * H + hk * G + g) * S;
-        float a = 0.0f;
-        for (int sl = 0; sl < S; ++sl) a += ld(&part_acc[(base + sl) * HD + e]) * s_c[g][sl];
-        out[(size_t)r * ldo + (hk * G + g) * HD + e] = a / s_den[g];
-    }
-    if (tid == 0) tickets[r * Hkv + hk] = 0;
 }
 
 // ---------------------------------------------------------------------------
@@ -458,7 +421,8 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(const float* __restric
 // The fp32 operands (rotated, scaled q and the probabilities) enter as hi + lo
 // bf16 pairs, two MFMAs each, so they keep 16 significant bits; K and V are
 // bf16 in the cache and enter exactly.  The new token is added from registers
-// by wave 0 of the last split, which also writes it to the cache.
+// by wave 0 of the last split, which also writes it to the cache.  With S > 1
+// the partials are merged by attn_combine_kernel.
 typedef __attribute__((ext_vector_type(8))) __bf16 abf16x8_t;
 typedef __attribute__((ext_vector_type(4))) short as16x4_t;
 typedef __attribute__((ext_vector_type(4))) float af32x4_t;
@@ -477,14 +441,14 @@ __device__ __forceinline__ void split_hi_lo8(const float x[8], abf16x8_t& hi, ab
 }
 
 template <int G, int NW>
-__global__ __launch_bounds__(NW * 64) void attn_decode_mfma_kernel(const float* __restrict__ qkv, int ldq,
+__global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void attn_decode_mfma_kernel(const float* __restrict__ qkv, int ldq,
                                                                    bf16_t* __restrict__ pool_layer,
                                                                    const int* __restrict__ block_table, int max_pages,
                                                                    const int* __restrict__ kv_len,
                                                                    const int* __restrict__ active,
                                                                    const float2* __restrict__ rope, int H, int Hkv,
                                                                    int S, float scale, float* __restrict__ out, int ldo,
-                                                                   float* part_acc, float* part_ml, int* tickets) {
+                                                                   float* __restrict__ part_acc, float* __restrict__ part_ml) {
     constexpr int HD = 128;
     const int r = blockIdx.x, hk = blockIdx.y, sp = blockIdx.z;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -520,28 +484,31 @@ __global__ __launch_bounds__(NW * 64) void attn_decode_mfma_kernel(const float* 
     if (S > 1 && p_begin + wave + lane * NW < p_end) bt_mine = bt[p_begin + wave + lane * NW];
     // i-th page of this wave (i < 64: a block never holds more than 64 * NW pages)
     auto fetch = [&](int i, uint4 k[4], uint2 v[8]) { fetch_phys(__shfl(bt_mine, i, RSD_WAVE), k, v); };
-    uint4 k2[4], k3[4];
-    uint2 v2[8], v3[8];          // three pages in flight ahead of the one being used
+    uint4 k2[4];
+    uint2 v2[8];                 // two pages in flight ahead of the one being used
     int pg = p_begin + wave, it = 0;
     if (pg < p_end) fetch(0, kc, vc);
     if (pg + NW < p_end) fetch(1, kn, vn);
-    if (pg + 2 * NW < p_end) fetch(2, k2, v2);
 
-    // Q^T operand: column l16 = head, k-group c
-    abf16x8_t qh[4], ql[4];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        float qv[8];
-        if (l16 < G) {
-            rope8<HD>(row + (hk * G + l16) * HD, cs, c * 32 + j * 8, qv);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) qv[e] *= scale;
-        } else {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) qv[e] = 0.0f;
+    // rotated, scaled queries of the group, computed once per block and kept in LDS as hi + lo bf16
+    // (rows >= G stay zero); the waves read their MFMA operands from there for every page
+    __shared__ __attribute__((aligned(16))) uint16_t s_qh[16][HD + 8];
+    __shared__ __attribute__((aligned(16))) uint16_t s_ql[16][HD + 8];
+    for (int idx = tid; idx < 16 * (HD / 2); idx += NW * 64) {
+        const int g = idx / (HD / 2), e = idx - g * (HD / 2);
+        float ra = 0.0f, rb = 0.0f;
+        if (g < G) {
+            const float* qp = row + (hk * G + g) * HD + e;
+            const float a = qp[0], b = qp[HD / 2];
+            const float2 t = cs[e];
+            ra = (a * t.x - b * t.y) * scale;
+            rb = (b * t.x + a * t.y) * scale;
         }
-        split_hi_lo8(qv, qh[j], ql[j]);
+        const uint16_t ha = f2bf(ra), hb = f2bf(rb);
+        s_qh[g][e] = ha; s_qh[g][e + HD / 2] = hb;
+        s_ql[g][e] = f2bf(ra - bf2f(ha)); s_ql[g][e + HD / 2] = f2bf(rb - bf2f(hb));
     }
+    __syncthreads();
 
     // the new token as a pseudo page whose only valid token is row 0 (wave 0 of the last split):
     // rotate its key, round key and value to bf16 as the cache stores them, write them to the cache.
@@ -583,8 +550,10 @@ __global__ __launch_bounds__(NW * 64) void attn_decode_mfma_kernel(const float* 
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const abf16x8_t ka = __builtin_bit_cast(abf16x8_t, k[j]);
-            s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, ql[j], s, 0, 0, 0);
-            s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, qh[j], s, 0, 0, 0);
+            const abf16x8_t qlo = __builtin_bit_cast(abf16x8_t, *reinterpret_cast<const uint4*>(&s_ql[l16][c * 32 + j * 8]));
+            const abf16x8_t qhi = __builtin_bit_cast(abf16x8_t, *reinterpret_cast<const uint4*>(&s_qh[l16][c * 32 + j * 8]));
+            s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, qlo, s, 0, 0, 0);
+            s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, qhi, s, 0, 0, 0);
         }
         float mloc = -INFINITY;
 #pragma unroll
@@ -626,27 +595,25 @@ __global__ __launch_bounds__(NW * 64) void attn_decode_mfma_kernel(const float* 
         }
     };
 
+    if (owns_new) process(k1, v1, c == 0 ? 1 : 0);          // order of accumulation is free
     while (pg < p_end) {
-        // the next two pages are in registers or on their way; start the third before using this one
-        if (pg + 3 * NW < p_end) fetch(it + 3, k3, v3);
+        // the next page is in registers or on its way; start the one after it before using this one
+        if (pg + 2 * NW < p_end) fetch(it + 2, k2, v2);
         int vmask = 0;
 #pragma unroll
         for (int i = 0; i < 4; ++i) vmask |= (pg * RSD_PAGE + c * 4 + i < pos) ? (1 << i) : 0;
         process(kc, vc, vmask);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) { kc[j] = kn[j]; kn[j] = k2[j]; k2[j] = k3[j]; }
+        for (int j = 0; j < 4; ++j) { kc[j] = kn[j]; kn[j] = k2[j]; }
 #pragma unroll
-        for (int nb = 0; nb < 8; ++nb) { vc[nb] = vn[nb]; vn[nb] = v2[nb]; v2[nb] = v3[nb]; }
+        for (int nb = 0; nb < 8; ++nb) { vc[nb] = vn[nb]; vn[nb] = v2[nb]; }
         pg += NW;
         ++it;
     }
 
-    if (owns_new) process(k1, v1, c == 0 ? 1 : 0);
-
     // ---- merge the waves of the block through LDS
     __shared__ float s_o[NW][G][HD];
     __shared__ float s_m[NW][16], s_l[NW][16];
-    __shared__ int s_last;
     if (c == 0) { s_m[wave][l16] = m_run; s_l[wave][l16] = l_run; }
 #pragma unroll
     for (int nb = 0; nb < 8; ++nb)
@@ -675,43 +642,6 @@ __global__ __launch_bounds__(NW * 64) void attn_decode_mfma_kernel(const float* 
             if (e == 0) { part_ml[pi * 2] = mn; part_ml[pi * 2 + 1] = ll; }
         }
     }
-    if (S == 1) return;
-    __threadfence();
-    __syncthreads();
-    if (tid == 0) s_last = (atomicAdd(&tickets[r * Hkv + hk], 1) == S - 1);
-    __syncthreads();
-    if (!s_last) return;
-    __threadfence();
-    auto ld = [](const float* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); };
-    __shared__ float s_c[G][64];       // S <= 64: weight exp(m_s - max) of every split
-    __shared__ float s_den[G];
-    for (int idx = tid; idx < G * 64; idx += NW * 64) {
-        const int g = idx >> 6, sl = idx & 63;
-        if (sl < S) s_c[g][sl] = ld(&part_ml[(((size_t)r * H + hk * G + g) * S + sl) * 2]);
-    }
-    __syncthreads();
-    if (tid < G) {
-        const int g = tid;
-        float mn = -INFINITY;
-        for (int sl = 0; sl < S; ++sl) mn = fmaxf(mn, s_c[g][sl]);
-        float den = 0.0f;
-        for (int sl = 0; sl < S; ++sl) {
-            const float m = s_c[g][sl];
-            const float cc = (m == -INFINITY) ? 0.0f : __expf(m - mn);
-            den += ld(&part_ml[(((size_t)r * H + hk * G + g) * S + sl) * 2 + 1]) * cc;
-            s_c[g][sl] = cc;
-        }
-        s_den[g] = den;
-    }
-    __syncthreads();
-    for (int idx = tid; idx < G * HD; idx += NW * 64) {
-        const int g = idx / HD, e = idx - g * HD;
-        const size_t base = ((size_t)r * H + hk * G + g) * S;
-        float a = 0.0f;
-        for (int sl = 0; sl < S; ++sl) a += ld(&part_acc[(base + sl) * HD + e]) * s_c[g][sl];
-        out[(size_t)r * ldo + (hk * G + g) * HD + e] = a / s_den[g];
-    }
-    if (tid == 0) tickets[r * Hkv + hk] = 0;
 }
 
 // ---------------------------------------------------------------------------
@@ -725,7 +655,7 @@ __global__ __launch_bounds__(NW * 64) void attn_decode_mfma_kernel(const float* 
 // registers.  Column (row, g) sees tokens <= position(row).  Same operand
 // layouts and hi + lo splitting as attn_decode_mfma_kernel.
 template <int G>
-__global__ __launch_bounds__(256) void attn_prefill_mfma_kernel(const float* __restrict__ qkv, int ldq,
+__global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(const float* __restrict__ qkv, int ldq,
                                                                 const bf16_t* __restrict__ pool_layer,
                                                                 const int* __restrict__ block_table, int max_pages,
                                                                 const int* __restrict__ row_seq,
@@ -749,13 +679,18 @@ __global__ __launch_bounds__(256) void attn_prefill_mfma_kernel(const float* __r
 
     // column l16 of tile t: row r0 + 2t + l16 / 8, head l16 % 8
     const int g_col = l16 & 7;
-    abf16x8_t qh[NT][4], ql[NT][4];
+    // Q^T operands of this wave's tiles live in LDS as hi + lo bf16: [wave][tile][hi|lo][16 columns][HD + 8]
+    extern __shared__ __attribute__((aligned(16))) uint16_t s_qop[];
+    constexpr int QSTR = HD + 8;
+    uint16_t* qbase = s_qop + (size_t)wave * NT * 2 * 16 * QSTR;
     int pos_col[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
         const int ri = 2 * t + (l16 >> 3);
         const bool live = ri < n && g_col < G;
         pos_col[t] = live ? p0 + ri : -1;                   // -1: the column sees no token
+        uint16_t* qh_row = qbase + ((size_t)(t * 2 + 0) * 16 + l16) * QSTR;
+        uint16_t* ql_row = qbase + ((size_t)(t * 2 + 1) * 16 + l16) * QSTR;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             float qv[8];
@@ -767,9 +702,13 @@ __global__ __launch_bounds__(256) void attn_prefill_mfma_kernel(const float* __r
 #pragma unroll
                 for (int e = 0; e < 8; ++e) qv[e] = 0.0f;
             }
-            split_hi_lo8(qv, qh[t][j], ql[t][j]);
+            abf16x8_t h8, l8;
+            split_hi_lo8(qv, h8, l8);
+            *reinterpret_cast<uint4*>(qh_row + c * 32 + j * 8) = __builtin_bit_cast(uint4, h8);
+            *reinterpret_cast<uint4*>(ql_row + c * 32 + j * 8) = __builtin_bit_cast(uint4, l8);
         }
     }
+    // (each wave reads back only what it wrote itself: no block barrier needed)
     float m_run[NT], l_run[NT];
     af32x4_t o[NT][8];
 #pragma unroll
@@ -807,8 +746,12 @@ __global__ __launch_bounds__(256) void attn_prefill_mfma_kernel(const float* __r
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const abf16x8_t ka = __builtin_bit_cast(abf16x8_t, kc[j]);
-                s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, ql[t][j], s, 0, 0, 0);
-                s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, qh[t][j], s, 0, 0, 0);
+                const abf16x8_t qhi = __builtin_bit_cast(abf16x8_t, *reinterpret_cast<const uint4*>(
+                    qbase + ((size_t)(t * 2 + 0) * 16 + l16) * QSTR + c * 32 + j * 8));
+                const abf16x8_t qlo = __builtin_bit_cast(abf16x8_t, *reinterpret_cast<const uint4*>(
+                    qbase + ((size_t)(t * 2 + 1) * 16 + l16) * QSTR + c * 32 + j * 8));
+                s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, qlo, s, 0, 0, 0);
+                s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, qhi, s, 0, 0, 0);
             }
             int vmask = 0;
 #pragma unroll

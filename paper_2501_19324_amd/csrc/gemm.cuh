@@ -183,6 +183,109 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
         }
 }
 
+// ---------------------------------------------------------------- bf16 MFMA, few rows
+// 9..64 activation rows (batched single-token decoding, short chunks): the time
+// is the one pass over W.  Each wave owns 32 rows of W and streams them from HBM
+// straight into MFMA operand registers (64 contiguous bytes per lane and 64-wide
+// K block, two blocks ahead of the arithmetic); only the activations go through
+// LDS (hi + lo bf16, double buffered), shared by the 4 waves of a block.
+// Within a K block of 64 the lane of k-group g (lane / 32) holds elements
+// g*32 + j*8 .. +8 for MFMA step j, for both operands: the same permutation of k
+// on both sides leaves the products unchanged.
+template <int MT, int EPI>     // MT: 32-row tiles of activations (1 or 2)
+__global__ __launch_bounds__(256) void gemm_skinny_kernel(const bf16_t* __restrict__ W, int N, int K,
+                                                          const float* __restrict__ X, int ldx,
+                                                          float* __restrict__ Y, int ldy, int M,
+                                                          float* __restrict__ part) {
+    constexpr int BK = 64, STR = BK + 8;                 // LDS row stride in bf16 (144 bytes)
+    constexpr int ROWS = 32 * MT;
+    __shared__ __attribute__((aligned(16))) uint16_t Ah[2][ROWS * STR];
+    __shared__ __attribute__((aligned(16))) uint16_t Al[2][ROWS * STR];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int nw = blockIdx.x * 128 + wave * 32;         // first W row of this wave
+    const int n_lane = min(nw + (lane & 31), N - 1), kg = lane >> 5;
+    const int nkb = K / BK;
+    const int per = (nkb + gridDim.z - 1) / gridDim.z;
+    const int kb0 = blockIdx.z * per, kb1 = min(nkb, kb0 + per);
+    const bf16_t* wp = W + (size_t)n_lane * K + kg * 32;
+
+    f32x16_t acc[MT];
+#pragma unroll
+    for (int t = 0; t < MT; ++t)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[t][v] = 0.0f;
+
+    uint4 w0[4], w1[4], w2[4];
+    auto fetch_w = [&](int kb, uint4 w[4]) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) w[j] = *reinterpret_cast<const uint4*>(wp + (size_t)kb * BK + j * 8);
+    };
+    constexpr int XF4 = ROWS * BK / 4 / 256;             // float4 of X per thread and K block (2 or 4)
+    float4 xv[XF4];
+    auto fetch_x = [&](int kb) {
+#pragma unroll
+        for (int i = 0; i < XF4; ++i) {
+            const int idx = tid + i * 256, row = idx >> 4, c4 = idx & 15;
+            xv[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (row < M) xv[i] = *reinterpret_cast<const float4*>(X + (size_t)row * ldx + (size_t)kb * BK + c4 * 4);
+        }
+    };
+    auto stage_x = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < XF4; ++i) {
+            const int idx = tid + i * 256, row = idx >> 4, c4 = idx & 15;
+            const float x[4] = {xv[i].x, xv[i].y, xv[i].z, xv[i].w};
+            uint16_t hi[4], lo[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { hi[e] = f2bf(x[e]); lo[e] = f2bf(x[e] - bf2f(hi[e])); }
+            *reinterpret_cast<uint2*>(&Ah[buf][row * STR + c4 * 4]) =
+                make_uint2((uint32_t)hi[0] | ((uint32_t)hi[1] << 16), (uint32_t)hi[2] | ((uint32_t)hi[3] << 16));
+            *reinterpret_cast<uint2*>(&Al[buf][row * STR + c4 * 4]) =
+                make_uint2((uint32_t)lo[0] | ((uint32_t)lo[1] << 16), (uint32_t)lo[2] | ((uint32_t)lo[3] << 16));
+        }
+    };
+    if (kb0 < kb1) { fetch_w(kb0, w0); fetch_x(kb0); }
+    if (kb0 + 1 < kb1) fetch_w(kb0 + 1, w1);
+    if (kb0 < kb1) stage_x(0);
+    __syncthreads();
+    for (int kb = kb0; kb < kb1; ++kb) {
+        const int buf = (kb - kb0) & 1;
+        if (kb + 2 < kb1) fetch_w(kb + 2, w2);
+        if (kb + 1 < kb1) fetch_x(kb + 1);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const bf16x8_t b = __builtin_bit_cast(bf16x8_t, w0[j]);
+#pragma unroll
+            for (int t = 0; t < MT; ++t) {
+                const int off = (t * 32 + (lane & 31)) * STR + kg * 32 + j * 8;
+                const bf16x8_t ah = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(&Ah[buf][off]));
+                const bf16x8_t al = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(&Al[buf][off]));
+                acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, b, acc[t], 0, 0, 0);
+                acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, b, acc[t], 0, 0, 0);
+            }
+        }
+        if (kb + 1 < kb1) stage_x(buf ^ 1);               // the other buffer was last read one iteration ago
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { w0[j] = w1[j]; w1[j] = w2[j]; }
+    }
+    const bool sliced = gridDim.z > 1;
+    const int n = nw + (lane & 31);
+#pragma unroll
+    for (int t = 0; t < MT; ++t)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int m = t * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+            if (m < M && n < N) {
+                if (sliced) part[((size_t)blockIdx.z * M + m) * N + n] = acc[t][v];
+                else {
+                    float* yp = Y + (size_t)m * ldy + n;
+                    *yp = (EPI == EPI_RESID) ? (*yp + acc[t][v]) : acc[t][v];
+                }
+            }
+        }
+}
+
 // Y[m][n] (+)= sum_z part[z][m][n], slices added in ascending z
 template <int EPI>
 __global__ void splitk_reduce_kernel(const float* __restrict__ part, int KS, int M, int N, float* __restrict__ Y, int ldy) {
@@ -225,6 +328,24 @@ static void gemm_bf16_launch(hipStream_t st, int epi, const bf16_t* W, int N, in
 static void gemm_launch(hipStream_t st, int epi, const bf16_t* W, int N, int K, const float* X, int ldx,
                         float* Y, int ldy, int M, float* part, size_t part_floats) {
     if (M <= 8) { gemv_launch<bf16_t>(st, PRO_NONE, epi, W, N, K, X, ldx, nullptr, 0.f, Y, ldy, M); return; }
+    if (M <= 64 && K % 64 == 0) {
+        // weight-streaming kernel: 128 rows of W per block, K slices until about 3 blocks per compute unit
+        const int nb = (N + 127) / 128;
+        int ks = 1;
+        while (ks < 32 && nb * ks < 768 && K / (ks * 2) >= 256 && (size_t)(ks * 2) * M * N <= part_floats) ks *= 2;
+        if (!part) ks = 1;
+        const dim3 grid(nb, 1, ks), block(256);
+#define RSD_SK_CASE(T, E) hipLaunchKernelGGL((gemm_skinny_kernel<T, E>), grid, block, 0, st, W, N, K, X, ldx, Y, ldy, M, part)
+        if (M <= 32) { if (epi == EPI_RESID) RSD_SK_CASE(1, EPI_RESID); else RSD_SK_CASE(1, EPI_STORE); }
+        else         { if (epi == EPI_RESID) RSD_SK_CASE(2, EPI_RESID); else RSD_SK_CASE(2, EPI_STORE); }
+#undef RSD_SK_CASE
+        if (ks > 1) {
+            const unsigned rb = (unsigned)(((size_t)M * N / 4 + 255) / 256);
+            if (epi == EPI_RESID) hipLaunchKernelGGL((splitk_reduce_kernel<EPI_RESID>), dim3(rb), block, 0, st, part, ks, M, N, Y, ldy);
+            else                  hipLaunchKernelGGL((splitk_reduce_kernel<EPI_STORE>), dim3(rb), block, 0, st, part, ks, M, N, Y, ldy);
+        }
+        return;
+    }
     // Tiles: 64 rows of activations when there are few; narrow weight tiles and K slices until
     // about two blocks per compute unit exist (these shapes are bound by streaming W once).
     const int bm = M <= 64 ? 64 : 128;

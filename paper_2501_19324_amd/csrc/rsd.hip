@@ -83,7 +83,6 @@ struct rsd_ctx {
     int ws_rows = 0;
     float *h = nullptr, *xn = nullptr, *qkv = nullptr, *att = nullptr, *gu = nullptr, *act = nullptr;
     float *part_acc = nullptr, *part_ml = nullptr;
-    int* tickets = nullptr;
     float* part_k = nullptr;         // K-slice partial sums of few-row GEMMs
     size_t part_k_floats = 0;
     // sampler workspace (per row: block maxima, histograms of the three radix levels, block masses, selections)
@@ -215,16 +214,12 @@ int setup_kv(rsd_ctx* c, Model& m, int which) {
     s = std::min(s, std::min(32, ceil_div(m.max_pages, 4)));
     m.splits = std::max(1, s);
     if (m.s.dtype == RSD_BF16) {
-        // MFMA kernel: a page costs a wave well under a microsecond.  A handful of (sequence, kv head)
-        // pairs with at most 2048 tokens stay one split of 8 waves (no partials to merge).  Otherwise
-        // 4-wave blocks: enough splits for about 384 blocks, none below 8 pages, none above 128 pages.
+        // MFMA kernel, 8 waves per block.  One split (nothing to merge) whenever the batch alone gives
+        // enough blocks or the context is short; otherwise enough splits for about 128 blocks, none
+        // below 16 pages.
         const int pairs = B * m.s.n_kv_heads;
-        if (m.max_pages <= 128 && pairs < 16) m.splits = 1;
-        else {
-            const int s_len = ceil_div(m.max_pages, 128);
-            const int s_par = std::min(ceil_div(384, pairs), ceil_div(m.max_pages, 8));
-            m.splits = std::min(64, std::max(s_len, s_par));
-        }
+        if (pairs >= 64 || m.max_pages <= 128) m.splits = 1;
+        else m.splits = std::max(1, std::min(64, std::min(ceil_div(128, pairs), ceil_div(m.max_pages, 16))));
     }
     return RSD_OK;
 }
@@ -304,6 +299,10 @@ struct ProbeScope {
     }
 };
 
+RowMap decode_map(rsd_ctx* c, int which) {
+    return RowMap{nullptr, nullptr, c->ds.kv_len + (size_t)which * c->B, c->ds.active};
+}
+
 template <typename KT, int HD>
 void launch_attn_decode(rsd_ctx* c, const Model& m, int l, int M, int which) {
     KT* pool_l = reinterpret_cast<KT*>(m.pool) + (size_t)l * m.pool_pages * m.page_elts;
@@ -314,16 +313,18 @@ void launch_attn_decode(rsd_ctx* c, const Model& m, int l, int M, int which) {
     case GG:                                                                                                  \
         hipLaunchKernelGGL((attn_decode_kernel<KT, HD, GG>), grid, block, 0, c->st, c->qkv, m.n_qkv, pool_l,  \
                            m.bt_dev, m.max_pages, c->ds.kv_len + (size_t)which * c->B, c->ds.active, m.rope,  \
-                           m.s.n_heads, m.s.n_kv_heads, S, scale, c->att, m.q_dim, c->part_acc, c->part_ml,   \
-                           c->tickets);                                                                       \
+                           m.s.n_heads, m.s.n_kv_heads, S, scale, c->att, m.q_dim, c->part_acc, c->part_ml);  \
         break;
     switch (m.G) {
         RSD_ATTN_CASE(1) RSD_ATTN_CASE(2) RSD_ATTN_CASE(4) RSD_ATTN_CASE(6) RSD_ATTN_CASE(7) RSD_ATTN_CASE(8)
     }
 #undef RSD_ATTN_CASE
+    if (S > 1)
+        hipLaunchKernelGGL((attn_combine_kernel<HD>), dim3(M, m.s.n_heads), dim3(HD), 0, c->st, c->part_acc,
+                           c->part_ml, decode_map(c, which), m.s.n_heads, S, c->att, m.q_dim);
 }
 
-// bf16 caches with head_dim 128: the MFMA kernel; 8 waves per block when the whole context is one split
+// bf16 caches with head_dim 128: the MFMA kernel, 8 waves per block
 void launch_attn_decode_mfma(rsd_ctx* c, const Model& m, int l, int M, int which) {
     bf16_t* pool_l = reinterpret_cast<bf16_t*>(m.pool) + (size_t)l * m.pool_pages * m.page_elts;
     const float scale = 1.0f / std::sqrt(128.0f);
@@ -331,21 +332,17 @@ void launch_attn_decode_mfma(rsd_ctx* c, const Model& m, int l, int M, int which
     const dim3 grid(M, m.s.n_kv_heads, S);
 #define RSD_ATTN_CASE(GG)                                                                                          \
     case GG:                                                                                                       \
-        if (S == 1)                                                                                                \
-            hipLaunchKernelGGL((attn_decode_mfma_kernel<GG, 8>), grid, dim3(512), 0, c->st, c->qkv, m.n_qkv, pool_l, \
-                               m.bt_dev, m.max_pages, c->ds.kv_len + (size_t)which * c->B, c->ds.active, m.rope,   \
-                               m.s.n_heads, m.s.n_kv_heads, S, scale, c->att, m.q_dim, c->part_acc, c->part_ml,    \
-                               c->tickets);                                                                        \
-        else                                                                                                       \
-            hipLaunchKernelGGL((attn_decode_mfma_kernel<GG, 4>), grid, dim3(256), 0, c->st, c->qkv, m.n_qkv, pool_l, \
-                               m.bt_dev, m.max_pages, c->ds.kv_len + (size_t)which * c->B, c->ds.active, m.rope,   \
-                               m.s.n_heads, m.s.n_kv_heads, S, scale, c->att, m.q_dim, c->part_acc, c->part_ml,    \
-                               c->tickets);                                                                        \
+        hipLaunchKernelGGL((attn_decode_mfma_kernel<GG, 8>), grid, dim3(512), 0, c->st, c->qkv, m.n_qkv, pool_l,   \
+                           m.bt_dev, m.max_pages, c->ds.kv_len + (size_t)which * c->B, c->ds.active, m.rope,       \
+                           m.s.n_heads, m.s.n_kv_heads, S, scale, c->att, m.q_dim, c->part_acc, c->part_ml);       \
         break;
     switch (m.G) {
         RSD_ATTN_CASE(1) RSD_ATTN_CASE(2) RSD_ATTN_CASE(4) RSD_ATTN_CASE(6) RSD_ATTN_CASE(7) RSD_ATTN_CASE(8)
     }
 #undef RSD_ATTN_CASE
+    if (S > 1)
+        hipLaunchKernelGGL((attn_combine_kernel<128>), dim3(M, m.s.n_heads), dim3(128), 0, c->st, c->part_acc,
+                           c->part_ml, decode_map(c, which), m.s.n_heads, S, c->att, m.q_dim);
 }
 
 // chunked prefill over a bf16 cache: rows of the pass are described by the context's item arrays
@@ -353,12 +350,19 @@ void launch_attn_prefill_mfma(rsd_ctx* c, const Model& m, int l, const RowMap& r
     const bf16_t* pool_l = reinterpret_cast<const bf16_t*>(m.pool) + (size_t)l * m.pool_pages * m.page_elts;
     const float scale = 1.0f / std::sqrt(128.0f);
     const dim3 grid(ceil_div(c->n_items, 4), m.s.n_kv_heads), block(256);
+    constexpr size_t qlds = (size_t)4 * 2 * 2 * 16 * (128 + 8) * sizeof(uint16_t);     // Q operands of 4 waves
 #define RSD_ATTN_CASE(GG)                                                                                     \
-    case GG:                                                                                                  \
-        hipLaunchKernelGGL((attn_prefill_mfma_kernel<GG>), grid, block, 0, c->st, c->qkv, m.n_qkv, pool_l,    \
+    case GG: {                                                                                                \
+        static bool raised = false;                                                                           \
+        if (!raised) {                                                                                        \
+            (void)hipFuncSetAttribute(reinterpret_cast<const void*>(attn_prefill_mfma_kernel<GG>),            \
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)qlds);                 \
+            raised = true;                                                                                    \
+        }                                                                                                     \
+        hipLaunchKernelGGL((attn_prefill_mfma_kernel<GG>), grid, block, qlds, c->st, c->qkv, m.n_qkv, pool_l, \
                            m.bt_dev, m.max_pages, rm.row_seq, rm.row_pos, c->item_row0_dev, c->item_n_dev,    \
                            c->n_items, m.s.n_heads, m.s.n_kv_heads, scale, c->att, m.q_dim);                  \
-        break;
+    } break;
     switch (m.G) {
         RSD_ATTN_CASE(1) RSD_ATTN_CASE(2) RSD_ATTN_CASE(4) RSD_ATTN_CASE(6) RSD_ATTN_CASE(7) RSD_ATTN_CASE(8)
     }
@@ -485,10 +489,6 @@ AppendArgs append_args(rsd_ctx* c, int which, const int* forced) {
     ap.sep_id = c->p.sep_id; ap.eos_id = c->p.eos_id; ap.step_cap = c->p.step_cap; ap.step = c->steps_done;
     ap.max_steps = c->p.max_steps;
     return ap;
-}
-
-RowMap decode_map(rsd_ctx* c, int which) {
-    return RowMap{nullptr, nullptr, c->ds.kv_len + (size_t)which * c->B, c->ds.active};
 }
 
 // One single-token iteration of an LM model over all sequences: forward, head, sample, append.
@@ -637,7 +637,7 @@ void rsd_destroy(rsd_ctx* c) {
         if (m.bt_host) (void)hipHostFree(m.bt_host);
     }
     void* dev[] = {c->sb_dev, c->ds.tokens, c->ds.sampled[0], c->ds.sampled[1], c->h, c->xn, c->qkv, c->att, c->gu, c->act,
-                   c->part_acc, c->part_ml, c->part_k, c->tickets, c->smp_pmax, c->smp_pidx, c->smp_hist, c->smp_psum, c->smp_sel, c->hl, c->xl, c->logits, c->tmp_reward, c->chosen, c->steptok_dev,
+                   c->part_acc, c->part_ml, c->part_k, c->smp_pmax, c->smp_pidx, c->smp_hist, c->smp_psum, c->smp_sel, c->hl, c->xl, c->logits, c->tmp_reward, c->chosen, c->steptok_dev,
                    c->row_seq_dev, c->row_pos_dev, c->last_row_dev, c->item_row0_dev, c->item_n_dev};
     for (void* p : dev) if (p) (void)hipFree(p);
     for (hipEvent_t e : c->probe_ev) (void)hipEventDestroy(e);
@@ -710,10 +710,6 @@ int rsd_init(rsd_ctx** out, const rsd_model_shape shape[3], const rsd_weights w[
     HIPCHK(c, dev_alloc(&c->act, R * F));
     HIPCHK(c, dev_alloc(&c->part_acc, (size_t)B * HS));
     HIPCHK(c, dev_alloc(&c->part_ml, (size_t)B * HS));
-    int max_hkv = 1;
-    for (auto& m : c->m) max_hkv = std::max(max_hkv, m.s.n_kv_heads);
-    HIPCHK(c, dev_alloc(&c->tickets, (size_t)B * max_hkv));
-    HIPCHK(c, hipMemsetAsync(c->tickets, 0, (size_t)B * max_hkv * sizeof(int), c->st));
     c->part_k_floats = (size_t)48 << 20;
     HIPCHK(c, dev_alloc(&c->part_k, c->part_k_floats));
     c->smp_rows = std::max(B, 64);
