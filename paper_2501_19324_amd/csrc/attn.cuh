@@ -596,19 +596,26 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void attn_decode_mfma_ker
     };
 
     if (owns_new) process(k1, v1, c == 0 ? 1 : 0);          // order of accumulation is free
+    // Three register buffers take fixed turns (no copies between them: a copy would have to wait for
+    // the load it copies): while page i is used, pages i+1 and i+2 are in flight.
+    auto page_mask = [&](int page) {
+        int vm = 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) vm |= (page * RSD_PAGE + c * 4 + i < pos) ? (1 << i) : 0;
+        return vm;
+    };
     while (pg < p_end) {
-        // the next page is in registers or on its way; start the one after it before using this one
         if (pg + 2 * NW < p_end) fetch(it + 2, k2, v2);
-        int vmask = 0;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) vmask |= (pg * RSD_PAGE + c * 4 + i < pos) ? (1 << i) : 0;
-        process(kc, vc, vmask);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) { kc[j] = kn[j]; kn[j] = k2[j]; }
-#pragma unroll
-        for (int nb = 0; nb < 8; ++nb) { vc[nb] = vn[nb]; vn[nb] = v2[nb]; }
-        pg += NW;
-        ++it;
+        process(kc, vc, page_mask(pg));
+        pg += NW; ++it;
+        if (pg >= p_end) break;
+        if (pg + 2 * NW < p_end) fetch(it + 2, kc, vc);
+        process(kn, vn, page_mask(pg));
+        pg += NW; ++it;
+        if (pg >= p_end) break;
+        if (pg + 2 * NW < p_end) fetch(it + 2, kn, vn);
+        process(k2, v2, page_mask(pg));
+        pg += NW; ++it;
     }
 
     // ---- merge the waves of the block through LDS
@@ -728,12 +735,7 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(const float* 
 #pragma unroll
         for (int nb = 0; nb < 8; ++nb) v[nb] = *reinterpret_cast<const uint2*>(kb + v_off + (nb * 16 + l16) * RSD_PAGE + c * 4);
     };
-    fetch(0, kc, vc);
-    for (int pg = 0; pg < n_pages; ++pg) {
-        if (pg + 1 < n_pages) {
-            if (((pg + 1) & 63) == 0) bt_mine = (pg + 1 + lane < n_pages) ? bt[pg + 1 + lane] : -1;
-            fetch(pg + 1, kn, vn);
-        }
+    auto do_page = [&](int pg, const uint4 k[4], const uint2 v[8]) {
         // slots past the last row's position hold whatever the pool held: zero those values
         int smask = 0;
 #pragma unroll
@@ -745,7 +747,7 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(const float* 
             af32x4_t s = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                const abf16x8_t ka = __builtin_bit_cast(abf16x8_t, kc[j]);
+                const abf16x8_t ka = __builtin_bit_cast(abf16x8_t, k[j]);
                 const abf16x8_t qhi = __builtin_bit_cast(abf16x8_t, *reinterpret_cast<const uint4*>(
                     qbase + ((size_t)(t * 2 + 0) * 16 + l16) * QSTR + c * 32 + j * 8));
                 const abf16x8_t qlo = __builtin_bit_cast(abf16x8_t, *reinterpret_cast<const uint4*>(
@@ -785,15 +787,24 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(const float* 
             for (int nb = 0; nb < 8; ++nb) {
 #pragma unroll
                 for (int i = 0; i < 4; ++i) o[t][nb][i] *= cr[i];
-                const as16x4_t vb = __builtin_bit_cast(as16x4_t, make_uint2(vc[nb].x & mk0, vc[nb].y & mk1));
+                const as16x4_t vb = __builtin_bit_cast(as16x4_t, make_uint2(v[nb].x & mk0, v[nb].y & mk1));
                 o[t][nb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pb, vb, o[t][nb], 0, 0, 0);
                 o[t][nb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pa, vb, o[t][nb], 0, 0, 0);
             }
         }
-#pragma unroll
-        for (int j = 0; j < 4; ++j) kc[j] = kn[j];
-#pragma unroll
-        for (int nb = 0; nb < 8; ++nb) vc[nb] = vn[nb];
+    };
+    auto prefetch = [&](int pg, uint4 k[4], uint2 v[8]) {     // pg < n_pages
+        if ((pg & 63) == 0) bt_mine = (pg + lane < n_pages) ? bt[pg + lane] : -1;
+        fetch(pg, k, v);
+    };
+    // two register buffers take turns (no copies between them: a copy would wait for the load)
+    fetch(0, kc, vc);
+    for (int pg = 0; pg < n_pages; pg += 2) {
+        if (pg + 1 < n_pages) prefetch(pg + 1, kn, vn);
+        do_page(pg, kc, vc);
+        if (pg + 1 >= n_pages) break;
+        if (pg + 2 < n_pages) prefetch(pg + 2, kc, vc);
+        do_page(pg + 1, kn, vn);
     }
     // accumulator row c*4+i of tile t is column (row r0 + 2t + (c*4+i)/8, head (c*4+i)%8)
 #pragma unroll

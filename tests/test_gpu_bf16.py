@@ -249,3 +249,97 @@ def test_long_context_split_attention(gpu, mid_models):
         err = float(np.max(np.abs(out[b, tail].cpu().numpy() - ref)))
         assert err < TOL, (b, err)
     s.close()
+
+
+def test_wide_shapes_batch16(gpu):
+    """Shapes of the third configuration at reduced depth: 72B-width target
+    (d 8192, 64/8 heads, FFN 29568), 7B-width reward model, batch 16 (the
+    few-row MFMA GEMM with one 32-row tile), two teacher-forced steps on the
+    first two sequences."""
+    from oracle import rsd_oracle as O
+    from rsd_inputs import workload
+    R, torch = gpu["R"], gpu["torch"]
+    w = workload("cfg3", n_layers=2, vocab=4096, batch=16, prompt_len_min=24, prompt_len_max=40, step_cap=6,
+                 max_steps=2, deltas=(0.5,), sep_logit_bias=2.3)
+    models = oracle_models(w)
+    s = gpu["Session"](w)
+    P = oracle_params(O, w)
+    n_check = 2
+    refs = [O.generate_sequence(*models, s.tokens_host[b, :s.prompt_len[b]], s.u_host["U_DRAFT"][b],
+                                s.u_host["U_TARGET"][b], s.u_host["U_GATE"][b], P) for b in range(n_check)]
+    forced, _ = teacher_arrays(w, refs + [dict(records=[])] * (w.batch - n_check), torch)
+    R.rsd_set_teacher(s.ctx, *forced)
+    s.reset()
+    for i in range(w.max_steps):
+        g = R.rsd_step(s.ctx)
+        st = R.rsd_export_state(s.ctx, want_tokens=False)
+        for b in range(n_check):
+            r = refs[b]["records"][i]
+            assert abs(float(g["reward"][b]) - r["reward"]) < TOL, (b, i, g["reward"][b], r["reward"])
+            if abs(r["reward"] - float(np.float32(w.delta))) > 1e-3:
+                assert bool(g["own_accept"][b]) == r["accepted"]
+            assert list(g["final_tokens"][b, :g["final_len"][b]]) == r["final_tokens"]
+            assert list(st["kv_len"][:, b]) == r["kv_len"]
+    own_d, own_t = R.rsd_export_sampled(s.ctx)
+    for b in range(n_check):
+        for r in refs[b]["records"]:
+            for toks, margins, own in ((r["draft_tokens"], r["draft_margins"], own_d),
+                                       (r["final_tokens"] if not r["accepted"] else [], r["final_margins"], own_t)):
+                for j, t in enumerate(toks):
+                    assert own[b, r["step"], j] == t or margins[j] < 2 * TOL
+    # target logits through both paths on one sequence
+    toks = np.zeros((w.batch, 20), np.int32)
+    lens = np.zeros(w.batch, np.int32)
+    toks[0] = np.random.default_rng(4).integers(0, 4096, 20)
+    lens[0] = 20
+    ref = O.lm_logits(models[1], O.forward_full(models[1], [int(t) for t in toks[0]], "bf16"))
+    for chunk in (1, 20):
+        out = R.rsd_forward(s.ctx, 1, toks, lens, chunk)
+        err = float(np.max(np.abs(out[0, :20].cpu().numpy() - ref)))
+        print(f"72B-width target, chunk {chunk}: max abs error {err:.2e}")
+        assert err < TOL
+    R.rsd_set_teacher(s.ctx, None, None, None)
+    s.close()
+
+
+def test_batch64_ragged_prompts(gpu, mid_models):
+    """Second configuration's structure at reduced depth: 64 sequences with
+    ragged prompts, independent accept/regenerate decisions; three sequences
+    are followed by the checker under the teacher, the rest run free, and the
+    batch must not leak between sequences (pages, offsets)."""
+    from oracle import rsd_oracle as O
+    R, torch = gpu["R"], gpu["torch"]
+    w = mid_workload(64, prompt_len_min=16, prompt_len_max=200, step_cap=8, max_steps=3)
+    s = gpu["Session"](w)
+    P = oracle_params(O, w)
+    check = [0, 31, 63]
+    refs = {b: O.generate_sequence(*mid_models, s.tokens_host[b, :s.prompt_len[b]], s.u_host["U_DRAFT"][b],
+                                   s.u_host["U_TARGET"][b], s.u_host["U_GATE"][b], P) for b in check}
+    allrefs = [refs.get(b, dict(records=[])) for b in range(w.batch)]
+    forced, _ = teacher_arrays(w, allrefs, torch)
+    R.rsd_set_teacher(s.ctx, *forced)
+    s.reset()
+    for i in range(w.max_steps):
+        g = R.rsd_step(s.ctx)
+        st = R.rsd_export_state(s.ctx, want_tokens=False)
+        for b in check:
+            r = refs[b]["records"][i]
+            assert abs(float(g["reward"][b]) - r["reward"]) < TOL
+            if abs(r["reward"] - float(np.float32(w.delta))) > 1e-3:
+                assert bool(g["own_accept"][b]) == r["accepted"]
+            assert list(g["final_tokens"][b, :g["final_len"][b]]) == r["final_tokens"]
+            assert list(st["kv_len"][:, b]) == r["kv_len"] and list(st["n_pages"][:, b]) == r["n_pages"]
+        # every sequence obeys the offset contract, whatever it decided
+        for b in range(w.batch):
+            kd, kt, kp = (int(v) for v in st["kv_len"][:, b])
+            ctx = int(st["ctx_len"][b])
+            if g["accepted"][b]:
+                assert kd == ctx - 1 and kp == ctx
+            else:
+                assert kd == kp == ctx - int(g["final_len"][b]) and kt == ctx - 1
+        for mdl in range(3):
+            pg = R.rsd_export_pages(s.ctx, mdl)
+            used = pg["block_table"][pg["block_table"] >= 0]
+            assert len(set(used.tolist())) == used.size and used.size + pg["free_pages"] == pg["pool_pages"]
+    R.rsd_set_teacher(s.ctx, None, None, None)
+    s.close()
