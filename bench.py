@@ -65,6 +65,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graphs", action="store_true")
     ap.add_argument("--max-steps", type=int, default=0, help="stop each pass after this many reasoning steps (debugging)")
+    ap.add_argument("--kv-pool-gb", default="", help="KV pool sizes in GB for draft,target,PRM (default: worst case)")
     ap.add_argument("--ops", action="store_true", help="extra passes after the timed region: per-projection table")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -84,13 +85,24 @@ def main():
     w = workload(args.workload, **kw)
     delta = w.delta if args.delta is None else args.delta
     t_setup = time.time()
-    s = Session(w, delta=delta, use_graphs=0 if args.no_graphs else 1)
+    pools = tuple(int(float(x) * 1e9) for x in args.kv_pool_gb.split(",")) if args.kv_pool_gb else (0, 0, 0)
+    s = Session(w, delta=delta, use_graphs=0 if args.no_graphs else 1, kv_pool_bytes=pools)
     torch.cuda.synchronize()
     t_setup = time.time() - t_setup
 
     def one_pass():
         s.reset()
-        return R.rsd_generate(s.ctx, max_steps=args.max_steps, want_tokens=False)
+        try:
+            return R.rsd_generate(s.ctx, max_steps=args.max_steps, want_tokens=False)
+        except R.RsdError as e:
+            if e.code != R.RSD_ENOMEM:
+                raise
+            # KV pool exhausted: a clean stop; report what was generated until then
+            st = R.rsd_export_state(s.ctx, want_tokens=False)
+            print(f"# KV pool exhausted: {e}; contexts reached {int(st['ctx_len'].min())}..{int(st['ctx_len'].max())}",
+                  file=sys.stderr)
+            return dict(n_committed=int((st["ctx_len"] - s.prompt_len).sum()), n_draft=0, n_target=0, n_accept=0,
+                        n_reject=0)
 
     for _ in range(args.warmup):
         one_pass()

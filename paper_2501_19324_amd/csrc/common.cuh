@@ -2,6 +2,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <type_traits>
 
 #define RSD_WAVE 64
 
@@ -48,6 +49,21 @@ __device__ __forceinline__ float wave_max(float v) {
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, RSD_WAVE));
     return v;
+}
+
+// Sum over the 64 lanes with cross-lane register moves (no LDS traffic).  All 64 lanes must be
+// active; every lane gets the result.
+__device__ __forceinline__ float wave_sum_dpp(float v) {
+    auto dpp_add = [](float x, auto ctrl) {
+        return x + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), decltype(ctrl)::value, 0xF, 0xF, true));
+    };
+    v = dpp_add(v, std::integral_constant<int, 0xB1>{});    // quad_perm [1,0,3,2]
+    v = dpp_add(v, std::integral_constant<int, 0x4E>{});    // quad_perm [2,3,0,1]
+    v = dpp_add(v, std::integral_constant<int, 0x141>{});   // row_half_mirror
+    v = dpp_add(v, std::integral_constant<int, 0x140>{});   // row_mirror: each row of 16 lanes holds its sum
+    const int bits = __float_as_int(v);
+    return (__int_as_float(__builtin_amdgcn_readlane(bits, 0)) + __int_as_float(__builtin_amdgcn_readlane(bits, 16))) +
+           (__int_as_float(__builtin_amdgcn_readlane(bits, 32)) + __int_as_float(__builtin_amdgcn_readlane(bits, 48)));
 }
 
 // Sum over a 256-thread block; `red` is 4 floats of LDS. All threads get the result.

@@ -214,18 +214,15 @@ __global__ __launch_bounds__(256) void gemv_full_kernel(const WT* __restrict__ W
 #pragma unroll
             for (int r = 0; r < R; ++r) acc[a][m][r] = 0.0f;
 
-    int g = 0, i = 0;
-    for (int t = 0; t < total; ++t) {
-        int gn = g, in = i + 1;
-        if (in == iters) { in = 0; gn = g + 1; }
-        if (t + 1 < total) fetch(gn, in, nxt);
+    // one step of the walk: use the registers in `buf` for step (g, i), finish the row group if it ends here
+    auto use = [&](int g, int i, const Raw8<WT> buf[U][NR]) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int s = (i * U + u) * 64 + lane;
             if (s < slots) {
                 float w[NR][8];
 #pragma unroll
-                for (int q = 0; q < NR; ++q) cur[u][q].unpack(w[q]);
+                for (int q = 0; q < NR; ++q) buf[u][q].unpack(w[q]);
 #pragma unroll
                 for (int m = 0; m < MT; ++m) {
                     const float4 xa = *reinterpret_cast<const float4*>(xs + (size_t)m * K + s * 8);
@@ -258,11 +255,20 @@ __global__ __launch_bounds__(256) void gemv_full_kernel(const WT* __restrict__ W
                     }
                 }
         }
-#pragma unroll
-        for (int u = 0; u < U; ++u)
-#pragma unroll
-            for (int q = 0; q < NR; ++q) cur[u][q] = nxt[u][q];
-        g = gn; i = in;
+    };
+    // the two register buffers take turns (a copy between them would have to wait for the load)
+    int g = 0, i = 0;
+    for (int t = 0; t < total; t += 2) {
+        int g1 = g, i1 = i + 1;
+        if (i1 == iters) { i1 = 0; g1 = g + 1; }
+        if (t + 1 < total) fetch(g1, i1, nxt);
+        use(g, i, cur);
+        if (t + 1 >= total) break;
+        int g2 = g1, i2 = i1 + 1;
+        if (i2 == iters) { i2 = 0; g2 = g1 + 1; }
+        if (t + 2 < total) fetch(g2, i2, cur);
+        use(g1, i1, nxt);
+        g = g2; i = i2;
     }
 }
 
@@ -295,6 +301,182 @@ static bool gemv_launch_full(hipStream_t st, int pro, int epi, const WT* W, int 
     RSD_GEMVF_CASE(PRO_NORM, EPI_STORE)
     RSD_GEMVF_CASE(PRO_NORM, EPI_SWIGLU)
 #undef RSD_GEMVF_CASE
+    return false;
+}
+
+// Single activation row.  A block owns a contiguous span of rows of W (for EPI_SWIGLU the
+// gate rows and the matching up rows); the span is cut into 1 KiB chunks (64 lanes x 16
+// bytes of one row) and every wave streams an equal, contiguous run of chunks, so all
+// waves of the launch do the same amount of work whatever N and K are.  The loop body
+// has no conditional loads (chunks past the end re-read the last one and count as zero),
+// which lets the compiler keep two stages of U loads in flight.  A wave finishes a row
+// (or its part of one) with a lane sum into its own LDS slot; the slots are added in wave
+// order at the end, so the result does not depend on timing.
+template <typename WT, int NW, int U, int PRO, int EPI>
+__global__ __launch_bounds__(NW * 64) void gemv_flat_kernel(const WT* __restrict__ W, int N, int K,
+                                                            const float* __restrict__ X,
+                                                            const WT* __restrict__ gain, float eps,
+                                                            float* __restrict__ Y, uint32_t cpr_magic) {
+    constexpr int NA = (EPI == EPI_SWIGLU) ? 2 : 1;
+    extern __shared__ float smem[];
+    const int CPR = (K + 511) >> 9;         // chunks per row
+    float* xs = smem;                       // [CPR][512], swizzled, zero beyond K
+    float* red = smem + (CPR << 9);         // [NW][NA][V]
+    __shared__ float red_ss[NW];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int G = gridDim.x, b = blockIdx.x;
+    const int r0 = (int)((long long)b * N / G), r1 = (int)((long long)(b + 1) * N / G);
+    const int V = r1 - r0;
+    if (V == 0) return;
+    const int C = V * CPR;
+    const int c0 = (int)((long long)wave * C / NW), c1 = (int)((long long)(wave + 1) * C / NW);
+    const int n_my = c1 - c0;
+    const int c_last = max(c1 - 1, 0);
+    const int n_stages = (n_my + U - 1) / U;
+    const int k_lane = lane * 8;
+
+    auto fetch = [&](Raw8<WT> buf[U][NA], int stage) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int c = min(c0 + stage * U + u, c_last);
+            const int v = CPR == 1 ? c : (int)__umulhi((uint32_t)c, cpr_magic);     // c / CPR
+            const int s = c - v * CPR;
+            const int k = min((s << 9) + k_lane, K - 8);
+#pragma unroll
+            for (int a = 0; a < NA; ++a) buf[u][a].load(W + ((size_t)a * N + r0 + v) * K + k);
+        }
+    };
+    Raw8<WT> b0[U][NA], b1[U][NA];
+    fetch(b0, 0);
+    fetch(b1, 1);
+
+    float ss = 0.0f;
+    for (int k = tid * 4; k < (CPR << 9); k += NW * 256) {
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (k < K) {
+            v = *reinterpret_cast<const float4*>(X + k);
+            if (PRO == PRO_NORM) {
+                ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+                const WT* gp = gain + k;
+                v.x *= ld1(gp); v.y *= ld1(gp + 1); v.z *= ld1(gp + 2); v.w *= ld1(gp + 3);
+            }
+        }
+        // within each 512-float chunk the two halves of every lane's 8 values are stored 1 KiB
+        // apart, so that both 16-byte LDS reads of a wave are contiguous across its lanes
+        const int c = k >> 9, o = k & 511;
+        *reinterpret_cast<float4*>(xs + (c << 9) + ((o >> 2) & 1) * 256 + (o >> 3) * 4) = v;
+    }
+    for (int i = tid; i < NW * NA * V; i += NW * 64) red[i] = 0.0f;
+    if (PRO == PRO_NORM) {
+        ss = wave_sum(ss);
+        if (lane == 0) red_ss[wave] = ss;
+    }
+    __syncthreads();
+    float rs = 1.0f;
+    if (PRO == PRO_NORM) {
+        float t = 0.0f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) t += red_ss[w];
+        rs = 1.0f / sqrtf(t / (float)K + eps);
+    }
+
+    float acc[NA];
+#pragma unroll
+    for (int a = 0; a < NA; ++a) acc[a] = 0.0f;
+    auto use = [&](const Raw8<WT> buf[U][NA], int stage) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int i = stage * U + u;
+            const int c = min(c0 + i, c_last);
+            const int v = CPR == 1 ? c : (int)__umulhi((uint32_t)c, cpr_magic);     // c / CPR
+            const int s = c - v * CPR;
+            const float4 xa = *reinterpret_cast<const float4*>(xs + (s << 9) + lane * 4);
+            const float4 xb = *reinterpret_cast<const float4*>(xs + (s << 9) + 256 + lane * 4);
+            const float keep = i < n_my ? 1.0f : 0.0f;
+#pragma unroll
+            for (int a = 0; a < NA; ++a) {
+                float w[8];
+                buf[u][a].unpack(w);
+                acc[a] += keep * (xa.x * w[0] + xa.y * w[1] + xa.z * w[2] + xa.w * w[3]
+                                + xb.x * w[4] + xb.y * w[5] + xb.z * w[6] + xb.w * w[7]);
+            }
+            if (i < n_my && (s == CPR - 1 || i == n_my - 1)) {
+#pragma unroll
+                for (int a = 0; a < NA; ++a) {
+                    const float t = wave_sum_dpp(acc[a]);
+                    if (lane == 0) red[(wave * NA + a) * V + v] = t;
+                    acc[a] = 0.0f;
+                }
+            }
+        }
+    };
+    int s = 0;
+    for (; s + 3 < n_stages; s += 2) {          // both refills are real stages
+        use(b0, s);     fetch(b0, s + 2);
+        use(b1, s + 1); fetch(b1, s + 3);
+    }
+    if (s < n_stages) {                          // at most three stages left
+        use(b0, s);
+        if (s + 2 < n_stages) fetch(b0, s + 2);
+        if (s + 1 < n_stages) use(b1, s + 1);
+        if (s + 2 < n_stages) use(b0, s + 2);
+    }
+    __syncthreads();
+    for (int t = tid; t < V; t += NW * 64) {
+        float g = 0.0f, up = 0.0f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+            g += red[w * NA * V + t];
+            if (EPI == EPI_SWIGLU) up += red[(w * NA + NA - 1) * V + t];
+        }
+        g *= rs;
+        float* yp = Y + r0 + t;
+        if (EPI == EPI_SWIGLU) *yp = g / (1.0f + expf(-g)) * (up * rs);
+        else *yp = (EPI == EPI_RESID) ? (*yp + g) : g;
+    }
+}
+
+// Launch of the single-row kernel: blocks_per_cu blocks of NW waves per compute unit (fewer when
+// LDS or the matrix is too small for that: a wave should still get min_chunks chunks).
+template <typename WT, int NW, int U>
+static bool gemv_launch_flat(hipStream_t st, int pro, int epi, const WT* W, int N, int K, const float* X,
+                             const WT* gain, float eps, float* Y, int blocks_per_cu, int min_chunks) {
+    if (pro == PRO_SWIGLU || (K & 7) || K < 8) return false;
+    const int NA = epi == EPI_SWIGLU ? 2 : 1;
+    const int CPR = (K + 511) / 512;
+    const size_t xs_bytes = (size_t)CPR * 512 * sizeof(float);
+    int per_cu = blocks_per_cu;
+    while (per_cu > 1 && per_cu * (xs_bytes + 4096) > 160 * 1024) --per_cu;
+    int G = 256 * per_cu;
+    {   // small matrices: fewer blocks, so that a wave still has min_chunks chunks
+        const long long chunks = (long long)N * CPR;
+        const int want = (int)std::max<long long>(1, chunks / ((long long)NW * min_chunks));
+        if (want < G) G = want;
+    }
+    // bound the per-wave row slots to 16 KB
+    while ((size_t)NW * NA * ((N + G - 1) / G) * sizeof(float) > 16 * 1024) G += 256 * per_cu;
+    const int max_v = (N + G - 1) / G;
+    if ((uint64_t)max_v * CPR * CPR >= (1ull << 31)) return false;      // range of the division by multiplication
+    const uint32_t magic = CPR == 1 ? 0u : (uint32_t)(((1ull << 32) + CPR - 1) / CPR);    // ceil(2^32 / CPR)
+    const size_t lds = xs_bytes + (size_t)NW * NA * max_v * sizeof(float);
+    if (lds > kGemvFullLds) return false;
+#define RSD_GEMVFLAT_CASE(P, E)                                                                              \
+    if (pro == P && epi == E) {                                                                              \
+        static bool raised = false;                                                                          \
+        if (!raised && lds > 64 * 1024) {                                                                    \
+            (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemv_flat_kernel<WT, NW, U, P, E>),      \
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)kGemvFullLds);        \
+            raised = true;                                                                                   \
+        }                                                                                                    \
+        hipLaunchKernelGGL((gemv_flat_kernel<WT, NW, U, P, E>), dim3(G), dim3(NW * 64), lds, st, W, N, K, X, \
+                           gain, eps, Y, magic);                                                             \
+        return true;                                                                                         \
+    }
+    RSD_GEMVFLAT_CASE(PRO_NONE, EPI_STORE)
+    RSD_GEMVFLAT_CASE(PRO_NONE, EPI_RESID)
+    RSD_GEMVFLAT_CASE(PRO_NORM, EPI_STORE)
+    RSD_GEMVFLAT_CASE(PRO_NORM, EPI_SWIGLU)
+#undef RSD_GEMVFLAT_CASE
     return false;
 }
 
@@ -335,6 +517,16 @@ static void gemv_launch_mt(hipStream_t st, int pro, int epi, const WT* W, int N,
     const int steps = (K / 8 + 63) / 64;          // KiB per row
     bool done = false;
     if (MT == 1) {
+        // single row: equal chunk runs per wave.  Long rows (activations above 40 KB) take one block of
+        // 16 waves per compute unit, so that the activations are staged once per unit; matrices of
+        // 100 MB and more are cut into more blocks than are resident, which evens out the tail.
+        const size_t w_bytes = (size_t)pairs * N * K * sizeof(WT);
+        if ((size_t)K * sizeof(float) > 40 * 1024)
+            done = gemv_launch_flat<WT, 16, 4>(st, pro, epi, W, N, K, X, gain, eps, Y, 1, 4);
+        else
+            done = gemv_launch_flat<WT, 8, 4>(st, pro, epi, W, N, K, X, gain, eps, Y, w_bytes >= (100u << 20) ? 3 : 2, 4);
+    }
+    if (!done && MT == 1) {
         int R = 8 / pairs;
         while (R > 1 && (N / R) < 2048) R >>= 1;
         int U = std::max(1, 8 / (R * pairs));
@@ -350,7 +542,7 @@ static void gemv_launch_mt(hipStream_t st, int pro, int epi, const WT* W, int N,
                                        : gemv_launch_full<WT, MT, 2, 2>(st, pro, epi, W, N, K, X, ldx, gain, eps, Y, ldy, M);
         else done = U >= 8 ? gemv_launch_full<WT, MT, 1, 8>(st, pro, epi, W, N, K, X, ldx, gain, eps, Y, ldy, M)
                            : gemv_launch_full<WT, MT, 1, 4>(st, pro, epi, W, N, K, X, ldx, gain, eps, Y, ldy, M);
-    } else {
+    } else if (!done) {
         if (pairs == 2) done = gemv_launch_full<WT, MT, 2, 1>(st, pro, epi, W, N, K, X, ldx, gain, eps, Y, ldy, M);
         else done = gemv_launch_full<WT, MT, 4, 1>(st, pro, epi, W, N, K, X, ldx, gain, eps, Y, ldy, M);
     }
