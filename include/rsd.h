@@ -201,6 +201,13 @@ int rsd_sample(rsd_ctx *c, const float *logits_dev, const float *u_dev, int32_t 
  * ms[3] target.  reset != 0 clears them after reading. */
 int rsd_stage_ms(rsd_ctx *c, double ms[4], int32_t reset);
 
+/* Launch statistics of the single-token decode loop (Algorithm 1's token-by-token generation of a
+ * step): iterations launched kernel by kernel, iterations replayed from a recorded graph, and the
+ * number of graphs recorded so far.  With use_graphs = 1 every iteration is a replay except a
+ * model's first one and those the timing probe brackets; replays = 0 there means that recording
+ * failed and the context fell back to kernel-by-kernel launches.  Host counters, no GPU work. */
+int rsd_decode_stats(rsd_ctx *c, int64_t *eager_iters, int64_t *graph_replays, int64_t *graphs_recorded);
+
 /* Kernel timing probe for roofline reports.  While armed, every `stride`-th
  * launch of one weight-streaming projection (op: 0 qkv, 1 attention output,
  * 2 gate+up, 3 down, 4 output head) in `model`'s single-token decode path is

@@ -16,7 +16,7 @@ import numpy as np
 __all__ = ["RSD_OK", "RSD_EINVAL", "RSD_ENOMEM", "RSD_ESTATE", "RSD_EHIP", "RSD_DRAFT", "RSD_TARGET", "RSD_PRM",
            "RsdError", "Context", "load_library", "rsd_init", "rsd_set_prompts", "rsd_set_uniforms",
            "rsd_set_criterion", "rsd_step", "rsd_generate", "rsd_export_state", "rsd_export_pages",
-           "rsd_set_teacher", "rsd_export_sampled", "rsd_forward", "rsd_sample", "rsd_stage_ms", "rsd_destroy",
+           "rsd_set_teacher", "rsd_export_sampled", "rsd_forward", "rsd_sample", "rsd_stage_ms", "rsd_decode_stats", "rsd_destroy",
            "rsd_probe_start", "rsd_probe_read",
            "EXPORTED_SYMBOLS"]
 
@@ -24,7 +24,7 @@ RSD_OK, RSD_EINVAL, RSD_ENOMEM, RSD_ESTATE, RSD_EHIP = 0, -1, -2, -3, -4
 RSD_DRAFT, RSD_TARGET, RSD_PRM = 0, 1, 2
 EXPORTED_SYMBOLS = ["rsd_init", "rsd_set_prompts", "rsd_set_uniforms", "rsd_set_criterion", "rsd_step",
                     "rsd_generate", "rsd_export_state", "rsd_export_pages", "rsd_set_teacher",
-                    "rsd_export_sampled", "rsd_forward", "rsd_sample", "rsd_stage_ms", "rsd_probe_start", "rsd_probe_read",
+                    "rsd_export_sampled", "rsd_forward", "rsd_sample", "rsd_stage_ms", "rsd_decode_stats", "rsd_probe_start", "rsd_probe_read",
                     "rsd_last_error", "rsd_destroy"]
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "librsd.so")
 
@@ -256,6 +256,12 @@ def rsd_stage_ms(ctx: Context, reset: bool = False) -> np.ndarray:
     ms = (C.c_double * 4)()
     ctx.check(load_library().rsd_stage_ms(ctx.handle, ms, C.c_int32(int(reset))))
     return np.array(list(ms))
+
+
+def rsd_decode_stats(ctx: Context) -> dict:
+    a, b, g = C.c_int64(), C.c_int64(), C.c_int64()
+    ctx.check(load_library().rsd_decode_stats(ctx.handle, C.byref(a), C.byref(b), C.byref(g)))
+    return dict(eager_iters=a.value, graph_replays=b.value, graphs_recorded=g.value)
 
 
 def rsd_probe_start(ctx: Context, model: int, op: int, max_samples: int = 4096, stride: int = 1) -> None:

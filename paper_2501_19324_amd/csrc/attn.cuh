@@ -452,21 +452,20 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void attn_decode_mfma_ker
     constexpr int HD = 128;
     const int r = blockIdx.x, hk = blockIdx.y, sp = blockIdx.z;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    // independent loads issued together.  With one split the pages of this wave are wave, wave + NW, ...
-    // whatever the position turns out to be, so their table entries (lane i holds the i-th) can be
-    // requested before the position is known; entries beyond the sequence are never used.
+    // Pages are dealt round-robin: the i-th page of (split sp, wave w) is sp + S * (w + NW * i), whatever
+    // the position turns out to be.  So the table entries (lane i holds the i-th; entries beyond the
+    // sequence are never used) are requested together with the position, not after it.
     const int is_active = active[r];
     const int pos = kv_len[r];
+    const int pg0 = sp + S * wave, pg_step = S * NW;
     int bt_mine = -1;
-    if (S == 1 && wave + lane * NW < max_pages) bt_mine = block_table[(size_t)r * max_pages + wave + lane * NW];
+    if (pg0 + pg_step * lane < max_pages) bt_mine = block_table[(size_t)r * max_pages + pg0 + pg_step * lane];
     if (!is_active) return;
     const int l16 = lane & 15, c = lane >> 4;
     const float* row = qkv + (size_t)r * ldq;
     const float2* cs = rope + (size_t)pos * (HD / 2);
 
     const int n_pages = (pos + RSD_PAGE - 1) / RSD_PAGE;      // pages holding cached positions 0..pos-1
-    const int pps = (n_pages + S - 1) / S;
-    const int p_begin = sp * pps, p_end = min(n_pages, p_begin + pps);
     const int* bt = block_table + (size_t)r * max_pages;
     const size_t page_elts = (size_t)2 * Hkv * RSD_PAGE * HD;
     const size_t head_off = (size_t)hk * RSD_PAGE * HD, v_off = (size_t)Hkv * RSD_PAGE * HD;
@@ -481,14 +480,13 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void attn_decode_mfma_ker
 #pragma unroll
         for (int nb = 0; nb < 8; ++nb) v[nb] = *reinterpret_cast<const uint2*>(kb + v_off + (nb * 16 + l16) * RSD_PAGE + c * 4);
     };
-    if (S > 1 && p_begin + wave + lane * NW < p_end) bt_mine = bt[p_begin + wave + lane * NW];
-    // i-th page of this wave (i < 64: a block never holds more than 64 * NW pages)
+    // i-th page of this wave (i < 64: a wave never holds more than 64 pages)
     auto fetch = [&](int i, uint4 k[4], uint2 v[8]) { fetch_phys(__shfl(bt_mine, i, RSD_WAVE), k, v); };
     uint4 k2[4];
     uint2 v2[8];                 // two pages in flight ahead of the one being used
-    int pg = p_begin + wave, it = 0;
-    if (pg < p_end) fetch(0, kc, vc);
-    if (pg + NW < p_end) fetch(1, kn, vn);
+    int pg = pg0, it = 0;
+    if (pg < n_pages) fetch(0, kc, vc);
+    if (pg + pg_step < n_pages) fetch(1, kn, vn);
 
     // rotated, scaled queries of the group, computed once per block and kept in LDS as hi + lo bf16
     // (rows >= G stay zero); the waves read their MFMA operands from there for every page
@@ -539,27 +537,31 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void attn_decode_mfma_ker
         }
     }
 
-    float m_run = -INFINITY, l_run = 0.0f;                 // of head l16 (replicated over the 4 lanes sharing it)
-    af32x4_t o[8];                                          // o[nb][i] = O[head c*4+i][nb*16 + l16]
+    // Scores come out transposed, S^T[token c*4+i][head l16], which is at once the layout of P^T as the
+    // B operand of O^T = V^T P^T.  So every lane works for ONE head (l16): its running maximum, sum and
+    // rescaling factor are its own, and sums over tokens run over i and over the four 16-lane rows.
+    float m_run = -INFINITY, l_run = 0.0f;
+    af32x4_t o[8];                                          // o[nb][i] = O[head l16][nb*16 + c*4 + i]
 #pragma unroll
     for (int nb = 0; nb < 8; ++nb) o[nb] = af32x4_t{0.f, 0.f, 0.f, 0.f};
 
     // one page: tokens c*4+i of it are valid iff (vmask >> i) & 1
     auto process = [&](const uint4 k[4], const uint2 v[8], int vmask) {
-        af32x4_t s = {0.f, 0.f, 0.f, 0.f};
+        af32x4_t s = {0.f, 0.f, 0.f, 0.f}, s2 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const abf16x8_t ka = __builtin_bit_cast(abf16x8_t, k[j]);
             const abf16x8_t qlo = __builtin_bit_cast(abf16x8_t, *reinterpret_cast<const uint4*>(&s_ql[l16][c * 32 + j * 8]));
             const abf16x8_t qhi = __builtin_bit_cast(abf16x8_t, *reinterpret_cast<const uint4*>(&s_qh[l16][c * 32 + j * 8]));
-            s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, qlo, s, 0, 0, 0);
+            s2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, qlo, s2, 0, 0, 0);
             s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, qhi, s, 0, 0, 0);
         }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) s[i] += s2[i];
         float mloc = -INFINITY;
 #pragma unroll
         for (int i = 0; i < 4; ++i) if ((vmask >> i) & 1) mloc = fmaxf(mloc, s[i]);
-        mloc = fmaxf(mloc, __shfl_xor(mloc, 16, RSD_WAVE));
-        mloc = fmaxf(mloc, __shfl_xor(mloc, 32, RSD_WAVE));
+        mloc = rows4_max(mloc);
         const float m_new = fmaxf(m_run, mloc);
         const float corr = (m_run == -INFINITY) ? 0.0f : __expf(m_run - m_new);
         float p[4], lsum = 0.0f;
@@ -568,30 +570,24 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void attn_decode_mfma_ker
             p[i] = (((vmask >> i) & 1) && m_new > -INFINITY) ? __expf(s[i] - m_new) : 0.0f;
             lsum += p[i];
         }
-        lsum += __shfl_xor(lsum, 16, RSD_WAVE);
-        lsum += __shfl_xor(lsum, 32, RSD_WAVE);
+        lsum = rows4_sum(lsum);
         l_run = l_run * corr + lsum;
         m_run = m_new;
-        // P as A operand (row = head l16, k = token c*4+i): hi and lo halves
         uint16_t ph[4], pl[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) { ph[i] = f2bf(p[i]); pl[i] = f2bf(p[i] - bf2f(ph[i])); }
         const as16x4_t pa = __builtin_bit_cast(as16x4_t, make_uint2((uint32_t)ph[0] | ((uint32_t)ph[1] << 16), (uint32_t)ph[2] | ((uint32_t)ph[3] << 16)));
         const as16x4_t pb = __builtin_bit_cast(as16x4_t, make_uint2((uint32_t)pl[0] | ((uint32_t)pl[1] << 16), (uint32_t)pl[2] | ((uint32_t)pl[3] << 16)));
-        // the accumulator rows of this lane are heads c*4+i: fetch their correction factors
-        float cr[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) cr[i] = __shfl(corr, c * 4 + i, RSD_WAVE);
         // slots past the sequence hold whatever the pool held: zero them (0 * NaN would poison the sum)
         const uint32_t mk0 = ((vmask & 1) ? 0xFFFFu : 0u) | ((vmask & 2) ? 0xFFFF0000u : 0u);
         const uint32_t mk1 = ((vmask & 4) ? 0xFFFFu : 0u) | ((vmask & 8) ? 0xFFFF0000u : 0u);
 #pragma unroll
         for (int nb = 0; nb < 8; ++nb) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) o[nb][i] *= cr[i];
+            for (int i = 0; i < 4; ++i) o[nb][i] *= corr;
             const as16x4_t vb = __builtin_bit_cast(as16x4_t, make_uint2(v[nb].x & mk0, v[nb].y & mk1));
-            o[nb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pb, vb, o[nb], 0, 0, 0);
-            o[nb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pa, vb, o[nb], 0, 0, 0);
+            o[nb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vb, pb, o[nb], 0, 0, 0);
+            o[nb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vb, pa, o[nb], 0, 0, 0);
         }
     };
 
@@ -604,29 +600,29 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void attn_decode_mfma_ker
         for (int i = 0; i < 4; ++i) vm |= (page * RSD_PAGE + c * 4 + i < pos) ? (1 << i) : 0;
         return vm;
     };
-    while (pg < p_end) {
-        if (pg + 2 * NW < p_end) fetch(it + 2, k2, v2);
+    while (pg < n_pages) {
+        if (pg + 2 * pg_step < n_pages) fetch(it + 2, k2, v2);
         process(kc, vc, page_mask(pg));
-        pg += NW; ++it;
-        if (pg >= p_end) break;
-        if (pg + 2 * NW < p_end) fetch(it + 2, kc, vc);
+        pg += pg_step; ++it;
+        if (pg >= n_pages) break;
+        if (pg + 2 * pg_step < n_pages) fetch(it + 2, kc, vc);
         process(kn, vn, page_mask(pg));
-        pg += NW; ++it;
-        if (pg >= p_end) break;
-        if (pg + 2 * NW < p_end) fetch(it + 2, kn, vn);
+        pg += pg_step; ++it;
+        if (pg >= n_pages) break;
+        if (pg + 2 * pg_step < n_pages) fetch(it + 2, kn, vn);
         process(k2, v2, page_mask(pg));
-        pg += NW; ++it;
+        pg += pg_step; ++it;
     }
 
     // ---- merge the waves of the block through LDS
-    __shared__ float s_o[NW][G][HD];
+    __shared__ __attribute__((aligned(16))) float s_o[NW][G][HD];
     __shared__ float s_m[NW][16], s_l[NW][16];
     if (c == 0) { s_m[wave][l16] = m_run; s_l[wave][l16] = l_run; }
+    if (l16 < G) {
 #pragma unroll
-    for (int nb = 0; nb < 8; ++nb)
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-            if (c * 4 + i < G) s_o[wave][c * 4 + i][nb * 16 + l16] = o[nb][i];
+        for (int nb = 0; nb < 8; ++nb)
+            *reinterpret_cast<float4*>(&s_o[wave][l16][nb * 16 + c * 4]) = make_float4(o[nb][0], o[nb][1], o[nb][2], o[nb][3]);
+    }
     __syncthreads();
     for (int idx = tid; idx < G * HD; idx += NW * 64) {
         const int g = idx / HD, e = idx - g * HD;

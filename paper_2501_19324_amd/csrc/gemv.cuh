@@ -5,12 +5,17 @@
 // staged in LDS, optionally transformed on the way in:
 //   PRO_NORM    x = X * rsqrt(mean(X^2) + eps) * gain   (RMSNorm fused in)
 //   PRO_SWIGLU  x = silu(X[k]) * X[K + k]               (SwiGLU fused in)
+//   PRO_ATTN    x = merged attention output of the splits (single row only)
 // and the result is either stored or added to Y (residual stream).
 #pragma once
 #include <algorithm>
 #include "common.cuh"
 
-enum { PRO_NONE = 0, PRO_NORM = 1, PRO_SWIGLU = 2 };
+enum { PRO_NONE = 0, PRO_NORM = 1, PRO_SWIGLU = 2, PRO_ATTN = 3 };
+
+// Partial attention results of one row, one per (head, split): unnormalised sums [H][S][128] and
+// (running maximum, sum of weights) pairs [H][S][2].  PRO_ATTN merges them while staging x.
+struct AttnParts { const float* acc; const float* ml; int S; };
 enum { EPI_STORE = 0, EPI_RESID = 1, EPI_SWIGLU = 2 };
 
 // Block = 256 threads working on R consecutive rows of W.  The K axis is cut
@@ -316,7 +321,8 @@ template <typename WT, int NW, int U, int PRO, int EPI>
 __global__ __launch_bounds__(NW * 64) void gemv_flat_kernel(const WT* __restrict__ W, int N, int K,
                                                             const float* __restrict__ X,
                                                             const WT* __restrict__ gain, float eps,
-                                                            float* __restrict__ Y, uint32_t cpr_magic) {
+                                                            float* __restrict__ Y, uint32_t cpr_magic,
+                                                            AttnParts parts) {
     constexpr int NA = (EPI == EPI_SWIGLU) ? 2 : 1;
     extern __shared__ float smem[];
     const int CPR = (K + 511) >> 9;         // chunks per row
@@ -353,7 +359,24 @@ __global__ __launch_bounds__(NW * 64) void gemv_flat_kernel(const WT* __restrict
     float ss = 0.0f;
     for (int k = tid * 4; k < (CPR << 9); k += NW * 256) {
         float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (k < K) {
+        if (PRO == PRO_ATTN) {
+            if (k < K) {        // head k / 128, elements k % 128 .. + 3
+                const int h = k >> 7, e = k & 127, S = parts.S;
+                const float* ml = parts.ml + (size_t)h * S * 2;
+                const float* pa = parts.acc + (size_t)h * S * 128 + e;
+                float mn = -INFINITY;
+                for (int sp = 0; sp < S; ++sp) mn = fmaxf(mn, ml[sp * 2]);
+                float ll = 0.0f;
+                for (int sp = 0; sp < S; ++sp) {
+                    const float m = ml[sp * 2];
+                    const float cc = (m == -INFINITY) ? 0.0f : __expf(m - mn);
+                    const float4 a = *reinterpret_cast<const float4*>(pa + (size_t)sp * 128);
+                    v.x += a.x * cc; v.y += a.y * cc; v.z += a.z * cc; v.w += a.w * cc;
+                    ll += ml[sp * 2 + 1] * cc;
+                }
+                v.x /= ll; v.y /= ll; v.z /= ll; v.w /= ll;
+            }
+        } else if (k < K) {
             v = *reinterpret_cast<const float4*>(X + k);
             if (PRO == PRO_NORM) {
                 ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
@@ -440,8 +463,10 @@ __global__ __launch_bounds__(NW * 64) void gemv_flat_kernel(const WT* __restrict
 // LDS or the matrix is too small for that: a wave should still get min_chunks chunks).
 template <typename WT, int NW, int U>
 static bool gemv_launch_flat(hipStream_t st, int pro, int epi, const WT* W, int N, int K, const float* X,
-                             const WT* gain, float eps, float* Y, int blocks_per_cu, int min_chunks) {
+                             const WT* gain, float eps, float* Y, int blocks_per_cu, int min_chunks,
+                             AttnParts parts = AttnParts{nullptr, nullptr, 0}) {
     if (pro == PRO_SWIGLU || (K & 7) || K < 8) return false;
+    if (pro == PRO_ATTN && (K & 127)) return false;
     const int NA = epi == EPI_SWIGLU ? 2 : 1;
     const int CPR = (K + 511) / 512;
     const size_t xs_bytes = (size_t)CPR * 512 * sizeof(float);
@@ -469,13 +494,14 @@ static bool gemv_launch_flat(hipStream_t st, int pro, int epi, const WT* W, int 
             raised = true;                                                                                   \
         }                                                                                                    \
         hipLaunchKernelGGL((gemv_flat_kernel<WT, NW, U, P, E>), dim3(G), dim3(NW * 64), lds, st, W, N, K, X, \
-                           gain, eps, Y, magic);                                                             \
+                           gain, eps, Y, magic, parts);                                                      \
         return true;                                                                                         \
     }
     RSD_GEMVFLAT_CASE(PRO_NONE, EPI_STORE)
     RSD_GEMVFLAT_CASE(PRO_NONE, EPI_RESID)
     RSD_GEMVFLAT_CASE(PRO_NORM, EPI_STORE)
     RSD_GEMVFLAT_CASE(PRO_NORM, EPI_SWIGLU)
+    RSD_GEMVFLAT_CASE(PRO_ATTN, EPI_RESID)
 #undef RSD_GEMVFLAT_CASE
     return false;
 }
@@ -547,6 +573,15 @@ static void gemv_launch_mt(hipStream_t st, int pro, int epi, const WT* W, int N,
         else done = gemv_launch_full<WT, MT, 4, 1>(st, pro, epi, W, N, K, X, ldx, gain, eps, Y, ldy, M);
     }
     if (!done) gemv_launch_chunked<WT, MT, 4>(st, pro, epi, W, N, K, X, ldx, gain, eps, Y, ldy, M);
+}
+
+// Output projection of a single row straight from the attention partials: Y += W . merge(parts).
+// Returns false if the shape does not fit (the caller then merges with a kernel of its own).
+template <typename WT>
+static bool gemv_launch_attn(hipStream_t st, const WT* W, int N, int K, AttnParts parts, float* Y) {
+    if ((size_t)K * sizeof(float) > 40 * 1024) return false;
+    return gemv_launch_flat<WT, 8, 4>(st, PRO_ATTN, EPI_RESID, W, N, K, (const float*)nullptr, (const WT*)nullptr, 0.f, Y,
+                                      2, 4, parts);
 }
 
 // M <= 8

@@ -106,6 +106,7 @@ struct SeqState {
     int* own_accept;    // decision the criterion took
     float* reward;
     int* n_active;      // [1] sequences still active after the last bookkeeping pass
+    int* cur_step;      // [1] index of the reasoning step in progress
     int* sampled[2];    // [B][max_steps][step_cap] each: tokens chosen by the draft / target samplers
 };
 

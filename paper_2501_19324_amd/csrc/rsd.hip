@@ -73,6 +73,7 @@ struct rsd_ctx {
     float* reward() { return reinterpret_cast<float*>(sb + 10 * B); }
     int* in_step() { return sb + 11 * B; }
     int* n_active() { return sb + 12 * B; }
+    int* cur_step() { return sb + 12 * B + 1; }
     std::vector<int> prompt_len;
     int steps_done = 0;
     bool have_prompts = false;
@@ -100,6 +101,15 @@ struct rsd_ctx {
     double stage_ms[4] = {0, 0, 0, 0};
     // kernel timing probe
     int probe_model = -1, probe_op = -1, probe_stride = 1, probe_seen = 0;
+    bool in_decode_loop = false, probe_iter_on = false;     // inside the decode loop whole iterations are probed
+    int probe_iters = 0;
+    // single-token decode iterations recorded as graphs, one per (model, uniforms, teacher tokens)
+    struct DecodeGraph { int which; const float* u; const int* forced; hipGraph_t graph; hipGraphExec_t exec; };
+    std::vector<DecodeGraph> graphs;
+    hipStream_t cap_st = nullptr;          // recording stream (the caller's may be the null stream)
+    bool graphs_ok = true;                 // cleared when recording fails: eager launches from then on
+    bool decode_warm[3] = {false, false, false};
+    long long n_eager_iters = 0, n_graph_replays = 0;
     size_t probe_used = 0;
     long long probe_bytes = 0;
     std::vector<hipEvent_t> probe_ev;
@@ -215,11 +225,13 @@ int setup_kv(rsd_ctx* c, Model& m, int which) {
     m.splits = std::max(1, s);
     if (m.s.dtype == RSD_BF16) {
         // MFMA kernel, 8 waves per block.  One split (nothing to merge) whenever the batch alone gives
-        // enough blocks or the context is short; otherwise enough splits for about 128 blocks, none
-        // below 16 pages.
+        // enough blocks, or the context is short and merging would cost a launch (a single sequence
+        // merges inside its output projection); otherwise enough splits for about 128 blocks, none
+        // below 16 pages.  A wave keeps at most 64 page-table entries.
         const int pairs = B * m.s.n_kv_heads;
-        if (pairs >= 64 || m.max_pages <= 128) m.splits = 1;
+        if (pairs >= 64 || (B > 1 && m.max_pages <= 128)) m.splits = 1;
         else m.splits = std::max(1, std::min(64, std::min(ceil_div(128, pairs), ceil_div(m.max_pages, 16))));
+        while (ceil_div(m.max_pages, m.splits * 8) > 64) ++m.splits;
     }
     return RSD_OK;
 }
@@ -250,6 +262,7 @@ int upload_tables(rsd_ctx* c, Model& m) {
 }
 
 int push_state(rsd_ctx* c) {
+    *c->cur_step() = c->steps_done;
     HIPCHK(c, hipMemcpyAsync(c->sb_dev, c->sb, c->sb_ints * sizeof(int), hipMemcpyHostToDevice, c->st));
     return RSD_OK;
 }
@@ -287,7 +300,8 @@ struct ProbeScope {
     ProbeScope(rsd_ctx* c_, const Model& m, int op, long long bytes) : c(c_) {
         if (c->probe_op != op || &m != &c->m[c->probe_model < 0 ? 0 : c->probe_model] || c->probe_model < 0) return;
         if (c->probe_used + 2 > c->probe_ev.size()) return;
-        if (c->probe_seen++ % c->probe_stride) return;
+        if (c->in_decode_loop) { if (!c->probe_iter_on) return; }
+        else if (c->probe_seen++ % c->probe_stride) return;
         on = true;
         c->probe_bytes = bytes;
         (void)hipEventRecord(c->probe_ev[c->probe_used], c->st);
@@ -325,7 +339,8 @@ void launch_attn_decode(rsd_ctx* c, const Model& m, int l, int M, int which) {
 }
 
 // bf16 caches with head_dim 128: the MFMA kernel, 8 waves per block
-void launch_attn_decode_mfma(rsd_ctx* c, const Model& m, int l, int M, int which) {
+// merge_here = false leaves the partial results of the splits to the caller (S > 1 only)
+void launch_attn_decode_mfma(rsd_ctx* c, const Model& m, int l, int M, int which, bool merge_here = true) {
     bf16_t* pool_l = reinterpret_cast<bf16_t*>(m.pool) + (size_t)l * m.pool_pages * m.page_elts;
     const float scale = 1.0f / std::sqrt(128.0f);
     const int S = m.splits;
@@ -340,7 +355,7 @@ void launch_attn_decode_mfma(rsd_ctx* c, const Model& m, int l, int M, int which
         RSD_ATTN_CASE(1) RSD_ATTN_CASE(2) RSD_ATTN_CASE(4) RSD_ATTN_CASE(6) RSD_ATTN_CASE(7) RSD_ATTN_CASE(8)
     }
 #undef RSD_ATTN_CASE
-    if (S > 1)
+    if (S > 1 && merge_here)
         hipLaunchKernelGGL((attn_combine_kernel<128>), dim3(M, m.s.n_heads), dim3(128), 0, c->st, c->part_acc,
                            c->part_ml, decode_map(c, which), m.s.n_heads, S, c->att, m.q_dim);
 }
@@ -378,6 +393,9 @@ void run_layers(rsd_ctx* c, Model& m, int M, const RowMap& rm, bool decode) {
                        c->p.max_ctx, rm, c->h);
     const int S = decode ? m.splits : 1;
     const bool fused = M <= 8;   // few rows: norm / SwiGLU / residual folded into the weight-streaming kernels
+    // single-row decode over a bf16 cache: the output projection merges the attention splits itself
+    const bool parts_to_o = decode && M == 1 && S > 1 && m.s.dtype == RSD_BF16 && m.hd == 128 &&
+                            (size_t)m.q_dim * sizeof(float) <= 40 * 1024;
     for (int l = 0; l < m.s.n_layers; ++l) {
         const LayerOff& o = m.layers[l];
         const long long esz = sizeof(WT);
@@ -392,7 +410,7 @@ void run_layers(rsd_ctx* c, Model& m, int M, const RowMap& rm, bool decode) {
         WT* pool_l = reinterpret_cast<WT*>(m.pool) + (size_t)l * m.pool_pages * m.page_elts;
         if (decode) {
             const int which = (int)(&m - &c->m[0]);
-            if (m.s.dtype == RSD_BF16) launch_attn_decode_mfma(c, m, l, M, which);
+            if (m.s.dtype == RSD_BF16) launch_attn_decode_mfma(c, m, l, M, which, !parts_to_o);
             else if (m.hd == 128) launch_attn_decode<WT, 128>(c, m, l, M, which);
             else launch_attn_decode<WT, 32>(c, m, l, M, which);
         } else if (m.hd == 128) {
@@ -408,8 +426,11 @@ void run_layers(rsd_ctx* c, Model& m, int M, const RowMap& rm, bool decode) {
         if (fused) {
             {
                 ProbeScope ps(c, m, 1, (long long)d * m.q_dim * esz + 4LL * M * (m.q_dim + 2 * d));
-                gemv_launch<WT>(st, PRO_NONE, EPI_RESID, wptr<WT>(m, o.wo), d, m.q_dim, c->att, m.q_dim,
-                                (const WT*)nullptr, 0.f, c->h, d, M);
+                if (parts_to_o)
+                    gemv_launch_attn<WT>(st, wptr<WT>(m, o.wo), d, m.q_dim, AttnParts{c->part_acc, c->part_ml, S}, c->h);
+                else
+                    gemv_launch<WT>(st, PRO_NONE, EPI_RESID, wptr<WT>(m, o.wo), d, m.q_dim, c->att, m.q_dim,
+                                    (const WT*)nullptr, 0.f, c->h, d, M);
             }
             if (gemv_can_fuse_swiglu(M, d) && gemv_can_fuse_swiglu(M, F)) {
                 {
@@ -486,7 +507,7 @@ void sample_rows(rsd_ctx* c, const float* logits, int ld, int V, const float* u,
 AppendArgs append_args(rsd_ctx* c, int which, const int* forced) {
     AppendArgs ap{};
     ap.enabled = 1; ap.st = c->ds; ap.B = c->B; ap.max_ctx = c->p.max_ctx; ap.model = which; ap.forced = forced;
-    ap.sep_id = c->p.sep_id; ap.eos_id = c->p.eos_id; ap.step_cap = c->p.step_cap; ap.step = c->steps_done;
+    ap.sep_id = c->p.sep_id; ap.eos_id = c->p.eos_id; ap.step_cap = c->p.step_cap;
     ap.max_steps = c->p.max_steps;
     return ap;
 }
@@ -499,6 +520,32 @@ void decode_iter(rsd_ctx* c, int which, const float* u, const int* forced) {
     lm_head<WT>(c, m, c->h, c->B, c->logits, m.s.vocab);
     sample_rows(c, c->logits, m.s.vocab, m.s.vocab, u, c->ds.ctx_len, c->p.max_ctx, c->p.temperature, c->p.top_p,
                 c->p.sep_id, c->p.sep_logit_bias, c->ds.active, c->B, nullptr, append_args(c, which, forced));
+}
+
+// The graph of one decode iteration of model `which`, recorded on first use.  Everything an
+// iteration reads that changes between replays (positions, activity flags, step index, block
+// tables, tokens) lives in device memory, so one recording serves every later iteration with the
+// same model, uniforms and teacher arrays.  nullptr: recording is not possible (eager from then on).
+template <typename WT>
+hipGraphExec_t decode_graph(rsd_ctx* c, int which, const float* u, const int* forced) {
+    for (const auto& g : c->graphs)
+        if (g.which == which && g.u == u && g.forced == forced) return g.exec;
+    auto give_up = [&]() { (void)hipGetLastError(); c->graphs_ok = false; return (hipGraphExec_t) nullptr; };
+    if (!c->cap_st && hipStreamCreateWithFlags(&c->cap_st, hipStreamNonBlocking) != hipSuccess) return give_up();
+    if (hipStreamBeginCapture(c->cap_st, hipStreamCaptureModeThreadLocal) != hipSuccess) return give_up();
+    hipStream_t user = c->st;
+    c->st = c->cap_st;
+    decode_iter<WT>(c, which, u, forced);
+    c->st = user;
+    hipGraph_t graph = nullptr;
+    if (hipStreamEndCapture(c->cap_st, &graph) != hipSuccess || !graph) return give_up();
+    hipGraphExec_t exec = nullptr;
+    if (hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0) != hipSuccess || !exec) {
+        (void)hipGraphDestroy(graph);
+        return give_up();
+    }
+    c->graphs.push_back(rsd_ctx::DecodeGraph{which, u, forced, graph, exec});
+    return exec;
 }
 
 // Chunked prefill of `pieces` (per sequence consecutive, ascending) through model `which`.
@@ -578,8 +625,24 @@ int gen_stage(rsd_ctx* c, int which, const float* u, const int* forced) {
                     c->p.sep_id, c->p.sep_logit_bias, c->ds.active, B, nullptr, append_args(c, which, forced));
         iters = 1;
     }
+    c->in_decode_loop = true;
     while (iters < c->p.step_cap) {
-        decode_iter<WT>(c, which, u, forced);
+        // an iteration whose launches are timed runs eagerly (events cannot bracket a node of a graph),
+        // and so does the first one of a model (it raises the kernels' LDS limits)
+        c->probe_iter_on = c->probe_model == which && c->probe_used + 2 <= c->probe_ev.size() &&
+                           (c->probe_iters++ % c->probe_stride) == 0;
+        hipGraphExec_t exec = nullptr;
+        if (c->p.use_graphs && c->graphs_ok && !c->probe_iter_on && c->decode_warm[which])
+            exec = decode_graph<WT>(c, which, u, forced);
+        if (exec) {
+            const hipError_t e = hipGraphLaunch(exec, c->st);
+            if (e != hipSuccess) { c->in_decode_loop = false; return fail(c, RSD_EHIP, "hipGraphLaunch: %s", hipGetErrorString(e)); }
+            ++c->n_graph_replays;
+        } else {
+            decode_iter<WT>(c, which, u, forced);
+            ++c->n_eager_iters;
+            c->decode_warm[which] = true;
+        }
         ++iters;
         if (iters % kPoll == 0 || iters == c->p.step_cap) {
             HIPCHK(c, hipMemcpyAsync(c->poll_h, c->ds.n_active, sizeof(int), hipMemcpyDeviceToHost, c->st));
@@ -587,6 +650,8 @@ int gen_stage(rsd_ctx* c, int which, const float* u, const int* forced) {
             if (*c->poll_h <= 0) break;
         }
     }
+    c->in_decode_loop = false;
+    c->probe_iter_on = false;
     HIPCHK(c, hipGetLastError());
     return RSD_OK;
 }
@@ -641,6 +706,8 @@ void rsd_destroy(rsd_ctx* c) {
                    c->row_seq_dev, c->row_pos_dev, c->last_row_dev, c->item_row0_dev, c->item_n_dev};
     for (void* p : dev) if (p) (void)hipFree(p);
     for (hipEvent_t e : c->probe_ev) (void)hipEventDestroy(e);
+    for (auto& g : c->graphs) { (void)hipGraphExecDestroy(g.exec); (void)hipGraphDestroy(g.graph); }
+    if (c->cap_st) (void)hipStreamDestroy(c->cap_st);
     void* pin[] = {c->sb, c->item_row0_h, c->item_n_h, c->row_seq_h, c->row_pos_h, c->last_row_h, c->steptok_h, c->poll_h};
     for (void* p : pin) if (p) (void)hipHostFree(p);
     delete c;
@@ -693,6 +760,7 @@ int rsd_init(rsd_ctx** out, const rsd_model_shape shape[3], const rsd_weights w[
     c->ds.reward = reinterpret_cast<float*>(c->sb_dev + 10 * B);
     c->in_step_dev = c->sb_dev + 11 * B;
     c->ds.n_active = c->sb_dev + 12 * B;
+    c->ds.cur_step = c->sb_dev + 12 * B + 1;
     // workspaces sized for the widest model
     int d = 0, nq = 0, qd = 0, F = 0, V = 0, HS = 0;
     for (auto& m : c->m) {
@@ -1025,6 +1093,14 @@ int rsd_export_sampled(rsd_ctx* c, int32_t* sampled_draft, int32_t* sampled_targ
 int rsd_stage_ms(rsd_ctx* c, double ms[4], int32_t reset) {
     if (!c || !ms) return RSD_EINVAL;
     for (int i = 0; i < 4; ++i) { ms[i] = c->stage_ms[i]; if (reset) c->stage_ms[i] = 0; }
+    return RSD_OK;
+}
+
+int rsd_decode_stats(rsd_ctx* c, int64_t* eager_iters, int64_t* graph_replays, int64_t* graphs_recorded) {
+    if (!c) return RSD_EINVAL;
+    if (eager_iters) *eager_iters = c->n_eager_iters;
+    if (graph_replays) *graph_replays = c->n_graph_replays;
+    if (graphs_recorded) *graphs_recorded = (int64_t)c->graphs.size();
     return RSD_OK;
 }
 

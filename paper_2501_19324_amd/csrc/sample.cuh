@@ -79,7 +79,7 @@ struct SampleArgs {
 struct AppendArgs {
     int enabled;
     SeqState st; int B, max_ctx, model;
-    const int* forced; int sep_id, eos_id, step_cap, step, max_steps;
+    const int* forced; int sep_id, eos_id, step_cap, max_steps;
 };
 
 __device__ __forceinline__ float smp_x(const SampleArgs& a, const float* lg, int i) {
@@ -327,7 +327,7 @@ __global__ __launch_bounds__(SMP_T) void sample_finish_kernel(SampleArgs a, Appe
     const SeqState& st = ap.st;
     const int b = row;
     const int pos = st.ctx_len[b];
-    const size_t rec = ((size_t)b * ap.max_steps + ap.step) * ap.step_cap + st.step_len[b];
+    const size_t rec = ((size_t)b * ap.max_steps + st.cur_step[0]) * ap.step_cap + st.step_len[b];
     st.sampled[ap.model][rec] = token;
     int tok = token;
     if (ap.forced) { const int f = ap.forced[rec]; if (f >= 0) tok = f; }
