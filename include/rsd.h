@@ -52,9 +52,10 @@ enum { RSD_RUNNING = 0, RSD_FIN_EOS = 1, RSD_FIN_MAX_CTX = 2, RSD_FIN_MAX_STEPS 
 
 /* Decoder-only transformer: RMSNorm, rotary embedding (rotate-half pairing,
  * angle pos * theta^(-2i/hd)), grouped-query attention with head_dim =
- * d_model / n_heads (32 or 128), SwiGLU MLP, untied head.  Constraints:
- * d_model, d_ffn and head_dim multiples of 8; n_heads % n_kv_heads == 0 with a
- * group of at most 8 query heads per KV head. */
+ * d_model / n_heads (32 or 128; bf16 models: 128), SwiGLU MLP, untied head.
+ * Constraints (rsd_init returns RSD_EINVAL otherwise): d_model and d_ffn
+ * multiples of 64 and at least 64; n_heads % n_kv_heads == 0 with a group of
+ * 1, 2, 4, 6, 7 or 8 query heads per KV head; vocab >= 2. */
 typedef struct rsd_model_shape {
     int32_t n_layers, d_model, n_heads, n_kv_heads, d_ffn, vocab;
     float   rope_theta, rms_eps;
