@@ -52,6 +52,27 @@ def cpu_baseline(w, budget_s=20.0):
                       f"roughly {w.draft.n_layers // layers}x lower"}
 
 
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "cfg1_target_gate_up_hbm_traffic.txt")
+KERNEL_SOURCES = ("paper_2501_19324_amd/csrc/gemv.cuh", "paper_2501_19324_amd/csrc/common.cuh")
+
+
+def measured_traffic():
+    """HBM bytes per launch of the probed kernel from the hardware counters recorded in
+    profiles/ (FETCH_SIZE and WRITE_SIZE, scaled by a plain copy kernel), or None when no
+    record exists or the kernel's sources have changed since it was taken."""
+    import hashlib
+    try:
+        rec = dict(line.strip().split("=", 1) for line in open(TRAFFIC_FILE) if "=" in line and " " not in line.strip())
+        h = hashlib.sha256()
+        for p in KERNEL_SOURCES:
+            h.update(open(os.path.join(ROOT, p), "rb").read())
+        if rec.get("kernel_source_sha256") != h.hexdigest():
+            return None
+        return int(rec["traffic_bytes_per_launch"])
+    except (OSError, KeyError, ValueError):
+        return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -67,6 +88,9 @@ def main():
     ap.add_argument("--max-steps", type=int, default=0, help="stop each pass after this many reasoning steps (debugging)")
     ap.add_argument("--kv-pool-gb", default="", help="KV pool sizes in GB for draft,target,PRM (default: worst case)")
     ap.add_argument("--ops", action="store_true", help="extra passes after the timed region: per-projection table")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="before the timed region run a plain 256 MiB device copy kernel three times (reference "
+                         "point for scaling hardware traffic counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (sequences are independent; more GPUs would shard the "
@@ -104,6 +128,13 @@ def main():
             return dict(n_committed=int((st["ctx_len"] - s.prompt_len).sum()), n_draft=0, n_target=0, n_accept=0,
                         n_reject=0)
 
+    if args.calib_copy:
+        src = torch.ones(64 << 20, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.add(src, 0.0, out=dst)       # one elementwise kernel: reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         one_pass()
     R.rsd_stage_ms(s.ctx, reset=True)
@@ -121,12 +152,14 @@ def main():
     stage = R.rsd_stage_ms(s.ctx)
 
     roof = None
+    traffic = measured_traffic() if (args.workload == "cfg1" and args.probe == "gate_up" and args.probe_model == 1
+                                     and not args.layers) else None
     if probe["n"] > 0:
         avg_s = probe["total_ms"] / probe["n"] * 1e-3
         gbs = probe["bytes_per_launch"] / avg_s / 1e9
         roof = {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None,
-                "kernel": f"gemv_kernel ({args.probe} projection of model {args.probe_model}, single-token decode)",
+                "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": traffic,
+                "kernel": f"gemv_flat_kernel ({args.probe} projection of model {args.probe_model}, single-token decode)",
                 "bytes_per_launch": probe["bytes_per_launch"], "avg_launch_us": round(avg_s * 1e6, 2),
                 "launches_timed": probe["n"]}
     # decode-stage view of the same roofline: bytes every sampled token has to read
