@@ -7,6 +7,8 @@
 //     multiplied with both (W.hi + W.lo, fp32 accumulation): the activations keep
 //     16 mantissa bits, which the bit-for-bit agreement of the bf16 KV-cache
 //     entries with an exact evaluation needs; one bf16 pass would leave 8.
+//   * 9..64 rows: weight-streaming kernel on activations split beforehand into hi and lo bf16
+//     matrices (gemm_rows_kernel with split_rows_kernel / rows_finish_kernel around it).
 // Requirements checked by the caller: K % 32 == 0; N, M arbitrary.
 #pragma once
 #include "common.cuh"
@@ -183,31 +185,53 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
         }
 }
 
-// ---------------------------------------------------------------- bf16 MFMA, few rows
-// 9..64 activation rows (batched single-token decoding, short chunks): the time
-// is the one pass over W.  Each wave owns 32 rows of W and streams them from HBM
-// straight into MFMA operand registers (64 contiguous bytes per lane and 64-wide
-// K block, two blocks ahead of the arithmetic); only the activations go through
-// LDS (hi + lo bf16, double buffered), shared by the 4 waves of a block.
-// Within a K block of 64 the lane of k-group g (lane / 32) holds elements
-// g*32 + j*8 .. +8 for MFMA step j, for both operands: the same permutation of k
-// on both sides leaves the products unchanged.
-template <int MT, int EPI>     // MT: 32-row tiles of activations (1 or 2)
-__global__ __launch_bounds__(256) void gemm_skinny_kernel(const bf16_t* __restrict__ W, int N, int K,
-                                                          const float* __restrict__ X, int ldx,
-                                                          float* __restrict__ Y, int ldy, int M,
-                                                          float* __restrict__ part) {
-    constexpr int BK = 64, STR = BK + 8;                 // LDS row stride in bf16 (144 bytes)
+// ---------------------------------------------------------------- bf16 MFMA, 9..64 rows, pre-split activations
+// The activations arrive as two bf16 matrices Xh + Xl = x (hi and lo halves, [MT*32][K]; rows beyond M
+// may hold anything: a row of x only ever meets its own row of the result).  A block of eight waves owns
+// 256 rows of W and one K slice.  Every wave reads its 32 rows of W in whole 128-byte lines (8 lanes per
+// row), two K blocks of 64 ahead in registers, and passes them through a private LDS tile into the MFMA
+// operand layout (a lane of an MFMA operand holds 16 bytes of ONE row, so loading operands directly would
+// touch every line with four separate instructions).  The activation tile of a K block (hi and lo) is
+// copied as it is into LDS, double buffered, and shared by the eight waves.  LDS tiles are [row][64 k]
+// with the eight 16-byte chunks of a row permuted by (row / 2) % 8, which makes both the line-wise
+// writes and the operand reads conflict-free without padding.  No load in the loop is conditional
+// (addresses past the end are clamped and never used), so the loads stay in flight across iterations.
+// Partial results go to part[z][m][n]; a finish kernel adds the slices and applies the epilogue.
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));    // native vector: stays in registers across LDS stores
+
+template <int MT>
+__global__ __launch_bounds__(512, 2) void gemm_rows_kernel(const bf16_t* __restrict__ W, int N, int K,
+                                                           const uint16_t* __restrict__ Xh,
+                                                           const uint16_t* __restrict__ Xl,
+                                                           float* __restrict__ part) {
+    constexpr int BK = 64, NWV = 8;
     constexpr int ROWS = 32 * MT;
-    __shared__ __attribute__((aligned(16))) uint16_t Ah[2][ROWS * STR];
-    __shared__ __attribute__((aligned(16))) uint16_t Al[2][ROWS * STR];
+    __shared__ __attribute__((aligned(16))) uint16_t Ah[2][ROWS * BK];
+    __shared__ __attribute__((aligned(16))) uint16_t Al[2][ROWS * BK];
+    __shared__ __attribute__((aligned(16))) uint16_t Ws[NWV][32 * BK];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int nw = blockIdx.x * 128 + wave * 32;         // first W row of this wave
-    const int n_lane = min(nw + (lane & 31), N - 1), kg = lane >> 5;
+    const int nw = blockIdx.x * (32 * NWV) + wave * 32;  // first W row of this wave
+    const int kg = lane >> 5, l32 = lane & 31;
     const int nkb = K / BK;
-    const int per = (nkb + gridDim.z - 1) / gridDim.z;
-    const int kb0 = blockIdx.z * per, kb1 = min(nkb, kb0 + per);
-    const bf16_t* wp = W + (size_t)n_lane * K + kg * 32;
+    const int per = (nkb + gridDim.y - 1) / gridDim.y;
+    const int kb0 = blockIdx.y * per, kb1 = min(nkb, kb0 + per);
+    const int nk = kb1 - kb0;                            // K blocks of this slice (may be <= 0)
+    const int kb_last = max(kb1 - 1, 0);
+    // loads: lane -> row lane / 8 (+ 8 p), 16-byte chunk lane % 8 of the row's 128 bytes
+    const int lrow = lane >> 3, lchunk = lane & 7;
+    const bf16_t* wr0 = W + (size_t)min(nw + lrow, N - 1) * K + lchunk * 8;
+    const bf16_t* wr1 = W + (size_t)min(nw + lrow + 8, N - 1) * K + lchunk * 8;
+    const bf16_t* wr2 = W + (size_t)min(nw + lrow + 16, N - 1) * K + lchunk * 8;
+    const bf16_t* wr3 = W + (size_t)min(nw + lrow + 24, N - 1) * K + lchunk * 8;
+    uint16_t* ws = Ws[wave];
+    // LDS offset (in bf16) of chunk c of row r
+    auto sw = [](int r, int c) { return r * BK + ((c ^ ((r >> 1) & 7)) << 3); };
+    const int ws_st0 = sw(lrow, lchunk), ws_st1 = sw(lrow + 8, lchunk), ws_st2 = sw(lrow + 16, lchunk), ws_st3 = sw(lrow + 24, lchunk);
+    // activation tile: MT = 2: thread -> (row tid / 8, chunk tid % 8) of both halves; MT = 1: threads 0..255 the hi half, the rest lo
+    const int xrow = (MT == 2) ? (tid >> 3) : ((tid & 255) >> 3);
+    const uint16_t* xp0 = ((MT == 2 || tid < 256) ? Xh : Xl) + (size_t)xrow * K + lchunk * 8;
+    const uint16_t* xp1 = Xl + (size_t)xrow * K + lchunk * 8;      // MT = 2 only
+    const int x_st = sw(xrow, lchunk);
 
     f32x16_t acc[MT];
 #pragma unroll
@@ -215,75 +239,192 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const bf16_t* __restri
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[t][v] = 0.0f;
 
-    uint4 w0[4], w1[4], w2[4];
-    auto fetch_w = [&](int kb, uint4 w[4]) {
-#pragma unroll
-        for (int j = 0; j < 4; ++j) w[j] = *reinterpret_cast<const uint4*>(wp + (size_t)kb * BK + j * 8);
-    };
-    constexpr int XF4 = ROWS * BK / 4 / 256;             // float4 of X per thread and K block (2 or 4)
-    float4 xv[XF4];
-    auto fetch_x = [&](int kb) {
-#pragma unroll
-        for (int i = 0; i < XF4; ++i) {
-            const int idx = tid + i * 256, row = idx >> 4, c4 = idx & 15;
-            xv[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (row < M) xv[i] = *reinterpret_cast<const float4*>(X + (size_t)row * ldx + (size_t)kb * BK + c4 * 4);
-        }
-    };
-    auto stage_x = [&](int buf) {
-#pragma unroll
-        for (int i = 0; i < XF4; ++i) {
-            const int idx = tid + i * 256, row = idx >> 4, c4 = idx & 15;
-            const float x[4] = {xv[i].x, xv[i].y, xv[i].z, xv[i].w};
-            uint16_t hi[4], lo[4];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) { hi[e] = f2bf(x[e]); lo[e] = f2bf(x[e] - bf2f(hi[e])); }
-            *reinterpret_cast<uint2*>(&Ah[buf][row * STR + c4 * 4]) =
-                make_uint2((uint32_t)hi[0] | ((uint32_t)hi[1] << 16), (uint32_t)hi[2] | ((uint32_t)hi[3] << 16));
-            *reinterpret_cast<uint2*>(&Al[buf][row * STR + c4 * 4]) =
-                make_uint2((uint32_t)lo[0] | ((uint32_t)lo[1] << 16), (uint32_t)lo[2] | ((uint32_t)lo[3] << 16));
-        }
-    };
-    if (kb0 < kb1) { fetch_w(kb0, w0); fetch_x(kb0); }
-    if (kb0 + 1 < kb1) fetch_w(kb0 + 1, w1);
-    if (kb0 < kb1) stage_x(0);
-    __syncthreads();
-    for (int kb = kb0; kb < kb1; ++kb) {
-        const int buf = (kb - kb0) & 1;
-        if (kb + 2 < kb1) fetch_w(kb + 2, w2);
-        if (kb + 1 < kb1) fetch_x(kb + 1);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const bf16x8_t b = __builtin_bit_cast(bf16x8_t, w0[j]);
-#pragma unroll
-            for (int t = 0; t < MT; ++t) {
-                const int off = (t * 32 + (lane & 31)) * STR + kg * 32 + j * 8;
-                const bf16x8_t ah = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(&Ah[buf][off]));
-                const bf16x8_t al = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(&Al[buf][off]));
-                acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, b, acc[t], 0, 0, 0);
-                acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, b, acc[t], 0, 0, 0);
-            }
-        }
-        if (kb + 1 < kb1) stage_x(buf ^ 1);               // the other buffer was last read one iteration ago
-        __syncthreads();
-#pragma unroll
-        for (int j = 0; j < 4; ++j) { w0[j] = w1[j]; w1[j] = w2[j]; }
+    // register sets named member by member (arrays indexed in loops end up in scratch memory)
+    struct WRegs { u32x4_t w0, w1, w2, w3; };
+    WRegs wa, wb;
+    u32x4_t x0, x1;
+#define RSD_FETCH_W(kb, R)                                                                       \
+    {                                                                                            \
+        const size_t k0_ = (size_t)min((kb), kb_last) * BK;                                      \
+        R.w0 = *reinterpret_cast<const u32x4_t*>(wr0 + k0_);                                     \
+        R.w1 = *reinterpret_cast<const u32x4_t*>(wr1 + k0_);                                     \
+        R.w2 = *reinterpret_cast<const u32x4_t*>(wr2 + k0_);                                     \
+        R.w3 = *reinterpret_cast<const u32x4_t*>(wr3 + k0_);                                     \
     }
-    const bool sliced = gridDim.z > 1;
-    const int n = nw + (lane & 31);
+#define RSD_FETCH_X(kb)                                                                          \
+    {                                                                                            \
+        const size_t k0_ = (size_t)min((kb), kb_last) * BK;                                      \
+        x0 = *reinterpret_cast<const u32x4_t*>(xp0 + k0_);                                       \
+        if (MT == 2) x1 = *reinterpret_cast<const u32x4_t*>(xp1 + k0_);                          \
+    }
+#define RSD_STAGE_W(R)                                                                           \
+    {                                                                                            \
+        *reinterpret_cast<u32x4_t*>(ws + ws_st0) = R.w0;                                         \
+        *reinterpret_cast<u32x4_t*>(ws + ws_st1) = R.w1;                                         \
+        *reinterpret_cast<u32x4_t*>(ws + ws_st2) = R.w2;                                         \
+        *reinterpret_cast<u32x4_t*>(ws + ws_st3) = R.w3;                                         \
+    }
+#define RSD_STAGE_X(buf)                                                                         \
+    {                                                                                            \
+        if (MT == 2) {                                                                           \
+            *reinterpret_cast<u32x4_t*>(&Ah[(buf)][x_st]) = x0;                                  \
+            *reinterpret_cast<u32x4_t*>(&Al[(buf)][x_st]) = x1;                                  \
+        } else {                                                                                 \
+            *reinterpret_cast<u32x4_t*>((tid < 256 ? &Ah[(buf)][0] : &Al[(buf)][0]) + x_st) = x0; \
+        }                                                                                        \
+    }
+    // one K block: W tile of this wave in ws, activation tile in LDS buffer `buf`
+#define RSD_COMPUTE(buf)                                                                         \
+    {                                                                                            \
+        _Pragma("unroll") for (int j_ = 0; j_ < 4; ++j_) {                                       \
+            const bf16x8_t b_ = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t*>(ws + sw(l32, kg * 4 + j_))); \
+            _Pragma("unroll") for (int t_ = 0; t_ < MT; ++t_) {                                  \
+                const int off_ = sw(t_ * 32 + l32, kg * 4 + j_);                                 \
+                const bf16x8_t ah_ = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t*>(&Ah[(buf)][off_])); \
+                const bf16x8_t al_ = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t*>(&Al[(buf)][off_])); \
+                acc[t_] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al_, b_, acc[t_], 0, 0, 0);    \
+                acc[t_] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah_, b_, acc[t_], 0, 0, 0);    \
+            }                                                                                    \
+        }                                                                                        \
+    }
+    // step i: the activation tile of block i + 1 moves into the LDS buffer that block i - 1 has left and
+    // its registers at once take the request of block i + 2; block i is multiplied while W of block i + 2
+    // is requested into the free set F; then W of block i + 1 (set S) replaces the wave's W tile
+#define RSD_STEP(i_step, F, S)                                                                   \
+    {                                                                                            \
+        RSD_STAGE_X(((i_step) + 1) & 1)                                                          \
+        RSD_FETCH_X(kb0 + (i_step) + 2)                                                          \
+        RSD_FETCH_W(kb0 + (i_step) + 2, F)                                                       \
+        RSD_COMPUTE((i_step) & 1)                                                                \
+        RSD_STAGE_W(S)                                                                           \
+        __syncthreads();                                                                         \
+    }
+    RSD_FETCH_W(kb0, wa)
+    RSD_FETCH_X(kb0)
+    RSD_FETCH_W(kb0 + 1, wb)
+    RSD_STAGE_W(wa)
+    RSD_STAGE_X(0)
+    RSD_FETCH_X(kb0 + 1)
+    __syncthreads();
+    int i = 0;
+    for (; i + 1 < nk; i += 2) {
+        RSD_STEP(i, wa, wb)
+        RSD_STEP(i + 1, wb, wa)
+    }
+    if (i < nk) RSD_STEP(i, wa, wb)
+#undef RSD_STEP
+#undef RSD_COMPUTE
+#undef RSD_STAGE_W
+#undef RSD_STAGE_X
+#undef RSD_FETCH_W
+#undef RSD_FETCH_X
+
+    const int n = nw + l32;
+    if (n < N) {
 #pragma unroll
-    for (int t = 0; t < MT; ++t)
+        for (int t = 0; t < MT; ++t)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int m = t * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-            if (m < M && n < N) {
-                if (sliced) part[((size_t)blockIdx.z * M + m) * N + n] = acc[t][v];
-                else {
-                    float* yp = Y + (size_t)m * ldy + n;
-                    *yp = (EPI == EPI_RESID) ? (*yp + acc[t][v]) : acc[t][v];
-                }
+            for (int v = 0; v < 16; ++v) {
+                const int m = t * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+                part[((size_t)blockIdx.y * ROWS + m) * N + n] = acc[t][v];
             }
+    }
+}
+
+// fp32 rows -> hi + lo bf16 rows, optionally through RMSNorm (gain != nullptr).  One block per row.
+template <typename WT>
+__global__ __launch_bounds__(256) void split_rows_kernel(const float* __restrict__ X, int ldx, int K,
+                                                         const WT* __restrict__ gain, float eps,
+                                                         uint16_t* __restrict__ Xh, uint16_t* __restrict__ Xl) {
+    __shared__ float red[4];
+    const float* xr = X + (size_t)blockIdx.x * ldx;
+    float rs = 1.0f;
+    if (gain) {
+        float ss = 0.0f;
+        for (int k = threadIdx.x * 4; k < K; k += 1024) {
+            const float4 v = *reinterpret_cast<const float4*>(xr + k);
+            ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
         }
+        ss = block256_sum(ss, red);
+        rs = 1.0f / sqrtf(ss / (float)K + eps);
+    }
+    for (int k = threadIdx.x * 4; k < K; k += 1024) {
+        float4 v = *reinterpret_cast<const float4*>(xr + k);
+        if (gain) {
+            v.x *= rs * ld1(gain + k);     v.y *= rs * ld1(gain + k + 1);
+            v.z *= rs * ld1(gain + k + 2); v.w *= rs * ld1(gain + k + 3);
+        }
+        const float x[4] = {v.x, v.y, v.z, v.w};
+        uint16_t hi[4], lo[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { hi[e] = f2bf(x[e]); lo[e] = f2bf(x[e] - bf2f(hi[e])); }
+        *reinterpret_cast<uint2*>(Xh + (size_t)blockIdx.x * K + k) =
+            make_uint2((uint32_t)hi[0] | ((uint32_t)hi[1] << 16), (uint32_t)hi[2] | ((uint32_t)hi[3] << 16));
+        *reinterpret_cast<uint2*>(Xl + (size_t)blockIdx.x * K + k) =
+            make_uint2((uint32_t)lo[0] | ((uint32_t)lo[1] << 16), (uint32_t)lo[2] | ((uint32_t)lo[3] << 16));
+    }
+}
+
+// Adds the K slices of gemm_rows_kernel (ascending z) and finishes:
+//   EPI_STORE   Y[m][n]  = sum
+//   EPI_RESID   Y[m][n] += sum
+//   EPI_SWIGLU  N = 2F columns [gate ; up]: act = silu(gate) * up, written as hi + lo bf16 rows [m][F]
+template <int EPI>
+__global__ void rows_finish_kernel(const float* __restrict__ part, int KS, int ROWS, int M, int N,
+                                   float* __restrict__ Y, int ldy, uint16_t* __restrict__ Oh, uint16_t* __restrict__ Ol) {
+    const int NO = (EPI == EPI_SWIGLU) ? N / 2 : N;
+    const size_t i = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
+    if (i >= (size_t)M * NO) return;
+    const size_t m = i / NO, n = i - m * NO;           // NO is a multiple of 4
+    auto sum = [&](size_t col) {
+        float4 a = *reinterpret_cast<const float4*>(part + m * N + col);
+        for (int z = 1; z < KS; ++z) {
+            const float4 b = *reinterpret_cast<const float4*>(part + ((size_t)z * ROWS + m) * N + col);
+            a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
+        }
+        return a;
+    };
+    float4 a = sum(n);
+    if (EPI == EPI_SWIGLU) {
+        const float4 u = sum(NO + n);
+        const float x[4] = {a.x / (1.0f + expf(-a.x)) * u.x, a.y / (1.0f + expf(-a.y)) * u.y,
+                            a.z / (1.0f + expf(-a.z)) * u.z, a.w / (1.0f + expf(-a.w)) * u.w};
+        uint16_t hi[4], lo[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { hi[e] = f2bf(x[e]); lo[e] = f2bf(x[e] - bf2f(hi[e])); }
+        *reinterpret_cast<uint2*>(Oh + m * NO + n) =
+            make_uint2((uint32_t)hi[0] | ((uint32_t)hi[1] << 16), (uint32_t)hi[2] | ((uint32_t)hi[3] << 16));
+        *reinterpret_cast<uint2*>(Ol + m * NO + n) =
+            make_uint2((uint32_t)lo[0] | ((uint32_t)lo[1] << 16), (uint32_t)lo[2] | ((uint32_t)lo[3] << 16));
+    } else {
+        float4* yp = reinterpret_cast<float4*>(Y + m * ldy + n);
+        if (EPI == EPI_RESID) { const float4 y = *yp; a.x += y.x; a.y += y.y; a.z += y.z; a.w += y.w; }
+        *yp = a;
+    }
+}
+
+// K slices for gemm_rows_kernel: the count that minimises (rounds of 512 resident blocks) x (K blocks per
+// slice) plus the traffic of the partial results, in units of one K block over 256 rows of W
+static int gemm_rows_slices(int N, int K, int rows, size_t part_floats) {
+    const int nb = (N + 255) / 256, nkb = K / 64;
+    int best = 1;
+    double best_cost = 1e30;
+    for (int ks = 1; ks <= 64 && ks <= nkb; ++ks) {
+        if ((size_t)ks * rows * N > part_floats) break;
+        const int per = (nkb + ks - 1) / ks;
+        if ((ks - 1) * per >= nkb) continue;                 // would leave a slice empty
+        const int rounds = (nb * ks + 511) / 512;
+        const double cost = (double)rounds * per * 512 * 256 * 128 + (double)ks * rows * N * 8;
+        if (cost < best_cost) { best_cost = cost; best = ks; }
+    }
+    return best;
+}
+
+static void gemm_rows_launch(hipStream_t st, const bf16_t* W, int N, int K, const uint16_t* Xh, const uint16_t* Xl,
+                             int M, float* part, int ks) {
+    const dim3 grid((N + 255) / 256, ks), block(512);
+    if (M <= 32) hipLaunchKernelGGL((gemm_rows_kernel<1>), grid, block, 0, st, W, N, K, Xh, Xl, part);
+    else         hipLaunchKernelGGL((gemm_rows_kernel<2>), grid, block, 0, st, W, N, K, Xh, Xl, part);
 }
 
 // Y[m][n] (+)= sum_z part[z][m][n], slices added in ascending z
@@ -328,24 +469,6 @@ static void gemm_bf16_launch(hipStream_t st, int epi, const bf16_t* W, int N, in
 static void gemm_launch(hipStream_t st, int epi, const bf16_t* W, int N, int K, const float* X, int ldx,
                         float* Y, int ldy, int M, float* part, size_t part_floats) {
     if (M <= 8) { gemv_launch<bf16_t>(st, PRO_NONE, epi, W, N, K, X, ldx, nullptr, 0.f, Y, ldy, M); return; }
-    if (M <= 64 && K % 64 == 0) {
-        // weight-streaming kernel: 128 rows of W per block, K slices until about 3 blocks per compute unit
-        const int nb = (N + 127) / 128;
-        int ks = 1;
-        while (ks < 32 && nb * ks < 768 && K / (ks * 2) >= 256 && (size_t)(ks * 2) * M * N <= part_floats) ks *= 2;
-        if (!part) ks = 1;
-        const dim3 grid(nb, 1, ks), block(256);
-#define RSD_SK_CASE(T, E) hipLaunchKernelGGL((gemm_skinny_kernel<T, E>), grid, block, 0, st, W, N, K, X, ldx, Y, ldy, M, part)
-        if (M <= 32) { if (epi == EPI_RESID) RSD_SK_CASE(1, EPI_RESID); else RSD_SK_CASE(1, EPI_STORE); }
-        else         { if (epi == EPI_RESID) RSD_SK_CASE(2, EPI_RESID); else RSD_SK_CASE(2, EPI_STORE); }
-#undef RSD_SK_CASE
-        if (ks > 1) {
-            const unsigned rb = (unsigned)(((size_t)M * N / 4 + 255) / 256);
-            if (epi == EPI_RESID) hipLaunchKernelGGL((splitk_reduce_kernel<EPI_RESID>), dim3(rb), block, 0, st, part, ks, M, N, Y, ldy);
-            else                  hipLaunchKernelGGL((splitk_reduce_kernel<EPI_STORE>), dim3(rb), block, 0, st, part, ks, M, N, Y, ldy);
-        }
-        return;
-    }
     // Tiles: 64 rows of activations when there are few; narrow weight tiles and K slices until
     // about two blocks per compute unit exist (these shapes are bound by streaming W once).
     const int bm = M <= 64 ? 64 : 128;

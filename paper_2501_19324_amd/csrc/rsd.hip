@@ -85,6 +85,7 @@ struct rsd_ctx {
     float *h = nullptr, *xn = nullptr, *qkv = nullptr, *att = nullptr, *gu = nullptr, *act = nullptr;
     float *part_acc = nullptr, *part_ml = nullptr;
     float* part_k = nullptr;         // K-slice partial sums of few-row GEMMs
+    uint16_t *xs_h = nullptr, *xs_l = nullptr;   // [64][widest K]: hi / lo bf16 halves of the activations of a 9..64-row GEMM
     size_t part_k_floats = 0;
     // sampler workspace (per row: block maxima, histograms of the three radix levels, block masses, selections)
     int smp_rows = 0;
@@ -384,6 +385,34 @@ void launch_attn_prefill_mfma(rsd_ctx* c, const Model& m, int l, const RowMap& r
 #undef RSD_ATTN_CASE
 }
 
+// 9..64 rows over bf16 weights whose K is a multiple of 64: the weight-streaming MFMA kernel on
+// activations split into hi + lo bf16 halves (held in c->xs_h / c->xs_l between the launches)
+template <typename WT>
+bool rows_path(const Model& m, int M) {
+    return std::is_same<WT, bf16_t>::value && M > 8 && M <= 64 && m.s.d_model % 64 == 0 && m.q_dim % 64 == 0 &&
+           m.s.d_ffn % 64 == 0 && m.s.vocab % 4 == 0;
+}
+// x (fp32 rows, optionally through RMSNorm with `gain`) -> the hi / lo halves
+void rows_split(rsd_ctx* c, const float* X, int ldx, int M, int K, const bf16_t* gain, float eps) {
+    hipLaunchKernelGGL((split_rows_kernel<bf16_t>), dim3(M), dim3(256), 0, c->st, X, ldx, K, gain, eps, c->xs_h, c->xs_l);
+}
+// Y (+)= halves . W^T with epilogue `epi`; EPI_SWIGLU (N = 2F) writes the activated values back as halves
+void rows_gemm(rsd_ctx* c, int epi, const bf16_t* W, int N, int K, int M, float* Y, int ldy) {
+    const int rows = M <= 32 ? 32 : 64;
+    const int ks = gemm_rows_slices(N, K, rows, c->part_k_floats);
+    gemm_rows_launch(c->st, W, N, K, c->xs_h, c->xs_l, M, c->part_k, ks);
+    const int NO = epi == EPI_SWIGLU ? N / 2 : N;
+    const dim3 grid((unsigned)(((size_t)M * NO / 4 + 255) / 256)), block(256);
+    if (epi == EPI_SWIGLU)
+        hipLaunchKernelGGL((rows_finish_kernel<EPI_SWIGLU>), grid, block, 0, c->st, c->part_k, ks, rows, M, N, Y, ldy, c->xs_h, c->xs_l);
+    else if (epi == EPI_RESID)
+        hipLaunchKernelGGL((rows_finish_kernel<EPI_RESID>), grid, block, 0, c->st, c->part_k, ks, rows, M, N, Y, ldy, c->xs_h, c->xs_l);
+    else
+        hipLaunchKernelGGL((rows_finish_kernel<EPI_STORE>), grid, block, 0, c->st, c->part_k, ks, rows, M, N, Y, ldy, c->xs_h, c->xs_l);
+}
+void rows_split(rsd_ctx*, const float*, int, int, int, const float*, float) {}    // fp32 weights never take this path
+void rows_gemm(rsd_ctx*, int, const float*, int, int, int, float*, int) {}
+
 template <typename WT>
 void run_layers(rsd_ctx* c, Model& m, int M, const RowMap& rm, bool decode) {
     hipStream_t st = c->st;
@@ -393,6 +422,7 @@ void run_layers(rsd_ctx* c, Model& m, int M, const RowMap& rm, bool decode) {
                        c->p.max_ctx, rm, c->h);
     const int S = decode ? m.splits : 1;
     const bool fused = M <= 8;   // few rows: norm / SwiGLU / residual folded into the weight-streaming kernels
+    const bool rows = rows_path<WT>(m, M);
     // single-row decode over a bf16 cache: the output projection merges the attention splits itself
     const bool parts_to_o = decode && M == 1 && S > 1 && m.s.dtype == RSD_BF16 && m.hd == 128 &&
                             (size_t)m.q_dim * sizeof(float) <= 40 * 1024;
@@ -403,6 +433,9 @@ void run_layers(rsd_ctx* c, Model& m, int M, const RowMap& rm, bool decode) {
             ProbeScope ps(c, m, 0, (long long)m.n_qkv * d * esz + 4LL * M * (d + m.n_qkv));
             gemv_launch<WT>(st, PRO_NORM, EPI_STORE, wptr<WT>(m, o.wqkv), m.n_qkv, d, c->h, d,
                             wptr<WT>(m, o.attn_norm), eps, c->qkv, m.n_qkv, M);
+        } else if (rows) {
+            rows_split(c, c->h, d, M, d, wptr<WT>(m, o.attn_norm), eps);
+            rows_gemm(c, EPI_STORE, wptr<WT>(m, o.wqkv), m.n_qkv, d, M, c->qkv, m.n_qkv);
         } else {
             hipLaunchKernelGGL((rmsnorm_kernel<WT>), dim3(M), dim3(256), 0, st, c->h, d, wptr<WT>(m, o.attn_norm), eps, c->xn);
             gemm_launch(st, EPI_STORE, wptr<WT>(m, o.wqkv), m.n_qkv, d, c->xn, d, c->qkv, m.n_qkv, M, c->part_k, c->part_k_floats);
@@ -455,6 +488,12 @@ void run_layers(rsd_ctx* c, Model& m, int M, const RowMap& rm, bool decode) {
                                     (const WT*)nullptr, 0.f, c->h, d, M);
                 }
             }
+        } else if (rows) {
+            rows_split(c, c->att, m.q_dim, M, m.q_dim, (const WT*)nullptr, 0.f);
+            rows_gemm(c, EPI_RESID, wptr<WT>(m, o.wo), d, m.q_dim, M, c->h, d);
+            rows_split(c, c->h, d, M, d, wptr<WT>(m, o.ffn_norm), eps);
+            rows_gemm(c, EPI_SWIGLU, wptr<WT>(m, o.wgu), 2 * F, d, M, nullptr, 0);     // activated values stay as halves
+            rows_gemm(c, EPI_RESID, wptr<WT>(m, o.wdown), d, F, M, c->h, d);
         } else {
             gemm_launch(st, EPI_RESID, wptr<WT>(m, o.wo), d, m.q_dim, c->att, m.q_dim, c->h, d, M, c->part_k, c->part_k_floats);
             hipLaunchKernelGGL((rmsnorm_kernel<WT>), dim3(M), dim3(256), 0, st, c->h, d, wptr<WT>(m, o.ffn_norm), eps, c->xn);
@@ -474,6 +513,9 @@ void lm_head(rsd_ctx* c, Model& m, const float* X, int M, float* Y, int ldy) {
         ProbeScope ps(c, m, 4, (long long)V * d * sizeof(WT) + 4LL * M * (d + V));
         gemv_launch<WT>(c->st, PRO_NORM, EPI_STORE, wptr<WT>(m, m.off_head), V, d, X, d, wptr<WT>(m, m.off_final_norm),
                         m.s.rms_eps, Y, ldy, M);
+    } else if (rows_path<WT>(m, M)) {
+        rows_split(c, X, d, M, d, wptr<WT>(m, m.off_final_norm), m.s.rms_eps);
+        rows_gemm(c, EPI_STORE, wptr<WT>(m, m.off_head), V, d, M, Y, ldy);
     } else {
         for (int r0 = 0; r0 < M; r0 += kMaxRows) {
             const int mm = std::min(kMaxRows, M - r0);
@@ -702,7 +744,7 @@ void rsd_destroy(rsd_ctx* c) {
         if (m.bt_host) (void)hipHostFree(m.bt_host);
     }
     void* dev[] = {c->sb_dev, c->ds.tokens, c->ds.sampled[0], c->ds.sampled[1], c->h, c->xn, c->qkv, c->att, c->gu, c->act,
-                   c->part_acc, c->part_ml, c->part_k, c->smp_pmax, c->smp_pidx, c->smp_hist, c->smp_psum, c->smp_sel, c->hl, c->xl, c->logits, c->tmp_reward, c->chosen, c->steptok_dev,
+                   c->part_acc, c->part_ml, c->part_k, c->xs_h, c->xs_l, c->smp_pmax, c->smp_pidx, c->smp_hist, c->smp_psum, c->smp_sel, c->hl, c->xl, c->logits, c->tmp_reward, c->chosen, c->steptok_dev,
                    c->row_seq_dev, c->row_pos_dev, c->last_row_dev, c->item_row0_dev, c->item_n_dev};
     for (void* p : dev) if (p) (void)hipFree(p);
     for (hipEvent_t e : c->probe_ev) (void)hipEventDestroy(e);
@@ -780,6 +822,13 @@ int rsd_init(rsd_ctx** out, const rsd_model_shape shape[3], const rsd_weights w[
     HIPCHK(c, dev_alloc(&c->part_ml, (size_t)B * HS));
     c->part_k_floats = (size_t)48 << 20;
     HIPCHK(c, dev_alloc(&c->part_k, c->part_k_floats));
+    {
+        const size_t kmax = (size_t)std::max(std::max(d, qd), F);
+        HIPCHK(c, dev_alloc(&c->xs_h, 64 * kmax));
+        HIPCHK(c, dev_alloc(&c->xs_l, 64 * kmax));
+        HIPCHK(c, hipMemsetAsync(c->xs_h, 0, 64 * kmax * sizeof(uint16_t), c->st));
+        HIPCHK(c, hipMemsetAsync(c->xs_l, 0, 64 * kmax * sizeof(uint16_t), c->st));
+    }
     c->smp_rows = std::max(B, 64);
     HIPCHK(c, dev_alloc(&c->smp_pmax, (size_t)c->smp_rows * SMP_NB));
     HIPCHK(c, dev_alloc(&c->smp_pidx, (size_t)c->smp_rows * SMP_NB));
