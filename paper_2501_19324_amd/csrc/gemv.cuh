@@ -580,8 +580,12 @@ static void gemv_launch_mt(hipStream_t st, int pro, int epi, const WT* W, int N,
 template <typename WT>
 static bool gemv_launch_attn(hipStream_t st, const WT* W, int N, int K, AttnParts parts, float* Y) {
     if ((size_t)K * sizeof(float) > 40 * 1024) return false;
+    // every block merges the whole row: one block per compute unit keeps that repeated work small
+    if (K > 2048)
+        return gemv_launch_flat<WT, 16, 4>(st, PRO_ATTN, EPI_RESID, W, N, K, (const float*)nullptr, (const WT*)nullptr, 0.f,
+                                           Y, 1, 4, parts);
     return gemv_launch_flat<WT, 8, 4>(st, PRO_ATTN, EPI_RESID, W, N, K, (const float*)nullptr, (const WT*)nullptr, 0.f, Y,
-                                      2, 4, parts);
+                                      1, 4, parts);
 }
 
 // M <= 8

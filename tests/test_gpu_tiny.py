@@ -246,3 +246,22 @@ def test_bad_arguments_are_rejected(gpu, tiny):
         R.rsd_step(s.ctx)
     assert e.value.code == R.RSD_ESTATE and out["steps_run"] == 4
     s.close()
+
+
+@pytest.mark.parametrize("kind,a", [(1, 0.6), (2, 0.0), (3, 0.0), (4, 8.0)])
+def test_general_weightings_on_gpu(gpu, tiny, kind, a):
+    """Table 1's other weighting functions (constant, clipped, r / (1 + r), logistic) through
+    Algorithm 2's uniform draw: rewards, decisions, tokens and offsets against the checker."""
+    from rsd_inputs import workload
+    w = workload("cfg0", omega_kind=kind, omega_a=a, sep_logit_bias=0.6, deltas=(0.55,), max_steps=6)
+    n_acc, n_rej = run_and_compare(gpu, tiny, w)
+    assert n_acc >= 1 and n_rej >= 1
+
+
+@pytest.mark.parametrize("batch,plen,cap", [(1, 1, 1), (2, 1, 3), (5, 17, 1)])
+def test_smallest_inputs(gpu, tiny, batch, plen, cap):
+    """One-token prompts, one-token steps, a single sequence."""
+    from rsd_inputs import workload
+    w = workload("cfg0", batch=batch, prompt_len_min=plen, prompt_len_max=plen, step_cap=cap, max_steps=5,
+                 sep_logit_bias=0.6, deltas=(0.5,))
+    run_and_compare(gpu, tiny, w)
