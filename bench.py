@@ -23,7 +23,7 @@ PROBE_OPS = {"qkv": 0, "o": 1, "gate_up": 2, "down": 3, "head": 4}
 
 def cpu_baseline(w, budget_s=20.0):
     """The fp64 CPU checker timed on a bounded sample of the same workload:
-    the three models at full width and vocabulary but 2 layers each, first
+    the three models at full width and vocabulary but 12 layers each, first
     reasoning step capped at 4 tokens (the full-depth models need > 100 GB as
     fp64 and minutes per token)."""
     import numpy as np
@@ -32,7 +32,7 @@ def cpu_baseline(w, budget_s=20.0):
     from rsd_inputs import workload, model_weights_np, prompt_tokens, prompt_lengths, uniforms
     from oracle import rsd_oracle as O
 
-    layers = 2
+    layers = 12
     ws = workload(w.name, n_layers=layers, batch=1, step_cap=4, max_steps=1)
     cores = min(16, os.cpu_count() or 1)
     models = [O.OracleModel(s, model_weights_np(ws.seed, i, s, threads=cores)) for i, s in enumerate(ws.shapes)]
