@@ -448,7 +448,8 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void attn_decode_mfma_ker
                                                                    const int* __restrict__ active,
                                                                    const float2* __restrict__ rope, int H, int Hkv,
                                                                    int S, float scale, float* __restrict__ out, int ldo,
-                                                                   float* __restrict__ part_acc, float* __restrict__ part_ml) {
+                                                                   float* __restrict__ part_acc, float* __restrict__ part_ml,
+                                                                   uint16_t* __restrict__ out_h, uint16_t* __restrict__ out_l) {
     constexpr int HD = 128;
     const int r = blockIdx.x, hk = blockIdx.y, sp = blockIdx.z;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -638,7 +639,14 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void attn_decode_mfma_ker
         }
         const int h = hk * G + g;
         if (S == 1) {
-            out[(size_t)r * ldo + h * HD + e] = a / ll;
+            const float y = a / ll;
+            if (out_h) {            // as hi + lo bf16 halves, for the MFMA projection that follows
+                const uint16_t hi = f2bf(y);
+                out_h[(size_t)r * ldo + h * HD + e] = hi;
+                out_l[(size_t)r * ldo + h * HD + e] = f2bf(y - bf2f(hi));
+            } else {
+                out[(size_t)r * ldo + h * HD + e] = y;
+            }
         } else {
             const size_t pi = ((size_t)r * H + h) * S + sp;
             part_acc[pi * HD + e] = a;

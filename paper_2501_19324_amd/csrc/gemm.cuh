@@ -365,6 +365,24 @@ __global__ __launch_bounds__(256) void split_rows_kernel(const float* __restrict
     }
 }
 
+// sum over z (ascending) of the float4 at p + z * stride; eight loads are requested at a time
+__device__ __forceinline__ float4 sum_slices(const float* __restrict__ p, size_t stride, int KS) {
+    float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
+    int z = 0;
+    for (; z + 8 <= KS; z += 8) {
+        float4 b[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) b[i] = *reinterpret_cast<const float4*>(p + (size_t)(z + i) * stride);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) { a.x += b[i].x; a.y += b[i].y; a.z += b[i].z; a.w += b[i].w; }
+    }
+    for (; z < KS; ++z) {
+        const float4 b = *reinterpret_cast<const float4*>(p + (size_t)z * stride);
+        a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
+    }
+    return a;
+}
+
 // Adds the K slices of gemm_rows_kernel (ascending z) and finishes:
 //   EPI_STORE   Y[m][n]  = sum
 //   EPI_RESID   Y[m][n] += sum
@@ -376,14 +394,7 @@ __global__ void rows_finish_kernel(const float* __restrict__ part, int KS, int R
     const size_t i = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
     if (i >= (size_t)M * NO) return;
     const size_t m = i / NO, n = i - m * NO;           // NO is a multiple of 4
-    auto sum = [&](size_t col) {
-        float4 a = *reinterpret_cast<const float4*>(part + m * N + col);
-        for (int z = 1; z < KS; ++z) {
-            const float4 b = *reinterpret_cast<const float4*>(part + ((size_t)z * ROWS + m) * N + col);
-            a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
-        }
-        return a;
-    };
+    auto sum = [&](size_t col) { return sum_slices(part + m * N + col, (size_t)ROWS * N, KS); };
     float4 a = sum(n);
     if (EPI == EPI_SWIGLU) {
         const float4 u = sum(NO + n);
@@ -400,6 +411,56 @@ __global__ void rows_finish_kernel(const float* __restrict__ part, int KS, int R
         float4* yp = reinterpret_cast<float4*>(Y + m * ldy + n);
         if (EPI == EPI_RESID) { const float4 y = *yp; a.x += y.x; a.y += y.y; a.z += y.z; a.w += y.w; }
         *yp = a;
+    }
+}
+
+// EPI_RESID finish for a whole row per block, with the RMSNorm of the NEXT projection folded in: adds the K
+// slices (ascending z) and the residual, stores the new residual stream H, and writes
+// RMSNorm(H row) * gain as hi + lo bf16 halves.  N <= 8192, N % 4 == 0.
+template <typename WT>
+__global__ __launch_bounds__(1024) void rows_finish_norm_kernel(const float* __restrict__ part, int KS, int ROWS, int N,
+                                                                float* __restrict__ H, int ldh,
+                                                                const WT* __restrict__ gain, float eps,
+                                                                uint16_t* __restrict__ Xh, uint16_t* __restrict__ Xl) {
+    __shared__ float red[16];
+    const int m = blockIdx.x, tid = threadIdx.x;
+    float4 v[2];
+    float ss = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int n = tid * 4 + i * 4096;
+        v[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (n < N) {
+            float4 a = sum_slices(part + (size_t)m * N + n, (size_t)ROWS * N, KS);
+            float4* hp = reinterpret_cast<float4*>(H + (size_t)m * ldh + n);
+            const float4 y = *hp;
+            a.x += y.x; a.y += y.y; a.z += y.z; a.w += y.w;
+            *hp = a;
+            v[i] = a;
+            ss += a.x * a.x + a.y * a.y + a.z * a.z + a.w * a.w;
+        }
+    }
+    ss = wave_sum(ss);
+    if ((tid & 63) == 0) red[tid >> 6] = ss;
+    __syncthreads();
+    float tot = 0.0f;
+#pragma unroll
+    for (int w = 0; w < 16; ++w) tot += red[w];
+    const float rs = 1.0f / sqrtf(tot / (float)N + eps);
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int n = tid * 4 + i * 4096;
+        if (n < N) {
+            const float x[4] = {v[i].x * (rs * ld1(gain + n)), v[i].y * (rs * ld1(gain + n + 1)),
+                                v[i].z * (rs * ld1(gain + n + 2)), v[i].w * (rs * ld1(gain + n + 3))};
+            uint16_t hi[4], lo[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { hi[e] = f2bf(x[e]); lo[e] = f2bf(x[e] - bf2f(hi[e])); }
+            *reinterpret_cast<uint2*>(Xh + (size_t)m * N + n) =
+                make_uint2((uint32_t)hi[0] | ((uint32_t)hi[1] << 16), (uint32_t)hi[2] | ((uint32_t)hi[3] << 16));
+            *reinterpret_cast<uint2*>(Xl + (size_t)m * N + n) =
+                make_uint2((uint32_t)lo[0] | ((uint32_t)lo[1] << 16), (uint32_t)lo[2] | ((uint32_t)lo[3] << 16));
+        }
     }
 }
 

@@ -341,7 +341,8 @@ void launch_attn_decode(rsd_ctx* c, const Model& m, int l, int M, int which) {
 
 // bf16 caches with head_dim 128: the MFMA kernel, 8 waves per block
 // merge_here = false leaves the partial results of the splits to the caller (S > 1 only)
-void launch_attn_decode_mfma(rsd_ctx* c, const Model& m, int l, int M, int which, bool merge_here = true) {
+void launch_attn_decode_mfma(rsd_ctx* c, const Model& m, int l, int M, int which, bool merge_here = true,
+                             bool halves = false) {
     bf16_t* pool_l = reinterpret_cast<bf16_t*>(m.pool) + (size_t)l * m.pool_pages * m.page_elts;
     const float scale = 1.0f / std::sqrt(128.0f);
     const int S = m.splits;
@@ -350,7 +351,8 @@ void launch_attn_decode_mfma(rsd_ctx* c, const Model& m, int l, int M, int which
     case GG:                                                                                                       \
         hipLaunchKernelGGL((attn_decode_mfma_kernel<GG, 8>), grid, dim3(512), 0, c->st, c->qkv, m.n_qkv, pool_l,   \
                            m.bt_dev, m.max_pages, c->ds.kv_len + (size_t)which * c->B, c->ds.active, m.rope,       \
-                           m.s.n_heads, m.s.n_kv_heads, S, scale, c->att, m.q_dim, c->part_acc, c->part_ml);       \
+                           m.s.n_heads, m.s.n_kv_heads, S, scale, c->att, m.q_dim, c->part_acc, c->part_ml,        \
+                           halves ? c->xs_h : nullptr, halves ? c->xs_l : nullptr);                                \
         break;
     switch (m.G) {
         RSD_ATTN_CASE(1) RSD_ATTN_CASE(2) RSD_ATTN_CASE(4) RSD_ATTN_CASE(6) RSD_ATTN_CASE(7) RSD_ATTN_CASE(8)
@@ -397,10 +399,18 @@ void rows_split(rsd_ctx* c, const float* X, int ldx, int M, int K, const bf16_t*
     hipLaunchKernelGGL((split_rows_kernel<bf16_t>), dim3(M), dim3(256), 0, c->st, X, ldx, K, gain, eps, c->xs_h, c->xs_l);
 }
 // Y (+)= halves . W^T with epilogue `epi`; EPI_SWIGLU (N = 2F) writes the activated values back as halves
-void rows_gemm(rsd_ctx* c, int epi, const bf16_t* W, int N, int K, int M, float* Y, int ldy) {
+// next_gain != nullptr (EPI_RESID, N <= 8192): the finish also emits RMSNorm(Y row) * next_gain as the halves
+// for the projection that follows
+void rows_gemm(rsd_ctx* c, int epi, const bf16_t* W, int N, int K, int M, float* Y, int ldy,
+               const bf16_t* next_gain = nullptr, float eps = 0.f) {
     const int rows = M <= 32 ? 32 : 64;
     const int ks = gemm_rows_slices(N, K, rows, c->part_k_floats);
     gemm_rows_launch(c->st, W, N, K, c->xs_h, c->xs_l, M, c->part_k, ks);
+    if (next_gain) {
+        hipLaunchKernelGGL((rows_finish_norm_kernel<bf16_t>), dim3(M), dim3(1024), 0, c->st, c->part_k, ks, rows, N, Y, ldy,
+                           next_gain, eps, c->xs_h, c->xs_l);
+        return;
+    }
     const int NO = epi == EPI_SWIGLU ? N / 2 : N;
     const dim3 grid((unsigned)(((size_t)M * NO / 4 + 255) / 256)), block(256);
     if (epi == EPI_SWIGLU)
@@ -411,7 +421,7 @@ void rows_gemm(rsd_ctx* c, int epi, const bf16_t* W, int N, int K, int M, float*
         hipLaunchKernelGGL((rows_finish_kernel<EPI_STORE>), grid, block, 0, c->st, c->part_k, ks, rows, M, N, Y, ldy, c->xs_h, c->xs_l);
 }
 void rows_split(rsd_ctx*, const float*, int, int, int, const float*, float) {}    // fp32 weights never take this path
-void rows_gemm(rsd_ctx*, int, const float*, int, int, int, float*, int) {}
+void rows_gemm(rsd_ctx*, int, const float*, int, int, int, float*, int, const float* = nullptr, float = 0.f) {}
 
 template <typename WT>
 void run_layers(rsd_ctx* c, Model& m, int M, const RowMap& rm, bool decode) {
@@ -423,6 +433,9 @@ void run_layers(rsd_ctx* c, Model& m, int M, const RowMap& rm, bool decode) {
     const int S = decode ? m.splits : 1;
     const bool fused = M <= 8;   // few rows: norm / SwiGLU / residual folded into the weight-streaming kernels
     const bool rows = rows_path<WT>(m, M);
+    const bool rows_fuse_norm = rows && d <= 8192;          // residual finish + next RMSNorm in one kernel
+    // batched decode with one split: the attention kernel writes its output as hi / lo halves itself
+    const bool att_halves = rows && decode && S == 1 && m.s.dtype == RSD_BF16 && m.hd == 128;
     // single-row decode over a bf16 cache: the output projection merges the attention splits itself
     const bool parts_to_o = decode && M == 1 && S > 1 && m.s.dtype == RSD_BF16 && m.hd == 128 &&
                             (size_t)m.q_dim * sizeof(float) <= 40 * 1024;
@@ -434,7 +447,8 @@ void run_layers(rsd_ctx* c, Model& m, int M, const RowMap& rm, bool decode) {
             gemv_launch<WT>(st, PRO_NORM, EPI_STORE, wptr<WT>(m, o.wqkv), m.n_qkv, d, c->h, d,
                             wptr<WT>(m, o.attn_norm), eps, c->qkv, m.n_qkv, M);
         } else if (rows) {
-            rows_split(c, c->h, d, M, d, wptr<WT>(m, o.attn_norm), eps);
+            // (after the first layer the halves of RMSNorm(h) come from the previous layer's last finish)
+            if (l == 0 || !rows_fuse_norm) rows_split(c, c->h, d, M, d, wptr<WT>(m, o.attn_norm), eps);
             rows_gemm(c, EPI_STORE, wptr<WT>(m, o.wqkv), m.n_qkv, d, M, c->qkv, m.n_qkv);
         } else {
             hipLaunchKernelGGL((rmsnorm_kernel<WT>), dim3(M), dim3(256), 0, st, c->h, d, wptr<WT>(m, o.attn_norm), eps, c->xn);
@@ -443,7 +457,7 @@ void run_layers(rsd_ctx* c, Model& m, int M, const RowMap& rm, bool decode) {
         WT* pool_l = reinterpret_cast<WT*>(m.pool) + (size_t)l * m.pool_pages * m.page_elts;
         if (decode) {
             const int which = (int)(&m - &c->m[0]);
-            if (m.s.dtype == RSD_BF16) launch_attn_decode_mfma(c, m, l, M, which, !parts_to_o);
+            if (m.s.dtype == RSD_BF16) launch_attn_decode_mfma(c, m, l, M, which, !parts_to_o, att_halves);
             else if (m.hd == 128) launch_attn_decode<WT, 128>(c, m, l, M, which);
             else launch_attn_decode<WT, 32>(c, m, l, M, which);
         } else if (m.hd == 128) {
@@ -489,11 +503,18 @@ void run_layers(rsd_ctx* c, Model& m, int M, const RowMap& rm, bool decode) {
                 }
             }
         } else if (rows) {
-            rows_split(c, c->att, m.q_dim, M, m.q_dim, (const WT*)nullptr, 0.f);
-            rows_gemm(c, EPI_RESID, wptr<WT>(m, o.wo), d, m.q_dim, M, c->h, d);
-            rows_split(c, c->h, d, M, d, wptr<WT>(m, o.ffn_norm), eps);
+            if (!att_halves) rows_split(c, c->att, m.q_dim, M, m.q_dim, (const WT*)nullptr, 0.f);
+            if (rows_fuse_norm) {
+                rows_gemm(c, EPI_RESID, wptr<WT>(m, o.wo), d, m.q_dim, M, c->h, d, wptr<WT>(m, o.ffn_norm), eps);
+            } else {
+                rows_gemm(c, EPI_RESID, wptr<WT>(m, o.wo), d, m.q_dim, M, c->h, d);
+                rows_split(c, c->h, d, M, d, wptr<WT>(m, o.ffn_norm), eps);
+            }
             rows_gemm(c, EPI_SWIGLU, wptr<WT>(m, o.wgu), 2 * F, d, M, nullptr, 0);     // activated values stay as halves
-            rows_gemm(c, EPI_RESID, wptr<WT>(m, o.wdown), d, F, M, c->h, d);
+            if (rows_fuse_norm && l + 1 < m.s.n_layers)
+                rows_gemm(c, EPI_RESID, wptr<WT>(m, o.wdown), d, F, M, c->h, d, wptr<WT>(m, m.layers[l + 1].attn_norm), eps);
+            else
+                rows_gemm(c, EPI_RESID, wptr<WT>(m, o.wdown), d, F, M, c->h, d);
         } else {
             gemm_launch(st, EPI_RESID, wptr<WT>(m, o.wo), d, m.q_dim, c->att, m.q_dim, c->h, d, M, c->part_k, c->part_k_floats);
             hipLaunchKernelGGL((rmsnorm_kernel<WT>), dim3(M), dim3(256), 0, st, c->h, d, wptr<WT>(m, o.ffn_norm), eps, c->xn);
