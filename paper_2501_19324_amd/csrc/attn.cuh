@@ -168,7 +168,8 @@ __global__ __launch_bounds__(256) void attn_rows_kernel(const float* __restrict_
 // Merge the S partial results of every (row, head).
 template <int HD>
 __global__ void attn_combine_kernel(const float* __restrict__ part_acc, const float* __restrict__ part_ml,
-                                    RowMap rm, int H, int S, float* __restrict__ out, int ldo) {
+                                    RowMap rm, int H, int S, float* __restrict__ out, int ldo,
+                                    uint16_t* __restrict__ out_h = nullptr, uint16_t* __restrict__ out_l = nullptr) {
     const int r = blockIdx.x, h = blockIdx.y, e = threadIdx.x;
     int seq, pos;
     if (!row_lookup(rm, r, seq, pos)) return;
@@ -182,7 +183,14 @@ __global__ void attn_combine_kernel(const float* __restrict__ part_acc, const fl
         a += part_acc[(base + s) * HD + e] * c;
         ll += part_ml[(base + s) * 2 + 1] * c;
     }
-    out[(size_t)r * ldo + h * HD + e] = a / ll;
+    const float y = a / ll;
+    if (out_h) {                // as hi + lo bf16 halves, for the MFMA projection that follows
+        const uint16_t hi = f2bf(y);
+        out_h[(size_t)r * ldo + h * HD + e] = hi;
+        out_l[(size_t)r * ldo + h * HD + e] = f2bf(y - bf2f(hi));
+    } else {
+        out[(size_t)r * ldo + h * HD + e] = y;
+    }
 }
 
 // Rotate q (in place, fp32) and k with the precomputed table rope[pos][i] =

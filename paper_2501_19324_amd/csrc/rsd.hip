@@ -360,7 +360,8 @@ void launch_attn_decode_mfma(rsd_ctx* c, const Model& m, int l, int M, int which
 #undef RSD_ATTN_CASE
     if (S > 1 && merge_here)
         hipLaunchKernelGGL((attn_combine_kernel<128>), dim3(M, m.s.n_heads), dim3(128), 0, c->st, c->part_acc,
-                           c->part_ml, decode_map(c, which), m.s.n_heads, S, c->att, m.q_dim);
+                           c->part_ml, decode_map(c, which), m.s.n_heads, S, c->att, m.q_dim,
+                           halves ? c->xs_h : nullptr, halves ? c->xs_l : nullptr);
 }
 
 // chunked prefill over a bf16 cache: rows of the pass are described by the context's item arrays
@@ -434,8 +435,8 @@ void run_layers(rsd_ctx* c, Model& m, int M, const RowMap& rm, bool decode) {
     const bool fused = M <= 8;   // few rows: norm / SwiGLU / residual folded into the weight-streaming kernels
     const bool rows = rows_path<WT>(m, M);
     const bool rows_fuse_norm = rows && d <= 8192;          // residual finish + next RMSNorm in one kernel
-    // batched decode with one split: the attention kernel writes its output as hi / lo halves itself
-    const bool att_halves = rows && decode && S == 1 && m.s.dtype == RSD_BF16 && m.hd == 128;
+    // batched decode: the attention kernel (or its merge kernel) writes the output as hi / lo halves itself
+    const bool att_halves = rows && decode && m.s.dtype == RSD_BF16 && m.hd == 128;
     // single-row decode over a bf16 cache: the output projection merges the attention splits itself
     const bool parts_to_o = decode && M == 1 && S > 1 && m.s.dtype == RSD_BF16 && m.hd == 128 &&
                             (size_t)m.q_dim * sizeof(float) <= 40 * 1024;
