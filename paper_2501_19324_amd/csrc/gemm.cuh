@@ -2,14 +2,14 @@
 // batches): Y[m][n] (+)= sum_k X[m][k] * W[n][k]; X fp32 [M][ldx], W row-major
 // [N][K], Y fp32 [M][ldy].  Both operands are contiguous along K ("NT" form).
 //   * fp32 weights: plain VALU tile kernel (the tiny configuration only).
-//   * bf16 weights: MFMA kernel.  An fp32 activation x is staged into LDS as two
-//     bf16 numbers, hi = bf16(x) and lo = bf16(x - hi), and every weight tile is
-//     multiplied with both (W.hi + W.lo, fp32 accumulation): the activations keep
-//     16 mantissa bits, which the bit-for-bit agreement of the bf16 KV-cache
-//     entries with an exact evaluation needs; one bf16 pass would leave 8.
-//   * 9..64 rows: weight-streaming kernel on activations split beforehand into hi and lo bf16
-//     matrices (gemm_rows_kernel with split_rows_kernel / rows_finish_kernel around it).
-// Requirements checked by the caller: K % 32 == 0; N, M arbitrary.
+//   * bf16 weights: MFMA kernels.  An fp32 activation x enters as two bf16 numbers,
+//     hi = bf16(x) and lo = bf16(x - hi) (split_rows_kernel, or the producing kernel
+//     writes the halves itself), and every weight tile is multiplied with both
+//     (W.hi + W.lo, fp32 accumulation): the activations keep 16 mantissa bits, which
+//     the bit-for-bit agreement of the bf16 KV-cache entries with an exact evaluation
+//     needs; one bf16 pass would leave 8.  9..64 rows: weight-streaming
+//     gemm_rows_kernel; more rows: 128 x 256 tiles, gemm_tile_kernel.
+// Requirements checked by the caller: K % 64 == 0; N, M arbitrary.
 #pragma once
 #include "common.cuh"
 #include "gemv.cuh"
@@ -65,124 +65,6 @@ __global__ __launch_bounds__(256) void sgemm_nt_kernel(const float* __restrict__
             }
         }
     }
-}
-
-// ---------------------------------------------------------------- bf16 MFMA
-// Block tile BM x BN (64 or 128 each), K step 32, 256 threads = 2 x 2 waves.
-// v_mfma_f32_32x32x16_bf16: per lane 8 consecutive-k bf16 of row (lane % 32) at
-// k offset 8 * (lane / 32) for each operand; the 16 results of a lane sit at
-// rows 8 * (v / 4) + 4 * (lane / 32) + v % 4, column lane % 32.
-// blockIdx.z cuts K into gridDim.z slices (few-row GEMMs stream the weights and
-// need more blocks than output tiles); with slices the tile is stored to
-// part[z][M][N] and splitk_reduce_kernel adds the slices in a fixed order.
-template <int BM, int BN, int EPI>
-__global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict__ W, int N, int K,
-                                                        const float* __restrict__ X, int ldx,
-                                                        float* __restrict__ Y, int ldy, int M,
-                                                        float* __restrict__ part) {
-    constexpr int BK = 32, LDS_STRIDE = BK + 8;             // 80-byte rows: 16-byte aligned, conflict-free
-    constexpr int WM = BM / 2, WN = BN / 2;                  // tile of one wave
-    constexpr int TI = WM / 32, TJ = WN / 32;                // 32x32 MFMA tiles per wave
-    __shared__ __attribute__((aligned(16))) uint16_t As[BM * LDS_STRIDE];    // hi parts
-    __shared__ __attribute__((aligned(16))) uint16_t Al[BM * LDS_STRIDE];    // lo parts
-    __shared__ __attribute__((aligned(16))) uint16_t Bs[BN * LDS_STRIDE];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
-    const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
-    const int ksl = ((K / BK + gridDim.z - 1) / gridDim.z) * BK;             // K slice of this block
-    const int k_begin = blockIdx.z * ksl, k_end = min(K, k_begin + ksl);
-
-    f32x16_t acc[TI][TJ];
-#pragma unroll
-    for (int i = 0; i < TI; ++i)
-#pragma unroll
-        for (int j = 0; j < TJ; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
-
-    constexpr int A_F4 = BM * BK / 4 / 256;   // float4 loads of X per thread (2 or 4)
-    constexpr int B_U4 = BN * BK / 8 / 256;   // uint4 loads of W per thread (1 or 2)
-    for (int k0 = k_begin; k0 < k_end; k0 += BK) {
-        float4 av[A_F4];
-        uint4 bv[B_U4];
-#pragma unroll
-        for (int i = 0; i < A_F4; ++i) {
-            const int idx = tid + i * 256, row = idx >> 3, c4 = idx & 7;
-            av[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (m0 + row < M) av[i] = *reinterpret_cast<const float4*>(X + (size_t)(m0 + row) * ldx + k0 + c4 * 4);
-        }
-#pragma unroll
-        for (int i = 0; i < B_U4; ++i) {
-            const int idx = tid + i * 256, row = idx >> 2, c8 = idx & 3;
-            bv[i] = make_uint4(0u, 0u, 0u, 0u);
-            if (n0 + row < N) bv[i] = *reinterpret_cast<const uint4*>(W + (size_t)(n0 + row) * K + k0 + c8 * 8);
-        }
-        __syncthreads();          // previous tile fully consumed
-#pragma unroll
-        for (int i = 0; i < A_F4; ++i) {
-            const int idx = tid + i * 256, row = idx >> 3, c4 = idx & 7;
-            const float x[4] = {av[i].x, av[i].y, av[i].z, av[i].w};
-            uint16_t hi[4], lo[4];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                hi[e] = f2bf(x[e]);
-                lo[e] = f2bf(x[e] - bf2f(hi[e]));
-            }
-            uint2 p, q;
-            p.x = (uint32_t)hi[0] | ((uint32_t)hi[1] << 16); p.y = (uint32_t)hi[2] | ((uint32_t)hi[3] << 16);
-            q.x = (uint32_t)lo[0] | ((uint32_t)lo[1] << 16); q.y = (uint32_t)lo[2] | ((uint32_t)lo[3] << 16);
-            *reinterpret_cast<uint2*>(&As[row * LDS_STRIDE + c4 * 4]) = p;
-            *reinterpret_cast<uint2*>(&Al[row * LDS_STRIDE + c4 * 4]) = q;
-        }
-#pragma unroll
-        for (int i = 0; i < B_U4; ++i) {
-            const int idx = tid + i * 256, row = idx >> 2, c8 = idx & 3;
-            *reinterpret_cast<uint4*>(&Bs[row * LDS_STRIDE + c8 * 8]) = bv[i];
-        }
-        __syncthreads();
-#pragma unroll
-        for (int kk = 0; kk < BK; kk += 16) {
-            bf16x8_t a[TI], al[TI], b[TJ];
-#pragma unroll
-            for (int i = 0; i < TI; ++i) {
-                const int off = (wm * WM + i * 32 + (lane & 31)) * LDS_STRIDE + kk + (lane >> 5) * 8;
-                a[i] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(&As[off]));
-                al[i] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(&Al[off]));
-            }
-#pragma unroll
-            for (int j = 0; j < TJ; ++j) {
-                const uint4 r = *reinterpret_cast<const uint4*>(
-                    &Bs[(wn * WN + j * 32 + (lane & 31)) * LDS_STRIDE + kk + (lane >> 5) * 8]);
-                b[j] = __builtin_bit_cast(bf16x8_t, r);
-            }
-#pragma unroll
-            for (int i = 0; i < TI; ++i)
-#pragma unroll
-                for (int j = 0; j < TJ; ++j) {
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[i], b[j], acc[i][j], 0, 0, 0);
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
-                }
-        }
-    }
-    const bool sliced = gridDim.z > 1;
-#pragma unroll
-    for (int i = 0; i < TI; ++i)
-#pragma unroll
-        for (int j = 0; j < TJ; ++j) {
-            const int n = n0 + wn * WN + j * 32 + (lane & 31);
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int m = m0 + wm * WM + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-                if (m < M && n < N) {
-                    if (sliced) {
-                        part[((size_t)blockIdx.z * M + m) * N + n] = acc[i][j][v];
-                    } else {
-                        float* yp = Y + (size_t)m * ldy + n;
-                        *yp = (EPI == EPI_RESID) ? (*yp + acc[i][j][v]) : acc[i][j][v];
-                    }
-                }
-            }
-        }
 }
 
 // ---------------------------------------------------------------- bf16 MFMA, 9..64 rows, pre-split activations
@@ -488,22 +370,6 @@ static void gemm_rows_launch(hipStream_t st, const bf16_t* W, int N, int K, cons
     else         hipLaunchKernelGGL((gemm_rows_kernel<2>), grid, block, 0, st, W, N, K, Xh, Xl, part);
 }
 
-// Y[m][n] (+)= sum_z part[z][m][n], slices added in ascending z
-template <int EPI>
-__global__ void splitk_reduce_kernel(const float* __restrict__ part, int KS, int M, int N, float* __restrict__ Y, int ldy) {
-    const size_t i = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
-    if (i >= (size_t)M * N) return;
-    const size_t m = i / N, n = i - m * N;           // N is a multiple of 4
-    float4 a = *reinterpret_cast<const float4*>(part + i);
-    for (int z = 1; z < KS; ++z) {
-        const float4 b = *reinterpret_cast<const float4*>(part + (size_t)z * M * N + i);
-        a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
-    }
-    float4* yp = reinterpret_cast<float4*>(Y + m * ldy + n);
-    if (EPI == EPI_RESID) { const float4 y = *yp; a.x += y.x; a.y += y.y; a.z += y.z; a.w += y.w; }
-    *yp = a;
-}
-
 // ---------------------------------------------------------------- dispatch
 static void gemm_launch(hipStream_t st, int epi, const float* W, int N, int K, const float* X, int ldx,
                         float* Y, int ldy, int M, float* part, size_t part_floats) {
@@ -514,37 +380,176 @@ static void gemm_launch(hipStream_t st, int epi, const float* W, int N, int K, c
     else                  hipLaunchKernelGGL((sgemm_nt_kernel<EPI_STORE>), grid, block, 0, st, W, N, K, X, ldx, Y, ldy, M);
 }
 
-template <int BM, int BN>
-static void gemm_bf16_launch(hipStream_t st, int epi, const bf16_t* W, int N, int K, const float* X, int ldx,
-                             float* Y, int ldy, int M, float* part, int KS) {
-    const dim3 grid((N + BN - 1) / BN, (M + BM - 1) / BM, KS), block(256);
-    if (epi == EPI_RESID) hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, EPI_RESID>), grid, block, 0, st, W, N, K, X, ldx, Y, ldy, M, part);
-    else                  hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, EPI_STORE>), grid, block, 0, st, W, N, K, X, ldx, Y, ldy, M, part);
-    if (KS > 1) {
-        const unsigned nb = (unsigned)(((size_t)M * N / 4 + 255) / 256);
-        if (epi == EPI_RESID) hipLaunchKernelGGL((splitk_reduce_kernel<EPI_RESID>), dim3(nb), block, 0, st, part, KS, M, N, Y, ldy);
-        else                  hipLaunchKernelGGL((splitk_reduce_kernel<EPI_STORE>), dim3(nb), block, 0, st, part, KS, M, N, Y, ldy);
+// ---------------------------------------------------------------- bf16 MFMA, many rows, pre-split activations
+// Y[m][n] (+)= sum_k (Xh + Xl)[m][k] * W[n][k] for more than 64 rows (prefill chunks, large decode batches).
+// Block tile 128 (m) x 256 (n), four waves of 64 x 128 (2 x 4 MFMA tiles of 32x32x16, hi and lo pass on
+// each: 32 MFMAs against 16 operand reads of 16 bytes per K block of 32).  LDS holds two stages of
+// [rows][32 k] tiles (Xh, Xl, W), chunks of 16 bytes permuted by (row / 4) % 4 so that both the
+// line-wise writes and the operand reads are conflict-free without padding.  While one stage is
+// multiplied the next one is already on its way from global memory in registers.  gridDim.z > 1 cuts K into
+// slices whose partial tiles go to part[z][M][N] (finished by rows_finish_kernel).
+template <int EPI>
+__global__ __launch_bounds__(256, 2) void gemm_tile_kernel(const bf16_t* __restrict__ W, int N, int K,
+                                                           const uint16_t* __restrict__ Xh,
+                                                           const uint16_t* __restrict__ Xl, int M,
+                                                           float* __restrict__ Y, int ldy,
+                                                           float* __restrict__ part) {
+    constexpr int BM = 128, BN = 256, BK = 32;
+    __shared__ __attribute__((aligned(16))) uint16_t Ah[2][BM * BK];
+    __shared__ __attribute__((aligned(16))) uint16_t Al[2][BM * BK];
+    __shared__ __attribute__((aligned(16))) uint16_t Bs[2][BN * BK];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;                 // wave tile: rows wm*64.., columns wn*128..
+    const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+    const int nkb = K / BK;
+    const int per = (nkb + gridDim.z - 1) / gridDim.z;
+    const int kb0 = blockIdx.z * per, kb1 = min(nkb, kb0 + per);
+    const int nk = kb1 - kb0;
+    const int kb_last = max(kb1 - 1, 0);
+    // LDS offset (in bf16) of 16-byte chunk c (0..3) of row r
+    auto sw = [](int r, int c) { return r * BK + ((c ^ ((r >> 2) & 3)) << 3); };
+    // global -> LDS copies: thread -> chunk tid % 4 of rows tid / 4 + 64 i
+    const int crow = tid >> 2, cch = tid & 3;
+    const uint16_t* ah0 = Xh + (size_t)min(m0 + crow, M - 1) * K + cch * 8;
+    const uint16_t* ah1 = Xh + (size_t)min(m0 + crow + 64, M - 1) * K + cch * 8;
+    const uint16_t* al0 = Xl + (size_t)min(m0 + crow, M - 1) * K + cch * 8;
+    const uint16_t* al1 = Xl + (size_t)min(m0 + crow + 64, M - 1) * K + cch * 8;
+    const bf16_t* b0 = W + (size_t)min(n0 + crow, N - 1) * K + cch * 8;
+    const bf16_t* b1 = W + (size_t)min(n0 + crow + 64, N - 1) * K + cch * 8;
+    const bf16_t* b2 = W + (size_t)min(n0 + crow + 128, N - 1) * K + cch * 8;
+    const bf16_t* b3 = W + (size_t)min(n0 + crow + 192, N - 1) * K + cch * 8;
+    const int st0 = sw(crow, cch), st1 = sw(crow + 64, cch), st2 = sw(crow + 128, cch), st3 = sw(crow + 192, cch);
+
+    f32x16_t acc[2][4];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+    // two register sets named member by member: a K block is requested two steps before it moves into LDS
+    struct Regs { u32x4_t h0, h1, l0, l1, b0, b1, b2, b3; };
+    Regs ra, rb;
+#define RSD_FETCH(kb, R)                                                                         \
+    {                                                                                            \
+        const size_t k0_ = (size_t)min((kb), kb_last) * BK;                                      \
+        R.h0 = *reinterpret_cast<const u32x4_t*>(ah0 + k0_);                                     \
+        R.h1 = *reinterpret_cast<const u32x4_t*>(ah1 + k0_);                                     \
+        R.l0 = *reinterpret_cast<const u32x4_t*>(al0 + k0_);                                     \
+        R.l1 = *reinterpret_cast<const u32x4_t*>(al1 + k0_);                                     \
+        R.b0 = *reinterpret_cast<const u32x4_t*>(b0 + k0_);                                      \
+        R.b1 = *reinterpret_cast<const u32x4_t*>(b1 + k0_);                                      \
+        R.b2 = *reinterpret_cast<const u32x4_t*>(b2 + k0_);                                      \
+        R.b3 = *reinterpret_cast<const u32x4_t*>(b3 + k0_);                                      \
     }
+#define RSD_STAGE(buf, R)                                                                        \
+    {                                                                                            \
+        *reinterpret_cast<u32x4_t*>(&Ah[(buf)][st0]) = R.h0;                                     \
+        *reinterpret_cast<u32x4_t*>(&Ah[(buf)][st1]) = R.h1;                                     \
+        *reinterpret_cast<u32x4_t*>(&Al[(buf)][st0]) = R.l0;                                     \
+        *reinterpret_cast<u32x4_t*>(&Al[(buf)][st1]) = R.l1;                                     \
+        *reinterpret_cast<u32x4_t*>(&Bs[(buf)][st0]) = R.b0;                                     \
+        *reinterpret_cast<u32x4_t*>(&Bs[(buf)][st1]) = R.b1;                                     \
+        *reinterpret_cast<u32x4_t*>(&Bs[(buf)][st2]) = R.b2;                                     \
+        *reinterpret_cast<u32x4_t*>(&Bs[(buf)][st3]) = R.b3;                                     \
+    }
+    const int l32 = lane & 31, kg = lane >> 5;
+#define RSD_COMPUTE(buf)                                                                         \
+    {                                                                                            \
+        _Pragma("unroll") for (int kk_ = 0; kk_ < 2; ++kk_) {                                    \
+            bf16x8_t a_[2], l_[2], b_[4];                                                        \
+            _Pragma("unroll") for (int i_ = 0; i_ < 2; ++i_) {                                   \
+                const int off_ = sw(wm * 64 + i_ * 32 + l32, kk_ * 2 + kg);                      \
+                a_[i_] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t*>(&Ah[(buf)][off_])); \
+                l_[i_] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t*>(&Al[(buf)][off_])); \
+            }                                                                                    \
+            _Pragma("unroll") for (int j_ = 0; j_ < 4; ++j_)                                     \
+                b_[j_] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t*>(&Bs[(buf)][sw(wn * 128 + j_ * 32 + l32, kk_ * 2 + kg)])); \
+            /* all lo passes, then all hi passes: two MFMAs on one accumulator are eight apart */ \
+            _Pragma("unroll") for (int i_ = 0; i_ < 2; ++i_)                                     \
+                _Pragma("unroll") for (int j_ = 0; j_ < 4; ++j_)                                 \
+                    acc[i_][j_] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(l_[i_], b_[j_], acc[i_][j_], 0, 0, 0); \
+            _Pragma("unroll") for (int i_ = 0; i_ < 2; ++i_)                                     \
+                _Pragma("unroll") for (int j_ = 0; j_ < 4; ++j_)                                 \
+                    acc[i_][j_] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_[i_], b_[j_], acc[i_][j_], 0, 0, 0); \
+        }                                                                                        \
+    }
+    RSD_FETCH(kb0, ra)
+    RSD_FETCH(kb0 + 1, rb)
+    RSD_STAGE(0, ra)
+    __syncthreads();
+    // step i: block i + 2 is requested into the set F that block i came from, block i is multiplied,
+    // block i + 1 (set S, requested a step ago) moves into the LDS buffer block i - 1 has left
+#define RSD_STEP(i_step, F, S)                                                                   \
+    {                                                                                            \
+        RSD_FETCH(kb0 + (i_step) + 2, F)                                                         \
+        RSD_COMPUTE((i_step) & 1)                                                                \
+        RSD_STAGE(((i_step) + 1) & 1, S)                                                         \
+        __syncthreads();                                                                         \
+    }
+    int i = 0;
+    for (; i + 1 < nk; i += 2) {
+        RSD_STEP(i, ra, rb)
+        RSD_STEP(i + 1, rb, ra)
+    }
+    if (i < nk) RSD_STEP(i, ra, rb)
+#undef RSD_STEP
+#undef RSD_FETCH
+#undef RSD_STAGE
+#undef RSD_COMPUTE
+
+    const bool sliced = gridDim.z > 1;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int n = n0 + wn * 128 + j * 32 + l32;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int m = m0 + wm * 64 + i * 32 + 8 * (v >> 2) + 4 * kg + (v & 3);
+                if (m < M && n < N) {
+                    if (sliced) {
+                        part[((size_t)blockIdx.z * M + m) * N + n] = acc[i][j][v];
+                    } else {
+                        float* yp = Y + (size_t)m * ldy + n;
+                        *yp = (EPI == EPI_RESID) ? (*yp + acc[i][j][v]) : acc[i][j][v];
+                    }
+                }
+            }
+        }
 }
 
-static void gemm_launch(hipStream_t st, int epi, const bf16_t* W, int N, int K, const float* X, int ldx,
-                        float* Y, int ldy, int M, float* part, size_t part_floats) {
-    if (M <= 8) { gemv_launch<bf16_t>(st, PRO_NONE, epi, W, N, K, X, ldx, nullptr, 0.f, Y, ldy, M); return; }
-    // Tiles: 64 rows of activations when there are few; narrow weight tiles and K slices until
-    // about two blocks per compute unit exist (these shapes are bound by streaming W once).
-    const int bm = M <= 64 ? 64 : 128;
-    const int tm = (M + bm - 1) / bm;
-    int bn = 128;
-    if (((N + 127) / 128) * tm < 512) bn = 64;
-    const int tiles = ((N + bn - 1) / bn) * tm;
+// K slices for gemm_tile_kernel: as many as bring the grid to about 512 blocks, none below 8 K blocks
+static int gemm_tile_slices(int N, int K, int M, size_t part_floats) {
+    const int tiles = ((N + 255) / 256) * ((M + 127) / 128);
     int ks = 1;
-    while (ks < 16 && tiles * ks < 512 && K / (ks * 2) >= 512 && (size_t)(ks * 2) * M * N <= part_floats) ks *= 2;
-    if (!part) ks = 1;
-    if (bm == 64) {
-        if (bn == 64) gemm_bf16_launch<64, 64>(st, epi, W, N, K, X, ldx, Y, ldy, M, part, ks);
-        else          gemm_bf16_launch<64, 128>(st, epi, W, N, K, X, ldx, Y, ldy, M, part, ks);
-    } else {
-        if (bn == 64) gemm_bf16_launch<128, 64>(st, epi, W, N, K, X, ldx, Y, ldy, M, part, ks);
-        else          gemm_bf16_launch<128, 128>(st, epi, W, N, K, X, ldx, Y, ldy, M, part, ks);
-    }
+    while (ks < 32 && tiles * ks < 512 && K / 32 / (ks * 2) >= 8 && (size_t)(ks * 2) * M * N <= part_floats) ks *= 2;
+    return ks;
+}
+
+static void gemm_tile_launch(hipStream_t st, int epi, const bf16_t* W, int N, int K, const uint16_t* Xh,
+                             const uint16_t* Xl, int M, float* Y, int ldy, float* part, int ks) {
+    const dim3 grid((N + 255) / 256, (M + 127) / 128, ks), block(256);
+    if (epi == EPI_RESID) hipLaunchKernelGGL((gemm_tile_kernel<EPI_RESID>), grid, block, 0, st, W, N, K, Xh, Xl, M, Y, ldy, part);
+    else                  hipLaunchKernelGGL((gemm_tile_kernel<EPI_STORE>), grid, block, 0, st, W, N, K, Xh, Xl, M, Y, ldy, part);
+}
+
+// act = silu(gate) * up for gu[M][2F] = [gate | up], written as hi + lo bf16 halves [M][F]
+__global__ void swiglu_split_kernel(const float* __restrict__ gu, int F, uint16_t* __restrict__ Oh,
+                                    uint16_t* __restrict__ Ol, size_t total) {
+    const size_t i = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
+    if (i >= total) return;
+    const size_t r = i / F, f = i - r * F;
+    const float4 g = *reinterpret_cast<const float4*>(gu + r * 2 * F + f);
+    const float4 u = *reinterpret_cast<const float4*>(gu + r * 2 * F + F + f);
+    const float x[4] = {g.x / (1.0f + expf(-g.x)) * u.x, g.y / (1.0f + expf(-g.y)) * u.y,
+                        g.z / (1.0f + expf(-g.z)) * u.z, g.w / (1.0f + expf(-g.w)) * u.w};
+    uint16_t hi[4], lo[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { hi[e] = f2bf(x[e]); lo[e] = f2bf(x[e] - bf2f(hi[e])); }
+    *reinterpret_cast<uint2*>(Oh + i) =
+        make_uint2((uint32_t)hi[0] | ((uint32_t)hi[1] << 16), (uint32_t)hi[2] | ((uint32_t)hi[3] << 16));
+    *reinterpret_cast<uint2*>(Ol + i) =
+        make_uint2((uint32_t)lo[0] | ((uint32_t)lo[1] << 16), (uint32_t)lo[2] | ((uint32_t)lo[3] << 16));
 }

@@ -10,6 +10,7 @@
 #include <cstdio>
 #include <cstring>
 #include <string>
+#include <type_traits>
 #include <vector>
 
 #include "rsd.h"
@@ -85,7 +86,7 @@ struct rsd_ctx {
     float *h = nullptr, *xn = nullptr, *qkv = nullptr, *att = nullptr, *gu = nullptr, *act = nullptr;
     float *part_acc = nullptr, *part_ml = nullptr;
     float* part_k = nullptr;         // K-slice partial sums of few-row GEMMs
-    uint16_t *xs_h = nullptr, *xs_l = nullptr;   // [64][widest K]: hi / lo bf16 halves of the activations of a 9..64-row GEMM
+    uint16_t *xs_h = nullptr, *xs_l = nullptr;   // [rows][widest K]: hi / lo bf16 halves of the activations of the MFMA GEMMs
     size_t part_k_floats = 0;
     // sampler workspace (per row: block maxima, histograms of the three radix levels, block masses, selections)
     int smp_rows = 0;
@@ -388,38 +389,58 @@ void launch_attn_prefill_mfma(rsd_ctx* c, const Model& m, int l, const RowMap& r
 #undef RSD_ATTN_CASE
 }
 
-// 9..64 rows over bf16 weights whose K is a multiple of 64: the weight-streaming MFMA kernel on
-// activations split into hi + lo bf16 halves (held in c->xs_h / c->xs_l between the launches)
+// More than 8 rows over bf16 weights: MFMA kernels on activations split into hi + lo bf16 halves, which
+// live in c->xs_h / c->xs_l between the launches (9..64 rows: weight-streaming kernel; more: tile kernel)
 template <typename WT>
 bool rows_path(const Model& m, int M) {
-    return std::is_same<WT, bf16_t>::value && M > 8 && M <= 64 && m.s.d_model % 64 == 0 && m.q_dim % 64 == 0 &&
-           m.s.d_ffn % 64 == 0 && m.s.vocab % 4 == 0;
+    return std::is_same<WT, bf16_t>::value && M > 8 && m.s.d_model % 64 == 0 && m.q_dim % 64 == 0 && m.s.d_ffn % 64 == 0;
 }
 // x (fp32 rows, optionally through RMSNorm with `gain`) -> the hi / lo halves
 void rows_split(rsd_ctx* c, const float* X, int ldx, int M, int K, const bf16_t* gain, float eps) {
     hipLaunchKernelGGL((split_rows_kernel<bf16_t>), dim3(M), dim3(256), 0, c->st, X, ldx, K, gain, eps, c->xs_h, c->xs_l);
 }
-// Y (+)= halves . W^T with epilogue `epi`; EPI_SWIGLU (N = 2F) writes the activated values back as halves
-// next_gain != nullptr (EPI_RESID, N <= 8192): the finish also emits RMSNorm(Y row) * next_gain as the halves
-// for the projection that follows
+template <int EPI>
+void rows_finish(rsd_ctx* c, int ks, int rows, int M, int N, float* Y, int ldy) {
+    const int NO = EPI == EPI_SWIGLU ? N / 2 : N;
+    const dim3 grid((unsigned)(((size_t)M * NO / 4 + 255) / 256)), block(256);
+    hipLaunchKernelGGL((rows_finish_kernel<EPI>), grid, block, 0, c->st, c->part_k, ks, rows, M, N, Y, ldy, c->xs_h, c->xs_l);
+}
+// Y (+)= halves . W^T with epilogue `epi`; EPI_SWIGLU (N = 2F) writes the activated values back as halves.
+// next_gain != nullptr (EPI_RESID): RMSNorm(Y row) * next_gain is left in the halves for the projection that
+// follows (inside the finish kernel where there is one and N <= 8192).
 void rows_gemm(rsd_ctx* c, int epi, const bf16_t* W, int N, int K, int M, float* Y, int ldy,
                const bf16_t* next_gain = nullptr, float eps = 0.f) {
-    const int rows = M <= 32 ? 32 : 64;
-    const int ks = gemm_rows_slices(N, K, rows, c->part_k_floats);
-    gemm_rows_launch(c->st, W, N, K, c->xs_h, c->xs_l, M, c->part_k, ks);
-    if (next_gain) {
+    const bool few = M <= 64 && N % 4 == 0;
+    const int rows = few ? (M <= 32 ? 32 : 64) : M;          // rows of one slice of partial results
+    int ks;
+    if (few) {
+        ks = gemm_rows_slices(N, K, rows, c->part_k_floats);
+        gemm_rows_launch(c->st, W, N, K, c->xs_h, c->xs_l, M, c->part_k, ks);
+    } else {
+        ks = N % 4 ? 1 : gemm_tile_slices(N, K, M, c->part_k_floats);
+        if (ks == 1) {      // the tile kernel finishes by itself
+            if (epi == EPI_SWIGLU) {
+                gemm_tile_launch(c->st, EPI_STORE, W, N, K, c->xs_h, c->xs_l, M, c->gu, N, nullptr, 1);
+                const size_t total = (size_t)M * (N / 2);
+                hipLaunchKernelGGL(swiglu_split_kernel, dim3((unsigned)((total / 4 + 255) / 256)), dim3(256), 0, c->st,
+                                   c->gu, N / 2, c->xs_h, c->xs_l, total);
+            } else {
+                gemm_tile_launch(c->st, epi, W, N, K, c->xs_h, c->xs_l, M, Y, ldy, nullptr, 1);
+                if (next_gain) rows_split(c, Y, ldy, M, N, next_gain, eps);
+            }
+            return;
+        }
+        gemm_tile_launch(c->st, EPI_STORE, W, N, K, c->xs_h, c->xs_l, M, nullptr, 0, c->part_k, ks);
+    }
+    if (next_gain && N <= 8192) {
         hipLaunchKernelGGL((rows_finish_norm_kernel<bf16_t>), dim3(M), dim3(1024), 0, c->st, c->part_k, ks, rows, N, Y, ldy,
                            next_gain, eps, c->xs_h, c->xs_l);
         return;
     }
-    const int NO = epi == EPI_SWIGLU ? N / 2 : N;
-    const dim3 grid((unsigned)(((size_t)M * NO / 4 + 255) / 256)), block(256);
-    if (epi == EPI_SWIGLU)
-        hipLaunchKernelGGL((rows_finish_kernel<EPI_SWIGLU>), grid, block, 0, c->st, c->part_k, ks, rows, M, N, Y, ldy, c->xs_h, c->xs_l);
-    else if (epi == EPI_RESID)
-        hipLaunchKernelGGL((rows_finish_kernel<EPI_RESID>), grid, block, 0, c->st, c->part_k, ks, rows, M, N, Y, ldy, c->xs_h, c->xs_l);
-    else
-        hipLaunchKernelGGL((rows_finish_kernel<EPI_STORE>), grid, block, 0, c->st, c->part_k, ks, rows, M, N, Y, ldy, c->xs_h, c->xs_l);
+    if (epi == EPI_SWIGLU) rows_finish<EPI_SWIGLU>(c, ks, rows, M, N, Y, ldy);
+    else if (epi == EPI_RESID) rows_finish<EPI_RESID>(c, ks, rows, M, N, Y, ldy);
+    else rows_finish<EPI_STORE>(c, ks, rows, M, N, Y, ldy);
+    if (next_gain) rows_split(c, Y, ldy, M, N, next_gain, eps);
 }
 void rows_split(rsd_ctx*, const float*, int, int, int, const float*, float) {}    // fp32 weights never take this path
 void rows_gemm(rsd_ctx*, int, const float*, int, int, int, float*, int, const float* = nullptr, float = 0.f) {}
@@ -434,7 +455,7 @@ void run_layers(rsd_ctx* c, Model& m, int M, const RowMap& rm, bool decode) {
     const int S = decode ? m.splits : 1;
     const bool fused = M <= 8;   // few rows: norm / SwiGLU / residual folded into the weight-streaming kernels
     const bool rows = rows_path<WT>(m, M);
-    const bool rows_fuse_norm = rows && d <= 8192;          // residual finish + next RMSNorm in one kernel
+    const bool rows_fuse_norm = rows;                        // the residual GEMMs leave RMSNorm(h) for the next projection
     // batched decode: the attention kernel (or its merge kernel) writes the output as hi / lo halves itself
     const bool att_halves = rows && decode && m.s.dtype == RSD_BF16 && m.hd == 128;
     // single-row decode over a bf16 cache: the output projection merges the attention splits itself
@@ -451,7 +472,7 @@ void run_layers(rsd_ctx* c, Model& m, int M, const RowMap& rm, bool decode) {
             // (after the first layer the halves of RMSNorm(h) come from the previous layer's last finish)
             if (l == 0 || !rows_fuse_norm) rows_split(c, c->h, d, M, d, wptr<WT>(m, o.attn_norm), eps);
             rows_gemm(c, EPI_STORE, wptr<WT>(m, o.wqkv), m.n_qkv, d, M, c->qkv, m.n_qkv);
-        } else {
+        } else if constexpr (std::is_same<WT, float>::value) {
             hipLaunchKernelGGL((rmsnorm_kernel<WT>), dim3(M), dim3(256), 0, st, c->h, d, wptr<WT>(m, o.attn_norm), eps, c->xn);
             gemm_launch(st, EPI_STORE, wptr<WT>(m, o.wqkv), m.n_qkv, d, c->xn, d, c->qkv, m.n_qkv, M, c->part_k, c->part_k_floats);
         }
@@ -516,7 +537,7 @@ void run_layers(rsd_ctx* c, Model& m, int M, const RowMap& rm, bool decode) {
                 rows_gemm(c, EPI_RESID, wptr<WT>(m, o.wdown), d, F, M, c->h, d, wptr<WT>(m, m.layers[l + 1].attn_norm), eps);
             else
                 rows_gemm(c, EPI_RESID, wptr<WT>(m, o.wdown), d, F, M, c->h, d);
-        } else {
+        } else if constexpr (std::is_same<WT, float>::value) {
             gemm_launch(st, EPI_RESID, wptr<WT>(m, o.wo), d, m.q_dim, c->att, m.q_dim, c->h, d, M, c->part_k, c->part_k_floats);
             hipLaunchKernelGGL((rmsnorm_kernel<WT>), dim3(M), dim3(256), 0, st, c->h, d, wptr<WT>(m, o.ffn_norm), eps, c->xn);
             gemm_launch(st, EPI_STORE, wptr<WT>(m, o.wgu), 2 * F, d, c->xn, d, c->gu, 2 * F, M, c->part_k, c->part_k_floats);
@@ -538,7 +559,7 @@ void lm_head(rsd_ctx* c, Model& m, const float* X, int M, float* Y, int ldy) {
     } else if (rows_path<WT>(m, M)) {
         rows_split(c, X, d, M, d, wptr<WT>(m, m.off_final_norm), m.s.rms_eps);
         rows_gemm(c, EPI_STORE, wptr<WT>(m, m.off_head), V, d, M, Y, ldy);
-    } else {
+    } else if constexpr (std::is_same<WT, float>::value) {
         for (int r0 = 0; r0 < M; r0 += kMaxRows) {
             const int mm = std::min(kMaxRows, M - r0);
             hipLaunchKernelGGL((rmsnorm_kernel<WT>), dim3(mm), dim3(256), 0, c->st, X + (size_t)r0 * d, d,
@@ -845,11 +866,11 @@ int rsd_init(rsd_ctx** out, const rsd_model_shape shape[3], const rsd_weights w[
     c->part_k_floats = (size_t)48 << 20;
     HIPCHK(c, dev_alloc(&c->part_k, c->part_k_floats));
     {
-        const size_t kmax = (size_t)std::max(std::max(d, qd), F);
-        HIPCHK(c, dev_alloc(&c->xs_h, 64 * kmax));
-        HIPCHK(c, dev_alloc(&c->xs_l, 64 * kmax));
-        HIPCHK(c, hipMemsetAsync(c->xs_h, 0, 64 * kmax * sizeof(uint16_t), c->st));
-        HIPCHK(c, hipMemsetAsync(c->xs_l, 0, 64 * kmax * sizeof(uint16_t), c->st));
+        const size_t kmax = (size_t)std::max(std::max(d, qd), F), xr = std::max<size_t>(R, 64);
+        HIPCHK(c, dev_alloc(&c->xs_h, xr * kmax));
+        HIPCHK(c, dev_alloc(&c->xs_l, xr * kmax));
+        HIPCHK(c, hipMemsetAsync(c->xs_h, 0, xr * kmax * sizeof(uint16_t), c->st));
+        HIPCHK(c, hipMemsetAsync(c->xs_l, 0, xr * kmax * sizeof(uint16_t), c->st));
     }
     c->smp_rows = std::max(B, 64);
     HIPCHK(c, dev_alloc(&c->smp_pmax, (size_t)c->smp_rows * SMP_NB));
