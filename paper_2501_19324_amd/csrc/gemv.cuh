@@ -9,9 +9,15 @@
 // and the result is either stored or added to Y (residual stream).
 #pragma once
 #include <algorithm>
+#include <hip/hip_ext.h>
 #include "common.cuh"
 
 enum { PRO_NONE = 0, PRO_NORM = 1, PRO_SWIGLU = 2, PRO_ATTN = 3 };
+
+// Timing hook: when set, the next single-row launch carries these two events in its own dispatch packet
+// (start and end of the kernel itself, no dispatch gap in between) and clears the hook.
+struct GemvTiming { hipEvent_t start = nullptr, stop = nullptr; };
+static thread_local GemvTiming gemv_timing;
 
 // Partial attention results of one row, one per (head, split): unnormalised sums [H][S][128] and
 // (running maximum, sum of weights) pairs [H][S][2].  PRO_ATTN merges them while staging x.
@@ -493,8 +499,15 @@ static bool gemv_launch_flat(hipStream_t st, int pro, int epi, const WT* W, int 
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)kGemvFullLds);        \
             raised = true;                                                                                   \
         }                                                                                                    \
-        hipLaunchKernelGGL((gemv_flat_kernel<WT, NW, U, P, E>), dim3(G), dim3(NW * 64), lds, st, W, N, K, X, \
-                           gain, eps, Y, magic, parts);                                                      \
+        if (gemv_timing.start) {                                                                             \
+            hipExtLaunchKernelGGL((gemv_flat_kernel<WT, NW, U, P, E>), dim3(G), dim3(NW * 64), lds, st,      \
+                                  gemv_timing.start, gemv_timing.stop, 0, W, N, K, X, gain, eps, Y, magic,   \
+                                  parts);                                                                    \
+            gemv_timing = GemvTiming{};                                                                      \
+        } else {                                                                                             \
+            hipLaunchKernelGGL((gemv_flat_kernel<WT, NW, U, P, E>), dim3(G), dim3(NW * 64), lds, st, W, N,   \
+                               K, X, gain, eps, Y, magic, parts);                                            \
+        }                                                                                                    \
         return true;                                                                                         \
     }
     RSD_GEMVFLAT_CASE(PRO_NONE, EPI_STORE)

@@ -298,19 +298,28 @@ void launch_attn_g(rsd_ctx* c, const Model& m, int l, int M, const RowMap& rm, i
 // Brackets one launch with a pair of events when the probe is armed for it.
 struct ProbeScope {
     rsd_ctx* c;
-    bool on = false;
-    ProbeScope(rsd_ctx* c_, const Model& m, int op, long long bytes) : c(c_) {
+    bool on = false, direct = false;
+    // direct: the launch inside the scope is a single-row projection, which can carry the events in its
+    // own dispatch packet (kernel start to kernel end); otherwise the events are recorded around it
+    ProbeScope(rsd_ctx* c_, const Model& m, int op, long long bytes, bool direct_ = false) : c(c_), direct(direct_) {
         if (c->probe_op != op || &m != &c->m[c->probe_model < 0 ? 0 : c->probe_model] || c->probe_model < 0) return;
         if (c->probe_used + 2 > c->probe_ev.size()) return;
         if (c->in_decode_loop) { if (!c->probe_iter_on) return; }
         else if (c->probe_seen++ % c->probe_stride) return;
         on = true;
         c->probe_bytes = bytes;
-        (void)hipEventRecord(c->probe_ev[c->probe_used], c->st);
+        if (direct) gemv_timing = GemvTiming{c->probe_ev[c->probe_used], c->probe_ev[c->probe_used + 1]};
+        else (void)hipEventRecord(c->probe_ev[c->probe_used], c->st);
     }
     ~ProbeScope() {
         if (!on) return;
-        (void)hipEventRecord(c->probe_ev[c->probe_used + 1], c->st);
+        if (direct) {
+            const bool taken = gemv_timing.start == nullptr;    // the launcher clears the hook when it uses it
+            gemv_timing = GemvTiming{};
+            if (!taken) return;                                  // another kernel served this shape: no sample
+        } else {
+            (void)hipEventRecord(c->probe_ev[c->probe_used + 1], c->st);
+        }
         c->probe_used += 2;
     }
 };
@@ -465,7 +474,7 @@ void run_layers(rsd_ctx* c, Model& m, int M, const RowMap& rm, bool decode) {
         const LayerOff& o = m.layers[l];
         const long long esz = sizeof(WT);
         if (fused) {
-            ProbeScope ps(c, m, 0, (long long)m.n_qkv * d * esz + 4LL * M * (d + m.n_qkv));
+            ProbeScope ps(c, m, 0, (long long)m.n_qkv * d * esz + 4LL * M * (d + m.n_qkv), M == 1);
             gemv_launch<WT>(st, PRO_NORM, EPI_STORE, wptr<WT>(m, o.wqkv), m.n_qkv, d, c->h, d,
                             wptr<WT>(m, o.attn_norm), eps, c->qkv, m.n_qkv, M);
         } else if (rows) {
@@ -494,7 +503,7 @@ void run_layers(rsd_ctx* c, Model& m, int M, const RowMap& rm, bool decode) {
         }
         if (fused) {
             {
-                ProbeScope ps(c, m, 1, (long long)d * m.q_dim * esz + 4LL * M * (m.q_dim + 2 * d));
+                ProbeScope ps(c, m, 1, (long long)d * m.q_dim * esz + 4LL * M * (m.q_dim + 2 * d), M == 1);
                 if (parts_to_o)
                     gemv_launch_attn<WT>(st, wptr<WT>(m, o.wo), d, m.q_dim, AttnParts{c->part_acc, c->part_ml, S}, c->h);
                 else
@@ -503,12 +512,12 @@ void run_layers(rsd_ctx* c, Model& m, int M, const RowMap& rm, bool decode) {
             }
             if (gemv_can_fuse_swiglu(M, d) && gemv_can_fuse_swiglu(M, F)) {
                 {
-                    ProbeScope ps(c, m, 2, 2LL * F * d * esz + 4LL * M * (d + F));
+                    ProbeScope ps(c, m, 2, 2LL * F * d * esz + 4LL * M * (d + F), M == 1);
                     gemv_launch<WT>(st, PRO_NORM, EPI_SWIGLU, wptr<WT>(m, o.wgu), F, d, c->h, d,
                                     wptr<WT>(m, o.ffn_norm), eps, c->act, F, M);
                 }
                 {
-                    ProbeScope ps(c, m, 3, (long long)d * F * esz + 4LL * M * (F + 2 * d));
+                    ProbeScope ps(c, m, 3, (long long)d * F * esz + 4LL * M * (F + 2 * d), M == 1);
                     gemv_launch<WT>(st, PRO_NONE, EPI_RESID, wptr<WT>(m, o.wdown), d, F, c->act, F,
                                     (const WT*)nullptr, 0.f, c->h, d, M);
                 }
@@ -553,7 +562,7 @@ template <typename WT>
 void lm_head(rsd_ctx* c, Model& m, const float* X, int M, float* Y, int ldy) {
     const int d = m.s.d_model, V = m.s.vocab;
     if (M <= 8) {
-        ProbeScope ps(c, m, 4, (long long)V * d * sizeof(WT) + 4LL * M * (d + V));
+        ProbeScope ps(c, m, 4, (long long)V * d * sizeof(WT) + 4LL * M * (d + V), M == 1);
         gemv_launch<WT>(c->st, PRO_NORM, EPI_STORE, wptr<WT>(m, m.off_head), V, d, X, d, wptr<WT>(m, m.off_final_norm),
                         m.s.rms_eps, Y, ldy, M);
     } else if (rows_path<WT>(m, M)) {
