@@ -265,3 +265,42 @@ def test_smallest_inputs(gpu, tiny, batch, plen, cap):
     w = workload("cfg0", batch=batch, prompt_len_min=plen, prompt_len_max=plen, step_cap=cap, max_steps=5,
                  sep_logit_bias=0.6, deltas=(0.5,))
     run_and_compare(gpu, tiny, w)
+
+
+@pytest.mark.parametrize("kind,a", [(0, 0.0), (3, 0.0)])
+def test_one_step_law_is_the_mixture_on_gpu(gpu, kind, a):
+    """Proposition 1 through the HIP path: with one-token steps the committed first token of a
+    sequence is distributed as omega_r P_m + nu P_M.  4096 sequences share one prompt and differ
+    only in their uniforms; P_m, P_M and the rewards come from the checker.  Vocabulary of 8 ids
+    so that 4096 draws settle every cell."""
+    from oracle import rsd_oracle as O
+    from rsd_inputs import workload, model_weights_np
+    R, torch = gpu["R"], gpu["torch"]
+    n = 4096
+    w0 = workload("cfg0", vocab=8, batch=n, prompt_len_min=6, prompt_len_max=6, step_cap=1, max_steps=1,
+                  temperature=1.0, top_p=1.0, sep_logit_bias=0.0, omega_kind=kind, omega_a=a)
+    models = [O.OracleModel(s, model_weights_np(w0.seed, i, s)) for i, s in enumerate(w0.shapes)]
+    from rsd_inputs import prompt_tokens
+    prompt = [int(t) for t in prompt_tokens(w0)[0, :6]]
+    p_m = O.softmax(O.lm_logits(models[0], O.forward_full(models[0], prompt)[-1]))
+    p_M = O.softmax(O.lm_logits(models[1], O.forward_full(models[1], prompt)[-1]))
+    rew = np.array([O.reward(models[2], O.forward_full(models[2], prompt + [i])[-1]) for i in range(8)])
+    delta = float(np.float32(np.median(rew)))
+    wts = np.array([O.omega(x, kind, delta, a) for x in rew])
+    assert 0 < wts.sum() < 8
+    expect, nu = O.mixture_distribution(p_m, p_M, wts)
+
+    from dataclasses import replace
+    w = replace(w0, deltas=(delta,))
+    s = gpu["Session"](w)
+    s.tokens_host[:, :6] = np.array(prompt, np.int32)[None, :]
+    s.tokens = torch.from_numpy(s.tokens_host).cuda()
+    s.reset()
+    g = R.rsd_step(s.ctx)
+    assert np.all(g["final_len"] == 1)
+    counts = np.bincount(g["final_tokens"][:, 0], minlength=8).astype(np.float64)
+    n_rej = int(np.sum(g["accepted"] == 0))
+    chi2 = np.sum((counts - n * expect) ** 2 / (n * expect))
+    assert chi2 < 35.0, (chi2, counts, n * expect)                 # 7 dof: P(chi2 > 35) ~ 1e-5
+    assert abs(n_rej / n - nu) < 5 * np.sqrt(nu * (1 - nu) / n), (n_rej / n, nu)
+    s.close()
