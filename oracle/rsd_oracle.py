@@ -277,6 +277,7 @@ class Params:
     omega_a: float = 0.0
     page_tokens: int = 16
     kv_dtype: str = "exact"      # "bf16": keys and values are stored rounded to bf16 (see KVCache)
+    merge: str = "none"          # "draft" / "target": the reward head sits on that model's trunk (Appendix "Model Merge")
 
 
 class _Runner:
@@ -340,7 +341,16 @@ def generate_sequence(draft: OracleModel, target: OracleModel, prm: OracleModel,
 
     Returns the committed tokens, the per-step records and, after every step,
     how many leading tokens each model holds keys/values for (the target is
-    only ever fed when a rejection needs it)."""
+    only ever fed when a rejection needs it).
+
+    P.merge = "draft" or "target" (Appendix "Model Merge": the reward model shares
+    every layer below the heads with a policy model and keeps only its own
+    projection): ``prm`` then contributes nothing but w_r and b_r, the reward is
+    read off the final-norm hidden state of that policy model at the step's last
+    token, and no third model or cache exists (its kv_len stays 0).  The policy
+    model is fed up to the last token for this; afterwards it drops that one
+    position again, so that its next use starts by feeding the last token, as
+    it would without the merge."""
     delta = float(np.float32(P.delta))       # the threshold is an fp32 argument
     tokens = [int(t) for t in prompt]
     rd = _Runner(draft, P.max_ctx, use_cache, P.kv_dtype)
@@ -357,7 +367,12 @@ def generate_sequence(draft: OracleModel, target: OracleModel, prm: OracleModel,
         ctx_pre = len(tokens)
         dm, fm = [], []
         draft_step = gen_step(rd, tokens, u_draft, P, dm)
-        r = reward(prm, rp.last_hidden(tokens))
+        if P.merge == "none":
+            r = reward(prm, rp.last_hidden(tokens))
+        else:
+            scorer = rd if P.merge == "draft" else rt
+            r = reward(prm, scorer.last_hidden(tokens))
+            scorer.truncate(len(tokens) - 1)
         ok = accept(r, P.omega_kind, delta, P.omega_a, float(u_gate[i]))
         if ok:
             final, fm = draft_step, dm
@@ -365,6 +380,8 @@ def generate_sequence(draft: OracleModel, target: OracleModel, prm: OracleModel,
             del tokens[ctx_pre:]
             rd.truncate(ctx_pre)
             rp.truncate(ctx_pre)
+            if P.merge == "target":
+                rt.truncate(ctx_pre - 1)
             final = gen_step(rt, tokens, u_target, P, fm)
         if P.eos_id >= 0 and P.eos_id in final:
             reason = FIN_EOS

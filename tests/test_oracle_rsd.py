@@ -347,3 +347,48 @@ def test_full_loop_with_one_token_steps_follows_the_mixture(tiny):
     chi2 = np.sum((counts - n * expect) ** 2 / (n * expect))
     assert chi2 < 35.0                                   # 7 dof: P(chi2 > 35) ~ 1e-5
     assert abs(n_rej / n - nu) < 5 * np.sqrt(nu * (1 - nu) / n)
+
+
+# ------------------------------------------------------------ merged trunk (Appendix "Model Merge")
+def merged_reward_model(policy, prm):
+    """A reward model that shares every layer below the heads with `policy` and keeps `prm`'s own
+    projection (cut or padded to the policy's width)."""
+    from dataclasses import replace
+    wv = {k: v for k, v in policy._w.items() if k != "lm_head"}
+    d = policy.s.d_model
+    w_r = np.zeros(d, np.float32)
+    n = min(d, prm._w["w_r"].size)
+    w_r[:n] = prm._w["w_r"][:n] * 40.0            # spread the rewards around 1/2 (the head is N(0, 0.02))
+    wv["w_r"], wv["b_r"] = w_r, prm._w["b_r"]
+    return O.OracleModel(replace(policy.s, head_kind=prm.s.head_kind), wv)
+
+
+@pytest.mark.parametrize("which", ["draft", "target"])
+def test_merged_trunk_equals_a_separate_reward_model_with_the_same_layers(tiny, which):
+    """With the reward head on a policy model's trunk the loop must produce what it produces with a
+    separate third model whose layers are copies of that trunk: the merged run reads the reward off
+    the policy model's own incremental forward, the separate run off an independent model with its
+    own cache fed in different chunks."""
+    d, t, p = tiny["models"]
+    pm = merged_reward_model(d if which == "draft" else t, p)
+    P = params(tiny["w"], temperature=0.7, top_p=0.95, sep_logit_bias=3.5, delta=0.5)
+    from dataclasses import replace
+    first = [run(tiny, b, P, models=(d, t, pm), max_steps=1)["records"][0]["reward"] for b in range(4)]
+    P = replace(P, delta=float(np.median(first)))             # a threshold that both accepts and rejects
+    n_acc = n_rej = 0
+    for b in range(4):
+        a = run(tiny, b, P, models=(d, t, pm))
+        m = run(tiny, b, replace(P, merge=which), models=(d, t, pm))
+        assert a["tokens"] == m["tokens"]
+        for ra, rm in zip(a["records"], m["records"]):
+            assert abs(ra["reward"] - rm["reward"]) < 1e-12
+            assert ra["accepted"] == rm["accepted"] and ra["final_tokens"] == rm["final_tokens"]
+            ctx = rm["ctx_len"]
+            assert rm["kv_len"][2] == 0                              # no third cache
+            assert rm["kv_len"][0] == (ctx - 1 if rm["accepted"] else rm["ctx_pre"])
+            if which == "target":
+                assert rm["kv_len"][1] == ctx - 1                    # the target has read every step
+            else:
+                assert rm["kv_len"][1] == ra["kv_len"][1]
+            n_acc += rm["accepted"]; n_rej += not rm["accepted"]
+    assert n_acc >= 2 and n_rej >= 2
