@@ -88,6 +88,8 @@ def main():
     ap.add_argument("--max-steps", type=int, default=0, help="stop each pass after this many reasoning steps (debugging)")
     ap.add_argument("--kv-pool-gb", default="", help="KV pool sizes in GB for draft,target,PRM (default: worst case)")
     ap.add_argument("--ops", action="store_true", help="extra passes after the timed region: per-projection table")
+    ap.add_argument("--merge", default="none", choices=["none", "draft", "target"],
+                    help="reward head on the draft's or the target's trunk instead of a third model (not the headline workload)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="before the timed region run a plain 256 MiB device copy kernel three times (reference "
                          "point for scaling hardware traffic counters)")
@@ -107,10 +109,14 @@ def main():
     if args.layers:
         kw["n_layers"] = args.layers
     w = workload(args.workload, **kw)
+    merge = {"none": 0, "draft": 1, "target": 2}[args.merge]
+    if merge:
+        from dataclasses import replace
+        w = replace(w, prm=replace(w.draft if merge == 1 else w.target, head_kind="reward"))
     delta = w.delta if args.delta is None else args.delta
     t_setup = time.time()
     pools = tuple(int(float(x) * 1e9) for x in args.kv_pool_gb.split(",")) if args.kv_pool_gb else (0, 0, 0)
-    s = Session(w, delta=delta, use_graphs=0 if args.no_graphs else 1, kv_pool_bytes=pools)
+    s = Session(w, delta=delta, use_graphs=0 if args.no_graphs else 1, kv_pool_bytes=pools, merge_prm=merge)
     torch.cuda.synchronize()
     t_setup = time.time() - t_setup
 
@@ -174,7 +180,7 @@ def main():
                                f"{w.target.n_layers}L-d{w.target.d_model}, PRM {w.prm.n_layers}L-d{w.prm.d_model}, "
                                f"vocab {w.draft.vocab}, prompts {w.prompt_len_min}-{w.prompt_len_max}, "
                                f"{w.max_steps} steps x <= {w.step_cap} tokens, T={w.temperature}, top_p={w.top_p}",
-                   "delta": delta, "committed_tokens_per_pass": tokens // max(args.steps, 1),
+                   "delta": delta, "merge_prm": args.merge, "committed_tokens_per_pass": tokens // max(args.steps, 1),
                    "accept_rate": round(acc / max(acc + rej, 1), 4), "draft_tokens": drafted, "target_tokens": targeted,
                    "stage_ms_per_pass": {k: round(v / args.steps, 2) for k, v in zip(("draft", "prm", "gate", "target"), stage)},
                    "decode_weight_stream_GBs": round(dec_bytes / dec_s / 1e9, 1) if dec_s > 0 else None,

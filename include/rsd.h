@@ -47,6 +47,14 @@ enum { RSD_OMEGA_BINARY = 0,    /* 1(r >= delta): the paper's default           
        RSD_OMEGA_CLIP = 2,      /* min(1, max(0, r))                                   */
        RSD_OMEGA_RATIO = 3,     /* max(0, r / (1 + r))                                 */
        RSD_OMEGA_LOGISTIC = 4   /* 1 / (1 + exp(-omega_a (r - delta)))                 */ };
+/* Model merge (Appendix "Model Merge"): the reward model may share every layer below the heads with a
+ * policy model and keep only its own projection.  NONE: three separate models.  DRAFT / TARGET: the reward
+ * is read off the final-norm hidden state of that model at the step's last token; shape[RSD_PRM] must
+ * then repeat that model's dimensions and dtype (head_kind RSD_HEAD_REWARD), weights[RSD_PRM] holds only
+ * w_r[d_model] followed by b_r (8 elements, the first is used), and no third KV cache exists
+ * (kv_len[RSD_PRM] stays 0).  After a step: DRAFT as without merge; TARGET: kv_len[RSD_TARGET] = ctx - 1
+ * for every sequence of the step (the target has read every committed token but the last). */
+enum { RSD_MERGE_NONE = 0, RSD_MERGE_DRAFT = 1, RSD_MERGE_TARGET = 2 };
 /* why a sequence stopped */
 enum { RSD_RUNNING = 0, RSD_FIN_EOS = 1, RSD_FIN_MAX_CTX = 2, RSD_FIN_MAX_STEPS = 3 };
 
@@ -91,7 +99,7 @@ typedef struct rsd_params {
     int32_t page_tokens;    /* tokens per KV page; must be 16 */
     uint64_t kv_pool_bytes[3]; /* KV page pool per model (draft, target, reward); 0: enough for batch * max_ctx */
     int32_t use_graphs;     /* 1: replay single-token decode iterations as HIP graphs */
-    int32_t reserved;
+    int32_t merge_prm;      /* RSD_MERGE_*: where the reward head sits */
 } rsd_params;
 
 /* Per-step record, all HOST buffers supplied by the caller (any may be NULL).

@@ -22,6 +22,7 @@ __all__ = ["RSD_OK", "RSD_EINVAL", "RSD_ENOMEM", "RSD_ESTATE", "RSD_EHIP", "RSD_
 
 RSD_OK, RSD_EINVAL, RSD_ENOMEM, RSD_ESTATE, RSD_EHIP = 0, -1, -2, -3, -4
 RSD_DRAFT, RSD_TARGET, RSD_PRM = 0, 1, 2
+RSD_MERGE_NONE, RSD_MERGE_DRAFT, RSD_MERGE_TARGET = 0, 1, 2
 EXPORTED_SYMBOLS = ["rsd_init", "rsd_set_prompts", "rsd_set_uniforms", "rsd_set_criterion", "rsd_step",
                     "rsd_generate", "rsd_export_state", "rsd_export_pages", "rsd_set_teacher",
                     "rsd_export_sampled", "rsd_forward", "rsd_sample", "rsd_stage_ms", "rsd_decode_stats", "rsd_probe_start", "rsd_probe_read",
@@ -50,7 +51,7 @@ class _Params(C.Structure):
                 ("eos_id", C.c_int32), ("step_cap", C.c_int32), ("max_steps", C.c_int32), ("max_ctx", C.c_int32),
                 ("temperature", C.c_float), ("top_p", C.c_float), ("sep_logit_bias", C.c_float),
                 ("page_tokens", C.c_int32), ("kv_pool_bytes", C.c_uint64 * 3), ("use_graphs", C.c_int32),
-                ("reserved", C.c_int32)]
+                ("merge_prm", C.c_int32)]
 
 
 class _StepOut(C.Structure):
@@ -127,8 +128,9 @@ def _shape_struct(s) -> _Shape:
 def rsd_init(shapes: Sequence, weights: Sequence, *, batch: int, delta: float, sep_id: int, step_cap: int,
              max_steps: int, max_ctx: int, eos_id: int = -1, temperature: float = 0.0, top_p: float = 1.0,
              sep_logit_bias: float = 0.0, omega_kind: int = 0, omega_a: float = 0.0, page_tokens: int = 16,
-             kv_pool_bytes=(0, 0, 0), use_graphs: int = 1, stream=None) -> Context:
-    """``weights``: three device tensors holding each model's blob."""
+             kv_pool_bytes=(0, 0, 0), use_graphs: int = 1, merge_prm: int = 0, stream=None) -> Context:
+    """``weights``: three device tensors holding each model's blob (with ``merge_prm`` the third holds
+    only the reward projection ``w_r`` and ``b_r``)."""
     import torch
 
     lib = load_library()
@@ -136,7 +138,7 @@ def rsd_init(shapes: Sequence, weights: Sequence, *, batch: int, delta: float, s
     sh = (_Shape * 3)(*[_shape_struct(s) for s in shapes])
     ws = (_Weights * 3)(*[_Weights(w.data_ptr(), w.numel() * w.element_size()) for w in weights])
     p = _Params(delta, omega_kind, omega_a, sep_id, eos_id, step_cap, max_steps, max_ctx, temperature, top_p,
-                sep_logit_bias, page_tokens, (C.c_uint64 * 3)(*[int(x) for x in kv_pool_bytes]), use_graphs, 0)
+                sep_logit_bias, page_tokens, (C.c_uint64 * 3)(*[int(x) for x in kv_pool_bytes]), use_graphs, merge_prm)
     st = stream if stream is not None else torch.cuda.current_stream()
     ctx.keep["weights"] = list(weights)
     ctx.keep["stream"] = st

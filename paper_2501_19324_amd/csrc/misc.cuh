@@ -114,7 +114,8 @@ struct SeqState {
 // then the rollback of rejected sequences to their pre-step context.
 __global__ void gate_kernel(SeqState st, int B, float delta, int omega_kind, float omega_a,
                             const float* __restrict__ u_gate, int max_steps, int step,
-                            const int* __restrict__ forced_accept, const int* __restrict__ in_step) {
+                            const int* __restrict__ forced_accept, const int* __restrict__ in_step,
+                            int merge) {
     const int b = blockIdx.x * blockDim.x + threadIdx.x;
     if (b >= B) return;
     if (!in_step[b]) { st.accepted[b] = 0; st.own_accept[b] = 0; st.active[b] = 0; return; }
@@ -137,7 +138,10 @@ __global__ void gate_kernel(SeqState st, int B, float delta, int omega_kind, flo
         const int pre = st.ctx_pre[b];
         st.ctx_len[b] = pre;
         st.kv_len[0 * B + b] = pre;     // draft: keys of the rejected step are dropped
-        st.kv_len[2 * B + b] = pre;     // reward model likewise
+        if (merge == 0) st.kv_len[2 * B + b] = pre;     // a separate reward model likewise
+        // a target that scored the step (reward head on its trunk, merge == 2) has read it too: back to
+        // the token before the step, which its regeneration feeds first
+        if (merge == 2) st.kv_len[1 * B + b] = pre - 1;
     }
     st.active[b] = !acc;                // the target stage runs on the rejected sequences
 }

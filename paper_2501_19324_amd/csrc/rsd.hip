@@ -144,7 +144,7 @@ hipError_t pin_alloc(T** p, size_t n) { return hipHostMalloc(reinterpret_cast<vo
 int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
 // ------------------------------------------------------------------ model set-up
-int setup_model(rsd_ctx* c, Model& m, const rsd_model_shape& s, const rsd_weights& w, int which) {
+int setup_model(rsd_ctx* c, Model& m, const rsd_model_shape& s, const rsd_weights& w, int which, bool head_only = false) {
     m.s = s;
     if (s.n_layers < 1 || s.d_model < 64 || s.n_heads < 1 || s.n_kv_heads < 1 || s.vocab < 2 || s.d_ffn < 64)
         return fail(c, RSD_EINVAL, "model %d: non-positive dimension", which);
@@ -181,6 +181,10 @@ int setup_model(rsd_ctx* c, Model& m, const rsd_model_shape& s, const rsd_weight
     m.off_head = off;
     if (s.head_kind == RSD_HEAD_LM) off += (size_t)s.vocab * d;
     else { off += d; m.off_br = off; off += 8; }
+    if (head_only) {     // merged reward model: the blob holds w_r and b_r only
+        m.layers.clear();
+        m.off_head = 0; m.off_br = d; off = d + 8;
+    }
     m.n_elts = off;
     if (!w.blob || w.nbytes < off * m.esz)
         return fail(c, RSD_EINVAL, "model %d: weight blob holds %llu bytes, %llu needed", which,
@@ -578,10 +582,12 @@ void lm_head(rsd_ctx* c, Model& m, const float* X, int M, float* Y, int ldy) {
     }
 }
 
+// `trunk` supplies the final RMSNorm (the reward model itself, or the policy model it is merged with)
 template <typename WT>
-void reward_rows(rsd_ctx* c, Model& m, const float* H, int n, const int* rows, float* out) {
+void reward_rows(rsd_ctx* c, Model& m, const float* H, int n, const int* rows, float* out, const Model* trunk = nullptr) {
+    const Model& t = trunk ? *trunk : m;
     hipLaunchKernelGGL((reward_head_kernel<WT>), dim3(n), dim3(256), 0, c->st, H, m.s.d_model, rows,
-                       wptr<WT>(m, m.off_final_norm), m.s.rms_eps, wptr<WT>(m, m.off_head), wptr<WT>(m, m.off_br), out);
+                       wptr<WT>(t, t.off_final_norm), t.s.rms_eps, wptr<WT>(m, m.off_head), wptr<WT>(m, m.off_br), out);
 }
 
 // Sample one token per row; with `ap` the chosen token is also appended to its sequence.
@@ -822,15 +828,27 @@ int rsd_init(rsd_ctx** out, const rsd_model_shape shape[3], const rsd_weights w[
     if (p->step_cap < 1 || p->max_steps < 1 || p->max_ctx < 2) return fail(c, RSD_EINVAL, "bad step_cap/max_steps/max_ctx");
     if (p->temperature < 0.f || p->top_p < 0.f || p->top_p > 1.f) return fail(c, RSD_EINVAL, "bad temperature/top_p");
     if (p->omega_kind < 0 || p->omega_kind > 4) return fail(c, RSD_EINVAL, "bad omega_kind");
+    if (p->merge_prm < RSD_MERGE_NONE || p->merge_prm > RSD_MERGE_TARGET) return fail(c, RSD_EINVAL, "bad merge_prm");
     for (int i = 0; i < 3; ++i) {
-        int rc = setup_model(c, c->m[i], shape[i], w[i], i);
+        int rc = setup_model(c, c->m[i], shape[i], w[i], i, i == RSD_PRM && p->merge_prm != RSD_MERGE_NONE);
         if (rc) return rc;
+    }
+    if (p->merge_prm != RSD_MERGE_NONE) {
+        const rsd_model_shape& a = shape[p->merge_prm == RSD_MERGE_DRAFT ? RSD_DRAFT : RSD_TARGET];
+        const rsd_model_shape& r = shape[RSD_PRM];
+        if (a.n_layers != r.n_layers || a.d_model != r.d_model || a.n_heads != r.n_heads || a.n_kv_heads != r.n_kv_heads ||
+            a.d_ffn != r.d_ffn || a.dtype != r.dtype)
+            return fail(c, RSD_EINVAL, "merged reward model: its shape must repeat the policy model's");
     }
     if (shape[0].vocab != shape[1].vocab || shape[0].vocab != shape[2].vocab)
         return fail(c, RSD_EINVAL, "the three models must share one vocabulary");
     if (p->sep_id < 0 || p->sep_id >= shape[0].vocab || p->eos_id >= shape[0].vocab)
         return fail(c, RSD_EINVAL, "sep_id/eos_id outside the vocabulary");
     for (int i = 0; i < 3; ++i) {
+        if (i == RSD_PRM && p->merge_prm != RSD_MERGE_NONE) {      // no third cache
+            c->m[i].n_pages.assign(batch, 0);
+            continue;
+        }
         int rc = setup_kv(c, c->m[i], i);
         if (rc) return rc;
     }
@@ -967,6 +985,7 @@ int rsd_step(rsd_ctx* c, rsd_step_out* out) {
     if (!c->have_prompts) return fail(c, RSD_ESTATE, "no prompts set");
     const int B = c->B;
     const rsd_params& P = c->p;
+    const int merge = P.merge_prm;
     if (P.temperature > 0.f && (!c->u_draft || !c->u_target)) return fail(c, RSD_ESTATE, "sampling needs uniforms");
     if (P.omega_kind != RSD_OMEGA_BINARY && !c->u_gate) return fail(c, RSD_ESTATE, "this omega needs u_gate");
     int n_in = 0;
@@ -993,7 +1012,9 @@ int rsd_step(rsd_ctx* c, rsd_step_out* out) {
     for (int b = 0; b < B; ++b)
         if (c->in_step()[b]) {
             const int need = ceil_div(std::min(c->ctx_pre()[b] + P.step_cap, P.max_ctx), RSD_PAGE);
-            if (!ensure_pages(c->m[RSD_DRAFT], b, need) || !ensure_pages(c->m[RSD_PRM], b, need)) {
+            // the model that scores the step needs room for it too: the reward model, or the target it is merged with
+            const int scorer = merge == RSD_MERGE_NONE ? RSD_PRM : merge == RSD_MERGE_TARGET ? RSD_TARGET : RSD_DRAFT;
+            if (!ensure_pages(c->m[RSD_DRAFT], b, need) || !ensure_pages(c->m[scorer], b, need)) {
                 trim_all();
                 return fail(c, RSD_ENOMEM, "KV pool exhausted reserving the draft step of sequence %d", b);
             }
@@ -1002,6 +1023,7 @@ int rsd_step(rsd_ctx* c, rsd_step_out* out) {
     if ((rc = push_state(c))) return rc;
     if ((rc = upload_tables(c, c->m[RSD_DRAFT]))) return rc;
     if ((rc = upload_tables(c, c->m[RSD_PRM]))) return rc;
+    if (merge == RSD_MERGE_TARGET && (rc = upload_tables(c, c->m[RSD_TARGET]))) return rc;
 
     // ---- draft step  (Algorithm 1: "Generate draft step")
     double t0 = now_ms();
@@ -1024,20 +1046,27 @@ int rsd_step(rsd_ctx* c, rsd_step_out* out) {
 
     // ---- reward of the draft step  ("Compute reward")
     {
+        // Without merge the reward model reads what it has not seen, [kv_p, ctx).  Merged with the draft:
+        // the draft reads the one token it has not been fed, [ctx - 1, ctx), and its kv_len stays ctx - 1
+        // (the next step feeds that token again and rewrites the same cache entry).  Merged with the
+        // target: the target reads [kv_t, ctx) and then stands at ctx - 1 for the same reason.
+        const int scorer = merge == RSD_MERGE_NONE ? RSD_PRM : merge == RSD_MERGE_TARGET ? RSD_TARGET : RSD_DRAFT;
         std::vector<Piece> pieces;
         for (int b = 0; b < B; ++b)
             if (c->in_step()[b]) {
-                pieces.push_back(Piece{b, c->kv_len(RSD_PRM)[b], c->ctx_len()[b]});
-                c->kv_len(RSD_PRM)[b] = c->ctx_len()[b];
+                pieces.push_back(Piece{b, c->kv_len(scorer)[b], c->ctx_len()[b]});
+                if (merge == RSD_MERGE_NONE) c->kv_len(RSD_PRM)[b] = c->ctx_len()[b];
+                else if (merge == RSD_MERGE_TARGET) c->kv_len(RSD_TARGET)[b] = c->ctx_len()[b] - 1;
             }
         if ((rc = push_state(c))) return rc;
         Model& pm = c->m[RSD_PRM];
+        const Model* trunk = merge == RSD_MERGE_NONE ? nullptr : &c->m[scorer];
         auto after = [&](const std::vector<Piece>&, const std::vector<int>&, int) {
-            if (pm.s.dtype == RSD_F32) reward_rows<float>(c, pm, c->h, B, c->last_row_dev, c->ds.reward);
-            else reward_rows<bf16_t>(c, pm, c->h, B, c->last_row_dev, c->ds.reward);
+            if (pm.s.dtype == RSD_F32) reward_rows<float>(c, pm, c->h, B, c->last_row_dev, c->ds.reward, trunk);
+            else reward_rows<bf16_t>(c, pm, c->h, B, c->last_row_dev, c->ds.reward, trunk);
             return RSD_OK;
         };
-        rc = pm.s.dtype == RSD_F32 ? prefill<float>(c, RSD_PRM, pieces, after) : prefill<bf16_t>(c, RSD_PRM, pieces, after);
+        rc = pm.s.dtype == RSD_F32 ? prefill<float>(c, scorer, pieces, after) : prefill<bf16_t>(c, scorer, pieces, after);
         if (rc) return rc;
     }
     HIPCHK(c, hipStreamSynchronize(c->st));
@@ -1046,7 +1075,7 @@ int rsd_step(rsd_ctx* c, rsd_step_out* out) {
 
     // ---- acceptance criterion and rollback  (Algorithm 2)
     hipLaunchKernelGGL(gate_kernel, dim3(ceil_div(B, 64)), dim3(64), 0, c->st, c->ds, B, P.delta, P.omega_kind, P.omega_a,
-                       c->u_gate, P.max_steps, c->steps_done, c->forced_accept, c->in_step_dev);
+                       c->u_gate, P.max_steps, c->steps_done, c->forced_accept, c->in_step_dev, merge);
     if ((rc = pull_state(c))) return rc;
     double t3 = now_ms();
     c->stage_ms[2] += t3 - t2;
@@ -1175,7 +1204,7 @@ int rsd_export_pages(rsd_ctx* c, int32_t model, int32_t* block_table, int32_t* m
                      int32_t* free_pages) {
     if (!c || model < 0 || model > 2) return fail(c, RSD_EINVAL, "bad model index");
     Model& m = c->m[model];
-    if (block_table) std::memcpy(block_table, m.bt_host, (size_t)c->B * m.max_pages * sizeof(int));
+    if (block_table && m.bt_host) std::memcpy(block_table, m.bt_host, (size_t)c->B * m.max_pages * sizeof(int));
     if (max_pages) *max_pages = m.max_pages;
     if (pool_pages) *pool_pages = m.pool_pages;
     if (free_pages) *free_pages = (int)m.free_list.size();
@@ -1316,6 +1345,8 @@ extern "C" int rsd_forward(rsd_ctx* c, int32_t model, const int32_t* tokens_host
                            int32_t chunk, float* out_dev) {
     if (!c || model < 0 || model > 2 || !tokens_host || !lens_host || !out_dev) return fail(c, RSD_EINVAL, "bad argument");
     if (T < 1 || T > c->p.max_ctx) return fail(c, RSD_EINVAL, "T outside [1, max_ctx]");
+    if (model == RSD_PRM && c->p.merge_prm != RSD_MERGE_NONE)
+        return fail(c, RSD_EINVAL, "the merged reward model has no layers of its own to run");
     return c->m[model].s.dtype == RSD_F32 ? forward_impl<float>(c, model, tokens_host, lens_host, T, chunk, out_dev)
                                            : forward_impl<bf16_t>(c, model, tokens_host, lens_host, T, chunk, out_dev);
 }

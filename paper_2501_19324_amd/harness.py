@@ -13,13 +13,18 @@ class Session:
     """A context plus the device buffers it borrows."""
 
     def __init__(self, w: Workload, delta=None, weights=None, use_graphs: int = 1, kv_pool_bytes=(0, 0, 0),
-                 omega_kind=None, omega_a=None):
+                 omega_kind=None, omega_a=None, merge_prm: int = 0):
+        """``merge_prm`` = 1 / 2: the reward head sits on the draft's / target's trunk.  ``w.prm`` must then
+        repeat that model's shape; of the reward model's generated blob only the projection (its last
+        d_model + 8 elements: w_r, b_r) is handed over."""
         import torch
 
         self.w = w
         dev = torch.device("cuda:0")
         self.weights = weights if weights is not None else [model_blob_torch(w.seed, i, s, dev) for i, s in enumerate(w.shapes)]
-        self.ctx = R.rsd_init(w.shapes, self.weights, batch=w.batch, delta=w.delta if delta is None else delta,
+        if merge_prm and weights is None:
+            self.weights[2] = self.weights[2][-(w.prm.d_model + 8):].clone()
+        self.ctx = R.rsd_init(w.shapes, self.weights, batch=w.batch, merge_prm=merge_prm, delta=w.delta if delta is None else delta,
                               sep_id=w.sep_id, step_cap=w.step_cap, max_steps=w.max_steps, max_ctx=w.max_ctx,
                               eos_id=w.eos_id, temperature=w.temperature, top_p=w.top_p,
                               sep_logit_bias=w.sep_logit_bias,

@@ -98,15 +98,33 @@ def teacher_arrays(w, refs, torch):
     return [torch.from_numpy(a).cuda() for a in (fd, ft, fa)], (fd, ft)
 
 
-@pytest.mark.parametrize("batch", [3, 12])
-def test_teacher_forced_steps_greedy(gpu, mid_models, batch):
+@pytest.mark.parametrize("batch,merge", [(3, 0), (12, 0), (3, 1), (3, 2)])
+def test_teacher_forced_steps_greedy(gpu, mid_models, batch, merge):
+    """merge = 1 / 2: the reward head sits on the draft's / target's trunk (Appendix "Model Merge")."""
+    from dataclasses import replace
     from oracle import rsd_oracle as O
     R, torch = gpu["R"], gpu["torch"]
     w = mid_workload(batch)
-    s = gpu["Session"](w)
-    P = oracle_params(O, w)
     n_check = min(batch, 4)                     # sequences the CPU checker follows
-    refs = [O.generate_sequence(*mid_models, s.tokens_host[b, :s.prompt_len[b]], s.u_host["U_DRAFT"][b],
+    models = mid_models
+    if merge:
+        from rsd_inputs import model_weights_np, prompt_tokens, prompt_lengths, uniforms
+        policy = w.draft if merge == 1 else w.target
+        w = replace(w, prm=replace(policy, head_kind="reward"))
+        head = model_weights_np(w.seed, 2, w.prm, threads=8)
+        trunk = mid_models[merge - 1]._w
+        pm = O.OracleModel(w.prm, {**{k: v for k, v in trunk.items() if k != "lm_head"}, "w_r": head["w_r"], "b_r": head["b_r"]})
+        models = [mid_models[0], mid_models[1], pm]
+        # a threshold that both accepts and rejects: the median reward of the first steps
+        toks, lens = prompt_tokens(w), prompt_lengths(w)
+        ud, ut, ug = uniforms(w, "U_DRAFT", w.max_ctx), uniforms(w, "U_TARGET", w.max_ctx), uniforms(w, "U_GATE", w.max_steps)
+        P1 = replace(oracle_params(O, w), merge=("none", "draft", "target")[merge])
+        first = [O.generate_sequence(*models, toks[b, :lens[b]], ud[b], ut[b], ug[b], P1, max_steps=1)["records"][0]["reward"]
+                 for b in range(n_check)]
+        w = replace(w, deltas=(float(np.float32(np.median(first))),))
+    s = gpu["Session"](w, merge_prm=merge)
+    P = replace(oracle_params(O, w), merge=("none", "draft", "target")[merge])
+    refs = [O.generate_sequence(*models, s.tokens_host[b, :s.prompt_len[b]], s.u_host["U_DRAFT"][b],
                                 s.u_host["U_TARGET"][b], s.u_host["U_GATE"][b], P) for b in range(n_check)]
     # the other sequences run free (no teacher entries): they only have to stay independent
     refs_all = refs + [dict(records=[])] * (batch - n_check)

@@ -92,13 +92,14 @@ def test_sampler_alone(gpu):
     s.close()
 
 
-def run_and_compare(gpu, tiny, w, n_steps=None):
+def run_and_compare(gpu, tiny, w, n_steps=None, models=None, merge=0):
     from oracle import rsd_oracle as O
     R = gpu["R"]
-    s = gpu["Session"](w)
-    P = oracle_params(O, w)
+    s = gpu["Session"](w, merge_prm=merge)
+    P = oracle_params(O, w, merge=("none", "draft", "target")[merge])
     n_steps = n_steps or w.max_steps
-    refs = [O.generate_sequence(*tiny["models"], s.tokens_host[b, :s.prompt_len[b]], s.u_host["U_DRAFT"][b],
+    models = models or tiny["models"]
+    refs = [O.generate_sequence(*models, s.tokens_host[b, :s.prompt_len[b]], s.u_host["U_DRAFT"][b],
                                 s.u_host["U_TARGET"][b], s.u_host["U_GATE"][b], P) for b in range(w.batch)]
     n_acc = n_rej = 0
     for i in range(n_steps):
@@ -122,7 +123,7 @@ def run_and_compare(gpu, tiny, w, n_steps=None):
             n_acc += r["accepted"]
             n_rej += not r["accepted"]
         # page tables: no page owned twice, used + free = pool
-        for m in range(3):
+        for m in range(3 if merge == 0 else 2):
             pg = R.rsd_export_pages(s.ctx, m)
             used = pg["block_table"][pg["block_table"] >= 0]
             assert len(set(used.tolist())) == used.size
@@ -304,3 +305,21 @@ def test_one_step_law_is_the_mixture_on_gpu(gpu, kind, a):
     assert chi2 < 35.0, (chi2, counts, n * expect)                 # 7 dof: P(chi2 > 35) ~ 1e-5
     assert abs(n_rej / n - nu) < 5 * np.sqrt(nu * (1 - nu) / n), (n_rej / n, nu)
     s.close()
+
+
+@pytest.mark.parametrize("merge", [1, 2])
+def test_merged_reward_head_on_gpu(gpu, tiny, merge):
+    """Appendix "Model Merge": the reward head on the draft's (1) or the target's (2) trunk, no third
+    model or cache.  Free-running against the checker: tokens, rewards, decisions, offsets, pages."""
+    from dataclasses import replace
+    from oracle import rsd_oracle as O
+    from rsd_inputs import workload, model_weights_np
+    w = workload("cfg0", sep_logit_bias=0.6, deltas=(0.5,), max_steps=6)
+    policy = w.draft if merge == 1 else w.target
+    w = replace(w, prm=replace(policy, head_kind="reward"))
+    d, t, _ = tiny["models"]
+    head = model_weights_np(w.seed, 2, w.prm)
+    trunk = (d if merge == 1 else t)._w
+    pm = O.OracleModel(w.prm, {**{k: v for k, v in trunk.items() if k != "lm_head"}, "w_r": head["w_r"], "b_r": head["b_r"]})
+    n_acc, n_rej = run_and_compare(gpu, tiny, w, models=(d, t, pm), merge=merge)
+    assert n_acc >= 2 and n_rej >= 2
