@@ -23,33 +23,42 @@ PROBE_OPS = {"qkv": 0, "o": 1, "gate_up": 2, "down": 3, "head": 4}
 
 def cpu_baseline(w, budget_s=20.0):
     """The fp64 CPU checker timed on a bounded sample of the same workload:
-    the three models at full width and vocabulary but 12 layers each, first
-    reasoning step capped at 4 tokens (the full-depth models need > 100 GB as
-    fp64 and minutes per token)."""
+    the three models at full width and vocabulary (full depth if the host has
+    the memory, else 12 layers each), one sequence, the first two reasoning steps
+    capped at 8 tokens."""
     import numpy as np
     import torch
     from dataclasses import replace
     from rsd_inputs import workload, model_weights_np, prompt_tokens, prompt_lengths, uniforms
     from oracle import rsd_oracle as O
 
+    # full depth where the host can hold the models twice over (fp32 as generated + the checker's fp64
+    # copies: about 130 GB for cfg1); 12 layers otherwise
     layers = 12
-    ws = workload(w.name, n_layers=layers, batch=1, step_cap=4, max_steps=1)
+    try:
+        import psutil
+        if psutil.virtual_memory().available > 200e9:
+            layers = w.draft.n_layers
+    except ImportError:
+        pass
+    ws = workload(w.name, n_layers=layers, batch=1, step_cap=8, max_steps=2)
     cores = min(16, os.cpu_count() or 1)
     models = [O.OracleModel(s, model_weights_np(ws.seed, i, s, threads=cores)) for i, s in enumerate(ws.shapes)]
     toks, lens = prompt_tokens(ws), prompt_lengths(ws)
-    P = O.Params(delta=ws.delta, sep_id=ws.sep_id, step_cap=ws.step_cap, max_steps=1, max_ctx=ws.max_ctx,
+    P = O.Params(delta=ws.delta, sep_id=ws.sep_id, step_cap=ws.step_cap, max_steps=ws.max_steps, max_ctx=ws.max_ctx,
                  temperature=float(np.float32(ws.temperature)), top_p=float(np.float32(ws.top_p)))
     t0 = time.time()
     out = O.generate_sequence(models[0], models[1], models[2], toks[0, :lens[0]],
                               uniforms(ws, "U_DRAFT", ws.max_ctx)[0], uniforms(ws, "U_TARGET", ws.max_ctx)[0],
-                              uniforms(ws, "U_GATE", 1)[0], P)
+                              uniforms(ws, "U_GATE", ws.max_steps)[0], P)
     dt = time.time() - t0
     n = len(out["tokens"]) - int(lens[0])
     return {"value": n / dt, "unit": "tokens/s", "cores": int(torch.get_num_threads()), "kind": "oracle",
             "sample": f"{ws.name} shapes at full width and vocabulary, {layers} of {w.draft.n_layers} layers per model, "
-                      f"1 sequence, prompt {int(lens[0])} tokens + first reasoning step of {n} tokens "
-                      f"(prompt prefill of all touched models included), {dt:.1f} s; at full depth the rate is "
-                      f"roughly {w.draft.n_layers // layers}x lower"}
+                      f"1 sequence, prompt {int(lens[0])} tokens + the first {ws.max_steps} reasoning steps of <= {ws.step_cap} tokens ({n} tokens) "
+                      f"(prompt prefill of all touched models included), {dt:.1f} s"
+                      + ("" if layers == w.draft.n_layers else
+                         f"; at full depth the rate is roughly {w.draft.n_layers / layers:.1f}x lower")}
 
 
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "cfg1_target_gate_up_hbm_traffic.txt")
