@@ -320,17 +320,18 @@ def test_wide_shapes_batch16(gpu):
     s.close()
 
 
-def test_batch64_ragged_prompts(gpu, mid_models):
-    """Second configuration's structure at reduced depth: 64 sequences with
-    ragged prompts, independent accept/regenerate decisions; three sequences
-    are followed by the checker under the teacher, the rest run free, and the
-    batch must not leak between sequences (pages, offsets)."""
+@pytest.mark.parametrize("batch", [64, 200])
+def test_large_batch_ragged_prompts(gpu, mid_models, batch):
+    """Second (64 sequences: the weight-streaming few-row GEMM) and fourth (200: the tile GEMM in the
+    decode loop) configuration's structure at reduced depth: ragged prompts, independent
+    accept/regenerate decisions; three sequences are followed by the checker under the teacher, the
+    rest run free, and the batch must not leak between sequences (pages, offsets)."""
     from oracle import rsd_oracle as O
     R, torch = gpu["R"], gpu["torch"]
-    w = mid_workload(64, prompt_len_min=16, prompt_len_max=200, step_cap=8, max_steps=3)
+    w = mid_workload(batch, prompt_len_min=16, prompt_len_max=200, step_cap=8, max_steps=3)
     s = gpu["Session"](w)
     P = oracle_params(O, w)
-    check = [0, 31, 63]
+    check = [0, batch // 2 - 1, batch - 1]
     refs = {b: O.generate_sequence(*mid_models, s.tokens_host[b, :s.prompt_len[b]], s.u_host["U_DRAFT"][b],
                                    s.u_host["U_TARGET"][b], s.u_host["U_GATE"][b], P) for b in check}
     allrefs = [refs.get(b, dict(records=[])) for b in range(w.batch)]
