@@ -382,19 +382,22 @@ static void gemm_launch(hipStream_t st, int epi, const float* W, int N, int K, c
 
 // ---------------------------------------------------------------- bf16 MFMA, many rows, pre-split activations
 // Y[m][n] (+)= sum_k (Xh + Xl)[m][k] * W[n][k] for more than 64 rows (prefill chunks, large decode batches).
-// Block tile 128 (m) x 256 (n), four waves of 64 x 128 (2 x 4 MFMA tiles of 32x32x16, hi and lo pass on
-// each: 32 MFMAs against 16 operand reads of 16 bytes per K block of 32).  LDS holds two stages of
+// Block tile BM (128 or 256 rows of X) x 256 (rows of W), BM / 32 waves of 64 x 128 (2 x 4 MFMA tiles of
+// 32x32x16, hi and lo pass on each: 32 MFMAs against 16 operand reads of 16 bytes per K block of 32).
+// The copies from L2 into LDS, not the MFMAs, bound this kernel (they alone take 85 % of its time at
+// BM = 128): per K block a tile pulls 64 B x (2 BM + 256) through L2, so the larger tile moves 25 %
+// fewer bytes per flop and is used whenever it still gives every compute unit two blocks.  LDS holds two stages of
 // [rows][32 k] tiles (Xh, Xl, W), chunks of 16 bytes permuted by (row / 4) % 4 so that both the
 // line-wise writes and the operand reads are conflict-free without padding.  While one stage is
 // multiplied the next one is already on its way from global memory in registers.  gridDim.z > 1 cuts K into
 // slices whose partial tiles go to part[z][M][N] (finished by rows_finish_kernel).
-template <int EPI>
-__global__ __launch_bounds__(256, 2) void gemm_tile_kernel(const bf16_t* __restrict__ W, int N, int K,
+template <int EPI, int BM>
+__global__ __launch_bounds__(BM * 2, BM == 128 ? 2 : 1) void gemm_tile_kernel(const bf16_t* __restrict__ W, int N, int K,
                                                            const uint16_t* __restrict__ Xh,
                                                            const uint16_t* __restrict__ Xl, int M,
                                                            float* __restrict__ Y, int ldy,
                                                            float* __restrict__ part) {
-    constexpr int BM = 128, BN = 256, BK = 32;
+    constexpr int BN = 256, BK = 32, CR = BM / 2;        // CR: rows covered by one round of copies (threads / 4)
     __shared__ __attribute__((aligned(16))) uint16_t Ah[2][BM * BK];
     __shared__ __attribute__((aligned(16))) uint16_t Al[2][BM * BK];
     __shared__ __attribute__((aligned(16))) uint16_t Bs[2][BN * BK];
@@ -408,17 +411,18 @@ __global__ __launch_bounds__(256, 2) void gemm_tile_kernel(const bf16_t* __restr
     const int kb_last = max(kb1 - 1, 0);
     // LDS offset (in bf16) of 16-byte chunk c (0..3) of row r
     auto sw = [](int r, int c) { return r * BK + ((c ^ ((r >> 2) & 3)) << 3); };
-    // global -> LDS copies: thread -> chunk tid % 4 of rows tid / 4 + 64 i
+    // global -> LDS copies: thread -> chunk tid % 4 of rows tid / 4 + CR i (two rounds cover the X tile;
+    // the W tile takes four rounds at BM = 128, two at BM = 256)
     const int crow = tid >> 2, cch = tid & 3;
     const uint16_t* ah0 = Xh + (size_t)min(m0 + crow, M - 1) * K + cch * 8;
-    const uint16_t* ah1 = Xh + (size_t)min(m0 + crow + 64, M - 1) * K + cch * 8;
+    const uint16_t* ah1 = Xh + (size_t)min(m0 + crow + CR, M - 1) * K + cch * 8;
     const uint16_t* al0 = Xl + (size_t)min(m0 + crow, M - 1) * K + cch * 8;
-    const uint16_t* al1 = Xl + (size_t)min(m0 + crow + 64, M - 1) * K + cch * 8;
+    const uint16_t* al1 = Xl + (size_t)min(m0 + crow + CR, M - 1) * K + cch * 8;
     const bf16_t* b0 = W + (size_t)min(n0 + crow, N - 1) * K + cch * 8;
-    const bf16_t* b1 = W + (size_t)min(n0 + crow + 64, N - 1) * K + cch * 8;
-    const bf16_t* b2 = W + (size_t)min(n0 + crow + 128, N - 1) * K + cch * 8;
+    const bf16_t* b1 = W + (size_t)min(n0 + crow + CR, N - 1) * K + cch * 8;
+    const bf16_t* b2 = W + (size_t)min(n0 + crow + 128, N - 1) * K + cch * 8;       // BM = 128 only
     const bf16_t* b3 = W + (size_t)min(n0 + crow + 192, N - 1) * K + cch * 8;
-    const int st0 = sw(crow, cch), st1 = sw(crow + 64, cch), st2 = sw(crow + 128, cch), st3 = sw(crow + 192, cch);
+    const int st0 = sw(crow, cch), st1 = sw(crow + CR, cch), st2 = sw(crow + 128, cch), st3 = sw(crow + 192, cch);
 
     f32x16_t acc[2][4];
 #pragma unroll
@@ -440,8 +444,10 @@ __global__ __launch_bounds__(256, 2) void gemm_tile_kernel(const bf16_t* __restr
         R.l1 = *reinterpret_cast<const u32x4_t*>(al1 + k0_);                                     \
         R.b0 = *reinterpret_cast<const u32x4_t*>(b0 + k0_);                                      \
         R.b1 = *reinterpret_cast<const u32x4_t*>(b1 + k0_);                                      \
-        R.b2 = *reinterpret_cast<const u32x4_t*>(b2 + k0_);                                      \
-        R.b3 = *reinterpret_cast<const u32x4_t*>(b3 + k0_);                                      \
+        if (BM == 128) {                                                                         \
+            R.b2 = *reinterpret_cast<const u32x4_t*>(b2 + k0_);                                  \
+            R.b3 = *reinterpret_cast<const u32x4_t*>(b3 + k0_);                                  \
+        }                                                                                        \
     }
 #define RSD_STAGE(buf, R)                                                                        \
     {                                                                                            \
@@ -451,8 +457,10 @@ __global__ __launch_bounds__(256, 2) void gemm_tile_kernel(const bf16_t* __restr
         *reinterpret_cast<u32x4_t*>(&Al[(buf)][st1]) = R.l1;                                     \
         *reinterpret_cast<u32x4_t*>(&Bs[(buf)][st0]) = R.b0;                                     \
         *reinterpret_cast<u32x4_t*>(&Bs[(buf)][st1]) = R.b1;                                     \
-        *reinterpret_cast<u32x4_t*>(&Bs[(buf)][st2]) = R.b2;                                     \
-        *reinterpret_cast<u32x4_t*>(&Bs[(buf)][st3]) = R.b3;                                     \
+        if (BM == 128) {                                                                         \
+            *reinterpret_cast<u32x4_t*>(&Bs[(buf)][st2]) = R.b2;                                 \
+            *reinterpret_cast<u32x4_t*>(&Bs[(buf)][st3]) = R.b3;                                 \
+        }                                                                                        \
     }
     const int l32 = lane & 31, kg = lane >> 5;
 #define RSD_COMPUTE(buf)                                                                         \
@@ -530,9 +538,16 @@ static int gemm_tile_slices(int N, int K, int M, size_t part_floats) {
 
 static void gemm_tile_launch(hipStream_t st, int epi, const bf16_t* W, int N, int K, const uint16_t* Xh,
                              const uint16_t* Xl, int M, float* Y, int ldy, float* part, int ks) {
-    const dim3 grid((N + 255) / 256, (M + 127) / 128, ks), block(256);
-    if (epi == EPI_RESID) hipLaunchKernelGGL((gemm_tile_kernel<EPI_RESID>), grid, block, 0, st, W, N, K, Xh, Xl, M, Y, ldy, part);
-    else                  hipLaunchKernelGGL((gemm_tile_kernel<EPI_STORE>), grid, block, 0, st, W, N, K, Xh, Xl, M, Y, ldy, part);
+    const int tn = (N + 255) / 256;
+    if (tn * ((M + 255) / 256) * ks >= 400) {       // enough 256-row tiles to fill the chip (one block per compute unit) about twice
+        const dim3 grid(tn, (M + 255) / 256, ks), block(512);
+        if (epi == EPI_RESID) hipLaunchKernelGGL((gemm_tile_kernel<EPI_RESID, 256>), grid, block, 0, st, W, N, K, Xh, Xl, M, Y, ldy, part);
+        else                  hipLaunchKernelGGL((gemm_tile_kernel<EPI_STORE, 256>), grid, block, 0, st, W, N, K, Xh, Xl, M, Y, ldy, part);
+        return;
+    }
+    const dim3 grid(tn, (M + 127) / 128, ks), block(256);
+    if (epi == EPI_RESID) hipLaunchKernelGGL((gemm_tile_kernel<EPI_RESID, 128>), grid, block, 0, st, W, N, K, Xh, Xl, M, Y, ldy, part);
+    else                  hipLaunchKernelGGL((gemm_tile_kernel<EPI_STORE, 128>), grid, block, 0, st, W, N, K, Xh, Xl, M, Y, ldy, part);
 }
 
 // act = silu(gate) * up for gu[M][2F] = [gate | up], written as hi + lo bf16 halves [M][F]
