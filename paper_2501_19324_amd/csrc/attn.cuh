@@ -479,13 +479,13 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void attn_decode_mfma_ker
     const size_t page_elts = (size_t)2 * Hkv * RSD_PAGE * HD;
     const size_t head_off = (size_t)hk * RSD_PAGE * HD, v_off = (size_t)Hkv * RSD_PAGE * HD;
 
-    // operands of one page: K chunk j of token l16 = K[l16][c*32 + j*8 ..+8]; V block nb = V^T[nb*16 + l16][c*4 ..+4]
+    // operands of one page: K chunk j of token l16 = K[l16][j*32 + c*8 ..+8] (the four lanes of a token read 64 contiguous bytes per request); V block nb = V^T[nb*16 + l16][c*4 ..+4]
     uint4 kc[4], kn[4];
     uint2 vc[8], vn[8];
     auto fetch_phys = [&](int phys, uint4 k[4], uint2 v[8]) {
         const bf16_t* kb = pool_layer + (size_t)phys * page_elts + head_off;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) k[j] = *reinterpret_cast<const uint4*>(kb + l16 * HD + c * 32 + j * 8);
+        for (int j = 0; j < 4; ++j) k[j] = *reinterpret_cast<const uint4*>(kb + l16 * HD + j * 32 + c * 8);
 #pragma unroll
         for (int nb = 0; nb < 8; ++nb) v[nb] = *reinterpret_cast<const uint2*>(kb + v_off + (nb * 16 + l16) * RSD_PAGE + c * 4);
     };
@@ -529,13 +529,13 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void attn_decode_mfma_ker
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             float kv[8];
-            rope8<HD>(row + (H + hk) * HD, cs, c * 32 + j * 8, kv);
+            rope8<HD>(row + (H + hk) * HD, cs, j * 32 + c * 8, kv);
             uint4 pk;
             pk.x = (uint32_t)f2bf(kv[0]) | ((uint32_t)f2bf(kv[1]) << 16);
             pk.y = (uint32_t)f2bf(kv[2]) | ((uint32_t)f2bf(kv[3]) << 16);
             pk.z = (uint32_t)f2bf(kv[4]) | ((uint32_t)f2bf(kv[5]) << 16);
             pk.w = (uint32_t)f2bf(kv[6]) | ((uint32_t)f2bf(kv[7]) << 16);
-            if (l16 == 0) *reinterpret_cast<uint4*>(kb + (size_t)slot * HD + c * 32 + j * 8) = pk;
+            if (l16 == 0) *reinterpret_cast<uint4*>(kb + (size_t)slot * HD + j * 32 + c * 8) = pk;
             k1[j] = (l16 == 0) ? pk : make_uint4(0u, 0u, 0u, 0u);
         }
 #pragma unroll
@@ -560,8 +560,8 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void attn_decode_mfma_ker
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const abf16x8_t ka = __builtin_bit_cast(abf16x8_t, k[j]);
-            const abf16x8_t qlo = __builtin_bit_cast(abf16x8_t, *reinterpret_cast<const uint4*>(&s_ql[l16][c * 32 + j * 8]));
-            const abf16x8_t qhi = __builtin_bit_cast(abf16x8_t, *reinterpret_cast<const uint4*>(&s_qh[l16][c * 32 + j * 8]));
+            const abf16x8_t qlo = __builtin_bit_cast(abf16x8_t, *reinterpret_cast<const uint4*>(&s_ql[l16][j * 32 + c * 8]));
+            const abf16x8_t qhi = __builtin_bit_cast(abf16x8_t, *reinterpret_cast<const uint4*>(&s_qh[l16][j * 32 + c * 8]));
             s2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, qlo, s2, 0, 0, 0);
             s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, qhi, s, 0, 0, 0);
         }
@@ -714,7 +714,7 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(const float* 
         for (int j = 0; j < 4; ++j) {
             float qv[8];
             if (live) {
-                load8(qkv + (size_t)(r0 + ri) * ldq + (hk * G + g_col) * HD + c * 32 + j * 8, qv);
+                load8(qkv + (size_t)(r0 + ri) * ldq + (hk * G + g_col) * HD + j * 32 + c * 8, qv);
 #pragma unroll
                 for (int e = 0; e < 8; ++e) qv[e] *= scale;
             } else {
@@ -723,8 +723,8 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(const float* 
             }
             abf16x8_t h8, l8;
             split_hi_lo8(qv, h8, l8);
-            *reinterpret_cast<uint4*>(qh_row + c * 32 + j * 8) = __builtin_bit_cast(uint4, h8);
-            *reinterpret_cast<uint4*>(ql_row + c * 32 + j * 8) = __builtin_bit_cast(uint4, l8);
+            *reinterpret_cast<uint4*>(qh_row + j * 32 + c * 8) = __builtin_bit_cast(uint4, h8);
+            *reinterpret_cast<uint4*>(ql_row + j * 32 + c * 8) = __builtin_bit_cast(uint4, l8);
         }
     }
     // (each wave reads back only what it wrote itself: no block barrier needed)
@@ -743,7 +743,7 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(const float* 
         const int phys = __shfl(bt_mine, pg & 63, RSD_WAVE);
         const bf16_t* kb = pool_layer + (size_t)phys * page_elts + head_off;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) k[j] = *reinterpret_cast<const uint4*>(kb + l16 * HD + c * 32 + j * 8);
+        for (int j = 0; j < 4; ++j) k[j] = *reinterpret_cast<const uint4*>(kb + l16 * HD + j * 32 + c * 8);
 #pragma unroll
         for (int nb = 0; nb < 8; ++nb) v[nb] = *reinterpret_cast<const uint2*>(kb + v_off + (nb * 16 + l16) * RSD_PAGE + c * 4);
     };
@@ -761,9 +761,9 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(const float* 
             for (int j = 0; j < 4; ++j) {
                 const abf16x8_t ka = __builtin_bit_cast(abf16x8_t, k[j]);
                 const abf16x8_t qhi = __builtin_bit_cast(abf16x8_t, *reinterpret_cast<const uint4*>(
-                    qbase + ((size_t)(t * 2 + 0) * 16 + l16) * QSTR + c * 32 + j * 8));
+                    qbase + ((size_t)(t * 2 + 0) * 16 + l16) * QSTR + j * 32 + c * 8));
                 const abf16x8_t qlo = __builtin_bit_cast(abf16x8_t, *reinterpret_cast<const uint4*>(
-                    qbase + ((size_t)(t * 2 + 1) * 16 + l16) * QSTR + c * 32 + j * 8));
+                    qbase + ((size_t)(t * 2 + 1) * 16 + l16) * QSTR + j * 32 + c * 8));
                 s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, qlo, s, 0, 0, 0);
                 s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, qhi, s, 0, 0, 0);
             }
