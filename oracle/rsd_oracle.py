@@ -16,6 +16,13 @@ What is written out here, and where the paper defines it:
   paper's default (Section 3, "Default Setting"; Proposition 3).
 * ``mixture_distribution`` - the law of one RSD step (Proposition 1):
   P_RSD = omega_r P_m + nu P_M with nu = 1 - E_{P_m}[omega_r].
+* ``gen_step_sd`` - regeneration of a rejected step by token-level speculative
+  decoding with the draft and the target (Section 5, "Combine RSD with SD";
+  the method itself is the cited speculative-decoding algorithm: the draft
+  proposes gamma tokens, the target scores them in one pass, each is kept with
+  probability min(1, p/q), the first refusal is replaced by a draw from the
+  normalised positive part of p - q, and a fully kept run earns one more
+  target token).  The paper runs SD greedily with gamma = 7 (Section 3).
 * ``reward`` - the reward model's head (Appendix, "Model Merge"): a projection
   of the final hidden state to one scalar, mapped to [0, 1] (Section 3,
   "Models") by a logistic function.
@@ -227,6 +234,58 @@ def sample(logits: np.ndarray, u: float, temperature: float, top_p: float) -> in
     return int(members[hit[0]] if hit.size else members[-1])
 
 
+def token_distribution(logits: np.ndarray, temperature: float, top_p: float) -> np.ndarray:
+    """The distribution ``sample`` draws from, as a vector over the vocabulary:
+    one-hot at the arg max for temperature 0, else softmax(logits/temperature)
+    restricted to the nucleus and renormalised."""
+    logits = np.asarray(logits, dtype=F64)
+    out = np.zeros(logits.shape[0], dtype=F64)
+    if temperature == 0.0:
+        out[int(np.argmax(logits))] = 1.0
+        return out
+    p = softmax(logits / F64(temperature))
+    order = np.argsort(-p, kind="stable")
+    cum = np.cumsum(p[order])
+    reach = np.nonzero(cum >= top_p)[0]
+    tau = p[order[reach[0]]] if reach.size else np.min(p)
+    keep = p >= tau
+    out[keep] = p[keep] / np.sum(p[keep])
+    return out
+
+
+def draw(dist: np.ndarray, u: float) -> int:
+    """Inverse-CDF draw in ascending token id: the first token whose running
+    mass exceeds u * total, or the last token of positive mass if none does."""
+    members = np.nonzero(dist > 0.0)[0]
+    run = np.cumsum(dist[members])
+    hit = np.nonzero(run > F64(u) * run[-1])[0]
+    return int(members[hit[0]] if hit.size else members[-1])
+
+
+def sd_verify(q_rows: Sequence[np.ndarray], p_rows: Sequence[np.ndarray], proposals: Sequence[int],
+              u_acc: Sequence[float], u_new: Sequence[float]):
+    """One verification of speculative decoding.  ``proposals[i]`` was drawn from
+    ``q_rows[i]``; ``p_rows`` holds the target's distributions at the same
+    positions plus one more.  Proposal i is kept iff u_acc[i] < p_i(x)/q_i(x);
+    the first refused one is replaced by a draw (uniform u_new[i]) from the
+    normalised positive part of p_i - q_i; if all are kept, one more token is
+    drawn from the last row of ``p_rows`` (uniform u_new[len(proposals)]).
+    Returns (tokens emitted, number of proposals kept)."""
+    g = len(proposals)
+    assert len(q_rows) == g and len(p_rows) == g + 1
+    out = []
+    for i, x in enumerate(proposals):
+        p, q = p_rows[i], q_rows[i]
+        if F64(u_acc[i]) * q[x] < p[x]:
+            out.append(int(x))
+            continue
+        res = np.maximum(p - q, 0.0)
+        out.append(draw(res, u_new[i]))
+        return out, i
+    out.append(draw(p_rows[g], u_new[g]))
+    return out, g
+
+
 def omega(r: float, kind: int, delta: float, a: float = 0.0) -> float:
     """Weighting functions of Table 1.  ``delta`` is the threshold of the
     binary step and the centre of the logistic; ``a`` is the constant p, or
@@ -278,6 +337,7 @@ class Params:
     page_tokens: int = 16
     kv_dtype: str = "exact"      # "bf16": keys and values are stored rounded to bf16 (see KVCache)
     merge: str = "none"          # "draft" / "target": the reward head sits on that model's trunk (Appendix "Model Merge")
+    sd_k: int = 0                # > 0: rejected steps are regenerated by speculative decoding with this many proposals per round
 
 
 class _Runner:
@@ -301,6 +361,18 @@ class _Runner:
             y = forward_chunk(self.m, self.kv, tokens[self.kv_len:n])[-1]
         else:
             y = forward_full(self.m, tokens, self.kv_dtype)[-1]
+        self.kv_len = n
+        return y
+
+    def last_hiddens(self, tokens: Sequence[int], count: int) -> np.ndarray:
+        """Final-norm hidden states at the last ``count`` of ``tokens`` (all of
+        which the model must not have been fed yet)."""
+        n = len(tokens)
+        if self.use_cache:
+            assert self.kv.length == self.kv_len <= n - count
+            y = forward_chunk(self.m, self.kv, tokens[self.kv_len:n])[-count:]
+        else:
+            y = forward_full(self.m, tokens, self.kv_dtype)[-count:]
         self.kv_len = n
         return y
 
@@ -333,10 +405,81 @@ def gen_step(run: _Runner, tokens: List[int], u_row: np.ndarray, P: Params, marg
             return tokens[start:]
 
 
+def gen_step_sd(rd: _Runner, rt: _Runner, tokens: List[int], u_prop: np.ndarray, u_acc: np.ndarray,
+                u_target: np.ndarray, P: Params, margins: Optional[list] = None,
+                rounds: Optional[list] = None, prop_margins: Optional[list] = None):
+    """Generate one reasoning step of the target model by speculative decoding
+    with the draft model (Section 5, "Combine RSD with SD"), appending to
+    ``tokens`` in place; the step ends exactly as in ``gen_step``.
+
+    Every round: with ``used`` tokens of the step so far, the draft proposes up
+    to g = min(sd_k, step_cap - used - 1, max_ctx - len - 1) tokens one by one
+    from its own distribution (uniform u_prop[position]), stopping early after a
+    separator or EOS; the target reads the unseen tokens and the proposals in
+    one pass and ``sd_verify`` decides (u_acc[position], and u_target[position]
+    for a token the target draws itself).  Emitted tokens are appended until one
+    of them ends the step.  Afterwards each model keeps keys/values only for the
+    committed tokens it was fed, never for the newest one.
+
+    ``rounds`` collects (proposed, kept) per round; ``margins`` the top-2 gap of
+    the target's logits at every committed position and ``prop_margins`` that of
+    the draft's at every proposal (diagnostics for parity tests)."""
+    def logits_of(run, y):
+        lg = lm_logits(run.m, y).copy()
+        lg[P.sep_id] += P.sep_logit_bias
+        return lg
+
+    def gap(lg):
+        top2 = np.partition(lg, -2)[-2:]
+        return float(top2[1] - top2[0])
+
+    def uni(arr, i):                 # greedy decoding draws nothing: the arrays may be absent
+        return 0.0 if arr is None else float(arr[i])
+
+    start = len(tokens)
+    while True:
+        n = len(tokens)
+        g = max(0, min(P.sd_k, P.step_cap - (n - start) - 1, P.max_ctx - n - 1))
+        rd.truncate(n - 1)
+        rt.truncate(n - 1)
+        spec, q_rows = list(tokens), []
+        for _ in range(g):
+            lg = logits_of(rd, rd.last_hidden(spec))
+            q = token_distribution(lg, P.temperature, P.top_p)
+            x = draw(q, uni(u_prop, len(spec)))
+            if prop_margins is not None:
+                prop_margins.append(gap(lg))
+            q_rows.append(q)
+            spec.append(x)
+            if x == P.sep_id or x == P.eos_id:
+                break
+        props = spec[n:]
+        ys = rt.last_hiddens(spec, len(props) + 1)
+        lgs = [logits_of(rt, y) for y in ys]
+        p_rows = [token_distribution(lg, P.temperature, P.top_p) for lg in lgs]
+        emitted, kept = sd_verify(q_rows, p_rows, props, [uni(u_acc, n + i) for i in range(len(props))],
+                                  [uni(u_target, n + i) for i in range(len(props) + 1)])
+        if rounds is not None:
+            rounds.append((len(props), kept))
+        done = False
+        for i, t in enumerate(emitted):
+            tokens.append(t)
+            if margins is not None:
+                margins.append(gap(lgs[i]))
+            if t == P.sep_id or t == P.eos_id or len(tokens) - start >= P.step_cap or len(tokens) >= P.max_ctx:
+                done = True
+                break
+        rd.truncate(len(tokens) - 1)
+        rt.truncate(len(tokens) - 1)
+        if done:
+            return tokens[start:]
+
+
 def generate_sequence(draft: OracleModel, target: OracleModel, prm: OracleModel,
                       prompt: Sequence[int], u_draft: np.ndarray, u_target: np.ndarray,
                       u_gate: np.ndarray, P: Params, use_cache: bool = True,
-                      max_steps: Optional[int] = None) -> dict:
+                      max_steps: Optional[int] = None, u_prop: Optional[np.ndarray] = None,
+                      u_acc: Optional[np.ndarray] = None) -> dict:
     """RSD for one sequence (Algorithm 1 with the criterion of Algorithm 2).
 
     Returns the committed tokens, the per-step records and, after every step,
@@ -365,7 +508,7 @@ def generate_sequence(draft: OracleModel, target: OracleModel, prm: OracleModel,
         if reason != RUNNING:
             break
         ctx_pre = len(tokens)
-        dm, fm = [], []
+        dm, fm, pm, sd_rounds = [], [], [], []
         draft_step = gen_step(rd, tokens, u_draft, P, dm)
         if P.merge == "none":
             r = reward(prm, rp.last_hidden(tokens))
@@ -382,7 +525,10 @@ def generate_sequence(draft: OracleModel, target: OracleModel, prm: OracleModel,
             rp.truncate(ctx_pre)
             if P.merge == "target":
                 rt.truncate(ctx_pre - 1)
-            final = gen_step(rt, tokens, u_target, P, fm)
+            if P.sd_k > 0:
+                final = gen_step_sd(rd, rt, tokens, u_prop, u_acc, u_target, P, fm, sd_rounds, pm)
+            else:
+                final = gen_step(rt, tokens, u_target, P, fm)
         if P.eos_id >= 0 and P.eos_id in final:
             reason = FIN_EOS
         elif len(tokens) >= P.max_ctx:
@@ -393,7 +539,7 @@ def generate_sequence(draft: OracleModel, target: OracleModel, prm: OracleModel,
         records.append(dict(step=i, ctx_pre=ctx_pre, draft_tokens=list(draft_step), reward=r,
                             accepted=bool(ok), final_tokens=list(final), ctx_len=len(tokens),
                             kv_len=kv, n_pages=[-(-n // P.page_tokens) for n in kv],
-                            draft_margins=dm, final_margins=fm,
+                            draft_margins=dm, final_margins=fm, sd_rounds=sd_rounds, proposal_margins=pm,
                             finished=reason))
     return dict(tokens=tokens, prompt_len=len(prompt), records=records, finished=reason,
                 kv_len=[rd.kv_len, rt.kv_len, rp.kv_len])
