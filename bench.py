@@ -99,6 +99,11 @@ def main():
     ap.add_argument("--ops", action="store_true", help="extra passes after the timed region: per-projection table")
     ap.add_argument("--merge", default="none", choices=["none", "draft", "target"],
                     help="reward head on the draft's or the target's trunk instead of a third model (not the headline workload)")
+    ap.add_argument("--sd-k", type=int, default=0,
+                    help="regenerate rejected steps by speculative decoding with this many proposals per round "
+                         "(greedy workloads only; not the headline workload)")
+    ap.add_argument("--greedy", action="store_true", help="override the workload's sampler with greedy decoding "
+                                                          "(the paper's default setting; needed by --sd-k on cfg1)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="before the timed region run a plain 256 MiB device copy kernel three times (reference "
                          "point for scaling hardware traffic counters)")
@@ -117,6 +122,8 @@ def main():
     kw = {}
     if args.layers:
         kw["n_layers"] = args.layers
+    if args.greedy:
+        kw.update(temperature=0.0, top_p=1.0)
     w = workload(args.workload, **kw)
     merge = {"none": 0, "draft": 1, "target": 2}[args.merge]
     if merge:
@@ -125,7 +132,7 @@ def main():
     delta = w.delta if args.delta is None else args.delta
     t_setup = time.time()
     pools = tuple(int(float(x) * 1e9) for x in args.kv_pool_gb.split(",")) if args.kv_pool_gb else (0, 0, 0)
-    s = Session(w, delta=delta, use_graphs=0 if args.no_graphs else 1, kv_pool_bytes=pools, merge_prm=merge)
+    s = Session(w, delta=delta, use_graphs=0 if args.no_graphs else 1, kv_pool_bytes=pools, merge_prm=merge, sd_k=args.sd_k)
     torch.cuda.synchronize()
     t_setup = time.time() - t_setup
 
@@ -157,10 +164,13 @@ def main():
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     tokens = drafted = targeted = acc = rej = 0
+    sd = dict(rounds=0, proposed=0, kept=0)
     for _ in range(args.steps):
         g = one_pass()
         tokens += g["n_committed"]; drafted += g["n_draft"]; targeted += g["n_target"]
         acc += g["n_accept"]; rej += g["n_reject"]
+        for k in sd:
+            sd[k] += g.get("n_sd_" + k, 0)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     probe = R.rsd_probe_read(s.ctx)
@@ -192,10 +202,14 @@ def main():
                    "delta": delta, "merge_prm": args.merge, "committed_tokens_per_pass": tokens // max(args.steps, 1),
                    "accept_rate": round(acc / max(acc + rej, 1), 4), "draft_tokens": drafted, "target_tokens": targeted,
                    "stage_ms_per_pass": {k: round(v / args.steps, 2) for k, v in zip(("draft", "prm", "gate", "target"), stage)},
-                   "decode_weight_stream_GBs": round(dec_bytes / dec_s / 1e9, 1) if dec_s > 0 else None,
+                   # (with speculative regeneration the target stage also holds draft proposals and chunked passes)
+                   "decode_weight_stream_GBs": round(dec_bytes / dec_s / 1e9, 1) if dec_s > 0 and not args.sd_k else None,
                    "setup_s": round(t_setup, 1)},
         "roofline": roof,
     }
+    if args.sd_k:
+        line["config"]["sd_k"] = args.sd_k
+        line["config"]["sd"] = sd
     if args.ops:
         table = {}
         for model, shape in ((0, w.draft), (1, w.target)):

@@ -100,6 +100,11 @@ typedef struct rsd_params {
     uint64_t kv_pool_bytes[3]; /* KV page pool per model (draft, target, reward); 0: enough for batch * max_ctx */
     int32_t use_graphs;     /* 1: replay single-token decode iterations as HIP graphs */
     int32_t merge_prm;      /* RSD_MERGE_*: where the reward head sits */
+    int32_t sd_k;           /* > 0: a rejected step is regenerated by token-level speculative decoding with
+                               the draft and the target (Section 5, "Combine RSD with SD"), this many
+                               proposals per round (the paper's SD runs use 7); 0: plain target decoding.
+                               Greedy decoding only (temperature 0, the paper's SD setting, Section 3
+                               "Default Setting"): rsd_init returns RSD_EINVAL otherwise.  At most 15. */
 } rsd_params;
 
 /* Per-step record, all HOST buffers supplied by the caller (any may be NULL).
@@ -113,6 +118,10 @@ typedef struct rsd_step_out {
     int32_t *final_len;     /* [B]            tokens in the committed step                               */
     int32_t *final_tokens;  /* [B][step_cap]                                                             */
     int32_t *finished;      /* [B]            RSD_RUNNING or a RSD_FIN_* reason, after this step         */
+    /* speculative regeneration of a rejected step (sd_k > 0), zero otherwise */
+    int32_t *sd_rounds;     /* [B]            propose-and-verify rounds of this step                     */
+    int32_t *sd_proposed;   /* [B]            tokens the draft proposed in them                          */
+    int32_t *sd_kept;       /* [B]            proposals the target kept                                  */
 } rsd_step_out;
 
 typedef struct rsd_gen_out {
@@ -125,6 +134,9 @@ typedef struct rsd_gen_out {
     int64_t  n_target;      /* tokens the target model sampled                            */
     int64_t  n_accept;      /* accepted steps */
     int64_t  n_reject;      /* rejected steps */
+    int64_t  n_sd_rounds;   /* sd_k > 0: propose-and-verify rounds, proposals made, proposals kept */
+    int64_t  n_sd_proposed;
+    int64_t  n_sd_kept;
 } rsd_gen_out;
 
 typedef struct rsd_ctx rsd_ctx;
@@ -155,7 +167,16 @@ int rsd_set_criterion(rsd_ctx *c, float delta, int32_t omega_kind, float omega_a
 
 /* One iteration of Algorithm 1's loop body for all unfinished sequences:
  * draft step, reward, criterion, target step for the rejected ones, EOS test.
- * On RSD_ENOMEM the sequences are left as before the call. */
+ * On RSD_ENOMEM the sequences are left as before the call.
+ *
+ * With sd_k > 0 the target step is produced in rounds: with `used` tokens of the
+ * step so far the draft proposes g = min(sd_k, step_cap - used - 1,
+ * max_ctx - ctx_len - 1) tokens one by one (stopping after a separator or EOS),
+ * the target reads what it has not seen plus the proposals in one chunked pass,
+ * and the step grows by the leading proposals that equal the target's own
+ * choices plus the target's choice at the first place that differs (or after the
+ * last proposal), until a committed token ends the step.  Afterwards neither
+ * model holds keys/values for the newest token or for a dropped proposal. */
 int rsd_step(rsd_ctx *c, rsd_step_out *out);
 
 /* Algorithm 1's loop: rsd_step until every sequence has finished or max_steps
@@ -187,6 +208,18 @@ int rsd_set_teacher(rsd_ctx *c, const int32_t *forced_draft_dev, const int32_t *
 /* The tokens each model's sampler chose: HOST [B][max_steps][step_cap] each,
  * -1 where the model sampled nothing. */
 int rsd_export_sampled(rsd_ctx *c, int32_t *sampled_draft, int32_t *sampled_target);
+
+/* Speculative regeneration (sd_k > 0), for parity tests.  Both arrays are
+ * [B][max_steps][step_cap * sd_k]; entry [b][i][n] belongs to the n-th proposal
+ * the draft makes while step i of sequence b is regenerated (a place of the step
+ * can be proposed for in several rounds, so proposals are counted, in the order
+ * they are made).  forced_proposal (BORROWED dev, NULL: off): when >= 0, the
+ * proposal is replaced by it.  proposed (HOST): the draft's own choices, -1
+ * beyond the proposals made.  With sd_k > 0 sampled_target of rsd_export_sampled
+ * holds the target's choice at every committed place of a regenerated step, kept
+ * proposals included. */
+int rsd_set_teacher_sd(rsd_ctx *c, const int32_t *forced_proposal_dev);
+int rsd_export_proposed(rsd_ctx *c, int32_t *proposed);
 
 /* Teacher-forced evaluation of one model for parity tests.  tokens is host
  * [B][T], lens host [B] (<= T).  Sequence b is fed in pieces of `chunk` tokens

@@ -407,7 +407,8 @@ def gen_step(run: _Runner, tokens: List[int], u_row: np.ndarray, P: Params, marg
 
 def gen_step_sd(rd: _Runner, rt: _Runner, tokens: List[int], u_prop: np.ndarray, u_acc: np.ndarray,
                 u_target: np.ndarray, P: Params, margins: Optional[list] = None,
-                rounds: Optional[list] = None, prop_margins: Optional[list] = None):
+                rounds: Optional[list] = None, prop_margins: Optional[list] = None,
+                proposed: Optional[list] = None):
     """Generate one reasoning step of the target model by speculative decoding
     with the draft model (Section 5, "Combine RSD with SD"), appending to
     ``tokens`` in place; the step ends exactly as in ``gen_step``.
@@ -423,7 +424,8 @@ def gen_step_sd(rd: _Runner, rt: _Runner, tokens: List[int], u_prop: np.ndarray,
 
     ``rounds`` collects (proposed, kept) per round; ``margins`` the top-2 gap of
     the target's logits at every committed position and ``prop_margins`` that of
-    the draft's at every proposal (diagnostics for parity tests)."""
+    the draft's at every proposal (diagnostics for parity tests); ``proposed``
+    (place in the step, token) of every proposal."""
     def logits_of(run, y):
         lg = lm_logits(run.m, y).copy()
         lg[P.sep_id] += P.sep_logit_bias
@@ -449,6 +451,8 @@ def gen_step_sd(rd: _Runner, rt: _Runner, tokens: List[int], u_prop: np.ndarray,
             x = draw(q, uni(u_prop, len(spec)))
             if prop_margins is not None:
                 prop_margins.append(gap(lg))
+            if proposed is not None:
+                proposed.append((len(spec) - start, x))
             q_rows.append(q)
             spec.append(x)
             if x == P.sep_id or x == P.eos_id:
@@ -508,7 +512,7 @@ def generate_sequence(draft: OracleModel, target: OracleModel, prm: OracleModel,
         if reason != RUNNING:
             break
         ctx_pre = len(tokens)
-        dm, fm, pm, sd_rounds = [], [], [], []
+        dm, fm, pm, sd_rounds, proposed = [], [], [], [], []
         draft_step = gen_step(rd, tokens, u_draft, P, dm)
         if P.merge == "none":
             r = reward(prm, rp.last_hidden(tokens))
@@ -526,7 +530,7 @@ def generate_sequence(draft: OracleModel, target: OracleModel, prm: OracleModel,
             if P.merge == "target":
                 rt.truncate(ctx_pre - 1)
             if P.sd_k > 0:
-                final = gen_step_sd(rd, rt, tokens, u_prop, u_acc, u_target, P, fm, sd_rounds, pm)
+                final = gen_step_sd(rd, rt, tokens, u_prop, u_acc, u_target, P, fm, sd_rounds, pm, proposed)
             else:
                 final = gen_step(rt, tokens, u_target, P, fm)
         if P.eos_id >= 0 and P.eos_id in final:
@@ -539,7 +543,7 @@ def generate_sequence(draft: OracleModel, target: OracleModel, prm: OracleModel,
         records.append(dict(step=i, ctx_pre=ctx_pre, draft_tokens=list(draft_step), reward=r,
                             accepted=bool(ok), final_tokens=list(final), ctx_len=len(tokens),
                             kv_len=kv, n_pages=[-(-n // P.page_tokens) for n in kv],
-                            draft_margins=dm, final_margins=fm, sd_rounds=sd_rounds, proposal_margins=pm,
+                            draft_margins=dm, final_margins=fm, sd_rounds=sd_rounds, proposal_margins=pm, proposed=proposed,
                             finished=reason))
     return dict(tokens=tokens, prompt_len=len(prompt), records=records, finished=reason,
                 kv_len=[rd.kv_len, rt.kv_len, rp.kv_len])

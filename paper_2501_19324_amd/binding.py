@@ -25,7 +25,7 @@ RSD_DRAFT, RSD_TARGET, RSD_PRM = 0, 1, 2
 RSD_MERGE_NONE, RSD_MERGE_DRAFT, RSD_MERGE_TARGET = 0, 1, 2
 EXPORTED_SYMBOLS = ["rsd_init", "rsd_set_prompts", "rsd_set_uniforms", "rsd_set_criterion", "rsd_step",
                     "rsd_generate", "rsd_export_state", "rsd_export_pages", "rsd_set_teacher",
-                    "rsd_export_sampled", "rsd_forward", "rsd_sample", "rsd_stage_ms", "rsd_decode_stats", "rsd_probe_start", "rsd_probe_read",
+                    "rsd_export_sampled", "rsd_set_teacher_sd", "rsd_export_proposed", "rsd_forward", "rsd_sample", "rsd_stage_ms", "rsd_decode_stats", "rsd_probe_start", "rsd_probe_read",
                     "rsd_last_error", "rsd_destroy"]
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "librsd.so")
 
@@ -51,18 +51,20 @@ class _Params(C.Structure):
                 ("eos_id", C.c_int32), ("step_cap", C.c_int32), ("max_steps", C.c_int32), ("max_ctx", C.c_int32),
                 ("temperature", C.c_float), ("top_p", C.c_float), ("sep_logit_bias", C.c_float),
                 ("page_tokens", C.c_int32), ("kv_pool_bytes", C.c_uint64 * 3), ("use_graphs", C.c_int32),
-                ("merge_prm", C.c_int32)]
+                ("merge_prm", C.c_int32), ("sd_k", C.c_int32)]
 
 
 class _StepOut(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in ("draft_len", "draft_tokens", "reward", "accepted", "own_accept",
-                                          "final_len", "final_tokens", "finished")]
+                                          "final_len", "final_tokens", "finished", "sd_rounds", "sd_proposed",
+                                          "sd_kept")]
 
 
 class _GenOut(C.Structure):
     _fields_ = [("tokens", C.c_void_p), ("ctx_len", C.c_void_p), ("finished", C.c_void_p), ("steps_run", C.c_int32),
                 ("n_committed", C.c_int64), ("n_draft", C.c_int64), ("n_target", C.c_int64),
-                ("n_accept", C.c_int64), ("n_reject", C.c_int64)]
+                ("n_accept", C.c_int64), ("n_reject", C.c_int64), ("n_sd_rounds", C.c_int64),
+                ("n_sd_proposed", C.c_int64), ("n_sd_kept", C.c_int64)]
 
 
 _lib = None
@@ -107,6 +109,7 @@ class Context:
         self.step_cap = 0
         self.max_steps = 0
         self.vocab = 0
+        self.sd_k = 0
 
     def check(self, rc: int):
         if rc != RSD_OK:
@@ -128,7 +131,7 @@ def _shape_struct(s) -> _Shape:
 def rsd_init(shapes: Sequence, weights: Sequence, *, batch: int, delta: float, sep_id: int, step_cap: int,
              max_steps: int, max_ctx: int, eos_id: int = -1, temperature: float = 0.0, top_p: float = 1.0,
              sep_logit_bias: float = 0.0, omega_kind: int = 0, omega_a: float = 0.0, page_tokens: int = 16,
-             kv_pool_bytes=(0, 0, 0), use_graphs: int = 1, merge_prm: int = 0, stream=None) -> Context:
+             kv_pool_bytes=(0, 0, 0), use_graphs: int = 1, merge_prm: int = 0, sd_k: int = 0, stream=None) -> Context:
     """``weights``: three device tensors holding each model's blob (with ``merge_prm`` the third holds
     only the reward projection ``w_r`` and ``b_r``)."""
     import torch
@@ -138,12 +141,13 @@ def rsd_init(shapes: Sequence, weights: Sequence, *, batch: int, delta: float, s
     sh = (_Shape * 3)(*[_shape_struct(s) for s in shapes])
     ws = (_Weights * 3)(*[_Weights(w.data_ptr(), w.numel() * w.element_size()) for w in weights])
     p = _Params(delta, omega_kind, omega_a, sep_id, eos_id, step_cap, max_steps, max_ctx, temperature, top_p,
-                sep_logit_bias, page_tokens, (C.c_uint64 * 3)(*[int(x) for x in kv_pool_bytes]), use_graphs, merge_prm)
+                sep_logit_bias, page_tokens, (C.c_uint64 * 3)(*[int(x) for x in kv_pool_bytes]), use_graphs, merge_prm, sd_k)
     st = stream if stream is not None else torch.cuda.current_stream()
     ctx.keep["weights"] = list(weights)
     ctx.keep["stream"] = st
     ctx.batch, ctx.max_ctx, ctx.step_cap, ctx.max_steps, ctx.vocab = batch, max_ctx, step_cap, max_steps, shapes[0].vocab
     ctx.shapes = list(shapes)
+    ctx.sd_k = sd_k
     rc = lib.rsd_init(C.byref(ctx.handle), sh, ws, C.byref(p), C.c_int32(batch), C.c_void_p(st.cuda_stream))
     ctx.check(rc)
     return ctx
@@ -184,7 +188,8 @@ def rsd_step(ctx: Context) -> dict:
     o = dict(draft_len=np.zeros(B, np.int32), draft_tokens=np.full((B, cap), -1, np.int32),
              reward=np.zeros(B, np.float32), accepted=np.zeros(B, np.int32), own_accept=np.zeros(B, np.int32),
              final_len=np.zeros(B, np.int32), final_tokens=np.full((B, cap), -1, np.int32),
-             finished=np.zeros(B, np.int32))
+             finished=np.zeros(B, np.int32), sd_rounds=np.zeros(B, np.int32), sd_proposed=np.zeros(B, np.int32),
+             sd_kept=np.zeros(B, np.int32))
     so = _StepOut(*[_np_ptr(o[n]) for n, _ in _StepOut._fields_])
     ctx.check(load_library().rsd_step(ctx.handle, C.byref(so)))
     return o
@@ -194,10 +199,11 @@ def rsd_generate(ctx: Context, max_steps: int = 0, want_tokens: bool = True) -> 
     B = ctx.batch
     toks = np.zeros((B, ctx.max_ctx), np.int32) if want_tokens else None
     cl, fin = np.zeros(B, np.int32), np.zeros(B, np.int32)
-    g = _GenOut(_np_ptr(toks), _np_ptr(cl), _np_ptr(fin), 0, 0, 0, 0, 0, 0)
+    g = _GenOut(_np_ptr(toks), _np_ptr(cl), _np_ptr(fin), 0, 0, 0, 0, 0, 0, 0, 0, 0)
     rc = load_library().rsd_generate(ctx.handle, C.c_int32(max_steps), C.byref(g))
     out = dict(tokens=toks, ctx_len=cl, finished=fin, steps_run=g.steps_run, n_committed=g.n_committed,
-               n_draft=g.n_draft, n_target=g.n_target, n_accept=g.n_accept, n_reject=g.n_reject, rc=rc)
+               n_draft=g.n_draft, n_target=g.n_target, n_accept=g.n_accept, n_reject=g.n_reject, n_sd_rounds=g.n_sd_rounds,
+               n_sd_proposed=g.n_sd_proposed, n_sd_kept=g.n_sd_kept, rc=rc)
     ctx.check(rc)
     return out
 
@@ -224,6 +230,17 @@ def rsd_export_sampled(ctx: Context):
     b = np.zeros((ctx.batch, ctx.max_steps, ctx.step_cap), np.int32)
     ctx.check(load_library().rsd_export_sampled(ctx.handle, _np_ptr(a), _np_ptr(b)))
     return a, b
+
+
+def rsd_set_teacher_sd(ctx: Context, forced_proposal=None) -> None:
+    ctx.keep["teacher_sd"] = forced_proposal
+    ctx.check(load_library().rsd_set_teacher_sd(ctx.handle, _dev_ptr(forced_proposal)))
+
+
+def rsd_export_proposed(ctx: Context) -> np.ndarray:
+    a = np.zeros((ctx.batch, ctx.max_steps, ctx.step_cap * ctx.sd_k), np.int32)
+    ctx.check(load_library().rsd_export_proposed(ctx.handle, _np_ptr(a)))
+    return a
 
 
 def rsd_forward(ctx: Context, model: int, tokens: np.ndarray, lens: np.ndarray, chunk: int):

@@ -107,7 +107,14 @@ struct SeqState {
     float* reward;
     int* n_active;      // [1] sequences still active after the last bookkeeping pass
     int* cur_step;      // [1] index of the reasoning step in progress
-    int* sampled[2];    // [B][max_steps][step_cap] each: tokens chosen by the draft / target samplers
+    int* sampled[3];    // [B][max_steps][step_cap] each: tokens chosen by the draft / target samplers; [2]: the draft's proposals
+    // speculative regeneration of rejected steps (Section 5, "Combine RSD with SD")
+    int* sd_live;       // the step of this sequence is still being regenerated
+    int* sd_base;       // ctx_len when the round began
+    int* sd_lim;        // proposals of the round stay below this position
+    int* sd_nprop;      // proposals made / kept and rounds run in the current step
+    int* sd_nkept;
+    int* sd_nround;
 };
 
 // Acceptance criterion A_omega (Algorithm 2) on the rewards of the draft steps,
@@ -144,6 +151,44 @@ __global__ void gate_kernel(SeqState st, int B, float delta, int omega_kind, flo
         if (merge == 2) st.kv_len[1 * B + b] = pre - 1;
     }
     st.active[b] = !acc;                // the target stage runs on the rejected sequences
+}
+
+// Verification of one round of speculative regeneration, greedy decoding (Section 5, "Combine RSD
+// with SD"; Section 3: SD runs greedily).  Sequence b proposed tokens[base .. ctx_len) and the target
+// chose choice[row0[b] + i] for position base + i, i = 0 .. number of proposals.  The step grows by
+// the target's choices up to and including the first one that differs from the proposal at its place
+// (or the one after the last proposal), or that ends the step.  Both models keep keys/values for the
+// committed tokens they were fed only, never for the newest one.
+__global__ void sd_verify_kernel(SeqState st, int B, const int* __restrict__ row0, const int* __restrict__ choice,
+                                 const int* __restrict__ forced, int max_ctx, int max_steps, int step_cap,
+                                 int sep_id, int eos_id) {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= B || !st.sd_live[b]) return;
+    const int base = st.sd_base[b], np = st.ctx_len[b] - base, r0 = row0[b];
+    int sl = st.step_len[b], live = 1, kept = 0, m = 0;
+    for (int i = 0; i <= np && live; ++i) {
+        const size_t rec = ((size_t)b * max_steps + st.cur_step[0]) * step_cap + sl;
+        int t = choice[r0 + i];
+        st.sampled[1][rec] = t;
+        if (forced) { const int f = forced[rec]; if (f >= 0) t = f; }
+        const int pos = base + i;
+        const bool same = i < np && st.tokens[(size_t)b * max_ctx + pos] == t;
+        st.tokens[(size_t)b * max_ctx + pos] = t;
+        ++sl;
+        m = i + 1;
+        kept += same;
+        if (t == sep_id || t == eos_id || sl >= step_cap || pos + 1 >= max_ctx) live = 0;
+        if (!same) break;
+    }
+    st.step_len[b] = sl;
+    st.ctx_len[b] = base + m;
+    st.kv_len[1 * B + b] = base + m - 1;
+    st.kv_len[0 * B + b] = min(st.kv_len[0 * B + b], base + m - 1);
+    st.sd_nprop[b] += np;
+    st.sd_nkept[b] += kept;
+    st.sd_nround[b] += 1;
+    st.sd_live[b] = live;
+    st.active[b] = 0;
 }
 
 __global__ void fill_int_kernel(int* p, int v, size_t n) {

@@ -75,12 +75,22 @@ struct rsd_ctx {
     int* in_step() { return sb + 11 * B; }
     int* n_active() { return sb + 12 * B; }
     int* cur_step() { return sb + 12 * B + 1; }
+    int* sd_live() { return sb + 12 * B + 4; }
+    int* sd_base() { return sb + 13 * B + 4; }
+    int* sd_lim() { return sb + 14 * B + 4; }
+    int* sd_nprop() { return sb + 15 * B + 4; }
+    int* sd_nkept() { return sb + 16 * B + 4; }
+    int* sd_nround() { return sb + 17 * B + 4; }
     std::vector<int> prompt_len;
     int steps_done = 0;
     bool have_prompts = false;
     // borrowed
     const float *u_draft = nullptr, *u_target = nullptr, *u_gate = nullptr;
-    const int *forced_draft = nullptr, *forced_target = nullptr, *forced_accept = nullptr;
+    const int *forced_draft = nullptr, *forced_target = nullptr, *forced_accept = nullptr, *forced_prop = nullptr;
+    // speculative regeneration: hidden rows and logits the target's head is applied to, its choices,
+    // and per round the rows to gather ([rows] then first row of every sequence [B]; pinned + device)
+    float *sd_h = nullptr, *sd_logits = nullptr;
+    int *sd_choice = nullptr, *sd_rows_dev = nullptr, *sd_rows_h = nullptr;
     // workspaces (fp32 unless noted)
     int ws_rows = 0;
     float *h = nullptr, *xn = nullptr, *qkv = nullptr, *att = nullptr, *gu = nullptr, *act = nullptr;
@@ -106,7 +116,7 @@ struct rsd_ctx {
     bool in_decode_loop = false, probe_iter_on = false;     // inside the decode loop whole iterations are probed
     int probe_iters = 0;
     // single-token decode iterations recorded as graphs, one per (model, uniforms, teacher tokens)
-    struct DecodeGraph { int which; const float* u; const int* forced; hipGraph_t graph; hipGraphExec_t exec; };
+    struct DecodeGraph { int which; const float* u; const int* forced; int mode; hipGraph_t graph; hipGraphExec_t exec; };
     std::vector<DecodeGraph> graphs;
     hipStream_t cap_st = nullptr;          // recording stream (the caller's may be the null stream)
     bool graphs_ok = true;                 // cleared when recording fails: eager launches from then on
@@ -402,11 +412,13 @@ void launch_attn_prefill_mfma(rsd_ctx* c, const Model& m, int l, const RowMap& r
 #undef RSD_ATTN_CASE
 }
 
-// More than 8 rows over bf16 weights: MFMA kernels on activations split into hi + lo bf16 halves, which
-// live in c->xs_h / c->xs_l between the launches (9..64 rows: weight-streaming kernel; more: tile kernel)
+// Two or more rows over bf16 weights: MFMA kernels on activations split into hi + lo bf16 halves, which
+// live in c->xs_h / c->xs_l between the launches (2..64 rows: weight-streaming kernel; more: tile kernel).
+// (Measured on the 7B shape: a pass over 2 / 4 / 8 rows takes 6.5 / 6.3 / 5.7 ms this way and
+// 6.8 / 8.5 / 16.1 ms through the multi-row vector kernel, which fp32 weights still use.)
 template <typename WT>
 bool rows_path(const Model& m, int M) {
-    return std::is_same<WT, bf16_t>::value && M > 8 && m.s.d_model % 64 == 0 && m.q_dim % 64 == 0 && m.s.d_ffn % 64 == 0;
+    return std::is_same<WT, bf16_t>::value && M >= 2 && m.s.d_model % 64 == 0 && m.q_dim % 64 == 0 && m.s.d_ffn % 64 == 0;
 }
 // x (fp32 rows, optionally through RMSNorm with `gain`) -> the hi / lo halves
 void rows_split(rsd_ctx* c, const float* X, int ldx, int M, int K, const bf16_t* gain, float eps) {
@@ -466,8 +478,8 @@ void run_layers(rsd_ctx* c, Model& m, int M, const RowMap& rm, bool decode) {
     hipLaunchKernelGGL((embed_kernel<WT>), dim3(M), dim3(256), 0, st, wptr<WT>(m, m.off_embed), d, c->ds.tokens,
                        c->p.max_ctx, rm, c->h);
     const int S = decode ? m.splits : 1;
-    const bool fused = M <= 8;   // few rows: norm / SwiGLU / residual folded into the weight-streaming kernels
     const bool rows = rows_path<WT>(m, M);
+    const bool fused = M <= 8 && !rows;   // few rows: norm / SwiGLU / residual folded into the weight-streaming kernels
     const bool rows_fuse_norm = rows;                        // the residual GEMMs leave RMSNorm(h) for the next projection
     // batched decode: the attention kernel (or its merge kernel) writes the output as hi / lo halves itself
     const bool att_halves = rows && decode && m.s.dtype == RSD_BF16 && m.hd == 128;
@@ -565,7 +577,7 @@ void run_layers(rsd_ctx* c, Model& m, int M, const RowMap& rm, bool decode) {
 template <typename WT>
 void lm_head(rsd_ctx* c, Model& m, const float* X, int M, float* Y, int ldy) {
     const int d = m.s.d_model, V = m.s.vocab;
-    if (M <= 8) {
+    if (M <= 8 && !rows_path<WT>(m, M)) {
         ProbeScope ps(c, m, 4, (long long)V * d * sizeof(WT) + 4LL * M * (d + V), M == 1);
         gemv_launch<WT>(c->st, PRO_NORM, EPI_STORE, wptr<WT>(m, m.off_head), V, d, X, d, wptr<WT>(m, m.off_final_norm),
                         m.s.rms_eps, Y, ldy, M);
@@ -604,22 +616,24 @@ void sample_rows(rsd_ctx* c, const float* logits, int ld, int V, const float* u,
     }
 }
 
-AppendArgs append_args(rsd_ctx* c, int which, const int* forced) {
+AppendArgs append_args(rsd_ctx* c, int which, const int* forced, int mode = 1) {
     AppendArgs ap{};
-    ap.enabled = 1; ap.st = c->ds; ap.B = c->B; ap.max_ctx = c->p.max_ctx; ap.model = which; ap.forced = forced;
+    ap.enabled = mode; ap.st = c->ds; ap.B = c->B; ap.max_ctx = c->p.max_ctx; ap.model = which; ap.forced = forced;
     ap.sep_id = c->p.sep_id; ap.eos_id = c->p.eos_id; ap.step_cap = c->p.step_cap;
     ap.max_steps = c->p.max_steps;
+    ap.prop_stride = c->p.step_cap * c->p.sd_k;
     return ap;
 }
 
 // One single-token iteration of an LM model over all sequences: forward, head, sample, append.
+// mode 1: the token belongs to a reasoning step; mode 2: it is a proposal of speculative regeneration.
 template <typename WT>
-void decode_iter(rsd_ctx* c, int which, const float* u, const int* forced) {
+void decode_iter(rsd_ctx* c, int which, const float* u, const int* forced, int mode = 1) {
     Model& m = c->m[which];
     run_layers<WT>(c, m, c->B, decode_map(c, which), true);
     lm_head<WT>(c, m, c->h, c->B, c->logits, m.s.vocab);
     sample_rows(c, c->logits, m.s.vocab, m.s.vocab, u, c->ds.ctx_len, c->p.max_ctx, c->p.temperature, c->p.top_p,
-                c->p.sep_id, c->p.sep_logit_bias, c->ds.active, c->B, nullptr, append_args(c, which, forced));
+                c->p.sep_id, c->p.sep_logit_bias, c->ds.active, c->B, nullptr, append_args(c, which, forced, mode));
 }
 
 // The graph of one decode iteration of model `which`, recorded on first use.  Everything an
@@ -627,15 +641,15 @@ void decode_iter(rsd_ctx* c, int which, const float* u, const int* forced) {
 // tables, tokens) lives in device memory, so one recording serves every later iteration with the
 // same model, uniforms and teacher arrays.  nullptr: recording is not possible (eager from then on).
 template <typename WT>
-hipGraphExec_t decode_graph(rsd_ctx* c, int which, const float* u, const int* forced) {
+hipGraphExec_t decode_graph(rsd_ctx* c, int which, const float* u, const int* forced, int mode = 1) {
     for (const auto& g : c->graphs)
-        if (g.which == which && g.u == u && g.forced == forced) return g.exec;
+        if (g.which == which && g.u == u && g.forced == forced && g.mode == mode) return g.exec;
     auto give_up = [&]() { (void)hipGetLastError(); c->graphs_ok = false; return (hipGraphExec_t) nullptr; };
     if (!c->cap_st && hipStreamCreateWithFlags(&c->cap_st, hipStreamNonBlocking) != hipSuccess) return give_up();
     if (hipStreamBeginCapture(c->cap_st, hipStreamCaptureModeThreadLocal) != hipSuccess) return give_up();
     hipStream_t user = c->st;
     c->st = c->cap_st;
-    decode_iter<WT>(c, which, u, forced);
+    decode_iter<WT>(c, which, u, forced, mode);
     c->st = user;
     hipGraph_t graph = nullptr;
     if (hipStreamEndCapture(c->cap_st, &graph) != hipSuccess || !graph) return give_up();
@@ -644,7 +658,7 @@ hipGraphExec_t decode_graph(rsd_ctx* c, int which, const float* u, const int* fo
         (void)hipGraphDestroy(graph);
         return give_up();
     }
-    c->graphs.push_back(rsd_ctx::DecodeGraph{which, u, forced, graph, exec});
+    c->graphs.push_back(rsd_ctx::DecodeGraph{which, u, forced, mode, graph, exec});
     return exec;
 }
 
@@ -698,9 +712,12 @@ int prefill(rsd_ctx* c, int which, std::vector<Piece> pieces, AfterPass after_pa
 // One stage of token generation (a reasoning step) with an LM model on the
 // currently active sequences.  The first iteration feeds whatever the model
 // has not seen yet (one token, or a catch-up chunk), the rest one token each.
+// mode 2 / max_iters: the draft's proposals of one round of speculative regeneration (at most
+// max_iters tokens per sequence, each sequence bounded by its own sd_lim).
 template <typename WT>
-int gen_stage(rsd_ctx* c, int which, const float* u, const int* forced) {
+int gen_stage(rsd_ctx* c, int which, const float* u, const int* forced, int mode = 1, int max_iters = 0) {
     const int B = c->B;
+    const int cap = mode == 2 ? max_iters : c->p.step_cap;
     Model& m = c->m[which];
     std::vector<Piece> pieces;
     bool all_single = true;
@@ -722,29 +739,29 @@ int gen_stage(rsd_ctx* c, int which, const float* u, const int* forced) {
         if (rc != RSD_OK) return rc;
         lm_head<WT>(c, m, c->hl, B, c->logits, m.s.vocab);
         sample_rows(c, c->logits, m.s.vocab, m.s.vocab, u, c->ds.ctx_len, c->p.max_ctx, c->p.temperature, c->p.top_p,
-                    c->p.sep_id, c->p.sep_logit_bias, c->ds.active, B, nullptr, append_args(c, which, forced));
+                    c->p.sep_id, c->p.sep_logit_bias, c->ds.active, B, nullptr, append_args(c, which, forced, mode));
         iters = 1;
     }
     c->in_decode_loop = true;
-    while (iters < c->p.step_cap) {
+    while (iters < cap) {
         // an iteration whose launches are timed runs eagerly (events cannot bracket a node of a graph),
         // and so does the first one of a model (it raises the kernels' LDS limits)
         c->probe_iter_on = c->probe_model == which && c->probe_used + 2 <= c->probe_ev.size() &&
                            (c->probe_iters++ % c->probe_stride) == 0;
         hipGraphExec_t exec = nullptr;
         if (c->p.use_graphs && c->graphs_ok && !c->probe_iter_on && c->decode_warm[which])
-            exec = decode_graph<WT>(c, which, u, forced);
+            exec = decode_graph<WT>(c, which, u, forced, mode);
         if (exec) {
             const hipError_t e = hipGraphLaunch(exec, c->st);
             if (e != hipSuccess) { c->in_decode_loop = false; return fail(c, RSD_EHIP, "hipGraphLaunch: %s", hipGetErrorString(e)); }
             ++c->n_graph_replays;
         } else {
-            decode_iter<WT>(c, which, u, forced);
+            decode_iter<WT>(c, which, u, forced, mode);
             ++c->n_eager_iters;
             c->decode_warm[which] = true;
         }
         ++iters;
-        if (iters % kPoll == 0 || iters == c->p.step_cap) {
+        if (iters % kPoll == 0 || iters == cap) {
             HIPCHK(c, hipMemcpyAsync(c->poll_h, c->ds.n_active, sizeof(int), hipMemcpyDeviceToHost, c->st));
             HIPCHK(c, hipStreamSynchronize(c->st));
             if (*c->poll_h <= 0) break;
@@ -756,8 +773,9 @@ int gen_stage(rsd_ctx* c, int which, const float* u, const int* forced) {
     return RSD_OK;
 }
 
-int gen_stage_any(rsd_ctx* c, int which, const float* u, const int* forced) {
-    return c->m[which].s.dtype == RSD_F32 ? gen_stage<float>(c, which, u, forced) : gen_stage<bf16_t>(c, which, u, forced);
+int gen_stage_any(rsd_ctx* c, int which, const float* u, const int* forced, int mode = 1, int max_iters = 0) {
+    return c->m[which].s.dtype == RSD_F32 ? gen_stage<float>(c, which, u, forced, mode, max_iters)
+                                          : gen_stage<bf16_t>(c, which, u, forced, mode, max_iters);
 }
 
 // tokens[b][ctx_pre[b] + j] -> dst[b][j], j < step_cap
@@ -773,6 +791,91 @@ int fetch_step_tokens(rsd_ctx* c) {
     hipLaunchKernelGGL(extract_step_kernel, dim3(c->B), dim3(64), 0, c->st, c->ds.tokens, c->ds.ctx_pre, c->ds.ctx_len,
                        c->p.max_ctx, c->p.step_cap, c->steptok_dev);
     HIPCHK(c, hipMemcpyAsync(c->steptok_h, c->steptok_dev, (size_t)c->B * c->p.step_cap * sizeof(int), hipMemcpyDeviceToHost, c->st));
+    return RSD_OK;
+}
+
+// Target step of the rejected sequences by token-level speculative decoding with the draft
+// (Section 5, "Combine RSD with SD"), greedy.  On entry the host mirror is current and active[] marks
+// the rejected sequences.  Each round: the host fixes every live sequence's proposal budget, the
+// draft decodes up to sd_k proposals, the target reads its unseen tokens and the proposals in one
+// chunked pass, its head and arg max run on the last proposals + 1 rows of every sequence, and
+// sd_verify_kernel commits.  The host reads the state back twice per round (it builds the row maps).
+template <typename WT>
+int sd_stage(rsd_ctx* c) {
+    const int B = c->B, k = c->p.sd_k;
+    const rsd_params& P = c->p;
+    Model& mt = c->m[RSD_TARGET];
+    const int d = mt.s.d_model, V = mt.s.vocab;
+    for (int b = 0; b < B; ++b) {
+        c->sd_live()[b] = c->active()[b];
+        c->sd_nprop()[b] = c->sd_nkept()[b] = c->sd_nround()[b] = 0;
+    }
+    int rc;
+    for (;;) {
+        int n_live = 0, n_prop = 0, max_g = 0;
+        for (int b = 0; b < B; ++b) {
+            c->active()[b] = 0;
+            if (!c->sd_live()[b]) continue;
+            ++n_live;
+            const int n = c->ctx_len()[b], used = n - c->ctx_pre()[b];
+            const int g = std::max(0, std::min(k, std::min(P.step_cap - used - 1, P.max_ctx - n - 1)));
+            c->sd_base()[b] = n;
+            c->sd_lim()[b] = n + g;
+            // both models feed the newest committed token again (its keys may be missing or stale)
+            c->kv_len(RSD_DRAFT)[b] = std::min(c->kv_len(RSD_DRAFT)[b], n - 1);
+            c->kv_len(RSD_TARGET)[b] = std::min(c->kv_len(RSD_TARGET)[b], n - 1);
+            if (g > 0) { c->active()[b] = 1; ++n_prop; max_g = std::max(max_g, g); }
+        }
+        if (!n_live) break;
+        *c->n_active() = n_prop;
+        if ((rc = push_state(c))) return rc;
+        if (n_prop) {
+            if ((rc = gen_stage_any(c, RSD_DRAFT, nullptr, c->forced_prop, 2, max_g))) return rc;
+            if ((rc = pull_state(c))) return rc;
+        }
+        // ---- the target's pass: catch-up first when everything together exceeds one pass
+        std::vector<Piece> pieces;
+        long long rows_all = 0;
+        for (int b = 0; b < B; ++b)
+            if (c->sd_live()[b]) rows_all += c->ctx_len()[b] - c->kv_len(RSD_TARGET)[b];
+        if (rows_all > kMaxRows) {
+            for (int b = 0; b < B; ++b)
+                if (c->sd_live()[b] && c->kv_len(RSD_TARGET)[b] < c->sd_base()[b] - 1)
+                    pieces.push_back(Piece{b, c->kv_len(RSD_TARGET)[b], c->sd_base()[b] - 1});
+            rc = prefill<WT>(c, RSD_TARGET, pieces, [](const std::vector<Piece>&, const std::vector<int>&, int) { return RSD_OK; });
+            if (rc) return rc;
+            for (const Piece& pc : pieces) c->kv_len(RSD_TARGET)[pc.b] = pc.end;
+            pieces.clear();
+        }
+        int n_rows = 0;
+        for (int b = 0; b < B; ++b)
+            if (c->sd_live()[b]) pieces.push_back(Piece{b, c->kv_len(RSD_TARGET)[b], c->ctx_len()[b]});
+        auto after = [&](const std::vector<Piece>& pass, const std::vector<int>& first_row, int) {
+            // one pass holds every piece whole here: the rows of the last proposals + 1 positions
+            int* rows = c->sd_rows_h;
+            int* row0 = c->sd_rows_h + (size_t)B * (k + 1);
+            std::fill(row0, row0 + B, 0);
+            for (size_t i = 0; i < pass.size(); ++i) {
+                const Piece& pc = pass[i];
+                const int cnt = pc.end - c->sd_base()[pc.b] + 1;
+                row0[pc.b] = n_rows;
+                for (int j = 0; j < cnt; ++j) rows[n_rows++] = first_row[i] + (pc.end - pc.start) - cnt + j;
+            }
+            HIPCHK(c, hipMemcpyAsync(c->sd_rows_dev, c->sd_rows_h, ((size_t)B * (k + 2)) * sizeof(int), hipMemcpyHostToDevice, c->st));
+            hipLaunchKernelGGL(gather_rows_kernel, dim3(n_rows), dim3(256), 0, c->st, c->h, c->sd_rows_dev, d, c->sd_h);
+            return RSD_OK;
+        };
+        if ((rc = prefill<WT>(c, RSD_TARGET, pieces, after))) return rc;
+        lm_head<WT>(c, mt, c->sd_h, n_rows, c->sd_logits, V);
+        AppendArgs off{};
+        sample_rows(c, c->sd_logits, V, V, nullptr, nullptr, 0, 0.0f, 1.0f, P.sep_id, P.sep_logit_bias, nullptr, n_rows,
+                    c->sd_choice, off);
+        hipLaunchKernelGGL(sd_verify_kernel, dim3(ceil_div(B, 64)), dim3(64), 0, c->st, c->ds, B,
+                           c->sd_rows_dev + (size_t)B * (k + 1), c->sd_choice, c->forced_target, P.max_ctx, P.max_steps,
+                           P.step_cap, P.sep_id, P.eos_id);
+        if ((rc = pull_state(c))) return rc;
+    }
+    HIPCHK(c, hipGetLastError());
     return RSD_OK;
 }
 
@@ -801,14 +904,14 @@ void rsd_destroy(rsd_ctx* c) {
         (void)hipFree(m.pool); (void)hipFree(m.bt_dev); (void)hipFree(m.rope);
         if (m.bt_host) (void)hipHostFree(m.bt_host);
     }
-    void* dev[] = {c->sb_dev, c->ds.tokens, c->ds.sampled[0], c->ds.sampled[1], c->h, c->xn, c->qkv, c->att, c->gu, c->act,
+    void* dev[] = {c->sb_dev, c->ds.tokens, c->ds.sampled[0], c->ds.sampled[1], c->ds.sampled[2], c->sd_h, c->sd_logits, c->sd_choice, c->sd_rows_dev, c->h, c->xn, c->qkv, c->att, c->gu, c->act,
                    c->part_acc, c->part_ml, c->part_k, c->xs_h, c->xs_l, c->smp_pmax, c->smp_pidx, c->smp_hist, c->smp_psum, c->smp_sel, c->hl, c->xl, c->logits, c->tmp_reward, c->chosen, c->steptok_dev,
                    c->row_seq_dev, c->row_pos_dev, c->last_row_dev, c->item_row0_dev, c->item_n_dev};
     for (void* p : dev) if (p) (void)hipFree(p);
     for (hipEvent_t e : c->probe_ev) (void)hipEventDestroy(e);
     for (auto& g : c->graphs) { (void)hipGraphExecDestroy(g.exec); (void)hipGraphDestroy(g.graph); }
     if (c->cap_st) (void)hipStreamDestroy(c->cap_st);
-    void* pin[] = {c->sb, c->item_row0_h, c->item_n_h, c->row_seq_h, c->row_pos_h, c->last_row_h, c->steptok_h, c->poll_h};
+    void* pin[] = {c->sb, c->sd_rows_h, c->item_row0_h, c->item_n_h, c->row_seq_h, c->row_pos_h, c->last_row_h, c->steptok_h, c->poll_h};
     for (void* p : pin) if (p) (void)hipHostFree(p);
     delete c;
 }
@@ -829,6 +932,11 @@ int rsd_init(rsd_ctx** out, const rsd_model_shape shape[3], const rsd_weights w[
     if (p->temperature < 0.f || p->top_p < 0.f || p->top_p > 1.f) return fail(c, RSD_EINVAL, "bad temperature/top_p");
     if (p->omega_kind < 0 || p->omega_kind > 4) return fail(c, RSD_EINVAL, "bad omega_kind");
     if (p->merge_prm < RSD_MERGE_NONE || p->merge_prm > RSD_MERGE_TARGET) return fail(c, RSD_EINVAL, "bad merge_prm");
+    if (p->sd_k < 0 || p->sd_k > 15) return fail(c, RSD_EINVAL, "sd_k %d outside [0, 15]", p->sd_k);
+    if (p->sd_k > 0 && p->temperature != 0.f)
+        return fail(c, RSD_EINVAL, "speculative regeneration (sd_k > 0) is implemented for greedy decoding only");
+    if (p->sd_k > 0 && (long long)batch * (p->sd_k + 1) > kMaxRows)
+        return fail(c, RSD_EINVAL, "batch * (sd_k + 1) exceeds the %d rows of one verification pass", kMaxRows);
     for (int i = 0; i < 3; ++i) {
         int rc = setup_model(c, c->m[i], shape[i], w[i], i, i == RSD_PRM && p->merge_prm != RSD_MERGE_NONE);
         if (rc) return rc;
@@ -854,13 +962,14 @@ int rsd_init(rsd_ctx** out, const rsd_model_shape shape[3], const rsd_weights w[
     }
     const int B = batch;
     const size_t mc = p->max_ctx;
-    c->sb_ints = (size_t)12 * B + 4;
+    c->sb_ints = (size_t)18 * B + 4;
     HIPCHK(c, dev_alloc(&c->sb_dev, c->sb_ints));
     HIPCHK(c, pin_alloc(&c->sb, c->sb_ints));
     std::fill(c->sb, c->sb + c->sb_ints, 0);
     HIPCHK(c, dev_alloc(&c->ds.tokens, B * mc));
     HIPCHK(c, dev_alloc(&c->ds.sampled[0], (size_t)B * p->max_steps * p->step_cap));
     HIPCHK(c, dev_alloc(&c->ds.sampled[1], (size_t)B * p->max_steps * p->step_cap));
+    HIPCHK(c, dev_alloc(&c->ds.sampled[2], (size_t)B * p->max_steps * p->step_cap * p->sd_k));
     c->ds.ctx_len = c->sb_dev;
     c->ds.kv_len = c->sb_dev + B;
     c->ds.active = c->sb_dev + 4 * B;
@@ -873,6 +982,12 @@ int rsd_init(rsd_ctx** out, const rsd_model_shape shape[3], const rsd_weights w[
     c->in_step_dev = c->sb_dev + 11 * B;
     c->ds.n_active = c->sb_dev + 12 * B;
     c->ds.cur_step = c->sb_dev + 12 * B + 1;
+    c->ds.sd_live = c->sb_dev + 12 * B + 4;
+    c->ds.sd_base = c->sb_dev + 13 * B + 4;
+    c->ds.sd_lim = c->sb_dev + 14 * B + 4;
+    c->ds.sd_nprop = c->sb_dev + 15 * B + 4;
+    c->ds.sd_nkept = c->sb_dev + 16 * B + 4;
+    c->ds.sd_nround = c->sb_dev + 17 * B + 4;
     // workspaces sized for the widest model
     int d = 0, nq = 0, qd = 0, F = 0, V = 0, HS = 0;
     for (auto& m : c->m) {
@@ -911,6 +1026,15 @@ int rsd_init(rsd_ctx** out, const rsd_model_shape shape[3], const rsd_weights w[
     HIPCHK(c, dev_alloc(&c->xl, (size_t)B * d));
     HIPCHK(c, dev_alloc(&c->logits, (size_t)B * V));
     HIPCHK(c, dev_alloc(&c->tmp_reward, R));
+    if (p->sd_k > 0) {
+        const size_t rows = (size_t)B * (p->sd_k + 1);
+        HIPCHK(c, dev_alloc(&c->sd_h, rows * d));
+        HIPCHK(c, dev_alloc(&c->sd_logits, rows * V));
+        HIPCHK(c, dev_alloc(&c->sd_choice, rows));
+        HIPCHK(c, dev_alloc(&c->sd_rows_dev, rows + B));
+        HIPCHK(c, pin_alloc(&c->sd_rows_h, rows + B));
+        std::fill(c->sd_rows_h, c->sd_rows_h + rows + B, 0);
+    }
     HIPCHK(c, dev_alloc(&c->chosen, (size_t)B));
     HIPCHK(c, dev_alloc(&c->steptok_dev, (size_t)B * p->step_cap));
     HIPCHK(c, dev_alloc(&c->row_seq_dev, R));
@@ -948,6 +1072,8 @@ int rsd_set_prompts(rsd_ctx* c, const int32_t* tokens_dev, const int32_t* prompt
     const size_t ns = (size_t)B * c->p.max_steps * c->p.step_cap;
     for (int s = 0; s < 2; ++s)
         hipLaunchKernelGGL(fill_int_kernel, dim3((unsigned)((ns + 255) / 256)), dim3(256), 0, c->st, c->ds.sampled[s], -1, ns);
+    if (const size_t np = ns * c->p.sd_k)
+        hipLaunchKernelGGL(fill_int_kernel, dim3((unsigned)((np + 255) / 256)), dim3(256), 0, c->st, c->ds.sampled[2], -1, np);
     for (int b = 0; b < B; ++b) {
         c->prompt_len[b] = prompt_len_host[b];
         c->ctx_len()[b] = prompt_len_host[b];
@@ -1007,6 +1133,7 @@ int rsd_step(rsd_ctx* c, rsd_step_out* out) {
         c->accepted()[b] = 0;
         c->own_accept()[b] = 0;
         c->reward()[b] = 0.f;
+        c->sd_live()[b] = c->sd_nprop()[b] = c->sd_nkept()[b] = c->sd_nround()[b] = 0;
     }
     *c->n_active() = n_in;
     for (int b = 0; b < B; ++b)
@@ -1113,7 +1240,9 @@ int rsd_step(rsd_ctx* c, rsd_step_out* out) {
         *c->n_active() = n_rej;
         if ((rc = push_state(c))) return rc;
         if ((rc = upload_tables(c, c->m[RSD_TARGET]))) return rc;
-        if ((rc = gen_stage_any(c, RSD_TARGET, c->u_target, c->forced_target))) return rc;
+        if (P.sd_k > 0) rc = c->m[RSD_TARGET].s.dtype == RSD_F32 ? sd_stage<float>(c) : sd_stage<bf16_t>(c);
+        else rc = gen_stage_any(c, RSD_TARGET, c->u_target, c->forced_target);
+        if (rc) return rc;
         if ((rc = fetch_step_tokens(c))) return rc;
         if ((rc = pull_state(c))) return rc;
         for (int b = 0; b < B; ++b)
@@ -1125,6 +1254,11 @@ int rsd_step(rsd_ctx* c, rsd_step_out* out) {
 
     // ---- termination test and record
     c->steps_done += 1;
+    for (int b = 0; b < B && out; ++b) {
+        if (out->sd_rounds) out->sd_rounds[b] = c->sd_nround()[b];
+        if (out->sd_proposed) out->sd_proposed[b] = c->sd_nprop()[b];
+        if (out->sd_kept) out->sd_kept[b] = c->sd_nkept()[b];
+    }
     for (int b = 0; b < B; ++b) {
         if (!c->in_step()[b]) {
             if (out && out->final_len) out->final_len[b] = 0;
@@ -1154,9 +1288,10 @@ int rsd_generate(rsd_ctx* c, int32_t max_steps, rsd_gen_out* out) {
     if (!c->have_prompts) return fail(c, RSD_ESTATE, "no prompts set");
     const int B = c->B;
     const int limit = max_steps > 0 ? std::min(max_steps, c->p.max_steps) : c->p.max_steps;
-    std::vector<int> dl(B), fl(B), acc(B);
+    std::vector<int> dl(B), fl(B), acc(B), sr(B), sp(B), sk(B);
     rsd_step_out so{};
     so.draft_len = dl.data(); so.final_len = fl.data(); so.accepted = acc.data();
+    so.sd_rounds = sr.data(); so.sd_proposed = sp.data(); so.sd_kept = sk.data();
     rsd_gen_out g{};
     if (out) { g.tokens = out->tokens; g.ctx_len = out->ctx_len; g.finished = out->finished; }
     while (c->steps_done < limit) {
@@ -1172,6 +1307,7 @@ int rsd_generate(rsd_ctx* c, int32_t max_steps, rsd_gen_out* out) {
             if (was[b]) {
                 g.n_draft += dl[b];
                 if (acc[b]) g.n_accept += 1; else { g.n_reject += 1; g.n_target += fl[b]; }
+                g.n_sd_rounds += sr[b]; g.n_sd_proposed += sp[b]; g.n_sd_kept += sk[b];
             }
     }
     for (int b = 0; b < B; ++b) g.n_committed += c->ctx_len()[b] - c->prompt_len[b];
@@ -1216,6 +1352,21 @@ int rsd_export_sampled(rsd_ctx* c, int32_t* sampled_draft, int32_t* sampled_targ
     const size_t n = (size_t)c->B * c->p.max_steps * c->p.step_cap * sizeof(int);
     if (sampled_draft) HIPCHK(c, hipMemcpyAsync(sampled_draft, c->ds.sampled[0], n, hipMemcpyDeviceToHost, c->st));
     if (sampled_target) HIPCHK(c, hipMemcpyAsync(sampled_target, c->ds.sampled[1], n, hipMemcpyDeviceToHost, c->st));
+    HIPCHK(c, hipStreamSynchronize(c->st));
+    return RSD_OK;
+}
+
+int rsd_set_teacher_sd(rsd_ctx* c, const int32_t* forced_proposal_dev) {
+    if (!c) return RSD_EINVAL;
+    c->forced_prop = forced_proposal_dev;
+    return RSD_OK;
+}
+
+int rsd_export_proposed(rsd_ctx* c, int32_t* proposed) {
+    if (!c || !proposed) return RSD_EINVAL;
+    if (c->p.sd_k <= 0) return fail(c, RSD_ESTATE, "no speculative regeneration in this context");
+    const size_t n = (size_t)c->B * c->p.max_steps * c->p.step_cap * c->p.sd_k * sizeof(int);
+    HIPCHK(c, hipMemcpyAsync(proposed, c->ds.sampled[2], n, hipMemcpyDeviceToHost, c->st));
     HIPCHK(c, hipStreamSynchronize(c->st));
     return RSD_OK;
 }

@@ -77,9 +77,10 @@ struct SampleArgs {
 
 // what phase F does with the chosen token besides (or instead of) storing it
 struct AppendArgs {
-    int enabled;
+    int enabled;                 // 0: off; 1: a token of a reasoning step; 2: a proposal of speculative regeneration
     SeqState st; int B, max_ctx, model;
     const int* forced; int sep_id, eos_id, step_cap, max_steps;
+    int prop_stride;             // proposals recorded per step (mode 2): step_cap * proposals per round
 };
 
 __device__ __forceinline__ float smp_x(const SampleArgs& a, const float* lg, int i) {
@@ -327,6 +328,23 @@ __global__ __launch_bounds__(SMP_T) void sample_finish_kernel(SampleArgs a, Appe
     const SeqState& st = ap.st;
     const int b = row;
     const int pos = st.ctx_len[b];
+    if (ap.enabled == 2) {
+        // a proposal: written behind the committed tokens and recorded as the n-th proposal of the
+        // step (a place of the step can be proposed for in several rounds); the step's own length
+        // and records wait for the target's verdict
+        const size_t rec = ((size_t)b * ap.max_steps + st.cur_step[0]) * ap.prop_stride + st.sd_nprop[b] + (pos - st.sd_base[b]);
+        st.sampled[2][rec] = token;
+        int tok = token;
+        if (ap.forced) { const int f = ap.forced[rec]; if (f >= 0) tok = f; }
+        st.tokens[(size_t)b * ap.max_ctx + pos] = tok;
+        st.ctx_len[b] = pos + 1;
+        st.kv_len[ap.model * ap.B + b] = pos;
+        if (tok == ap.sep_id || tok == ap.eos_id || pos + 1 >= st.sd_lim[b]) {
+            st.active[b] = 0;
+            atomicSub(st.n_active, 1);
+        }
+        return;
+    }
     const size_t rec = ((size_t)b * ap.max_steps + st.cur_step[0]) * ap.step_cap + st.step_len[b];
     st.sampled[ap.model][rec] = token;
     int tok = token;

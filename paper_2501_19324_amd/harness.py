@@ -13,7 +13,7 @@ class Session:
     """A context plus the device buffers it borrows."""
 
     def __init__(self, w: Workload, delta=None, weights=None, use_graphs: int = 1, kv_pool_bytes=(0, 0, 0),
-                 omega_kind=None, omega_a=None, merge_prm: int = 0):
+                 omega_kind=None, omega_a=None, merge_prm: int = 0, sd_k: int = 0):
         """``merge_prm`` = 1 / 2: the reward head sits on the draft's / target's trunk.  ``w.prm`` must then
         repeat that model's shape; of the reward model's generated blob only the projection (its last
         d_model + 8 elements: w_r, b_r) is handed over."""
@@ -30,7 +30,7 @@ class Session:
                               sep_logit_bias=w.sep_logit_bias,
                               omega_kind=w.omega_kind if omega_kind is None else omega_kind,
                               omega_a=w.omega_a if omega_a is None else omega_a,
-                              kv_pool_bytes=kv_pool_bytes, use_graphs=use_graphs)
+                              kv_pool_bytes=kv_pool_bytes, use_graphs=use_graphs, sd_k=sd_k)
         self.prompt_len = prompt_lengths(w)
         self.tokens_host = prompt_tokens(w)
         self.tokens = torch.from_numpy(self.tokens_host).to(dev)

@@ -54,8 +54,8 @@ def mid_models():
 
 @pytest.mark.parametrize("batch,chunk", [(3, 1), (3, 64), (12, 1), (12, 7)])
 def test_forward_logits_and_rewards_bf16(gpu, mid_models, batch, chunk):
-    """batch 3 runs the fused weight-streaming kernels in the single-token path,
-    batch 12 the tiled MFMA GEMMs; chunks > 1 run the chunked prefill."""
+    """batch 3 and 12 run the few-row MFMA weight-streaming GEMM in the single-token path (3 rows: one
+    partly filled 16-row block); chunks > 1 run the chunked prefill."""
     from oracle import rsd_oracle as O
     R = gpu["R"]
     w = mid_workload(batch)

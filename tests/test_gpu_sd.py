@@ -1,0 +1,257 @@
+"""GPU parity of the speculative regeneration of rejected steps (Section 5,
+"Combine RSD with SD"; greedy, as the paper runs SD): the HIP path against the
+CPU checker on the same seeded inputs - committed tokens, the draft's proposals,
+rounds / proposals / kept counts and KV offsets exact in the tiny fp32
+configuration; under a teacher in bf16."""
+from dataclasses import replace
+
+import numpy as np
+import pytest
+
+from test_gpu_tiny import gpu, oracle_params, TOL  # noqa: F401  (fixture)
+
+pytestmark = pytest.mark.gpu
+
+
+def compare_sd(gpu, w, models, sd_k, merge=0, weights=None, min_margin=0.0):
+    """min_margin: sequences in which the checker met a top-2 logit gap below it (a near-tie the fp32
+    path may resolve the other way) still run but are not compared."""
+    from oracle import rsd_oracle as O
+    R = gpu["R"]
+    s = gpu["Session"](w, merge_prm=merge, sd_k=sd_k, weights=weights)
+    P = oracle_params(O, w, merge=("none", "draft", "target")[merge], sd_k=sd_k)
+    refs = [O.generate_sequence(*models, s.tokens_host[b, :s.prompt_len[b]], s.u_host["U_DRAFT"][b],
+                                s.u_host["U_TARGET"][b], s.u_host["U_GATE"][b], P) for b in range(w.batch)]
+    tot = dict(rej=0, rounds=0, prop=0, kept=0, skipped=0)
+    skip = set()
+    for b, ref in enumerate(refs):
+        gaps = [x for r in ref["records"] for x in r["draft_margins"] + r["final_margins"] + r["proposal_margins"]]
+        if min(gaps) < min_margin:
+            skip.add(b)
+    tot["skipped"] = len(skip)
+    for i in range(w.max_steps):
+        if all(len(r["records"]) <= i for r in refs):
+            break
+        g = R.rsd_step(s.ctx)
+        st = R.rsd_export_state(s.ctx)
+        for b in range(w.batch):
+            if b in skip:
+                continue
+            if len(refs[b]["records"]) <= i:
+                assert g["final_len"][b] == 0
+                continue
+            r = refs[b]["records"][i]
+            assert list(g["draft_tokens"][b, :g["draft_len"][b]]) == r["draft_tokens"], (b, i)
+            assert abs(float(g["reward"][b]) - r["reward"]) < TOL, (b, i)
+            assert bool(g["accepted"][b]) == r["accepted"], (b, i)
+            assert list(g["final_tokens"][b, :g["final_len"][b]]) == r["final_tokens"], (b, i)
+            assert g["finished"][b] == r["finished"], (b, i)
+            assert st["ctx_len"][b] == r["ctx_len"]
+            assert list(st["kv_len"][:, b]) == r["kv_len"], (b, i, st["kv_len"][:, b], r["kv_len"])
+            assert list(st["n_pages"][:, b]) == r["n_pages"], (b, i)
+            rounds = r["sd_rounds"]
+            assert g["sd_rounds"][b] == len(rounds), (b, i, g["sd_rounds"][b], rounds)
+            assert g["sd_proposed"][b] == sum(p for p, _ in rounds) and g["sd_kept"][b] == sum(k for _, k in rounds), (b, i, rounds)
+            tot["rej"] += not r["accepted"]
+            tot["rounds"] += len(rounds); tot["prop"] += sum(p for p, _ in rounds); tot["kept"] += sum(k for _, k in rounds)
+    prop = R.rsd_export_proposed(s.ctx)
+    _, own_t = R.rsd_export_sampled(s.ctx)
+    for b in range(w.batch):
+        if b in skip:
+            continue
+        want = np.full(prop.shape[1:], -1, np.int32)
+        for r in refs[b]["records"]:
+            for n, (_, t) in enumerate(r["proposed"]):
+                want[r["step"], n] = t
+            if not r["accepted"]:
+                assert list(own_t[b, r["step"], :len(r["final_tokens"])]) == r["final_tokens"]
+        assert np.array_equal(prop[b], want), b
+    st = R.rsd_export_state(s.ctx)
+    for b in range(w.batch):
+        n = st["ctx_len"][b]
+        assert b in skip or list(st["tokens"][b, :n]) == refs[b]["tokens"][:n]
+    s.close()
+    return tot
+
+
+@pytest.mark.parametrize("sd_k", [1, 3, 7])
+def test_config0_regeneration_by_speculation(gpu, tiny, sd_k):
+    from rsd_inputs import workload
+    w = workload("cfg0", sep_logit_bias=0.6, deltas=(0.55,))
+    tot = compare_sd(gpu, w, tiny["models"], sd_k)
+    assert tot["rej"] >= 2 and tot["rounds"] > 0 and tot["prop"] >= tot["rounds"] - tot["rej"]
+    print(tot)
+
+
+@pytest.mark.parametrize("merge", [1, 2])
+def test_config0_speculation_with_merged_reward_head(gpu, tiny, merge):
+    from rsd_inputs import workload, model_weights_np
+    from oracle import rsd_oracle as O
+    w = workload("cfg0", sep_logit_bias=0.6)
+    policy = w.draft if merge == 1 else w.target
+    w = replace(w, prm=replace(policy, head_kind="reward"))
+    head = model_weights_np(w.seed, 2, w.prm)
+    trunk = tiny["models"][merge - 1]._w
+    pm = O.OracleModel(w.prm, {**{k: v for k, v in trunk.items() if k != "lm_head"}, "w_r": head["w_r"], "b_r": head["b_r"]})
+    models = [tiny["models"][0], tiny["models"][1], pm]
+    w = replace(w, deltas=(1.01,))                # every step rejected
+    tot = compare_sd(gpu, w, models, 3, merge=merge)
+    assert tot["rej"] >= 8
+
+
+def test_a_draft_equal_to_the_target_has_every_proposal_kept(gpu, tiny):
+    """Two copies of one model: every proposal is kept, rounds commit sd_k + 1 tokens, and the draft
+    then has two tokens to catch up with (its chunked path inside the proposal stage)."""
+    from rsd_inputs import workload, model_blob_torch
+    import torch
+    w = workload("cfg0", sep_logit_bias=0.3, deltas=(1.01,))
+    w = replace(w, draft=w.target)
+    d, t, p = tiny["models"]
+    dev = torch.device("cuda:0")
+    blobs = [model_blob_torch(w.seed, 1, w.target, dev), model_blob_torch(w.seed, 1, w.target, dev),
+             model_blob_torch(w.seed, 2, w.prm, dev)]
+    tot = compare_sd(gpu, w, [t, t, p], 3, weights=blobs)
+    assert tot["prop"] == tot["kept"] > 0
+
+
+def test_a_draft_close_to_the_target_has_some_proposals_kept(gpu, tiny):
+    """The draft is the target with a perturbed output head: rounds end at every place from the first
+    proposal to the extra token, and the draft's cache is cut back by a different amount each time."""
+    from rsd_inputs import workload, model_blob_np, model_blob_torch, weights_from_blob
+    from oracle import rsd_oracle as O
+    import torch
+    w = workload("cfg0", sep_logit_bias=0.6, deltas=(1.01,), max_steps=3)
+    w = replace(w, draft=w.target)
+    blob = model_blob_np(w.seed, 1, w.target).copy()
+    wd = weights_from_blob(blob, w.target)
+    r = np.random.default_rng(4)
+    wd["lm_head"] += (0.012 * r.standard_normal(wd["lm_head"].shape)).astype(np.float32)    # views: edits the blob
+    dm = O.OracleModel(w.draft, wd)
+    d, t, p = tiny["models"]
+    dev = torch.device("cuda:0")
+    blobs = [torch.from_numpy(blob).to(dev), model_blob_torch(w.seed, 1, w.target, dev), model_blob_torch(w.seed, 2, w.prm, dev)]
+    tot = compare_sd(gpu, w, [dm, t, p], 4, weights=blobs, min_margin=5e-5)
+    print(tot)
+    assert tot["skipped"] <= 1 and 0.05 * tot["prop"] < tot["kept"] < 0.9 * tot["prop"]
+
+
+def test_speculation_leaves_the_committed_tokens_unchanged(gpu, tiny):
+    """Greedy: with and without speculation the HIP path commits the same tokens."""
+    from rsd_inputs import workload
+    R = gpu["R"]
+    w = workload("cfg0", sep_logit_bias=0.6, deltas=(0.55,))
+    outs = []
+    for k in (0, 5):
+        s = gpu["Session"](w, sd_k=k)
+        outs.append(R.rsd_generate(s.ctx))
+        s.close()
+    a, b = outs
+    assert np.array_equal(a["ctx_len"], b["ctx_len"])
+    for i in range(w.batch):
+        assert np.array_equal(a["tokens"][i, :a["ctx_len"][i]], b["tokens"][i, :b["ctx_len"][i]])
+    assert a["n_sd_rounds"] == 0 and b["n_sd_rounds"] > 0 and b["n_sd_proposed"] >= b["n_sd_kept"]
+
+
+def test_speculation_needs_greedy_decoding(gpu, tiny):
+    from rsd_inputs import workload
+    R = gpu["R"]
+    w = workload("cfg0", temperature=0.7, top_p=0.95)
+    with pytest.raises(R.RsdError):
+        gpu["Session"](w, sd_k=3)
+
+
+# ------------------------------------------------------------------ bf16, under a teacher
+def _bf16_setup(gpu, batch, sd_k, check, **kw):
+    import test_gpu_bf16 as T
+    from oracle import rsd_oracle as O
+    R, torch = gpu["R"], gpu["torch"]
+    w = T.mid_workload(batch, **kw)
+    models = T.oracle_models(T.mid_workload(3))
+    s = gpu["Session"](w, sd_k=sd_k)
+    P = replace(T.oracle_params(O, w), sd_k=sd_k)
+    refs = {b: O.generate_sequence(*models, s.tokens_host[b, :s.prompt_len[b]], s.u_host["U_DRAFT"][b],
+                                   s.u_host["U_TARGET"][b], s.u_host["U_GATE"][b], P) for b in check}
+    allrefs = [refs.get(b, dict(records=[])) for b in range(w.batch)]
+    forced, _ = T.teacher_arrays(w, allrefs, torch)
+    fp = np.full((w.batch, w.max_steps, w.step_cap * sd_k), -1, np.int32)
+    for b, ref in refs.items():
+        for r in ref["records"]:
+            for n, (_, t) in enumerate(r["proposed"]):
+                fp[b, r["step"], n] = t
+    fp_dev = torch.from_numpy(fp).cuda()
+    R.rsd_set_teacher(s.ctx, *forced)
+    R.rsd_set_teacher_sd(s.ctx, fp_dev)
+    s.reset()
+    return w, s, refs
+
+
+def _bf16_follow(gpu, w, s, refs):
+    import test_gpu_bf16 as T
+    R = gpu["R"]
+    tot = dict(rej=0, rounds=0, prop=0, kept=0, excused=0, tokens=0)
+    for i in range(w.max_steps):
+        g = R.rsd_step(s.ctx)
+        st = R.rsd_export_state(s.ctx, want_tokens=False)
+        for b, ref in refs.items():
+            r = ref["records"][i]
+            assert abs(float(g["reward"][b]) - r["reward"]) < T.TOL
+            assert bool(g["accepted"][b]) == r["accepted"]
+            assert list(g["final_tokens"][b, :g["final_len"][b]]) == r["final_tokens"]
+            assert list(st["kv_len"][:, b]) == r["kv_len"], (b, i, list(st["kv_len"][:, b]), r["kv_len"])
+            assert list(st["n_pages"][:, b]) == r["n_pages"] and st["ctx_len"][b] == r["ctx_len"]
+            rounds = r["sd_rounds"]
+            want = (len(rounds), sum(p for p, _ in rounds), sum(k for _, k in rounds))
+            assert (g["sd_rounds"][b], g["sd_proposed"][b], g["sd_kept"][b]) == want, (b, i, rounds)
+            tot["rej"] += not r["accepted"]; tot["rounds"] += len(rounds)
+            tot["prop"] += sum(p for p, _ in rounds); tot["kept"] += sum(k for _, k in rounds)
+        for b in range(w.batch):                       # the offset contract holds for every sequence
+            kd, kt, kp = (int(v) for v in st["kv_len"][:, b])
+            ctx = int(st["ctx_len"][b])
+            if g["accepted"][b]:
+                assert kd == ctx - 1 and kp == ctx and g["sd_rounds"][b] == 0
+            elif g["final_len"][b]:
+                assert kt == ctx - 1 and kd <= ctx - 1 and kp == ctx - int(g["final_len"][b])
+                assert 0 <= g["sd_kept"][b] <= g["sd_proposed"][b] and g["sd_rounds"][b] >= 1
+    # the models' own choices: equal to the checker's except at near-ties
+    prop = R.rsd_export_proposed(s.ctx)
+    _, own_t = R.rsd_export_sampled(s.ctx)
+    for b, ref in refs.items():
+        for r in ref["records"]:
+            for n, ((j, t), gap) in enumerate(zip(r["proposed"], r["proposal_margins"])):
+                tot["tokens"] += 1
+                if prop[b, r["step"], n] != t:
+                    assert gap < 2 * T.TOL, (b, r["step"], n, j, gap)
+                    tot["excused"] += 1
+            if not r["accepted"]:
+                for j, (t, gap) in enumerate(zip(r["final_tokens"], r["final_margins"])):
+                    tot["tokens"] += 1
+                    if own_t[b, r["step"], j] != t:
+                        assert gap < 2 * T.TOL, (b, r["step"], j, gap)
+                        tot["excused"] += 1
+    R.rsd_set_teacher(s.ctx, None, None, None)
+    R.rsd_set_teacher_sd(s.ctx, None)
+    s.close()
+    return tot
+
+
+@pytest.mark.parametrize("batch,sd_k", [(1, 7), (3, 3), (12, 2)])
+def test_teacher_forced_speculation_bf16(gpu, batch, sd_k):
+    """Batch 1 and 3: the verification rows go through the weight-streaming kernels (<= 8 rows) or the
+    few-row MFMA GEMM; batch 12: more rows."""
+    check = list(range(min(batch, 3)))
+    w, s, refs = _bf16_setup(gpu, batch, sd_k, check, step_cap=10)
+    tot = _bf16_follow(gpu, w, s, refs)
+    print(tot)
+    assert tot["rej"] >= 1 and tot["rounds"] > 0 and tot["excused"] <= max(2, tot["tokens"] // 10)
+
+
+def test_large_batch_speculation_bf16(gpu):
+    """64 sequences with prompts of up to 400 tokens: the target's first verification pass would exceed
+    one prefill pass, so the unseen prefixes are read first (several passes) and the proposals after."""
+    batch = 64
+    check = [0, 31, 63]
+    w, s, refs = _bf16_setup(gpu, batch, 4, check, prompt_len_min=16, prompt_len_max=400, step_cap=8, max_steps=3,
+                             deltas=(0.75,))
+    tot = _bf16_follow(gpu, w, s, refs)
+    print(tot)
+    assert tot["rej"] >= 1
