@@ -103,8 +103,9 @@ typedef struct rsd_params {
     int32_t sd_k;           /* > 0: a rejected step is regenerated by token-level speculative decoding with
                                the draft and the target (Section 5, "Combine RSD with SD"), this many
                                proposals per round (the paper's SD runs use 7); 0: plain target decoding.
-                               Greedy decoding only (temperature 0, the paper's SD setting, Section 3
-                               "Default Setting"): rsd_init returns RSD_EINVAL otherwise.  At most 15. */
+                               Greedy (the paper's SD setting, Section 3 "Default Setting") or
+                               sampled (then rsd_set_uniforms_sd supplies two more uniform streams).
+                               At most 15. */
 } rsd_params;
 
 /* Per-step record, all HOST buffers supplied by the caller (any may be NULL).
@@ -173,9 +174,14 @@ int rsd_set_criterion(rsd_ctx *c, float delta, int32_t omega_kind, float omega_a
  * step so far the draft proposes g = min(sd_k, step_cap - used - 1,
  * max_ctx - ctx_len - 1) tokens one by one (stopping after a separator or EOS),
  * the target reads what it has not seen plus the proposals in one chunked pass,
- * and the step grows by the leading proposals that equal the target's own
- * choices plus the target's choice at the first place that differs (or after the
- * last proposal), until a committed token ends the step.  Afterwards neither
+ * and the step grows by the leading proposals the target keeps plus one token of
+ * its own at the first refused place (or after the last proposal), until a
+ * committed token ends the step.  Greedy: a proposal is kept iff it equals the
+ * target's arg max, which is also the token of its own.  Sampled: proposal x,
+ * drawn from the draft's distribution q, is kept iff u_accept * q(x) < p(x) with p
+ * the target's distribution at that place (both as the sampler draws from them:
+ * temperature, nucleus, renormalised); the replacement is drawn from the
+ * normalised positive part of p - q, the token after a fully kept run from p.  Afterwards neither
  * model holds keys/values for the newest token or for a dropped proposal. */
 int rsd_step(rsd_ctx *c, rsd_step_out *out);
 
@@ -219,7 +225,31 @@ int rsd_export_sampled(rsd_ctx *c, int32_t *sampled_draft, int32_t *sampled_targ
  * holds the target's choice at every committed place of a regenerated step, kept
  * proposals included. */
 int rsd_set_teacher_sd(rsd_ctx *c, const int32_t *forced_proposal_dev);
-int rsd_export_proposed(rsd_ctx *c, int32_t *proposed);
+/* kept_flags (HOST, same shape, may be NULL; sampled decoding only): 1 / 0 = the
+ * acceptance test u * q(x) < p(x) kept / refused that proposal (taken for every
+ * proposal of a round, also those behind its first refusal), -1 elsewhere. */
+int rsd_export_proposed(rsd_ctx *c, int32_t *proposed, int32_t *kept_flags);
+
+/* Uniforms of sampled speculative regeneration (temperature > 0 and sd_k > 0),
+ * BORROWED dev arrays [B][max_ctx]: the proposal for absolute position i of
+ * sequence b is drawn with u_proposal[b][i] and judged with u_accept[b][i]; a token
+ * the target draws itself at position i (replacement of a refused proposal, or
+ * the token after a fully kept run) uses u_target[b][i] of rsd_set_uniforms. */
+int rsd_set_uniforms_sd(rsd_ctx *c, const float *u_proposal_dev, const float *u_accept_dev);
+
+/* The verification rule alone, for parity tests (context with sd_k > 0 and
+ * temperature > 0; its temperature, top_p and separator bias apply).  n <= batch
+ * cases; case s has n_proposals[s] <= sd_k proposals (HOST array).  dev inputs:
+ * p_logits [n][sd_k+1][vocab] (target), q_logits [n][sd_k][vocab] (draft),
+ * proposals [n][sd_k], u_accept [n][sd_k+1] (last column unused), u_new
+ * [n][sd_k+1] (uniform of a token the target draws at that place).  dev outputs:
+ * emitted [n][sd_k+1]: the kept proposals, then the replacement of the first
+ * refused one or, after a fully kept run, the draw from the next target row
+ * (entries behind that one are unspecified); kept [n]. */
+int rsd_sd_verify(rsd_ctx *c, const float *p_logits_dev, const float *q_logits_dev,
+                  const int32_t *proposals_dev, const int32_t *n_proposals_host,
+                  const float *u_accept_dev, const float *u_new_dev, int32_t n,
+                  int32_t *emitted_dev, int32_t *kept_dev);
 
 /* Teacher-forced evaluation of one model for parity tests.  tokens is host
  * [B][T], lens host [B] (<= T).  Sequence b is fed in pieces of `chunk` tokens

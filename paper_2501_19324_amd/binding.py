@@ -25,7 +25,7 @@ RSD_DRAFT, RSD_TARGET, RSD_PRM = 0, 1, 2
 RSD_MERGE_NONE, RSD_MERGE_DRAFT, RSD_MERGE_TARGET = 0, 1, 2
 EXPORTED_SYMBOLS = ["rsd_init", "rsd_set_prompts", "rsd_set_uniforms", "rsd_set_criterion", "rsd_step",
                     "rsd_generate", "rsd_export_state", "rsd_export_pages", "rsd_set_teacher",
-                    "rsd_export_sampled", "rsd_set_teacher_sd", "rsd_export_proposed", "rsd_forward", "rsd_sample", "rsd_stage_ms", "rsd_decode_stats", "rsd_probe_start", "rsd_probe_read",
+                    "rsd_export_sampled", "rsd_set_teacher_sd", "rsd_export_proposed", "rsd_set_uniforms_sd", "rsd_sd_verify", "rsd_forward", "rsd_sample", "rsd_stage_ms", "rsd_decode_stats", "rsd_probe_start", "rsd_probe_read",
                     "rsd_last_error", "rsd_destroy"]
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "librsd.so")
 
@@ -237,10 +237,33 @@ def rsd_set_teacher_sd(ctx: Context, forced_proposal=None) -> None:
     ctx.check(load_library().rsd_set_teacher_sd(ctx.handle, _dev_ptr(forced_proposal)))
 
 
-def rsd_export_proposed(ctx: Context) -> np.ndarray:
+def rsd_export_proposed(ctx: Context, want_flags: bool = False):
     a = np.zeros((ctx.batch, ctx.max_steps, ctx.step_cap * ctx.sd_k), np.int32)
-    ctx.check(load_library().rsd_export_proposed(ctx.handle, _np_ptr(a)))
-    return a
+    f = np.zeros_like(a) if want_flags else None
+    ctx.check(load_library().rsd_export_proposed(ctx.handle, _np_ptr(a), _np_ptr(f)))
+    return (a, f) if want_flags else a
+
+
+def rsd_set_uniforms_sd(ctx: Context, u_proposal=None, u_accept=None) -> None:
+    for u in (u_proposal, u_accept):
+        assert u is None or tuple(u.shape) == (ctx.batch, ctx.max_ctx)
+    ctx.keep["uniforms_sd"] = (u_proposal, u_accept)
+    ctx.check(load_library().rsd_set_uniforms_sd(ctx.handle, _dev_ptr(u_proposal), _dev_ptr(u_accept)))
+
+
+def rsd_sd_verify(ctx: Context, p_logits, q_logits, proposals, n_proposals: np.ndarray, u_accept, u_new):
+    """The sampled verification rule on given logits: returns (emitted [n, sd_k+1], kept [n]) as numpy."""
+    import torch
+    n, k = int(p_logits.shape[0]), ctx.sd_k
+    assert tuple(p_logits.shape) == (n, k + 1, ctx.vocab) and tuple(q_logits.shape) == (n, k, ctx.vocab)
+    assert tuple(proposals.shape) == (n, k) and tuple(u_accept.shape) == (n, k + 1) and tuple(u_new.shape) == (n, k + 1)
+    assert p_logits.dtype == torch.float32 and q_logits.dtype == torch.float32 and proposals.dtype == torch.int32
+    cnt = np.ascontiguousarray(n_proposals, dtype=np.int32)
+    em = torch.full((n, k + 1), -1, dtype=torch.int32, device=p_logits.device)
+    kept = torch.zeros(n, dtype=torch.int32, device=p_logits.device)
+    ctx.check(load_library().rsd_sd_verify(ctx.handle, _dev_ptr(p_logits), _dev_ptr(q_logits), _dev_ptr(proposals), _np_ptr(cnt),
+                                           _dev_ptr(u_accept), _dev_ptr(u_new), C.c_int32(n), _dev_ptr(em), _dev_ptr(kept)))
+    return em.cpu().numpy(), kept.cpu().numpy()
 
 
 def rsd_forward(ctx: Context, model: int, tokens: np.ndarray, lens: np.ndarray, chunk: int):

@@ -20,6 +20,7 @@
 #include "attn.cuh"
 #include "misc.cuh"
 #include "sample.cuh"
+#include "specdec.cuh"
 
 namespace {
 
@@ -91,6 +92,15 @@ struct rsd_ctx {
     // and per round the rows to gather ([rows] then first row of every sequence [B]; pinned + device)
     float *sd_h = nullptr, *sd_logits = nullptr;
     int *sd_choice = nullptr, *sd_rows_dev = nullptr, *sd_rows_h = nullptr;
+    // sampled speculation: the draft's logits of every proposal of the round ([B][sd_k][V]), sampler
+    // workspaces for the target's rows and the draft's rows, uniforms of proposals / acceptance tests
+    const float *u_prop = nullptr, *u_acc = nullptr;
+    float* sd_qlogits = nullptr;
+    struct SmpWs { float* pmax; int* pidx; u64_t *hist, *psum, *sel; } sd_ws[2] = {};
+    int *sd_aux_dev = nullptr, *sd_aux_h = nullptr;      // per round: uniform index of every p row, of every q row, q row in use
+    int *sd_kept_own = nullptr, *sd_where = nullptr, *sd_acc_own = nullptr, *sd_acc_rec = nullptr;
+    u64_t* sd_rpart = nullptr;
+    SdVerifyArgs sd_va{};                                 // arguments of the round in flight
     // workspaces (fp32 unless noted)
     int ws_rows = 0;
     float *h = nullptr, *xn = nullptr, *qkv = nullptr, *att = nullptr, *gu = nullptr, *act = nullptr;
@@ -626,12 +636,31 @@ AppendArgs append_args(rsd_ctx* c, int which, const int* forced, int mode = 1) {
 }
 
 // One single-token iteration of an LM model over all sequences: forward, head, sample, append.
+// logits[b][:] -> q[b * k + (ctx_len[b] - sd_base[b])][:] for the active sequences: the distribution a
+// sampled proposal is about to be drawn from, kept for its acceptance test
+__global__ void sd_stash_kernel(const float* __restrict__ logits, int V, SeqState st, int k, float* __restrict__ q) {
+    const int b = blockIdx.y;
+    if (!st.active[b]) return;
+    const int slot = st.ctx_len[b] - st.sd_base[b];
+    if (slot < 0 || slot >= k) return;
+    const float* src = logits + (size_t)b * V;
+    float* dst = q + ((size_t)b * k + slot) * V;
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < V; i += gridDim.x * blockDim.x) dst[i] = src[i];
+}
+void propose_stash(rsd_ctx* c, int mode) {
+    if (mode != 2 || c->p.temperature == 0.f) return;
+    const int V = c->m[RSD_DRAFT].s.vocab;
+    hipLaunchKernelGGL(sd_stash_kernel, dim3(std::min(64, ceil_div(V, 256)), c->B), dim3(256), 0, c->st, c->logits, V, c->ds,
+                       c->p.sd_k, c->sd_qlogits);
+}
+
 // mode 1: the token belongs to a reasoning step; mode 2: it is a proposal of speculative regeneration.
 template <typename WT>
 void decode_iter(rsd_ctx* c, int which, const float* u, const int* forced, int mode = 1) {
     Model& m = c->m[which];
     run_layers<WT>(c, m, c->B, decode_map(c, which), true);
     lm_head<WT>(c, m, c->h, c->B, c->logits, m.s.vocab);
+    propose_stash(c, mode);
     sample_rows(c, c->logits, m.s.vocab, m.s.vocab, u, c->ds.ctx_len, c->p.max_ctx, c->p.temperature, c->p.top_p,
                 c->p.sep_id, c->p.sep_logit_bias, c->ds.active, c->B, nullptr, append_args(c, which, forced, mode));
 }
@@ -738,6 +767,7 @@ int gen_stage(rsd_ctx* c, int which, const float* u, const int* forced, int mode
         });
         if (rc != RSD_OK) return rc;
         lm_head<WT>(c, m, c->hl, B, c->logits, m.s.vocab);
+        propose_stash(c, mode);
         sample_rows(c, c->logits, m.s.vocab, m.s.vocab, u, c->ds.ctx_len, c->p.max_ctx, c->p.temperature, c->p.top_p,
                     c->p.sep_id, c->p.sep_logit_bias, c->ds.active, B, nullptr, append_args(c, which, forced, mode));
         iters = 1;
@@ -794,6 +824,42 @@ int fetch_step_tokens(rsd_ctx* c) {
     return RSD_OK;
 }
 
+// Sampled verification, shared by the engine and the stand-alone entry point: the sampler's phases on
+// the target's rows (their own draws land in `choice`) and on the draft's rows in use, then the
+// acceptance test of every proposal.  sd_sampled_replace then draws the replacement at where[s].
+int sd_sampled_verify(rsd_ctx* c, const float* p_logits, int p_rows, const float* q_logits, const int* p_uidx,
+                      const int* q_uidx, const int* q_active, const float* u_new, int* choice, int nseq, const int* live,
+                      const int* n_prop_base, const int* n_prop_end, const int* p_row0, const int* tok, int tok_stride,
+                      const int* tok_off, const float* u_acc, int u_stride, const int* u_off, int* kept_own) {
+    const rsd_params& P = c->p;
+    const int V = c->m[RSD_TARGET].s.vocab, k = P.sd_k;
+    AppendArgs off{};
+    auto& wp = c->sd_ws[0];
+    auto& wq = c->sd_ws[1];
+    SampleArgs ap{p_logits, V, V, u_new, p_uidx, 0, P.temperature, P.top_p, P.sep_id, P.sep_logit_bias, nullptr, choice,
+                  wp.pmax, wp.pidx, wp.hist, wp.psum, wp.sel};
+    sample_launch(c->st, ap, off, p_rows);
+    SampleArgs aq{q_logits, V, V, u_new, q_uidx, 0, P.temperature, P.top_p, P.sep_id, P.sep_logit_bias, q_active, nullptr,
+                  wq.pmax, wq.pidx, wq.hist, wq.psum, wq.sel};
+    sample_launch(c->st, aq, off, nseq * k);
+    SdVerifyArgs& va = c->sd_va;
+    va = SdVerifyArgs{};
+    va.p = SdRowSet{p_logits, V, wp.pmax, wp.psum, wp.sel};
+    va.q = SdRowSet{q_logits, V, wq.pmax, wq.psum, wq.sel};
+    va.V = V; va.k = k; va.temperature = P.temperature; va.sep_id = P.sep_id; va.sep_bias = P.sep_logit_bias;
+    va.live = live; va.n_prop_base = n_prop_base; va.n_prop_end = n_prop_end; va.p_row0 = p_row0;
+    va.tok = tok; va.tok_stride = tok_stride; va.tok_off = tok_off;
+    va.u_acc = u_acc; va.u_stride = u_stride; va.u_off = u_off; va.u_new = u_new;
+    va.kept_own = kept_own; va.acc_own = c->sd_acc_own; va.choice = choice; va.rpart = c->sd_rpart;
+    hipLaunchKernelGGL(sd_accept_kernel, dim3(nseq), dim3(64), 0, c->st, va);
+    HIPCHK(c, hipGetLastError());
+    return RSD_OK;
+}
+void sd_sampled_replace(rsd_ctx* c, int nseq, const int* where) {
+    hipLaunchKernelGGL(sd_residual_mass_kernel, dim3(SMP_NB, nseq), dim3(SMP_T), 0, c->st, c->sd_va, where);
+    hipLaunchKernelGGL(sd_residual_draw_kernel, dim3(nseq), dim3(SMP_T), 0, c->st, c->sd_va, where);
+}
+
 // Target step of the rejected sequences by token-level speculative decoding with the draft
 // (Section 5, "Combine RSD with SD"), greedy.  On entry the host mirror is current and active[] marks
 // the rejected sequences.  Each round: the host fixes every live sequence's proposal budget, the
@@ -830,7 +896,7 @@ int sd_stage(rsd_ctx* c) {
         *c->n_active() = n_prop;
         if ((rc = push_state(c))) return rc;
         if (n_prop) {
-            if ((rc = gen_stage_any(c, RSD_DRAFT, nullptr, c->forced_prop, 2, max_g))) return rc;
+            if ((rc = gen_stage_any(c, RSD_DRAFT, c->u_prop, c->forced_prop, 2, max_g))) return rc;
             if ((rc = pull_state(c))) return rc;
         }
         // ---- the target's pass: catch-up first when everything together exceeds one pass
@@ -868,8 +934,32 @@ int sd_stage(rsd_ctx* c) {
         if ((rc = prefill<WT>(c, RSD_TARGET, pieces, after))) return rc;
         lm_head<WT>(c, mt, c->sd_h, n_rows, c->sd_logits, V);
         AppendArgs off{};
-        sample_rows(c, c->sd_logits, V, V, nullptr, nullptr, 0, 0.0f, 1.0f, P.sep_id, P.sep_logit_bias, nullptr, n_rows,
-                    c->sd_choice, off);
+        if (P.temperature == 0.f) {
+            sample_rows(c, c->sd_logits, V, V, nullptr, nullptr, 0, 0.0f, 1.0f, P.sep_id, P.sep_logit_bias, nullptr, n_rows,
+                        c->sd_choice, off);
+        } else {
+            // uniform of every target row (the token the target would draw at that place) and the draft rows in use
+            const int rows = B * (k + 1), qrows = B * k;
+            int *pu = c->sd_aux_h, *qu = pu + rows, *qa = qu + qrows;
+            std::fill(qa, qa + qrows, 0);
+            const int* row0 = c->sd_rows_h + (size_t)B * (k + 1);
+            for (int b = 0; b < B; ++b) {
+                if (!c->sd_live()[b]) continue;
+                const int base = c->sd_base()[b], np = c->ctx_len()[b] - base;
+                for (int i = 0; i <= np; ++i) pu[row0[b] + i] = b * P.max_ctx + base + i;
+                for (int i = 0; i < np; ++i) { qu[b * k + i] = b * P.max_ctx + base + i; qa[b * k + i] = 1; }
+            }
+            HIPCHK(c, hipMemcpyAsync(c->sd_aux_dev, c->sd_aux_h, (size_t)(rows + 2 * qrows) * sizeof(int), hipMemcpyHostToDevice, c->st));
+            int rc2 = sd_sampled_verify(c, c->sd_logits, n_rows, c->sd_qlogits, c->sd_aux_dev, c->sd_aux_dev + rows,
+                                        c->sd_aux_dev + rows + qrows, c->u_target, c->sd_choice, B, c->ds.sd_live, c->ds.sd_base,
+                                        c->ds.ctx_len, c->sd_rows_dev + (size_t)B * (k + 1), c->ds.tokens, P.max_ctx, c->ds.sd_base,
+                                        c->u_acc, P.max_ctx, c->ds.sd_base, c->sd_kept_own);
+            if (rc2) return rc2;
+            hipLaunchKernelGGL(sd_where_kernel, dim3(ceil_div(B, 64)), dim3(64), 0, c->st, c->ds, B, k, c->forced_target,
+                               c->sd_kept_own, c->sd_acc_own, P.max_ctx, P.max_steps, P.step_cap, P.step_cap * k, c->sd_where,
+                               c->sd_acc_rec);
+            sd_sampled_replace(c, B, c->sd_where);
+        }
         hipLaunchKernelGGL(sd_verify_kernel, dim3(ceil_div(B, 64)), dim3(64), 0, c->st, c->ds, B,
                            c->sd_rows_dev + (size_t)B * (k + 1), c->sd_choice, c->forced_target, P.max_ctx, P.max_steps,
                            P.step_cap, P.sep_id, P.eos_id);
@@ -904,14 +994,17 @@ void rsd_destroy(rsd_ctx* c) {
         (void)hipFree(m.pool); (void)hipFree(m.bt_dev); (void)hipFree(m.rope);
         if (m.bt_host) (void)hipHostFree(m.bt_host);
     }
-    void* dev[] = {c->sb_dev, c->ds.tokens, c->ds.sampled[0], c->ds.sampled[1], c->ds.sampled[2], c->sd_h, c->sd_logits, c->sd_choice, c->sd_rows_dev, c->h, c->xn, c->qkv, c->att, c->gu, c->act,
+    void* dev[] = {c->sb_dev, c->ds.tokens, c->ds.sampled[0], c->ds.sampled[1], c->ds.sampled[2], c->sd_h, c->sd_logits, c->sd_choice, c->sd_rows_dev, c->sd_qlogits, c->sd_aux_dev,
+                   c->sd_kept_own, c->sd_where, c->sd_acc_own, c->sd_acc_rec, c->sd_rpart,
+                   c->sd_ws[0].pmax, c->sd_ws[0].pidx, c->sd_ws[0].hist, c->sd_ws[0].psum, c->sd_ws[0].sel,
+                   c->sd_ws[1].pmax, c->sd_ws[1].pidx, c->sd_ws[1].hist, c->sd_ws[1].psum, c->sd_ws[1].sel, c->h, c->xn, c->qkv, c->att, c->gu, c->act,
                    c->part_acc, c->part_ml, c->part_k, c->xs_h, c->xs_l, c->smp_pmax, c->smp_pidx, c->smp_hist, c->smp_psum, c->smp_sel, c->hl, c->xl, c->logits, c->tmp_reward, c->chosen, c->steptok_dev,
                    c->row_seq_dev, c->row_pos_dev, c->last_row_dev, c->item_row0_dev, c->item_n_dev};
     for (void* p : dev) if (p) (void)hipFree(p);
     for (hipEvent_t e : c->probe_ev) (void)hipEventDestroy(e);
     for (auto& g : c->graphs) { (void)hipGraphExecDestroy(g.exec); (void)hipGraphDestroy(g.graph); }
     if (c->cap_st) (void)hipStreamDestroy(c->cap_st);
-    void* pin[] = {c->sb, c->sd_rows_h, c->item_row0_h, c->item_n_h, c->row_seq_h, c->row_pos_h, c->last_row_h, c->steptok_h, c->poll_h};
+    void* pin[] = {c->sb, c->sd_rows_h, c->sd_aux_h, c->item_row0_h, c->item_n_h, c->row_seq_h, c->row_pos_h, c->last_row_h, c->steptok_h, c->poll_h};
     for (void* p : pin) if (p) (void)hipHostFree(p);
     delete c;
 }
@@ -933,8 +1026,6 @@ int rsd_init(rsd_ctx** out, const rsd_model_shape shape[3], const rsd_weights w[
     if (p->omega_kind < 0 || p->omega_kind > 4) return fail(c, RSD_EINVAL, "bad omega_kind");
     if (p->merge_prm < RSD_MERGE_NONE || p->merge_prm > RSD_MERGE_TARGET) return fail(c, RSD_EINVAL, "bad merge_prm");
     if (p->sd_k < 0 || p->sd_k > 15) return fail(c, RSD_EINVAL, "sd_k %d outside [0, 15]", p->sd_k);
-    if (p->sd_k > 0 && p->temperature != 0.f)
-        return fail(c, RSD_EINVAL, "speculative regeneration (sd_k > 0) is implemented for greedy decoding only");
     if (p->sd_k > 0 && (long long)batch * (p->sd_k + 1) > kMaxRows)
         return fail(c, RSD_EINVAL, "batch * (sd_k + 1) exceeds the %d rows of one verification pass", kMaxRows);
     for (int i = 0; i < 3; ++i) {
@@ -1034,6 +1125,29 @@ int rsd_init(rsd_ctx** out, const rsd_model_shape shape[3], const rsd_weights w[
         HIPCHK(c, dev_alloc(&c->sd_rows_dev, rows + B));
         HIPCHK(c, pin_alloc(&c->sd_rows_h, rows + B));
         std::fill(c->sd_rows_h, c->sd_rows_h + rows + B, 0);
+        HIPCHK(c, dev_alloc(&c->sd_acc_rec, (size_t)B * p->max_steps * p->step_cap * p->sd_k));
+        if (p->temperature > 0.f) {
+            const size_t qrows = (size_t)B * p->sd_k;
+            HIPCHK(c, dev_alloc(&c->sd_qlogits, qrows * V));
+            for (int i = 0; i < 2; ++i) {
+                const size_t n = i == 0 ? rows : qrows;
+                auto& ws = c->sd_ws[i];
+                HIPCHK(c, dev_alloc(&ws.pmax, n * SMP_NB));
+                HIPCHK(c, dev_alloc(&ws.pidx, n * SMP_NB));
+                HIPCHK(c, dev_alloc(&ws.hist, n * 3 * SMP_BINS));
+                HIPCHK(c, dev_alloc(&ws.psum, n * SMP_NB));
+                HIPCHK(c, dev_alloc(&ws.sel, n * 8));
+                HIPCHK(c, hipMemsetAsync(ws.hist, 0, n * 3 * SMP_BINS * sizeof(u64_t), c->st));
+                HIPCHK(c, hipMemsetAsync(ws.sel, 0, n * 8 * sizeof(u64_t), c->st));
+            }
+            HIPCHK(c, dev_alloc(&c->sd_aux_dev, rows + 2 * qrows));
+            HIPCHK(c, pin_alloc(&c->sd_aux_h, rows + 2 * qrows));
+            std::fill(c->sd_aux_h, c->sd_aux_h + rows + 2 * qrows, 0);
+            HIPCHK(c, dev_alloc(&c->sd_kept_own, (size_t)B));
+            HIPCHK(c, dev_alloc(&c->sd_where, (size_t)B));
+            HIPCHK(c, dev_alloc(&c->sd_acc_own, qrows));
+            HIPCHK(c, dev_alloc(&c->sd_rpart, (size_t)B * SMP_NB));
+        }
     }
     HIPCHK(c, dev_alloc(&c->chosen, (size_t)B));
     HIPCHK(c, dev_alloc(&c->steptok_dev, (size_t)B * p->step_cap));
@@ -1072,8 +1186,10 @@ int rsd_set_prompts(rsd_ctx* c, const int32_t* tokens_dev, const int32_t* prompt
     const size_t ns = (size_t)B * c->p.max_steps * c->p.step_cap;
     for (int s = 0; s < 2; ++s)
         hipLaunchKernelGGL(fill_int_kernel, dim3((unsigned)((ns + 255) / 256)), dim3(256), 0, c->st, c->ds.sampled[s], -1, ns);
-    if (const size_t np = ns * c->p.sd_k)
+    if (const size_t np = ns * c->p.sd_k) {
         hipLaunchKernelGGL(fill_int_kernel, dim3((unsigned)((np + 255) / 256)), dim3(256), 0, c->st, c->ds.sampled[2], -1, np);
+        hipLaunchKernelGGL(fill_int_kernel, dim3((unsigned)((np + 255) / 256)), dim3(256), 0, c->st, c->sd_acc_rec, -1, np);
+    }
     for (int b = 0; b < B; ++b) {
         c->prompt_len[b] = prompt_len_host[b];
         c->ctx_len()[b] = prompt_len_host[b];
@@ -1114,6 +1230,8 @@ int rsd_step(rsd_ctx* c, rsd_step_out* out) {
     const int merge = P.merge_prm;
     if (P.temperature > 0.f && (!c->u_draft || !c->u_target)) return fail(c, RSD_ESTATE, "sampling needs uniforms");
     if (P.omega_kind != RSD_OMEGA_BINARY && !c->u_gate) return fail(c, RSD_ESTATE, "this omega needs u_gate");
+    if (P.sd_k > 0 && P.temperature > 0.f && (!c->u_prop || !c->u_acc))
+        return fail(c, RSD_ESTATE, "sampled speculative regeneration needs the proposal and acceptance uniforms");
     int n_in = 0;
     for (int b = 0; b < B; ++b) n_in += c->finished()[b] == RSD_RUNNING;
     if (!n_in) return fail(c, RSD_ESTATE, "every sequence has finished");
@@ -1362,12 +1480,54 @@ int rsd_set_teacher_sd(rsd_ctx* c, const int32_t* forced_proposal_dev) {
     return RSD_OK;
 }
 
-int rsd_export_proposed(rsd_ctx* c, int32_t* proposed) {
-    if (!c || !proposed) return RSD_EINVAL;
+int rsd_export_proposed(rsd_ctx* c, int32_t* proposed, int32_t* kept_flags) {
+    if (!c) return RSD_EINVAL;
     if (c->p.sd_k <= 0) return fail(c, RSD_ESTATE, "no speculative regeneration in this context");
     const size_t n = (size_t)c->B * c->p.max_steps * c->p.step_cap * c->p.sd_k * sizeof(int);
-    HIPCHK(c, hipMemcpyAsync(proposed, c->ds.sampled[2], n, hipMemcpyDeviceToHost, c->st));
+    if (proposed) HIPCHK(c, hipMemcpyAsync(proposed, c->ds.sampled[2], n, hipMemcpyDeviceToHost, c->st));
+    if (kept_flags) HIPCHK(c, hipMemcpyAsync(kept_flags, c->sd_acc_rec, n, hipMemcpyDeviceToHost, c->st));
     HIPCHK(c, hipStreamSynchronize(c->st));
+    return RSD_OK;
+}
+
+int rsd_set_uniforms_sd(rsd_ctx* c, const float* u_proposal_dev, const float* u_accept_dev) {
+    if (!c) return RSD_EINVAL;
+    c->u_prop = u_proposal_dev; c->u_acc = u_accept_dev;
+    return RSD_OK;
+}
+
+int rsd_sd_verify(rsd_ctx* c, const float* p_logits_dev, const float* q_logits_dev, const int32_t* proposals_dev,
+                  const int32_t* n_proposals_host, const float* u_accept_dev, const float* u_new_dev, int32_t n,
+                  int32_t* emitted_dev, int32_t* kept_dev) {
+    if (!c || !p_logits_dev || !q_logits_dev || !proposals_dev || !n_proposals_host || !u_accept_dev || !u_new_dev ||
+        !emitted_dev || !kept_dev)
+        return fail(c, RSD_EINVAL, "null argument");
+    const int k = c->p.sd_k;
+    if (k <= 0 || c->p.temperature <= 0.f) return fail(c, RSD_ESTATE, "needs a context with sd_k > 0 and temperature > 0");
+    if (n < 1 || n > c->B) return fail(c, RSD_EINVAL, "n outside [1, batch]");
+    for (int s = 0; s < n; ++s)
+        if (n_proposals_host[s] < 0 || n_proposals_host[s] > k) return fail(c, RSD_EINVAL, "n_proposals[%d] outside [0, sd_k]", s);
+    HIPCHK(c, hipStreamSynchronize(c->st));
+    // index arrays: zeros [n], proposals per sequence [n], first target row [n]; uniform index per row; draft rows in use
+    int *zeros = c->sd_rows_h, *cnt = zeros + n, *row0 = cnt + n;
+    const int rows = c->B * (k + 1), qrows = c->B * k;
+    int *pu = c->sd_aux_h, *qu = pu + rows, *qa = qu + qrows;
+    std::fill(qa, qa + qrows, 0);
+    for (int s = 0; s < n; ++s) {
+        zeros[s] = 0; cnt[s] = n_proposals_host[s]; row0[s] = s * (k + 1);
+        for (int i = 0; i <= k; ++i) pu[s * (k + 1) + i] = s * (k + 1) + i;
+        for (int i = 0; i < cnt[s]; ++i) { qu[s * k + i] = s * (k + 1) + i; qa[s * k + i] = 1; }
+    }
+    HIPCHK(c, hipMemcpyAsync(c->sd_rows_dev, c->sd_rows_h, (size_t)3 * n * sizeof(int), hipMemcpyHostToDevice, c->st));
+    HIPCHK(c, hipMemcpyAsync(c->sd_aux_dev, c->sd_aux_h, (size_t)(rows + 2 * qrows) * sizeof(int), hipMemcpyHostToDevice, c->st));
+    const int *zeros_d = c->sd_rows_dev, *cnt_d = zeros_d + n, *row0_d = cnt_d + n;
+    int rc = sd_sampled_verify(c, p_logits_dev, n * (k + 1), q_logits_dev, c->sd_aux_dev, c->sd_aux_dev + rows,
+                               c->sd_aux_dev + rows + qrows, u_new_dev, emitted_dev, n, nullptr, zeros_d, cnt_d, row0_d,
+                               proposals_dev, k, zeros_d, u_accept_dev, k + 1, zeros_d, kept_dev);
+    if (rc) return rc;
+    sd_sampled_replace(c, n, kept_dev);
+    HIPCHK(c, hipStreamSynchronize(c->st));
+    HIPCHK(c, hipGetLastError());
     return RSD_OK;
 }
 

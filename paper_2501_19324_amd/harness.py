@@ -37,6 +37,11 @@ class Session:
         self.u_host = {k: uniforms(w, k, n) for k, n in (("U_DRAFT", w.max_ctx), ("U_TARGET", w.max_ctx), ("U_GATE", w.max_steps))}
         self.u = {k: torch.from_numpy(v).to(dev) for k, v in self.u_host.items()}
         R.rsd_set_uniforms(self.ctx, self.u["U_DRAFT"], self.u["U_TARGET"], self.u["U_GATE"])
+        if sd_k and w.temperature > 0:
+            for k in ("U_PROP", "U_ACC"):
+                self.u_host[k] = uniforms(w, k, w.max_ctx)
+                self.u[k] = torch.from_numpy(self.u_host[k]).to(dev)
+            R.rsd_set_uniforms_sd(self.ctx, self.u["U_PROP"], self.u["U_ACC"])
         self.reset()
 
     def reset(self):

@@ -20,7 +20,7 @@ import numpy as np
 from .configs import ModelShape, Workload, blob_layout
 
 STREAMS = {"W_DRAFT": 1, "W_TARGET": 2, "W_PRM": 3, "PLEN": 4, "PTOK": 5,
-           "U_DRAFT": 6, "U_TARGET": 7, "U_GATE": 8}
+           "U_DRAFT": 6, "U_TARGET": 7, "U_GATE": 8, "U_PROP": 9, "U_ACC": 10}
 WEIGHT_STD = 0.02
 _M32 = 0xFFFFFFFF
 
