@@ -673,6 +673,9 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void attn_decode_mfma_ker
 // last row's position once and feeds both tiles from the same K / V^T
 // registers.  Column (row, g) sees tokens <= position(row).  Same operand
 // layouts and hi + lo splitting as attn_decode_mfma_kernel.
+// gridDim.z = S > 1 (few rows over a long context): split sp walks its share of
+// the pages and leaves a partial (max, sum, accumulator) per (row, head) for
+// attn_combine_kernel, in the layout of the decode kernels.
 template <int G>
 __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(const float* __restrict__ qkv, int ldq,
                                                                 const bf16_t* __restrict__ pool_layer,
@@ -682,10 +685,12 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(const float* 
                                                                 const int* __restrict__ item_row0,
                                                                 const int* __restrict__ item_n, int n_items,
                                                                 int H, int Hkv, float scale,
-                                                                float* __restrict__ out, int ldo) {
+                                                                float* __restrict__ out, int ldo,
+                                                                float* __restrict__ part_acc,
+                                                                float* __restrict__ part_ml) {
     constexpr int HD = 128, NT = 2;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int item = blockIdx.x * 4 + wave, hk = blockIdx.y;
+    const int item = blockIdx.x * 4 + wave, hk = blockIdx.y, sp = blockIdx.z, S = gridDim.z;
     if (item >= n_items) return;
     const int r0 = item_row0[item], n = item_n[item];
     const int seq = row_seq[r0], p0 = row_pos[r0];
@@ -694,7 +699,9 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(const float* 
     const size_t page_elts = (size_t)2 * Hkv * RSD_PAGE * HD;
     const size_t head_off = (size_t)hk * RSD_PAGE * HD, v_off = (size_t)Hkv * RSD_PAGE * HD;
     const int p_last = p0 + n - 1, n_pages = p_last / RSD_PAGE + 1;
-    int bt_mine = (lane < n_pages) ? bt[lane] : -1;        // refreshed every 64 pages
+    const int per = (n_pages + S - 1) / S;
+    const int pg_lo = min(n_pages, sp * per), pg_hi = min(n_pages, pg_lo + per);     // this split's pages
+    int bt_mine = ((pg_lo & ~63) + lane < n_pages) ? bt[(pg_lo & ~63) + lane] : -1;  // refreshed every 64 pages
 
     // column l16 of tile t: row r0 + 2t + l16 / 8, head l16 % 8
     const int g_col = l16 & 7;
@@ -810,12 +817,12 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(const float* 
         fetch(pg, k, v);
     };
     // two register buffers take turns (no copies between them: a copy would wait for the load)
-    fetch(0, kc, vc);
-    for (int pg = 0; pg < n_pages; pg += 2) {
-        if (pg + 1 < n_pages) prefetch(pg + 1, kn, vn);
+    if (pg_lo < pg_hi) fetch(pg_lo, kc, vc);
+    for (int pg = pg_lo; pg < pg_hi; pg += 2) {
+        if (pg + 1 < pg_hi) prefetch(pg + 1, kn, vn);
         do_page(pg, kc, vc);
-        if (pg + 1 >= n_pages) break;
-        if (pg + 2 < n_pages) prefetch(pg + 2, kc, vc);
+        if (pg + 1 >= pg_hi) break;
+        if (pg + 2 < pg_hi) prefetch(pg + 2, kc, vc);
         do_page(pg + 1, kn, vn);
     }
     // accumulator row c*4+i of tile t is column (row r0 + 2t + (c*4+i)/8, head (c*4+i)%8)
@@ -825,12 +832,21 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(const float* 
         for (int i = 0; i < 4; ++i) {
             const int col = c * 4 + i;
             const float den = __shfl(l_run[t], col, RSD_WAVE);
+            const float mx = __shfl(m_run[t], col, RSD_WAVE);
             const int ri = 2 * t + (col >> 3), g = col & 7;
             if (ri < n && g < G) {
-                float* dst = out + (size_t)(r0 + ri) * ldo + (hk * G + g) * HD + l16;
-                const float inv = 1.0f / den;
+                if (S == 1) {
+                    float* dst = out + (size_t)(r0 + ri) * ldo + (hk * G + g) * HD + l16;
+                    const float inv = 1.0f / den;
 #pragma unroll
-                for (int nb = 0; nb < 8; ++nb) dst[nb * 16] = o[t][nb][i] * inv;
+                    for (int nb = 0; nb < 8; ++nb) dst[nb * 16] = o[t][nb][i] * inv;
+                } else {
+                    const size_t pi = ((size_t)(r0 + ri) * H + hk * G + g) * S + sp;
+                    float* dst = part_acc + pi * HD + l16;
+#pragma unroll
+                    for (int nb = 0; nb < 8; ++nb) dst[nb * 16] = o[t][nb][i];
+                    if (l16 == 0) { part_ml[pi * 2] = mx; part_ml[pi * 2 + 1] = den; }
+                }
             }
         }
     }

@@ -26,6 +26,8 @@ namespace {
 
 constexpr int kMaxRows = 8192;   // rows of one chunked-prefill pass (bounds the workspaces)
 constexpr int kPoll = 16;        // decode iterations between looks at the active counter
+constexpr int kPfSplitRows = 128;   // chunked-prefill passes of at most this many rows may split the context
+constexpr int kPfSplits = 16;       // ... into at most this many parts
 
 struct LayerOff { size_t attn_norm, wqkv, wo, ffn_norm, wgu, wdown; };
 
@@ -119,6 +121,7 @@ struct rsd_ctx {
     // chunked-prefill attention work items: first row and row count (<= 4 rows of one sequence)
     int *item_row0_dev = nullptr, *item_n_dev = nullptr, *item_row0_h = nullptr, *item_n_h = nullptr;
     int n_items = 0;
+    int pf_rows = 0, pf_max_end = 0;     // rows of the chunked pass in flight and the longest context among its pieces
     int *poll_h = nullptr;
     double stage_ms[4] = {0, 0, 0, 0};
     // kernel timing probe
@@ -402,7 +405,13 @@ void launch_attn_decode_mfma(rsd_ctx* c, const Model& m, int l, int M, int which
 void launch_attn_prefill_mfma(rsd_ctx* c, const Model& m, int l, const RowMap& rm) {
     const bf16_t* pool_l = reinterpret_cast<const bf16_t*>(m.pool) + (size_t)l * m.pool_pages * m.page_elts;
     const float scale = 1.0f / std::sqrt(128.0f);
-    const dim3 grid(ceil_div(c->n_items, 4), m.s.n_kv_heads), block(256);
+    // few rows over long contexts (a verification pass, the scoring of one step, a short catch-up): the
+    // work items alone leave most of the chip idle, so every item's pages are dealt to several splits
+    int S = 1;
+    const int waves = c->n_items * m.s.n_kv_heads, pages = ceil_div(c->pf_max_end, RSD_PAGE);
+    if (waves < 512 && pages > 8 && c->pf_rows <= kPfSplitRows)
+        S = std::max(1, std::min(kPfSplits, std::min(ceil_div(pages, 4), 1024 / waves)));
+    const dim3 grid(ceil_div(c->n_items, 4), m.s.n_kv_heads, S), block(256);
     constexpr size_t qlds = (size_t)4 * 2 * 2 * 16 * (128 + 8) * sizeof(uint16_t);     // Q operands of 4 waves
 #define RSD_ATTN_CASE(GG)                                                                                     \
     case GG: {                                                                                                \
@@ -414,12 +423,16 @@ void launch_attn_prefill_mfma(rsd_ctx* c, const Model& m, int l, const RowMap& r
         }                                                                                                     \
         hipLaunchKernelGGL((attn_prefill_mfma_kernel<GG>), grid, block, qlds, c->st, c->qkv, m.n_qkv, pool_l, \
                            m.bt_dev, m.max_pages, rm.row_seq, rm.row_pos, c->item_row0_dev, c->item_n_dev,    \
-                           c->n_items, m.s.n_heads, m.s.n_kv_heads, scale, c->att, m.q_dim);                  \
+                           c->n_items, m.s.n_heads, m.s.n_kv_heads, scale, c->att, m.q_dim, c->part_acc,      \
+                           c->part_ml);                                                                       \
     } break;
     switch (m.G) {
         RSD_ATTN_CASE(1) RSD_ATTN_CASE(2) RSD_ATTN_CASE(4) RSD_ATTN_CASE(6) RSD_ATTN_CASE(7) RSD_ATTN_CASE(8)
     }
 #undef RSD_ATTN_CASE
+    if (S > 1)
+        hipLaunchKernelGGL((attn_combine_kernel<128>), dim3(c->pf_rows, m.s.n_heads), dim3(128), 0, c->st, c->part_acc,
+                           c->part_ml, rm, m.s.n_heads, S, c->att, m.q_dim, (uint16_t*)nullptr, (uint16_t*)nullptr);
 }
 
 // Two or more rows over bf16 weights: MFMA kernels on activations split into hi + lo bf16 halves, which
@@ -729,6 +742,9 @@ int prefill(rsd_ctx* c, int which, std::vector<Piece> pieces, AfterPass after_pa
         HIPCHK(c, hipMemcpyAsync(c->item_row0_dev, c->item_row0_h, n_items * sizeof(int), hipMemcpyHostToDevice, c->st));
         HIPCHK(c, hipMemcpyAsync(c->item_n_dev, c->item_n_h, n_items * sizeof(int), hipMemcpyHostToDevice, c->st));
         c->n_items = n_items;
+        c->pf_rows = M;
+        c->pf_max_end = 0;
+        for (const Piece& pc : pass) c->pf_max_end = std::max(c->pf_max_end, pc.end);
         RowMap rm{c->row_seq_dev, c->row_pos_dev, nullptr, nullptr};
         run_layers<WT>(c, m, M, rm, false);
         const int rc = after_pass(pass, first_row, M);
@@ -1094,8 +1110,10 @@ int rsd_init(rsd_ctx** out, const rsd_model_shape shape[3], const rsd_weights w[
     HIPCHK(c, dev_alloc(&c->att, R * qd));
     HIPCHK(c, dev_alloc(&c->gu, R * 2 * F));
     HIPCHK(c, dev_alloc(&c->act, R * F));
-    HIPCHK(c, dev_alloc(&c->part_acc, (size_t)B * HS));
-    HIPCHK(c, dev_alloc(&c->part_ml, (size_t)B * HS));
+    size_t part = (size_t)B * HS;        // decode splits, or the splits of a small chunked pass
+    for (auto& m : c->m) part = std::max(part, (size_t)kPfSplitRows * m.s.n_heads * kPfSplits * m.hd);
+    HIPCHK(c, dev_alloc(&c->part_acc, part));
+    HIPCHK(c, dev_alloc(&c->part_ml, part));
     c->part_k_floats = (size_t)48 << 20;
     HIPCHK(c, dev_alloc(&c->part_k, c->part_k_floats));
     {
