@@ -173,6 +173,28 @@ def test_config0_sampled_speculation(gpu, tiny, sd_k, top_p):
     assert tot["rej"] >= 2 and 0 < tot["kept"] < tot["prop"]
 
 
+def test_speculation_replayed_from_graphs_matches_eager_launches(gpu):
+    """The proposal iterations are replayed from their own recorded graph (the append works in its
+    "proposal" flavour there, and under sampling a copy of the draft's logits is part of the graph):
+    same kernels as the kernel-by-kernel run, so everything must agree bit for bit."""
+    from rsd_inputs import workload
+    R = gpu["R"]
+    w = workload("cfg0", sep_logit_bias=3.5, deltas=(0.55,), temperature=0.7, top_p=0.95)
+    outs = []
+    for use_graphs in (0, 1):
+        s = gpu["Session"](w, sd_k=4, use_graphs=use_graphs)
+        g = R.rsd_generate(s.ctx)
+        st = R.rsd_decode_stats(s.ctx)
+        outs.append((g, R.rsd_export_proposed(s.ctx, want_flags=True), st))
+        s.close()
+    (a, pa, sa), (b, pb, sb) = outs
+    assert sa["graph_replays"] == 0 and sb["graph_replays"] > 0 and sb["graphs_recorded"] >= 2
+    assert np.array_equal(a["tokens"], b["tokens"]) and np.array_equal(a["ctx_len"], b["ctx_len"])
+    assert np.array_equal(pa[0], pb[0]) and np.array_equal(pa[1], pb[1])
+    assert (a["n_sd_rounds"], a["n_sd_proposed"], a["n_sd_kept"]) == (b["n_sd_rounds"], b["n_sd_proposed"], b["n_sd_kept"])
+    assert a["n_sd_kept"] > 0
+
+
 def test_sampled_verification_rule_alone(gpu):
     """rsd_sd_verify on given logits against the checker's rule on the same fp32 logits: kept counts and
     emitted tokens, over cases with 0..sd_k proposals, drafts close to and far from the target, equal rows
