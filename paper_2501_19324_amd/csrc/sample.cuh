@@ -331,7 +331,7 @@ __global__ __launch_bounds__(SMP_T) void sample_finish_kernel(SampleArgs a, Appe
     if (ap.enabled == 2) {
         // a proposal: written behind the committed tokens and recorded as the n-th proposal of the
         // step (a place of the step can be proposed for in several rounds); the step's own length
-        // and records wait for the target's verdict
+        // and records wait for the target's decision
         const size_t rec = ((size_t)b * ap.max_steps + st.cur_step[0]) * ap.prop_stride + st.sd_nprop[b] + (pos - st.sd_base[b]);
         st.sampled[2][rec] = token;
         int tok = token;
