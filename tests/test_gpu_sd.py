@@ -173,6 +173,41 @@ def test_config0_sampled_speculation(gpu, tiny, sd_k, top_p):
     assert tot["rej"] >= 2 and 0 < tot["kept"] < tot["prop"]
 
 
+def _tight(w, max_ctx):
+    """The same workload with a context limit below prompt + steps x cap, so that sequences fill up mid-step."""
+    from dataclasses import fields
+
+    class Tight(type(w)):
+        @property
+        def max_ctx(self):
+            return max_ctx
+
+    return Tight(**{f.name: getattr(w, f.name) for f in fields(w)})
+
+
+@pytest.mark.parametrize("case", ["cap1", "cap2", "eos_sampled", "ctx_greedy", "ctx_sampled"])
+def test_speculation_edge_cases(gpu, tiny, case):
+    """One-token steps (no room for a proposal: every round is a plain target token), two-token steps (one
+    proposal), EOS among proposals and committed tokens, and a context that fills up in the middle of a
+    round (the proposal budget shrinks to what the context leaves after the target's own token)."""
+    from rsd_inputs import workload
+    if case == "cap1":
+        w, k = workload("cfg0", step_cap=1, max_steps=6, deltas=(1.01,)), 3
+    elif case == "cap2":
+        w, k = workload("cfg0", step_cap=2, max_steps=6, deltas=(1.01,), temperature=0.7, top_p=0.95), 3
+    elif case == "eos_sampled":
+        w, k = workload("cfg0", sep_logit_bias=3.5, deltas=(0.55,), temperature=0.7, top_p=0.95, eos_id=517, max_steps=5), 3
+    elif case == "ctx_greedy":
+        w, k = _tight(workload("cfg0", sep_logit_bias=0.6, deltas=(1.01,)), 32 + 37), 5
+    else:
+        w, k = _tight(workload("cfg0", sep_logit_bias=2.0, deltas=(1.01,), temperature=0.7, top_p=0.95), 32 + 27), 4
+    tot = compare_sd(gpu, w, tiny["models"], k)
+    print(case, tot)
+    assert tot["rej"] >= 2
+    if case == "cap1":
+        assert tot["prop"] == 0 and tot["rounds"] == tot["rej"]
+
+
 def test_speculation_replayed_from_graphs_matches_eager_launches(gpu):
     """The proposal iterations are replayed from their own recorded graph (the append works in its
     "proposal" flavour there, and under sampling a copy of the draft's logits is part of the graph):
