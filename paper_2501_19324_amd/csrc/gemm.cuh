@@ -483,13 +483,23 @@ __global__ __launch_bounds__(1024) void rows_finish_norm_kernel(const float* __r
     }
 }
 
-// K slices for gemm_rows_kernel: the count that minimises (rounds of 512 resident blocks) x (K blocks per
-// slice) plus the traffic of the partial results, in units of one K block over 256 rows of W
+// K slices for gemm_rows_kernel.  Measured (K-slice sweeps over the 1.5B / 7B / 72B shapes at 16 and 64 rows):
+// the kernel is fastest when the grid has at most one block per compute unit and covers most of them
+// (7B down: 252 or 224 blocks 32 us, 280 blocks 45 us, 462 blocks 35 us); two co-resident blocks only
+// pay when one per unit would leave the chip half empty (7B gate/up: 148 x 3 blocks 59 us, 148 x 1 86 us).
+// So: the largest count with rows-of-blocks x slices <= 256 if that fills 200 units or more; otherwise the
+// count that minimises (rounds of 512 resident blocks) x (K blocks per slice) plus the traffic of the
+// partial results, in units of one K block over 256 rows of W.
 static int gemm_rows64_slices(int N, int K, int rows, size_t part_floats);
 static bool gemm_rows_small(int N, int K);
 static int gemm_rows_slices(int N, int K, int rows, size_t part_floats) {
     if (gemm_rows_small(N, K)) return gemm_rows64_slices(N, K, rows, part_floats);
     const int nb = (N + 255) / 256, nkb = K / 64;
+    {
+        int ks = std::min(256 / nb, nkb / 2);
+        while (ks > 1 && ((size_t)ks * rows * N > part_floats || (ks - 1) * ((nkb + ks - 1) / ks) >= nkb)) --ks;
+        if (ks >= 1 && nb * ks >= 200 && (size_t)ks * rows * N <= part_floats) return ks;
+    }
     int best = 1;
     double best_cost = 1e30;
     for (int ks = 1; ks <= 64 && ks <= nkb; ++ks) {
@@ -503,10 +513,10 @@ static int gemm_rows_slices(int N, int K, int rows, size_t part_floats) {
     return best;
 }
 
-// Small matrices (at most 20 M weights; the 1.5B gate/up pair with 27.5 M is already better off with 256-row
-// blocks: 21.2 against 23.6 us) go to the 64-row kernel, with as many K slices as bring the grid
-// to about 450 blocks (4..8, and at least two K blocks each).
-static bool gemm_rows_small(int N, int K) { return (size_t)N * K <= ((size_t)20 << 20); }
+// Small matrices (at most 14 M weights: the 7B output projection, the 1.5B down and attention projections;
+// from the 7B QKV with 16.5 M on, 256-row blocks at one block per unit are faster) go to the 64-row kernel,
+// with as many K slices as bring the grid to about 450 blocks (4..8, and at least two K blocks each).
+static bool gemm_rows_small(int N, int K) { return (size_t)N * K <= ((size_t)14 << 20); }
 static int gemm_rows64_slices(int N, int K, int rows, size_t part_floats) {
     const int nb = (N + 63) / 64, nkb = K / 64;
     int ks = std::max(4, std::min(8, (448 + nb / 2) / nb));
