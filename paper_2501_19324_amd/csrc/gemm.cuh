@@ -384,7 +384,8 @@ __global__ __launch_bounds__(256) void split_rows_kernel(const float* __restrict
     }
 }
 
-// sum over z (ascending) of the float4 at p + z * stride; eight loads are requested at a time
+// sum over z (ascending) of the float4 at p + z * stride; eight loads are requested at a time, the last
+// batch with clamped addresses (one round trip for the remainder instead of one per slice)
 __device__ __forceinline__ float4 sum_slices(const float* __restrict__ p, size_t stride, int KS) {
     float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
     int z = 0;
@@ -395,9 +396,13 @@ __device__ __forceinline__ float4 sum_slices(const float* __restrict__ p, size_t
 #pragma unroll
         for (int i = 0; i < 8; ++i) { a.x += b[i].x; a.y += b[i].y; a.z += b[i].z; a.w += b[i].w; }
     }
-    for (; z < KS; ++z) {
-        const float4 b = *reinterpret_cast<const float4*>(p + (size_t)z * stride);
-        a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
+    if (z < KS) {
+        float4 b[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) b[i] = *reinterpret_cast<const float4*>(p + (size_t)min(z + i, KS - 1) * stride);
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            if (z + i < KS) { a.x += b[i].x; a.y += b[i].y; a.z += b[i].z; a.w += b[i].w; }
     }
     return a;
 }
