@@ -136,10 +136,22 @@ def main():
     torch.cuda.synchronize()
     t_setup = time.time() - t_setup
 
+    first = dict(ms=0.0, tokens=0)       # the first reasoning step (it holds the prompt prefills), summed over the timed passes
+
     def one_pass():
         s.reset()
         try:
-            return R.rsd_generate(s.ctx, max_steps=args.max_steps, want_tokens=False)
+            # Algorithm 1's loop in two calls, so that the first step can be told apart from the steady state
+            t_first = time.perf_counter()
+            g1 = R.rsd_generate(s.ctx, max_steps=1, want_tokens=False)
+            first["ms"] += (time.perf_counter() - t_first) * 1e3
+            first["tokens"] += g1["n_committed"]
+            if args.max_steps == 1 or (g1["finished"] != 0).all():
+                return g1
+            g = R.rsd_generate(s.ctx, max_steps=args.max_steps, want_tokens=False)
+            for k in ("n_draft", "n_target", "n_accept", "n_reject", "n_sd_rounds", "n_sd_proposed", "n_sd_kept"):
+                g[k] += g1[k]
+            return g
         except R.RsdError as e:
             if e.code != R.RSD_ENOMEM:
                 raise
@@ -159,6 +171,7 @@ def main():
         del src, dst
     for _ in range(args.warmup):
         one_pass()
+    first.update(ms=0.0, tokens=0)
     R.rsd_stage_ms(s.ctx, reset=True)
     R.rsd_probe_start(s.ctx, args.probe_model, PROBE_OPS[args.probe], 8192, 4)
     torch.cuda.synchronize()
@@ -204,6 +217,17 @@ def main():
                    "stage_ms_per_pass": {k: round(v / args.steps, 2) for k, v in zip(("draft", "prm", "gate", "target"), stage)},
                    # (with speculative regeneration the target stage also holds draft proposals and chunked passes)
                    "decode_weight_stream_GBs": round(dec_bytes / dec_s / 1e9, 1) if dec_s > 0 and not args.sd_k else None,
+                   # generation after the first step (which holds the prompt prefills of the models it touches)
+                   "steady_state_tokens_per_s": round((tokens - first["tokens"]) / (dt - first["ms"] * 1e-3), 2)
+                   if tokens > first["tokens"] and dt > first["ms"] * 1e-3 else None,
+                   "first_step_ms_per_pass": round(first["ms"] / max(args.steps, 1), 2),
+                   "mean_step_tokens": round(tokens / max(acc + rej, 1), 2),
+                   "target_token_fraction": round(targeted / max(tokens, 1), 4),
+                   # forward cost by the rule of 2 x parameters per token (Section 3, "Computation Analysis"; the reward model is counted): draft tokens through
+                   # the draft, the same tokens through the reward model, target tokens through the target; against
+                   # every committed token through the target alone
+                   "flops_2N": {"rsd": 2.0 * (drafted * (w.draft.n_params() + w.prm.n_params()) + targeted * w.target.n_params()),
+                                "target_only": 2.0 * tokens * w.target.n_params()},
                    "setup_s": round(t_setup, 1)},
         "roofline": roof,
     }
