@@ -3,8 +3,9 @@
 //
 // KV pool of one model: [layer][page][K|V][kv_head][16 tokens][head_dim], so
 // the keys (or values) of one page and KV head are 16*head_dim contiguous
-// elements.  Token at position p of a sequence lives in logical page p / 16,
-// slot p % 16; block_table[seq][logical page] gives the physical page.
+// elements (in which order inside that block depends on the cache type, see
+// KvTraits / KvTiled below).  Token at position p of a sequence lives in logical
+// page p / 16, slot p % 16; block_table[seq][logical page] gives the physical page.
 #pragma once
 #include "common.cuh"
 
@@ -16,10 +17,30 @@
 template <typename KT> struct KvTraits { static constexpr bool v_transposed = false; };
 template <> struct KvTraits<bf16_t> { static constexpr bool v_transposed = true; };
 
+// bf16 caches with head_dim 128 (the MFMA kernels) go one step further: inside the 4 KB key block and the
+// 4 KB value block of a (page, KV head) the elements are stored in the order the MFMA operands are loaded,
+// so that every operand load of a wave (lane l takes 16 bytes) reads 1 KB of consecutive memory:
+//   keys:   chunk j (elements 32 j .. 32 j + 31) of the 16 tokens is 1 KB; lane l = 16 c + t holds
+//           elements 32 j + 8 c .. + 7 of token t            -> offset ((4 j + c) * 16 + t) * 8 + i
+//   values: head dims 32 m .. 32 m + 31 are 1 KB; lane l = 16 c + (d % 16) holds tokens 4 c .. 4 c + 3 of
+//           dims 32 m + d % 16 and 32 m + 16 + d % 16        -> offset ((64 m + l) * 2 + (d / 16) % 2) * 4 + t % 4
+template <typename KT, int HD> struct KvTiled { static constexpr bool value = false; };
+template <> struct KvTiled<bf16_t, 128> { static constexpr bool value = true; };
+__device__ __forceinline__ int kv_tiled_k(int t, int e) { return ((((e >> 5) * 4 + ((e >> 3) & 3)) * 16) + t) * 8 + (e & 7); }
+__device__ __forceinline__ int kv_tiled_v(int t, int d) {
+    return ((((d >> 5) * 64 + ((t >> 2) * 16 + (d & 15))) * 2 + ((d >> 4) & 1)) * 4) + (t & 3);
+}
+// offset of elements [e0, e0 + 8) (e0 a multiple of 8: they are contiguous in either layout) of token `slot` in a key block
+template <typename KT, int HD>
+__device__ __forceinline__ int k_off8(int slot, int e0) { return KvTiled<KT, HD>::value ? kv_tiled_k(slot, e0) : slot * HD + e0; }
+
 // 8 consecutive head-dim elements [e0, e0+8) of token `slot` from one head's value page
 template <typename KT, int HD>
 __device__ __forceinline__ void load_v8(const KT* __restrict__ vhead, int slot, int e0, float o[8]) {
-    if (KvTraits<KT>::v_transposed) {
+    if (KvTiled<KT, HD>::value) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] = ld1(vhead + kv_tiled_v(slot, e0 + e));
+    } else if (KvTraits<KT>::v_transposed) {
 #pragma unroll
         for (int e = 0; e < 8; ++e) o[e] = ld1(vhead + (e0 + e) * RSD_PAGE + slot);
     } else {
@@ -28,6 +49,7 @@ __device__ __forceinline__ void load_v8(const KT* __restrict__ vhead, int slot, 
 }
 template <typename KT, int HD>
 __device__ __forceinline__ KT* v_addr(KT* vhead, int slot, int e) {
+    if (KvTiled<KT, HD>::value) return vhead + kv_tiled_v(slot, e);
     return KvTraits<KT>::v_transposed ? vhead + e * RSD_PAGE + slot : vhead + slot * HD + e;
 }
 
@@ -85,7 +107,7 @@ __global__ __launch_bounds__(256) void attn_rows_kernel(const float* __restrict_
             const int slot = it * TPW + tsub;
             const int t = pg * RSD_PAGE + slot;
             float kx[8], vx[8];
-            load8(kbase + slot * HD + part * 8, kx);
+            load8(kbase + k_off8<KT, HD>(slot, part * 8), kx);
             load_v8<KT, HD>(vbase, slot, part * 8, vx);
             float s[G];
 #pragma unroll
@@ -210,7 +232,7 @@ __global__ __launch_bounds__(256) void rope_kv_kernel(float* __restrict__ qkv, i
     const float2* cs = rope + (size_t)pos * HALF;
     const int page = block_table[(size_t)seq * max_pages + pos / RSD_PAGE], slot = pos % RSD_PAGE;
     const size_t page_elts = (size_t)2 * Hkv * RSD_PAGE * HD;
-    KT* kdst = pool_layer + (size_t)page * page_elts + (size_t)slot * HD;
+    KT* kpage = pool_layer + (size_t)page * page_elts;
     KT* vpage = pool_layer + (size_t)page * page_elts + (size_t)Hkv * RSD_PAGE * HD;
     const int nq = H * HALF, nk = Hkv * HALF, nv = Hkv * HD;
     for (int idx = threadIdx.x; idx < nq + nk + nv; idx += 256) {
@@ -222,8 +244,9 @@ __global__ __launch_bounds__(256) void rope_kv_kernel(float* __restrict__ qkv, i
             const float ra = a * c.x - b * c.y, rb = b * c.x + a * c.y;
             if (h < H) { p[0] = ra; p[HALF] = rb; }
             else {
-                KT* d = kdst + (size_t)(h - H) * RSD_PAGE * HD + i;
-                st1(d, ra); st1(d + HALF, rb);
+                KT* khead = kpage + (size_t)(h - H) * RSD_PAGE * HD;
+                st1(khead + k_off8<KT, HD>(slot, i & ~7) + (i & 7), ra);
+                st1(khead + k_off8<KT, HD>(slot, (i + HALF) & ~7) + (i & 7), rb);
             }
         } else {
             const int j = idx - nq - nk, hk = j / HD, e = j - hk * HD;
@@ -342,7 +365,7 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(const float* __restric
 #pragma unroll
         for (int it = 0; it < ITERS; ++it) {
             const int slot = it * TPW + tsub;
-            load8(kbase + slot * HD + part * 8, kx[it]);
+            load8(kbase + k_off8<KT, HD>(slot, part * 8), kx[it]);
             load_v8<KT, HD>(kbase + v_off, slot, part * 8, vx[it]);
         }
 #pragma unroll
@@ -357,7 +380,7 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(const float* __restric
         for (int e = 0; e < 8; ++e) { kn[e] = round_store<KT>(kn[e]); vn[e] = round_store<KT>(vn[e]); }
         if (tsub == 0) {
             KT* khead = pool_layer + (size_t)bt[pos / RSD_PAGE] * page_elts + head_off;
-            store8(khead + (size_t)(pos % RSD_PAGE) * HD + part * 8, kn);
+            store8(khead + k_off8<KT, HD>(pos % RSD_PAGE, part * 8), kn);
 #pragma unroll
             for (int e = 0; e < 8; ++e) st1(v_addr<KT, HD>(khead + v_off, pos % RSD_PAGE, part * 8 + e), vn[e]);
         }
@@ -479,20 +502,22 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void attn_decode_mfma_ker
     const size_t page_elts = (size_t)2 * Hkv * RSD_PAGE * HD;
     const size_t head_off = (size_t)hk * RSD_PAGE * HD, v_off = (size_t)Hkv * RSD_PAGE * HD;
 
-    // operands of one page: K chunk j of token l16 = K[l16][j*32 + c*8 ..+8] (the four lanes of a token read 64 contiguous bytes per request); V block nb = V^T[nb*16 + l16][c*4 ..+4]
+    // operands of one page (tiled page layout, see KvTiled): K chunk j of token l16 = K[l16][j*32 + c*8 ..+8] is
+    // the lane's 16 bytes of the j-th KB of the key block; the lane's 16 bytes of the m-th KB of the value
+    // block hold V^T[(2m)*16 + l16][c*4 ..+4] (.x, .y) and V^T[(2m+1)*16 + l16][c*4 ..+4] (.z, .w)
     uint4 kc[4], kn[4];
-    uint2 vc[8], vn[8];
-    auto fetch_phys = [&](int phys, uint4 k[4], uint2 v[8]) {
+    uint4 vc[4], vn[4];
+    auto fetch_phys = [&](int phys, uint4 k[4], uint4 v[4]) {
         const bf16_t* kb = pool_layer + (size_t)phys * page_elts + head_off;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) k[j] = *reinterpret_cast<const uint4*>(kb + l16 * HD + j * 32 + c * 8);
+        for (int j = 0; j < 4; ++j) k[j] = *reinterpret_cast<const uint4*>(kb + (j * 64 + lane) * 8);
 #pragma unroll
-        for (int nb = 0; nb < 8; ++nb) v[nb] = *reinterpret_cast<const uint2*>(kb + v_off + (nb * 16 + l16) * RSD_PAGE + c * 4);
+        for (int m = 0; m < 4; ++m) v[m] = *reinterpret_cast<const uint4*>(kb + v_off + (m * 64 + lane) * 8);
     };
     // i-th page of this wave (i < 64: a wave never holds more than 64 pages)
-    auto fetch = [&](int i, uint4 k[4], uint2 v[8]) { fetch_phys(__shfl(bt_mine, i, RSD_WAVE), k, v); };
+    auto fetch = [&](int i, uint4 k[4], uint4 v[4]) { fetch_phys(__shfl(bt_mine, i, RSD_WAVE), k, v); };
     uint4 k2[4];
-    uint2 v2[8];                 // two pages in flight ahead of the one being used
+    uint4 v2[4];                 // two pages in flight ahead of the one being used
     int pg = pg0, it = 0;
     if (pg < n_pages) fetch(0, kc, vc);
     if (pg + pg_step < n_pages) fetch(1, kn, vn);
@@ -522,7 +547,7 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void attn_decode_mfma_ker
     // Done before the page loop so that its loads overlap the first page fetches.
     const bool owns_new = (sp == S - 1 && wave == 0);
     uint4 k1[4];
-    uint2 v1[8];
+    uint4 v1[4];
     if (owns_new) {
         bf16_t* kb = pool_layer + (size_t)bt[pos / RSD_PAGE] * page_elts + head_off;
         const int slot = pos % RSD_PAGE;
@@ -535,14 +560,18 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void attn_decode_mfma_ker
             pk.y = (uint32_t)f2bf(kv[2]) | ((uint32_t)f2bf(kv[3]) << 16);
             pk.z = (uint32_t)f2bf(kv[4]) | ((uint32_t)f2bf(kv[5]) << 16);
             pk.w = (uint32_t)f2bf(kv[6]) | ((uint32_t)f2bf(kv[7]) << 16);
-            if (l16 == 0) *reinterpret_cast<uint4*>(kb + (size_t)slot * HD + j * 32 + c * 8) = pk;
+            if (l16 == 0) *reinterpret_cast<uint4*>(kb + kv_tiled_k(slot, j * 32 + c * 8)) = pk;
             k1[j] = (l16 == 0) ? pk : make_uint4(0u, 0u, 0u, 0u);
         }
 #pragma unroll
-        for (int nb = 0; nb < 8; ++nb) {
-            const uint16_t vb = f2bf(row[(H + Hkv + hk) * HD + nb * 16 + l16]);
-            if (c == 0) kb[v_off + (size_t)(nb * 16 + l16) * RSD_PAGE + slot].v = vb;
-            v1[nb] = make_uint2(c == 0 ? (uint32_t)vb : 0u, 0u);
+        for (int m = 0; m < 4; ++m) {
+            const uint16_t va = f2bf(row[(H + Hkv + hk) * HD + (2 * m) * 16 + l16]);
+            const uint16_t vb = f2bf(row[(H + Hkv + hk) * HD + (2 * m + 1) * 16 + l16]);
+            if (c == 0) {
+                kb[v_off + kv_tiled_v(slot, (2 * m) * 16 + l16)].v = va;
+                kb[v_off + kv_tiled_v(slot, (2 * m + 1) * 16 + l16)].v = vb;
+            }
+            v1[m] = make_uint4(c == 0 ? (uint32_t)va : 0u, 0u, c == 0 ? (uint32_t)vb : 0u, 0u);
         }
     }
 
@@ -555,7 +584,7 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void attn_decode_mfma_ker
     for (int nb = 0; nb < 8; ++nb) o[nb] = af32x4_t{0.f, 0.f, 0.f, 0.f};
 
     // one page: tokens c*4+i of it are valid iff (vmask >> i) & 1
-    auto process = [&](const uint4 k[4], const uint2 v[8], int vmask) {
+    auto process = [&](const uint4 k[4], const uint4 v[4], int vmask) {
         af32x4_t s = {0.f, 0.f, 0.f, 0.f}, s2 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -594,7 +623,8 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void attn_decode_mfma_ker
         for (int nb = 0; nb < 8; ++nb) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) o[nb][i] *= corr;
-            const as16x4_t vb = __builtin_bit_cast(as16x4_t, make_uint2(v[nb].x & mk0, v[nb].y & mk1));
+            const uint32_t vx = (nb & 1) ? v[nb >> 1].z : v[nb >> 1].x, vy = (nb & 1) ? v[nb >> 1].w : v[nb >> 1].y;
+            const as16x4_t vb = __builtin_bit_cast(as16x4_t, make_uint2(vx & mk0, vy & mk1));
             o[nb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vb, pb, o[nb], 0, 0, 0);
             o[nb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vb, pa, o[nb], 0, 0, 0);
         }
@@ -745,16 +775,16 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(const float* 
     }
 
     uint4 kc[4], kn[4];
-    uint2 vc[8], vn[8];
-    auto fetch = [&](int pg, uint4 k[4], uint2 v[8]) {
+    uint4 vc[4], vn[4];
+    auto fetch = [&](int pg, uint4 k[4], uint4 v[4]) {
         const int phys = __shfl(bt_mine, pg & 63, RSD_WAVE);
         const bf16_t* kb = pool_layer + (size_t)phys * page_elts + head_off;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) k[j] = *reinterpret_cast<const uint4*>(kb + l16 * HD + j * 32 + c * 8);
+        for (int j = 0; j < 4; ++j) k[j] = *reinterpret_cast<const uint4*>(kb + (j * 64 + lane) * 8);
 #pragma unroll
-        for (int nb = 0; nb < 8; ++nb) v[nb] = *reinterpret_cast<const uint2*>(kb + v_off + (nb * 16 + l16) * RSD_PAGE + c * 4);
+        for (int m = 0; m < 4; ++m) v[m] = *reinterpret_cast<const uint4*>(kb + v_off + (m * 64 + lane) * 8);
     };
-    auto do_page = [&](int pg, const uint4 k[4], const uint2 v[8]) {
+    auto do_page = [&](int pg, const uint4 k[4], const uint4 v[4]) {
         // slots past the last row's position hold whatever the pool held: zero those values
         int smask = 0;
 #pragma unroll
@@ -806,13 +836,14 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(const float* 
             for (int nb = 0; nb < 8; ++nb) {
 #pragma unroll
                 for (int i = 0; i < 4; ++i) o[t][nb][i] *= cr[i];
-                const as16x4_t vb = __builtin_bit_cast(as16x4_t, make_uint2(v[nb].x & mk0, v[nb].y & mk1));
+                const uint32_t vx = (nb & 1) ? v[nb >> 1].z : v[nb >> 1].x, vy = (nb & 1) ? v[nb >> 1].w : v[nb >> 1].y;
+                const as16x4_t vb = __builtin_bit_cast(as16x4_t, make_uint2(vx & mk0, vy & mk1));
                 o[t][nb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pb, vb, o[t][nb], 0, 0, 0);
                 o[t][nb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pa, vb, o[t][nb], 0, 0, 0);
             }
         }
     };
-    auto prefetch = [&](int pg, uint4 k[4], uint2 v[8]) {     // pg < n_pages
+    auto prefetch = [&](int pg, uint4 k[4], uint4 v[4]) {     // pg < n_pages
         if ((pg & 63) == 0) bt_mine = (pg + lane < n_pages) ? bt[pg + lane] : -1;
         fetch(pg, k, v);
     };
