@@ -280,15 +280,43 @@ int rsd_stage_ms(rsd_ctx *c, double ms[4], int32_t reset);
  * failed and the context fell back to kernel-by-kernel launches.  Host counters, no GPU work. */
 int rsd_decode_stats(rsd_ctx *c, int64_t *eager_iters, int64_t *graph_replays, int64_t *graphs_recorded);
 
-/* Kernel timing probe for roofline reports.  While armed, every `stride`-th
- * launch of one weight-streaming projection (op: 0 qkv, 1 attention output,
- * 2 gate+up, 3 down, 4 output head) in `model`'s single-token decode path is
- * bracketed by a pair of HIP events on the context's stream, up to
- * max_samples pairs.  rsd_probe_read synchronises, returns the number of
- * timed launches, their summed duration and the algorithmic bytes one such
- * launch moves (weights once + activations in and out), and disarms. */
-int rsd_probe_start(rsd_ctx *c, int32_t model, int32_t op, int32_t max_samples, int32_t stride);
-int rsd_probe_read(rsd_ctx *c, int64_t *n_samples, double *total_ms, int64_t *bytes_per_launch);
+/* Kernel timing probes for roofline reports.  RSD_PROBE_SLOTS independent probes; while slot `slot` is armed,
+ * every `stride`-th launch of one weight-streaming projection (op: 0 qkv, 1 attention output, 2 gate+up,
+ * 3 down, 4 output head) of `model` is bracketed by a pair of HIP events on the context's stream, up to
+ * max_samples pairs.  phase RSD_PROBE_DECODE: launches of the single-token decode iteration (Algorithm 1's
+ * token-by-token generation of a step; inside the decode loop every stride-th *iteration* is launched kernel
+ * by kernel with its launch timed, the others are replayed from the recorded graph); phase RSD_PROBE_PREFILL:
+ * launches of chunked passes (reward scoring of a step, catch-up).  Only the matrix kernel itself is timed
+ * (not the kernels that add K slices or apply the epilogue).  rsd_probe_read synchronises, returns the
+ * number of timed launches, their summed duration, and over the same launches the summed algorithmic bytes
+ * (weights once + activations in and out) and floating-point operations (2 * rows * N * K), and disarms. */
+#define RSD_PROBE_SLOTS 4
+enum { RSD_PROBE_DECODE = 0, RSD_PROBE_PREFILL = 1 };
+int rsd_probe_start(rsd_ctx *c, int32_t slot, int32_t model, int32_t phase, int32_t op, int32_t max_samples,
+                    int32_t stride);
+int rsd_probe_read(rsd_ctx *c, int32_t slot, int64_t *n_samples, double *total_ms, int64_t *total_bytes,
+                   int64_t *total_flops);
+
+/* Accounting of the single-token decode loop of one policy model (RSD_DRAFT or RSD_TARGET; the loop that
+ * generates a reasoning step token by token, Algorithm 1) since the context was created or the counters
+ * were last reset: iterations launched (each streams the model's weights once, whatever the number of
+ * sequences), GPU time between HIP events recorded before the first and after the last iteration of every
+ * loop (the polls of the active counter inside are included, chunked first passes are not), sequence-
+ * iterations (one per token sampled in the loop), and the keys/values read: the sum over those
+ * sequence-iterations of the context length attended to.  Iterations of speculative regeneration are not
+ * counted.  reset != 0 clears the counters after reading.  Host outputs, any may be NULL. */
+int rsd_iter_stats(rsd_ctx *c, int32_t model, int64_t *iterations, double *gpu_ms, int64_t *seq_iterations,
+                   int64_t *kv_tokens_read, int32_t reset);
+
+/* Timing of the decode attention kernel alone (grouped-query attention of one new token per sequence over
+ * the paged cache, rotary embedding and cache write included), for roofline reports.  Sequence b gets a
+ * context of ctx_len_host[b] tokens (1 .. max_ctx; HOST array [B]) in `model`'s cache, whose pool is
+ * cleared; the kernel (and the kernel merging context splits, when the context is split) is launched
+ * `reps` times in the launch configuration of the decode iteration, cycling through the layers so that
+ * successive launches read different memory, between two HIP events.  *total_ms is the time between the
+ * events.  Resets the sequences: call rsd_set_prompts before stepping again.  RSD_ENOMEM when the pool
+ * cannot hold the contexts. */
+int rsd_probe_attention(rsd_ctx *c, int32_t model, const int32_t *ctx_len_host, int32_t reps, double *total_ms);
 
 const char *rsd_last_error(const rsd_ctx *c);
 void rsd_destroy(rsd_ctx *c);

@@ -17,7 +17,7 @@ __all__ = ["RSD_OK", "RSD_EINVAL", "RSD_ENOMEM", "RSD_ESTATE", "RSD_EHIP", "RSD_
            "RsdError", "Context", "load_library", "rsd_init", "rsd_set_prompts", "rsd_set_uniforms",
            "rsd_set_criterion", "rsd_step", "rsd_generate", "rsd_export_state", "rsd_export_pages",
            "rsd_set_teacher", "rsd_export_sampled", "rsd_forward", "rsd_sample", "rsd_stage_ms", "rsd_decode_stats", "rsd_destroy",
-           "rsd_probe_start", "rsd_probe_read",
+           "rsd_probe_start", "rsd_probe_read", "rsd_iter_stats", "rsd_probe_attention",
            "EXPORTED_SYMBOLS"]
 
 RSD_OK, RSD_EINVAL, RSD_ENOMEM, RSD_ESTATE, RSD_EHIP = 0, -1, -2, -3, -4
@@ -26,7 +26,7 @@ RSD_MERGE_NONE, RSD_MERGE_DRAFT, RSD_MERGE_TARGET = 0, 1, 2
 EXPORTED_SYMBOLS = ["rsd_init", "rsd_set_prompts", "rsd_set_uniforms", "rsd_set_criterion", "rsd_step",
                     "rsd_generate", "rsd_export_state", "rsd_export_pages", "rsd_set_teacher",
                     "rsd_export_sampled", "rsd_set_teacher_sd", "rsd_export_proposed", "rsd_set_uniforms_sd", "rsd_sd_verify", "rsd_forward", "rsd_sample", "rsd_stage_ms", "rsd_decode_stats", "rsd_probe_start", "rsd_probe_read",
-                    "rsd_last_error", "rsd_destroy"]
+                    "rsd_iter_stats", "rsd_probe_attention", "rsd_last_error", "rsd_destroy"]
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "librsd.so")
 
 
@@ -306,12 +306,28 @@ def rsd_decode_stats(ctx: Context) -> dict:
     return dict(eager_iters=a.value, graph_replays=b.value, graphs_recorded=g.value)
 
 
-def rsd_probe_start(ctx: Context, model: int, op: int, max_samples: int = 4096, stride: int = 1) -> None:
-    ctx.check(load_library().rsd_probe_start(ctx.handle, C.c_int32(model), C.c_int32(op), C.c_int32(max_samples),
-                                             C.c_int32(stride)))
+def rsd_probe_start(ctx: Context, slot: int, model: int, phase: int, op: int, max_samples: int = 4096, stride: int = 1) -> None:
+    ctx.check(load_library().rsd_probe_start(ctx.handle, C.c_int32(slot), C.c_int32(model), C.c_int32(phase), C.c_int32(op),
+                                             C.c_int32(max_samples), C.c_int32(stride)))
 
 
-def rsd_probe_read(ctx: Context) -> dict:
-    n, ms, by = C.c_int64(), C.c_double(), C.c_int64()
-    ctx.check(load_library().rsd_probe_read(ctx.handle, C.byref(n), C.byref(ms), C.byref(by)))
-    return dict(n=n.value, total_ms=ms.value, bytes_per_launch=by.value)
+def rsd_probe_read(ctx: Context, slot: int) -> dict:
+    n, ms, by, fl = C.c_int64(), C.c_double(), C.c_int64(), C.c_int64()
+    ctx.check(load_library().rsd_probe_read(ctx.handle, C.c_int32(slot), C.byref(n), C.byref(ms), C.byref(by), C.byref(fl)))
+    return dict(n=n.value, total_ms=ms.value, total_bytes=by.value, total_flops=fl.value)
+
+
+def rsd_iter_stats(ctx: Context, model: int, reset: bool = False) -> dict:
+    it, ms, si, kv = C.c_int64(), C.c_double(), C.c_int64(), C.c_int64()
+    ctx.check(load_library().rsd_iter_stats(ctx.handle, C.c_int32(model), C.byref(it), C.byref(ms), C.byref(si), C.byref(kv),
+                                            C.c_int32(int(reset))))
+    return dict(iterations=it.value, gpu_ms=ms.value, seq_iterations=si.value, kv_tokens_read=kv.value)
+
+
+def rsd_probe_attention(ctx: Context, model: int, ctx_len: np.ndarray, reps: int) -> float:
+    """Milliseconds for ``reps`` launches of the decode attention of ``model`` over contexts ``ctx_len``."""
+    cl = np.ascontiguousarray(ctx_len, dtype=np.int32)
+    assert cl.shape == (ctx.batch,)
+    ms = C.c_double()
+    ctx.check(load_library().rsd_probe_attention(ctx.handle, C.c_int32(model), _np_ptr(cl), C.c_int32(reps), C.byref(ms)))
+    return ms.value

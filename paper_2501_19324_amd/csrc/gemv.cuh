@@ -9,6 +9,7 @@
 // and the result is either stored or added to Y (residual stream).
 #pragma once
 #include <algorithm>
+#include <atomic>
 #include <hip/hip_ext.h>
 #include "common.cuh"
 
@@ -297,11 +298,11 @@ static bool gemv_launch_full(hipStream_t st, int pro, int epi, const WT* W, int 
     const dim3 grid(std::min((n_groups + 3) / 4, 256 * per_cu)), block(256);
 #define RSD_GEMVF_CASE(P, E)                                                                                 \
     if (pro == P && epi == E) {                                                                              \
-        static bool raised = false;   /* one flag per kernel instance: dynamic LDS above 64 KB must be allowed */ \
-        if (!raised && full > 64 * 1024) {                                                                   \
+        static std::atomic<bool> raised{false};   /* per kernel instance: dynamic LDS above 64 KB must be allowed */ \
+        if (!raised.load(std::memory_order_relaxed) && full > 64 * 1024) {                                                                   \
             (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemv_full_kernel<WT, MT, R, U, P, E>),   \
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)kGemvFullLds);        \
-            raised = true;                                                                                   \
+            raised.store(true, std::memory_order_relaxed);                                                                                 \
         }                                                                                                    \
         hipLaunchKernelGGL((gemv_full_kernel<WT, MT, R, U, P, E>), grid, block, full, st, W, N, K, X, ldx,   \
                            gain, eps, Y, ldy, M);                                                            \
@@ -493,11 +494,11 @@ static bool gemv_launch_flat(hipStream_t st, int pro, int epi, const WT* W, int 
     if (lds > kGemvFullLds) return false;
 #define RSD_GEMVFLAT_CASE(P, E)                                                                              \
     if (pro == P && epi == E) {                                                                              \
-        static bool raised = false;                                                                          \
-        if (!raised && lds > 64 * 1024) {                                                                    \
+        static std::atomic<bool> raised{false};                                                              \
+        if (!raised.load(std::memory_order_relaxed) && lds > 64 * 1024) {                                                                    \
             (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemv_flat_kernel<WT, NW, U, P, E>),      \
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)kGemvFullLds);        \
-            raised = true;                                                                                   \
+            raised.store(true, std::memory_order_relaxed);                                                                                 \
         }                                                                                                    \
         if (gemv_timing.start) {                                                                             \
             hipExtLaunchKernelGGL((gemv_flat_kernel<WT, NW, U, P, E>), dim3(G), dim3(NW * 64), lds, st,      \

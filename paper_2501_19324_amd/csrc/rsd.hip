@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
 #include <chrono>
 #include <cmath>
 #include <cstdarg>
@@ -124,10 +125,18 @@ struct rsd_ctx {
     int pf_rows = 0, pf_max_end = 0;     // rows of the chunked pass in flight and the longest context among its pieces
     int *poll_h = nullptr;
     double stage_ms[4] = {0, 0, 0, 0};
-    // kernel timing probe
-    int probe_model = -1, probe_op = -1, probe_stride = 1, probe_seen = 0;
-    bool in_decode_loop = false, probe_iter_on = false;     // inside the decode loop whole iterations are probed
-    int probe_iters = 0;
+    // kernel timing probes
+    struct Probe {
+        int model = -1, phase = 0, op = -1, stride = 1, seen = 0, iters = 0;
+        bool iter_on = false;                                // inside the decode loop whole iterations are probed
+        size_t used = 0;
+        long long bytes = 0, flops = 0;
+        std::vector<hipEvent_t> ev;
+    } probe[RSD_PROBE_SLOTS];
+    bool in_decode_loop = false;
+    int cur_phase = RSD_PROBE_DECODE;                        // what run_layers is launching for
+    // accounting of the decode loops of the draft and the target
+    struct IterStats { long long iters = 0, seq_iters = 0, kv_read = 0; double ms = 0; hipEvent_t e0 = nullptr, e1 = nullptr; } it[2];
     // single-token decode iterations recorded as graphs, one per (model, uniforms, teacher tokens)
     struct DecodeGraph { int which; const float* u; const int* forced; int mode; hipGraph_t graph; hipGraphExec_t exec; };
     std::vector<DecodeGraph> graphs;
@@ -135,9 +144,6 @@ struct rsd_ctx {
     bool graphs_ok = true;                 // cleared when recording fails: eager launches from then on
     bool decode_warm[3] = {false, false, false};
     long long n_eager_iters = 0, n_graph_replays = 0;
-    size_t probe_used = 0;
-    long long probe_bytes = 0;
-    std::vector<hipEvent_t> probe_ev;
 };
 
 namespace {
@@ -322,32 +328,41 @@ void launch_attn_g(rsd_ctx* c, const Model& m, int l, int M, const RowMap& rm, i
                            c->part_ml, rm, m.s.n_heads, S, c->att, m.q_dim);
 }
 
-// Brackets one launch with a pair of events when the probe is armed for it.
+// Brackets one launch with a pair of events when a probe is armed for it.
 struct ProbeScope {
     rsd_ctx* c;
-    bool on = false, direct = false;
+    rsd_ctx::Probe* p = nullptr;
+    bool direct = false;
+    long long bytes, flops;
     // direct: the launch inside the scope is a single-row projection, which can carry the events in its
     // own dispatch packet (kernel start to kernel end); otherwise the events are recorded around it
-    ProbeScope(rsd_ctx* c_, const Model& m, int op, long long bytes, bool direct_ = false) : c(c_), direct(direct_) {
-        if (c->probe_op != op || &m != &c->m[c->probe_model < 0 ? 0 : c->probe_model] || c->probe_model < 0) return;
-        if (c->probe_used + 2 > c->probe_ev.size()) return;
-        if (c->in_decode_loop) { if (!c->probe_iter_on) return; }
-        else if (c->probe_seen++ % c->probe_stride) return;
-        on = true;
-        c->probe_bytes = bytes;
-        if (direct) gemv_timing = GemvTiming{c->probe_ev[c->probe_used], c->probe_ev[c->probe_used + 1]};
-        else (void)hipEventRecord(c->probe_ev[c->probe_used], c->st);
+    ProbeScope(rsd_ctx* c_, const Model& m, int op, long long bytes_, long long flops_, bool direct_ = false)
+        : c(c_), direct(direct_), bytes(bytes_), flops(flops_) {
+        const int which = (int)(&m - &c->m[0]);
+        for (auto& q : c->probe) {
+            if (q.model != which || q.op != op || q.phase != c->cur_phase) continue;
+            if (q.used + 2 > q.ev.size()) continue;
+            if (c->in_decode_loop) { if (!q.iter_on) continue; }
+            else if (q.seen++ % q.stride) continue;
+            p = &q;
+            break;
+        }
+        if (!p) return;
+        if (direct) gemv_timing = GemvTiming{p->ev[p->used], p->ev[p->used + 1]};
+        else (void)hipEventRecord(p->ev[p->used], c->st);
     }
     ~ProbeScope() {
-        if (!on) return;
+        if (!p) return;
         if (direct) {
             const bool taken = gemv_timing.start == nullptr;    // the launcher clears the hook when it uses it
             gemv_timing = GemvTiming{};
             if (!taken) return;                                  // another kernel served this shape: no sample
         } else {
-            (void)hipEventRecord(c->probe_ev[c->probe_used + 1], c->st);
+            (void)hipEventRecord(p->ev[p->used + 1], c->st);
         }
-        c->probe_used += 2;
+        p->used += 2;
+        p->bytes += bytes;
+        p->flops += flops;
     }
 };
 
@@ -415,11 +430,12 @@ void launch_attn_prefill_mfma(rsd_ctx* c, const Model& m, int l, const RowMap& r
     constexpr size_t qlds = (size_t)4 * 2 * 2 * 16 * (128 + 8) * sizeof(uint16_t);     // Q operands of 4 waves
 #define RSD_ATTN_CASE(GG)                                                                                     \
     case GG: {                                                                                                \
-        static bool raised = false;                                                                           \
-        if (!raised) {                                                                                        \
+        /* set once per process; the call is idempotent, so a race between contexts costs a repeat at most */ \
+        static std::atomic<bool> raised{false};                                                               \
+        if (!raised.load(std::memory_order_relaxed)) {                                                        \
             (void)hipFuncSetAttribute(reinterpret_cast<const void*>(attn_prefill_mfma_kernel<GG>),            \
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)qlds);                 \
-            raised = true;                                                                                    \
+            raised.store(true, std::memory_order_relaxed);                                                    \
         }                                                                                                     \
         hipLaunchKernelGGL((attn_prefill_mfma_kernel<GG>), grid, block, qlds, c->st, c->qkv, m.n_qkv, pool_l, \
                            m.bt_dev, m.max_pages, rm.row_seq, rm.row_pos, c->item_row0_dev, c->item_n_dev,    \
@@ -456,28 +472,40 @@ void rows_finish(rsd_ctx* c, int ks, int rows, int M, int N, float* Y, int ldy) 
 // Y (+)= halves . W^T with epilogue `epi`; EPI_SWIGLU (N = 2F) writes the activated values back as halves.
 // next_gain != nullptr (EPI_RESID): RMSNorm(Y row) * next_gain is left in the halves for the projection that
 // follows (inside the finish kernel where there is one and N <= 8192).
-void rows_gemm(rsd_ctx* c, int epi, const bf16_t* W, int N, int K, int M, float* Y, int ldy,
+// (m, op) name the projection for the timing probes: the matrix kernel alone is bracketed.
+void rows_gemm(rsd_ctx* c, const Model& m, int op, int epi, const bf16_t* W, int N, int K, int M, float* Y, int ldy,
                const bf16_t* next_gain = nullptr, float eps = 0.f) {
     const bool few = M <= 64 && N % 4 == 0;
     const int rows = few ? (M <= 32 ? 32 : 64) : M;          // rows of one slice of partial results
+    // algorithmic traffic: the weights once, fp32 activations in and out (SwiGLU leaves N / 2 columns)
+    const long long pb = (long long)N * K * 2 + 4LL * M * (K + (epi == EPI_SWIGLU ? N / 2 : N) + (epi == EPI_RESID ? N : 0));
+    const long long pf = 2LL * M * N * K;
     int ks;
     if (few) {
         ks = gemm_rows_slices(N, K, rows, c->part_k_floats);
+        ProbeScope ps(c, m, op, pb, pf);
         gemm_rows_launch(c->st, W, N, K, c->xs_h, c->xs_l, M, c->part_k, ks);
     } else {
         ks = N % 4 ? 1 : gemm_tile_slices(N, K, M, c->part_k_floats);
         if (ks == 1) {      // the tile kernel finishes by itself
             if (epi == EPI_SWIGLU) {
-                gemm_tile_launch(c->st, EPI_STORE, W, N, K, c->xs_h, c->xs_l, M, c->gu, N, nullptr, 1);
+                {
+                    ProbeScope ps(c, m, op, pb, pf);
+                    gemm_tile_launch(c->st, EPI_STORE, W, N, K, c->xs_h, c->xs_l, M, c->gu, N, nullptr, 1);
+                }
                 const size_t total = (size_t)M * (N / 2);
                 hipLaunchKernelGGL(swiglu_split_kernel, dim3((unsigned)((total / 4 + 255) / 256)), dim3(256), 0, c->st,
                                    c->gu, N / 2, c->xs_h, c->xs_l, total);
             } else {
-                gemm_tile_launch(c->st, epi, W, N, K, c->xs_h, c->xs_l, M, Y, ldy, nullptr, 1);
+                {
+                    ProbeScope ps(c, m, op, pb, pf);
+                    gemm_tile_launch(c->st, epi, W, N, K, c->xs_h, c->xs_l, M, Y, ldy, nullptr, 1);
+                }
                 if (next_gain) rows_split(c, Y, ldy, M, N, next_gain, eps);
             }
             return;
         }
+        ProbeScope ps(c, m, op, pb, pf);
         gemm_tile_launch(c->st, EPI_STORE, W, N, K, c->xs_h, c->xs_l, M, nullptr, 0, c->part_k, ks);
     }
     if (next_gain && N <= 8192) {
@@ -491,7 +519,7 @@ void rows_gemm(rsd_ctx* c, int epi, const bf16_t* W, int N, int K, int M, float*
     if (next_gain) rows_split(c, Y, ldy, M, N, next_gain, eps);
 }
 void rows_split(rsd_ctx*, const float*, int, int, int, const float*, float) {}    // fp32 weights never take this path
-void rows_gemm(rsd_ctx*, int, const float*, int, int, int, float*, int, const float* = nullptr, float = 0.f) {}
+void rows_gemm(rsd_ctx*, const Model&, int, int, const float*, int, int, int, float*, int, const float* = nullptr, float = 0.f) {}
 
 template <typename WT>
 void run_layers(rsd_ctx* c, Model& m, int M, const RowMap& rm, bool decode) {
@@ -501,6 +529,7 @@ void run_layers(rsd_ctx* c, Model& m, int M, const RowMap& rm, bool decode) {
     hipLaunchKernelGGL((embed_kernel<WT>), dim3(M), dim3(256), 0, st, wptr<WT>(m, m.off_embed), d, c->ds.tokens,
                        c->p.max_ctx, rm, c->h);
     const int S = decode ? m.splits : 1;
+    c->cur_phase = decode ? RSD_PROBE_DECODE : RSD_PROBE_PREFILL;
     const bool rows = rows_path<WT>(m, M);
     const bool fused = M <= 8 && !rows;   // few rows: norm / SwiGLU / residual folded into the weight-streaming kernels
     const bool rows_fuse_norm = rows;                        // the residual GEMMs leave RMSNorm(h) for the next projection
@@ -513,13 +542,13 @@ void run_layers(rsd_ctx* c, Model& m, int M, const RowMap& rm, bool decode) {
         const LayerOff& o = m.layers[l];
         const long long esz = sizeof(WT);
         if (fused) {
-            ProbeScope ps(c, m, 0, (long long)m.n_qkv * d * esz + 4LL * M * (d + m.n_qkv), M == 1);
+            ProbeScope ps(c, m, 0, (long long)m.n_qkv * d * esz + 4LL * M * (d + m.n_qkv), 2LL * M * m.n_qkv * d, M == 1);
             gemv_launch<WT>(st, PRO_NORM, EPI_STORE, wptr<WT>(m, o.wqkv), m.n_qkv, d, c->h, d,
                             wptr<WT>(m, o.attn_norm), eps, c->qkv, m.n_qkv, M);
         } else if (rows) {
             // (after the first layer the halves of RMSNorm(h) come from the previous layer's last finish)
             if (l == 0 || !rows_fuse_norm) rows_split(c, c->h, d, M, d, wptr<WT>(m, o.attn_norm), eps);
-            rows_gemm(c, EPI_STORE, wptr<WT>(m, o.wqkv), m.n_qkv, d, M, c->qkv, m.n_qkv);
+            rows_gemm(c, m, 0, EPI_STORE, wptr<WT>(m, o.wqkv), m.n_qkv, d, M, c->qkv, m.n_qkv);
         } else if constexpr (std::is_same<WT, float>::value) {
             hipLaunchKernelGGL((rmsnorm_kernel<WT>), dim3(M), dim3(256), 0, st, c->h, d, wptr<WT>(m, o.attn_norm), eps, c->xn);
             gemm_launch(st, EPI_STORE, wptr<WT>(m, o.wqkv), m.n_qkv, d, c->xn, d, c->qkv, m.n_qkv, M, c->part_k, c->part_k_floats);
@@ -542,7 +571,7 @@ void run_layers(rsd_ctx* c, Model& m, int M, const RowMap& rm, bool decode) {
         }
         if (fused) {
             {
-                ProbeScope ps(c, m, 1, (long long)d * m.q_dim * esz + 4LL * M * (m.q_dim + 2 * d), M == 1);
+                ProbeScope ps(c, m, 1, (long long)d * m.q_dim * esz + 4LL * M * (m.q_dim + 2 * d), 2LL * M * d * m.q_dim, M == 1);
                 if (parts_to_o)
                     gemv_launch_attn<WT>(st, wptr<WT>(m, o.wo), d, m.q_dim, AttnParts{c->part_acc, c->part_ml, S}, c->h);
                 else
@@ -551,23 +580,23 @@ void run_layers(rsd_ctx* c, Model& m, int M, const RowMap& rm, bool decode) {
             }
             if (gemv_can_fuse_swiglu(M, d) && gemv_can_fuse_swiglu(M, F)) {
                 {
-                    ProbeScope ps(c, m, 2, 2LL * F * d * esz + 4LL * M * (d + F), M == 1);
+                    ProbeScope ps(c, m, 2, 2LL * F * d * esz + 4LL * M * (d + F), 4LL * M * F * d, M == 1);
                     gemv_launch<WT>(st, PRO_NORM, EPI_SWIGLU, wptr<WT>(m, o.wgu), F, d, c->h, d,
                                     wptr<WT>(m, o.ffn_norm), eps, c->act, F, M);
                 }
                 {
-                    ProbeScope ps(c, m, 3, (long long)d * F * esz + 4LL * M * (F + 2 * d), M == 1);
+                    ProbeScope ps(c, m, 3, (long long)d * F * esz + 4LL * M * (F + 2 * d), 2LL * M * d * F, M == 1);
                     gemv_launch<WT>(st, PRO_NONE, EPI_RESID, wptr<WT>(m, o.wdown), d, F, c->act, F,
                                     (const WT*)nullptr, 0.f, c->h, d, M);
                 }
             } else {
                 {
-                    ProbeScope ps(c, m, 2, 2LL * F * d * esz + 4LL * M * (d + 2 * F));
+                    ProbeScope ps(c, m, 2, 2LL * F * d * esz + 4LL * M * (d + 2 * F), 4LL * M * F * d);
                     gemv_launch<WT>(st, PRO_NORM, EPI_STORE, wptr<WT>(m, o.wgu), 2 * F, d, c->h, d,
                                     wptr<WT>(m, o.ffn_norm), eps, c->gu, 2 * F, M);
                 }
                 {
-                    ProbeScope ps(c, m, 3, (long long)d * F * esz + 4LL * M * (2 * F + 2 * d));
+                    ProbeScope ps(c, m, 3, (long long)d * F * esz + 4LL * M * (2 * F + 2 * d), 2LL * M * d * F);
                     gemv_launch<WT>(st, PRO_SWIGLU, EPI_RESID, wptr<WT>(m, o.wdown), d, F, c->gu, 2 * F,
                                     (const WT*)nullptr, 0.f, c->h, d, M);
                 }
@@ -575,16 +604,16 @@ void run_layers(rsd_ctx* c, Model& m, int M, const RowMap& rm, bool decode) {
         } else if (rows) {
             if (!att_halves) rows_split(c, c->att, m.q_dim, M, m.q_dim, (const WT*)nullptr, 0.f);
             if (rows_fuse_norm) {
-                rows_gemm(c, EPI_RESID, wptr<WT>(m, o.wo), d, m.q_dim, M, c->h, d, wptr<WT>(m, o.ffn_norm), eps);
+                rows_gemm(c, m, 1, EPI_RESID, wptr<WT>(m, o.wo), d, m.q_dim, M, c->h, d, wptr<WT>(m, o.ffn_norm), eps);
             } else {
-                rows_gemm(c, EPI_RESID, wptr<WT>(m, o.wo), d, m.q_dim, M, c->h, d);
+                rows_gemm(c, m, 1, EPI_RESID, wptr<WT>(m, o.wo), d, m.q_dim, M, c->h, d);
                 rows_split(c, c->h, d, M, d, wptr<WT>(m, o.ffn_norm), eps);
             }
-            rows_gemm(c, EPI_SWIGLU, wptr<WT>(m, o.wgu), 2 * F, d, M, nullptr, 0);     // activated values stay as halves
+            rows_gemm(c, m, 2, EPI_SWIGLU, wptr<WT>(m, o.wgu), 2 * F, d, M, nullptr, 0);     // activated values stay as halves
             if (rows_fuse_norm && l + 1 < m.s.n_layers)
-                rows_gemm(c, EPI_RESID, wptr<WT>(m, o.wdown), d, F, M, c->h, d, wptr<WT>(m, m.layers[l + 1].attn_norm), eps);
+                rows_gemm(c, m, 3, EPI_RESID, wptr<WT>(m, o.wdown), d, F, M, c->h, d, wptr<WT>(m, m.layers[l + 1].attn_norm), eps);
             else
-                rows_gemm(c, EPI_RESID, wptr<WT>(m, o.wdown), d, F, M, c->h, d);
+                rows_gemm(c, m, 3, EPI_RESID, wptr<WT>(m, o.wdown), d, F, M, c->h, d);
         } else if constexpr (std::is_same<WT, float>::value) {
             gemm_launch(st, EPI_RESID, wptr<WT>(m, o.wo), d, m.q_dim, c->att, m.q_dim, c->h, d, M, c->part_k, c->part_k_floats);
             hipLaunchKernelGGL((rmsnorm_kernel<WT>), dim3(M), dim3(256), 0, st, c->h, d, wptr<WT>(m, o.ffn_norm), eps, c->xn);
@@ -601,12 +630,12 @@ template <typename WT>
 void lm_head(rsd_ctx* c, Model& m, const float* X, int M, float* Y, int ldy) {
     const int d = m.s.d_model, V = m.s.vocab;
     if (M <= 8 && !rows_path<WT>(m, M)) {
-        ProbeScope ps(c, m, 4, (long long)V * d * sizeof(WT) + 4LL * M * (d + V), M == 1);
+        ProbeScope ps(c, m, 4, (long long)V * d * sizeof(WT) + 4LL * M * (d + V), 2LL * M * V * d, M == 1);
         gemv_launch<WT>(c->st, PRO_NORM, EPI_STORE, wptr<WT>(m, m.off_head), V, d, X, d, wptr<WT>(m, m.off_final_norm),
                         m.s.rms_eps, Y, ldy, M);
     } else if (rows_path<WT>(m, M)) {
         rows_split(c, X, d, M, d, wptr<WT>(m, m.off_final_norm), m.s.rms_eps);
-        rows_gemm(c, EPI_STORE, wptr<WT>(m, m.off_head), V, d, M, Y, ldy);
+        rows_gemm(c, m, 4, EPI_STORE, wptr<WT>(m, m.off_head), V, d, M, Y, ldy);
     } else if constexpr (std::is_same<WT, float>::value) {
         for (int r0 = 0; r0 < M; r0 += kMaxRows) {
             const int mm = std::min(kMaxRows, M - r0);
@@ -776,6 +805,11 @@ int gen_stage(rsd_ctx* c, int which, const float* u, const int* forced, int mode
         }
     if (!n_act) return RSD_OK;
     int iters = 0;
+    // decode-loop accounting (steps of the reasoning loop only): contexts before the stage
+    const bool count = mode == 1 && which < 2;
+    std::vector<int> ctx0;
+    if (count) ctx0.assign(c->ctx_len(), c->ctx_len() + B);
+    const std::vector<int> was_active(c->active(), c->active() + B);
     if (!all_single) {
         int rc = prefill<WT>(c, which, pieces, [&](const std::vector<Piece>&, const std::vector<int>&, int) {
             hipLaunchKernelGGL(gather_rows_kernel, dim3(B), dim3(256), 0, c->st, c->h, c->last_row_dev, m.s.d_model, c->hl);
@@ -788,14 +822,20 @@ int gen_stage(rsd_ctx* c, int which, const float* u, const int* forced, int mode
                     c->p.sep_id, c->p.sep_logit_bias, c->ds.active, B, nullptr, append_args(c, which, forced, mode));
         iters = 1;
     }
+    const int first = iters;
+    if (count) HIPCHK(c, hipEventRecord(c->it[which].e0, c->st));
     c->in_decode_loop = true;
     while (iters < cap) {
         // an iteration whose launches are timed runs eagerly (events cannot bracket a node of a graph),
         // and so does the first one of a model (it raises the kernels' LDS limits)
-        c->probe_iter_on = c->probe_model == which && c->probe_used + 2 <= c->probe_ev.size() &&
-                           (c->probe_iters++ % c->probe_stride) == 0;
+        bool timed = false;
+        for (auto& q : c->probe) {
+            q.iter_on = q.model == which && q.phase == RSD_PROBE_DECODE && q.used + 2 <= q.ev.size() &&
+                        (q.iters++ % q.stride) == 0;
+            timed |= q.iter_on;
+        }
         hipGraphExec_t exec = nullptr;
-        if (c->p.use_graphs && c->graphs_ok && !c->probe_iter_on && c->decode_warm[which])
+        if (c->p.use_graphs && c->graphs_ok && !timed && c->decode_warm[which])
             exec = decode_graph<WT>(c, which, u, forced, mode);
         if (exec) {
             const hipError_t e = hipGraphLaunch(exec, c->st);
@@ -814,7 +854,26 @@ int gen_stage(rsd_ctx* c, int which, const float* u, const int* forced, int mode
         }
     }
     c->in_decode_loop = false;
-    c->probe_iter_on = false;
+    for (auto& q : c->probe) q.iter_on = false;
+    if (count) {
+        rsd_ctx::IterStats& is = c->it[which];
+        HIPCHK(c, hipEventRecord(is.e1, c->st));
+        int rc = pull_state(c);
+        if (rc) return rc;
+        if (iters > first) {
+            float ms = 0.f;
+            HIPCHK(c, hipEventElapsedTime(&ms, is.e0, is.e1));
+            is.ms += ms;
+            is.iters += iters - first;
+            for (int b = 0; b < B; ++b) {
+                if (!was_active[b]) continue;
+                // tokens this sequence sampled inside the loop; its j-th one attends to ctx0 + first + j keys
+                const long long n = std::max(0, c->ctx_len()[b] - ctx0[b] - first);
+                is.seq_iters += n;
+                is.kv_read += n * (ctx0[b] + first) + n * (n - 1) / 2;
+            }
+        }
+    }
     HIPCHK(c, hipGetLastError());
     return RSD_OK;
 }
@@ -985,6 +1044,24 @@ int sd_stage(rsd_ctx* c) {
     return RSD_OK;
 }
 
+// Recorded decode iterations bake in the uniform and teacher arrays they were recorded with: drop those
+// whose arrays the caller has replaced, so that the cache holds at most one graph per live combination.
+int drop_stale_graphs(rsd_ctx* c) {
+    if (c->graphs.empty()) return RSD_OK;
+    auto live_u = [&](const float* u) { return u == c->u_draft || u == c->u_target || u == c->u_prop; };
+    auto live_f = [&](const int* f) { return f == c->forced_draft || f == c->forced_target || f == c->forced_prop; };
+    bool synced = false;
+    for (size_t i = 0; i < c->graphs.size();) {
+        const auto& g = c->graphs[i];
+        if (live_u(g.u) && live_f(g.forced)) { ++i; continue; }
+        if (!synced) { HIPCHK(c, hipStreamSynchronize(c->st)); synced = true; }
+        (void)hipGraphExecDestroy(g.exec);
+        (void)hipGraphDestroy(g.graph);
+        c->graphs.erase(c->graphs.begin() + i);
+    }
+    return RSD_OK;
+}
+
 double now_ms() {
     return std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now().time_since_epoch()).count();
 }
@@ -1017,7 +1094,12 @@ void rsd_destroy(rsd_ctx* c) {
                    c->part_acc, c->part_ml, c->part_k, c->xs_h, c->xs_l, c->smp_pmax, c->smp_pidx, c->smp_hist, c->smp_psum, c->smp_sel, c->hl, c->xl, c->logits, c->tmp_reward, c->chosen, c->steptok_dev,
                    c->row_seq_dev, c->row_pos_dev, c->last_row_dev, c->item_row0_dev, c->item_n_dev};
     for (void* p : dev) if (p) (void)hipFree(p);
-    for (hipEvent_t e : c->probe_ev) (void)hipEventDestroy(e);
+    for (auto& q : c->probe)
+        for (hipEvent_t e : q.ev) (void)hipEventDestroy(e);
+    for (auto& is : c->it) {
+        if (is.e0) (void)hipEventDestroy(is.e0);
+        if (is.e1) (void)hipEventDestroy(is.e1);
+    }
     for (auto& g : c->graphs) { (void)hipGraphExecDestroy(g.exec); (void)hipGraphDestroy(g.graph); }
     if (c->cap_st) (void)hipStreamDestroy(c->cap_st);
     void* pin[] = {c->sb, c->sd_rows_h, c->sd_aux_h, c->item_row0_h, c->item_n_h, c->row_seq_h, c->row_pos_h, c->last_row_h, c->steptok_h, c->poll_h};
@@ -1181,6 +1263,10 @@ int rsd_init(rsd_ctx** out, const rsd_model_shape shape[3], const rsd_weights w[
     HIPCHK(c, pin_alloc(&c->last_row_h, (size_t)B));
     HIPCHK(c, pin_alloc(&c->steptok_h, (size_t)B * p->step_cap));
     HIPCHK(c, pin_alloc(&c->poll_h, 4));
+    for (auto& is : c->it) {
+        HIPCHK(c, hipEventCreate(&is.e0));
+        HIPCHK(c, hipEventCreate(&is.e1));
+    }
     HIPCHK(c, hipMemsetAsync(c->h, 0, R * d * sizeof(float), c->st));
     HIPCHK(c, hipMemsetAsync(c->hl, 0, (size_t)B * d * sizeof(float), c->st));
     HIPCHK(c, hipMemsetAsync(c->att, 0, R * qd * sizeof(float), c->st));
@@ -1223,7 +1309,7 @@ int rsd_set_prompts(rsd_ctx* c, const int32_t* tokens_dev, const int32_t* prompt
 int rsd_set_uniforms(rsd_ctx* c, const float* u_draft_dev, const float* u_target_dev, const float* u_gate_dev) {
     if (!c) return RSD_EINVAL;
     c->u_draft = u_draft_dev; c->u_target = u_target_dev; c->u_gate = u_gate_dev;
-    return RSD_OK;
+    return drop_stale_graphs(c);
 }
 
 int rsd_set_criterion(rsd_ctx* c, float delta, int32_t omega_kind, float omega_a) {
@@ -1237,7 +1323,7 @@ int rsd_set_teacher(rsd_ctx* c, const int32_t* forced_draft_dev, const int32_t* 
                     const int32_t* forced_accept_dev) {
     if (!c) return RSD_EINVAL;
     c->forced_draft = forced_draft_dev; c->forced_target = forced_target_dev; c->forced_accept = forced_accept_dev;
-    return RSD_OK;
+    return drop_stale_graphs(c);
 }
 
 int rsd_step(rsd_ctx* c, rsd_step_out* out) {
@@ -1495,7 +1581,7 @@ int rsd_export_sampled(rsd_ctx* c, int32_t* sampled_draft, int32_t* sampled_targ
 int rsd_set_teacher_sd(rsd_ctx* c, const int32_t* forced_proposal_dev) {
     if (!c) return RSD_EINVAL;
     c->forced_prop = forced_proposal_dev;
-    return RSD_OK;
+    return drop_stale_graphs(c);
 }
 
 int rsd_export_proposed(rsd_ctx* c, int32_t* proposed, int32_t* kept_flags) {
@@ -1511,7 +1597,7 @@ int rsd_export_proposed(rsd_ctx* c, int32_t* proposed, int32_t* kept_flags) {
 int rsd_set_uniforms_sd(rsd_ctx* c, const float* u_proposal_dev, const float* u_accept_dev) {
     if (!c) return RSD_EINVAL;
     c->u_prop = u_proposal_dev; c->u_acc = u_accept_dev;
-    return RSD_OK;
+    return drop_stale_graphs(c);
 }
 
 int rsd_sd_verify(rsd_ctx* c, const float* p_logits_dev, const float* q_logits_dev, const int32_t* proposals_dev,
@@ -1563,34 +1649,105 @@ int rsd_decode_stats(rsd_ctx* c, int64_t* eager_iters, int64_t* graph_replays, i
     return RSD_OK;
 }
 
-int rsd_probe_start(rsd_ctx* c, int32_t model, int32_t op, int32_t max_samples, int32_t stride) {
+int rsd_probe_start(rsd_ctx* c, int32_t slot, int32_t model, int32_t phase, int32_t op, int32_t max_samples,
+                    int32_t stride) {
     if (!c) return RSD_EINVAL;
-    if (model < -1 || model > 2 || op < 0 || op > 4 || max_samples < 0 || max_samples > (1 << 20) || stride < 1)
+    if (slot < 0 || slot >= RSD_PROBE_SLOTS || model < 0 || model > 2 || op < 0 || op > 4 || max_samples < 0 ||
+        max_samples > (1 << 20) || stride < 1 || (phase != RSD_PROBE_DECODE && phase != RSD_PROBE_PREFILL))
         return fail(c, RSD_EINVAL, "bad probe argument");
     HIPCHK(c, hipStreamSynchronize(c->st));
-    while (c->probe_ev.size() < 2 * (size_t)max_samples) {
+    rsd_ctx::Probe& q = c->probe[slot];
+    while (q.ev.size() < 2 * (size_t)max_samples) {
         hipEvent_t e;
         HIPCHK(c, hipEventCreate(&e));
-        c->probe_ev.push_back(e);
+        q.ev.push_back(e);
     }
-    c->probe_model = model; c->probe_op = op; c->probe_stride = stride;
-    c->probe_seen = 0; c->probe_used = 0; c->probe_bytes = 0;
+    q.model = model; q.phase = phase; q.op = op; q.stride = stride;
+    q.seen = 0; q.iters = 0; q.used = 0; q.bytes = 0; q.flops = 0; q.iter_on = false;
     return RSD_OK;
 }
 
-int rsd_probe_read(rsd_ctx* c, int64_t* n_samples, double* total_ms, int64_t* bytes_per_launch) {
+int rsd_probe_read(rsd_ctx* c, int32_t slot, int64_t* n_samples, double* total_ms, int64_t* total_bytes,
+                   int64_t* total_flops) {
     if (!c) return RSD_EINVAL;
+    if (slot < 0 || slot >= RSD_PROBE_SLOTS) return fail(c, RSD_EINVAL, "bad probe slot");
     HIPCHK(c, hipStreamSynchronize(c->st));
+    rsd_ctx::Probe& q = c->probe[slot];
     double tot = 0;
-    for (size_t i = 0; i + 1 < c->probe_used; i += 2) {
+    for (size_t i = 0; i + 1 < q.used; i += 2) {
         float ms = 0.f;
-        HIPCHK(c, hipEventElapsedTime(&ms, c->probe_ev[i], c->probe_ev[i + 1]));
+        HIPCHK(c, hipEventElapsedTime(&ms, q.ev[i], q.ev[i + 1]));
         tot += ms;
     }
-    if (n_samples) *n_samples = (int64_t)(c->probe_used / 2);
+    if (n_samples) *n_samples = (int64_t)(q.used / 2);
     if (total_ms) *total_ms = tot;
-    if (bytes_per_launch) *bytes_per_launch = c->probe_bytes;
-    c->probe_model = -1;
+    if (total_bytes) *total_bytes = q.bytes;
+    if (total_flops) *total_flops = q.flops;
+    q.model = -1;
+    return RSD_OK;
+}
+
+int rsd_iter_stats(rsd_ctx* c, int32_t model, int64_t* iterations, double* gpu_ms, int64_t* seq_iterations,
+                   int64_t* kv_tokens_read, int32_t reset) {
+    if (!c) return RSD_EINVAL;
+    if (model != RSD_DRAFT && model != RSD_TARGET) return fail(c, RSD_EINVAL, "decode loops exist for the draft and the target only");
+    rsd_ctx::IterStats& is = c->it[model];
+    if (iterations) *iterations = is.iters;
+    if (gpu_ms) *gpu_ms = is.ms;
+    if (seq_iterations) *seq_iterations = is.seq_iters;
+    if (kv_tokens_read) *kv_tokens_read = is.kv_read;
+    if (reset) { is.iters = is.seq_iters = is.kv_read = 0; is.ms = 0; }
+    return RSD_OK;
+}
+
+int rsd_probe_attention(rsd_ctx* c, int32_t model, const int32_t* ctx_len_host, int32_t reps, double* total_ms) {
+    if (!c || !ctx_len_host || !total_ms) return fail(c, RSD_EINVAL, "null argument");
+    if (model < 0 || model > 2 || reps < 1 || reps > (1 << 20)) return fail(c, RSD_EINVAL, "bad model or reps");
+    if (model == RSD_PRM && c->p.merge_prm != RSD_MERGE_NONE) return fail(c, RSD_EINVAL, "the merged reward model has no cache");
+    const int B = c->B;
+    Model& m = c->m[model];
+    for (int b = 0; b < B; ++b)
+        if (ctx_len_host[b] < 1 || ctx_len_host[b] > c->p.max_ctx) return fail(c, RSD_EINVAL, "ctx_len[%d] outside [1, max_ctx]", b);
+    HIPCHK(c, hipStreamSynchronize(c->st));
+    reset_sequences(c);
+    c->have_prompts = false;
+    for (int b = 0; b < B; ++b) {
+        if (!ensure_pages(m, b, ceil_div(ctx_len_host[b], RSD_PAGE))) {
+            reset_sequences(c);
+            return fail(c, RSD_ENOMEM, "KV pool too small for these contexts");
+        }
+        c->ctx_len()[b] = ctx_len_host[b];
+        c->kv_len(model)[b] = ctx_len_host[b] - 1;       // the new token sits at the last position
+        c->active()[b] = 1;
+    }
+    int rc;
+    if ((rc = push_state(c))) return rc;
+    if ((rc = upload_tables(c, m))) return rc;
+    HIPCHK(c, hipMemsetAsync(m.pool, 0, (size_t)m.pool_pages * m.page_elts * m.esz * m.s.n_layers, c->st));
+    HIPCHK(c, hipMemsetAsync(c->qkv, 0, (size_t)B * m.n_qkv * sizeof(float), c->st));
+    hipEvent_t e0, e1;
+    HIPCHK(c, hipEventCreate(&e0));
+    HIPCHK(c, hipEventCreate(&e1));
+    const bool halves = B >= 2 && m.s.dtype == RSD_BF16;
+    // a single sequence leaves the merge of its context splits to the output projection, as run_layers does
+    const bool merge_here = !(B == 1 && m.splits > 1 && (size_t)m.q_dim * sizeof(float) <= 40 * 1024);
+    auto one = [&](int l) {
+        if (m.s.dtype == RSD_BF16) launch_attn_decode_mfma(c, m, l, B, model, merge_here, halves);
+        else if (m.hd == 128) launch_attn_decode<float, 128>(c, m, l, B, model);
+        else launch_attn_decode<float, 32>(c, m, l, B, model);
+    };
+    for (int l = 0; l < std::min(2, m.s.n_layers); ++l) one(l);      // untimed: first-use costs
+    HIPCHK(c, hipEventRecord(e0, c->st));
+    for (int r = 0; r < reps; ++r) one(r % m.s.n_layers);
+    HIPCHK(c, hipEventRecord(e1, c->st));
+    HIPCHK(c, hipEventSynchronize(e1));
+    float ms = 0.f;
+    HIPCHK(c, hipEventElapsedTime(&ms, e0, e1));
+    *total_ms = ms;
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    HIPCHK(c, hipGetLastError());
+    reset_sequences(c);
     return RSD_OK;
 }
 
