@@ -215,6 +215,178 @@ __global__ __launch_bounds__(512, 2) void gemm_rows_kernel(const bf16_t* __restr
     }
 }
 
+// The same kernel with the work dealt evenly: the (256-row block of W) x (K block of 64) units of the product,
+// numbered row block by row block, are cut into gridDim.x equal runs, one per thread block, whatever N and K
+// are.  A run crosses at most a few row blocks; each stretch inside one row block is computed like a K slice
+// above and written as a partial tile.  The partial tiles of row block rb come from the consecutive thread
+// blocks first(rb) .. last(rb); thread block g writes its tile of rb into slice z = g - first(rb), so the slices
+// of a row block are in ascending K order and the finish kernels add them in that fixed order.  D = 2 or 4 W
+// register sets (K blocks requested ahead of their use).
+struct SkGeom {
+    int nkb;            // K blocks of 64
+    int units;          // row blocks x K blocks
+    int G;              // thread blocks the units are dealt to
+    int zmax;           // most partial tiles any row block receives (slices of the partial buffer)
+};
+__host__ __device__ __forceinline__ long long sk_start(const SkGeom& g, int b) { return (long long)b * g.units / g.G; }
+// first / last thread block whose run holds units of row block rb
+__host__ __device__ __forceinline__ int sk_first(const SkGeom& g, int rb) {
+    const long long x = (long long)rb * g.nkb;                       // largest b with start(b) <= x
+    return (int)(((x + 1) * g.G + g.units - 1) / g.units) - 1;
+}
+__host__ __device__ __forceinline__ int sk_last(const SkGeom& g, int rb) {
+    const long long y = (long long)(rb + 1) * g.nkb;                 // largest b with start(b) < y
+    return (int)((y * g.G + g.units - 1) / g.units) - 1;
+}
+
+template <int MT, int D>
+__global__ __launch_bounds__(512, D == 2 ? 2 : 1) void gemm_rows_sk_kernel(const bf16_t* __restrict__ W, int N, int K,
+                                                                        const uint16_t* __restrict__ Xh,
+                                                                        const uint16_t* __restrict__ Xl,
+                                                                        float* __restrict__ part, SkGeom geo) {
+    constexpr int BK = 64, NWV = 8;
+    constexpr int ROWS = 32 * MT;
+    __shared__ __attribute__((aligned(16))) uint16_t Ah[2][ROWS * BK];
+    __shared__ __attribute__((aligned(16))) uint16_t Al[2][ROWS * BK];
+    __shared__ __attribute__((aligned(16))) uint16_t Ws[NWV][32 * BK];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int kg = lane >> 5, l32 = lane & 31;
+    const int lrow = lane >> 3, lchunk = lane & 7;
+    uint16_t* ws = Ws[wave];
+    auto sw = [](int r, int c) { return r * BK + ((c ^ ((r >> 1) & 7)) << 3); };
+    const int ws_st0 = sw(lrow, lchunk), ws_st1 = sw(lrow + 8, lchunk), ws_st2 = sw(lrow + 16, lchunk), ws_st3 = sw(lrow + 24, lchunk);
+    const int xrow = (MT == 2) ? (tid >> 3) : ((tid & 255) >> 3);
+    const uint16_t* xp0 = ((MT == 2 || tid < 256) ? Xh : Xl) + (size_t)xrow * K + lchunk * 8;
+    const uint16_t* xp1 = Xl + (size_t)xrow * K + lchunk * 8;      // MT = 2 only
+    const int x_st = sw(xrow, lchunk);
+
+    long long u = sk_start(geo, blockIdx.x);
+    const long long u_end = sk_start(geo, blockIdx.x + 1);
+    while (u < u_end) {
+        const int rb = (int)(u / geo.nkb);
+        const int kb0 = (int)(u - (long long)rb * geo.nkb);
+        const int kb1 = (int)min((long long)geo.nkb, kb0 + (u_end - u));
+        const int nk = kb1 - kb0, kb_last = kb1 - 1;
+        u += nk;
+        const int nw = rb * (32 * NWV) + wave * 32;      // first W row of this wave
+        const bf16_t* wr0 = W + (size_t)min(nw + lrow, N - 1) * K + lchunk * 8;
+        const bf16_t* wr1 = W + (size_t)min(nw + lrow + 8, N - 1) * K + lchunk * 8;
+        const bf16_t* wr2 = W + (size_t)min(nw + lrow + 16, N - 1) * K + lchunk * 8;
+        const bf16_t* wr3 = W + (size_t)min(nw + lrow + 24, N - 1) * K + lchunk * 8;
+
+        f32x16_t acc[MT];
+#pragma unroll
+        for (int t = 0; t < MT; ++t)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[t][v] = 0.0f;
+
+        struct WRegs { u32x4_t w0, w1, w2, w3; };
+        WRegs wa, wb, wc, wd;
+        u32x4_t x0, x1;
+#define SK_FETCH_W(kb, R)                                                                        \
+    {                                                                                            \
+        const size_t k0_ = (size_t)min((kb), kb_last) * BK;                                      \
+        R.w0 = *reinterpret_cast<const u32x4_t*>(wr0 + k0_);                                     \
+        R.w1 = *reinterpret_cast<const u32x4_t*>(wr1 + k0_);                                     \
+        R.w2 = *reinterpret_cast<const u32x4_t*>(wr2 + k0_);                                     \
+        R.w3 = *reinterpret_cast<const u32x4_t*>(wr3 + k0_);                                     \
+    }
+#define SK_FETCH_X(kb)                                                                           \
+    {                                                                                            \
+        const size_t k0_ = (size_t)min((kb), kb_last) * BK;                                      \
+        x0 = *reinterpret_cast<const u32x4_t*>(xp0 + k0_);                                       \
+        if (MT == 2) x1 = *reinterpret_cast<const u32x4_t*>(xp1 + k0_);                          \
+    }
+#define SK_STAGE_W(R)                                                                            \
+    {                                                                                            \
+        *reinterpret_cast<u32x4_t*>(ws + ws_st0) = R.w0;                                         \
+        *reinterpret_cast<u32x4_t*>(ws + ws_st1) = R.w1;                                         \
+        *reinterpret_cast<u32x4_t*>(ws + ws_st2) = R.w2;                                         \
+        *reinterpret_cast<u32x4_t*>(ws + ws_st3) = R.w3;                                         \
+    }
+#define SK_STAGE_X(buf)                                                                          \
+    {                                                                                            \
+        if (MT == 2) {                                                                           \
+            *reinterpret_cast<u32x4_t*>(&Ah[(buf)][x_st]) = x0;                                  \
+            *reinterpret_cast<u32x4_t*>(&Al[(buf)][x_st]) = x1;                                  \
+        } else {                                                                                 \
+            *reinterpret_cast<u32x4_t*>((tid < 256 ? &Ah[(buf)][0] : &Al[(buf)][0]) + x_st) = x0; \
+        }                                                                                        \
+    }
+#define SK_COMPUTE(buf)                                                                          \
+    {                                                                                            \
+        _Pragma("unroll") for (int j_ = 0; j_ < 4; ++j_) {                                       \
+            const bf16x8_t b_ = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t*>(ws + sw(l32, kg * 4 + j_))); \
+            _Pragma("unroll") for (int t_ = 0; t_ < MT; ++t_) {                                  \
+                const int off_ = sw(t_ * 32 + l32, kg * 4 + j_);                                 \
+                const bf16x8_t ah_ = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t*>(&Ah[(buf)][off_])); \
+                const bf16x8_t al_ = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t*>(&Al[(buf)][off_])); \
+                acc[t_] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al_, b_, acc[t_], 0, 0, 0);    \
+                acc[t_] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah_, b_, acc[t_], 0, 0, 0);    \
+            }                                                                                    \
+        }                                                                                        \
+    }
+        // step i: the activation tile of block i + 1 moves into the LDS buffer that block i - 1 has left and its
+        // registers take the request of block i + 2; W of block i + D is requested into the set F that block i
+        // came from; block i is multiplied; W of block i + 1 (set S) replaces the wave's W tile
+#define SK_STEP(i_step, F, S)                                                                    \
+    {                                                                                            \
+        SK_STAGE_X(((i_step) + 1) & 1)                                                           \
+        SK_FETCH_X(kb0 + (i_step) + 2)                                                           \
+        SK_FETCH_W(kb0 + (i_step) + D, F)                                                        \
+        SK_COMPUTE((i_step) & 1)                                                                 \
+        SK_STAGE_W(S)                                                                            \
+        __syncthreads();                                                                         \
+    }
+        SK_FETCH_W(kb0, wa)
+        SK_FETCH_X(kb0)
+        SK_FETCH_W(kb0 + 1, wb)
+        if (D == 4) {
+            SK_FETCH_W(kb0 + 2, wc)
+            SK_FETCH_W(kb0 + 3, wd)
+        }
+        SK_STAGE_W(wa)
+        SK_STAGE_X(0)
+        SK_FETCH_X(kb0 + 1)
+        __syncthreads();
+        int i = 0;
+        if (D == 2) {
+            for (; i + 1 < nk; i += 2) {
+                SK_STEP(i, wa, wb)
+                SK_STEP(i + 1, wb, wa)
+            }
+            if (i < nk) SK_STEP(i, wa, wb)
+        } else {
+            for (; i + 3 < nk; i += 4) {
+                SK_STEP(i, wa, wb)
+                SK_STEP(i + 1, wb, wc)
+                SK_STEP(i + 2, wc, wd)
+                SK_STEP(i + 3, wd, wa)
+            }
+            if (i < nk) { SK_STEP(i, wa, wb) ++i; }
+            if (i < nk) { SK_STEP(i, wb, wc) ++i; }
+            if (i < nk) { SK_STEP(i, wc, wd) }
+        }
+#undef SK_STEP
+#undef SK_COMPUTE
+#undef SK_STAGE_W
+#undef SK_STAGE_X
+#undef SK_FETCH_W
+#undef SK_FETCH_X
+        const int z = (int)blockIdx.x - sk_first(geo, rb);
+        const int n = nw + l32;
+        if (n < N) {
+#pragma unroll
+            for (int t = 0; t < MT; ++t)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int m = t * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+                    part[((size_t)z * ROWS + m) * N + n] = acc[t][v];
+                }
+        }
+    }
+}
+
 // The same product for small weight matrices (attention projections, the draft's MLP): with 256 rows of W
 // per block such a matrix gives few blocks, the K slices needed to fill the chip get short (two K blocks
 // for the 7B output projection) and their partial results weigh as much as the weights.  Here a block of
@@ -411,14 +583,21 @@ __device__ __forceinline__ float4 sum_slices(const float* __restrict__ p, size_t
 //   EPI_STORE   Y[m][n]  = sum
 //   EPI_RESID   Y[m][n] += sum
 //   EPI_SWIGLU  N = 2F columns [gate ; up]: act = silu(gate) * up, written as hi + lo bf16 rows [m][F]
+// geo.G > 0: the slices come from gemm_rows_sk_kernel, and a column of row block rb = n / 256 has
+// sk_last(rb) - sk_first(rb) + 1 of them (KS is ignored).
 template <int EPI>
 __global__ void rows_finish_kernel(const float* __restrict__ part, int KS, int ROWS, int M, int N,
-                                   float* __restrict__ Y, int ldy, uint16_t* __restrict__ Oh, uint16_t* __restrict__ Ol) {
+                                   float* __restrict__ Y, int ldy, uint16_t* __restrict__ Oh, uint16_t* __restrict__ Ol,
+                                   SkGeom geo) {
     const int NO = (EPI == EPI_SWIGLU) ? N / 2 : N;
     const size_t i = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
     if (i >= (size_t)M * NO) return;
     const size_t m = i / NO, n = i - m * NO;           // NO is a multiple of 4
-    auto sum = [&](size_t col) { return sum_slices(part + m * N + col, (size_t)ROWS * N, KS); };
+    auto sum = [&](size_t col) {
+        int ks = KS;
+        if (geo.G > 0) { const int rb = (int)(col >> 8); ks = sk_last(geo, rb) - sk_first(geo, rb) + 1; }
+        return sum_slices(part + m * N + col, (size_t)ROWS * N, ks);
+    };
     float4 a = sum(n);
     if (EPI == EPI_SWIGLU) {
         const float4 u = sum(NO + n);
@@ -445,7 +624,8 @@ template <typename WT>
 __global__ __launch_bounds__(1024) void rows_finish_norm_kernel(const float* __restrict__ part, int KS, int ROWS, int N,
                                                                 float* __restrict__ H, int ldh,
                                                                 const WT* __restrict__ gain, float eps,
-                                                                uint16_t* __restrict__ Xh, uint16_t* __restrict__ Xl) {
+                                                                uint16_t* __restrict__ Xh, uint16_t* __restrict__ Xl,
+                                                                SkGeom geo) {
     __shared__ float red[16];
     const int m = blockIdx.x, tid = threadIdx.x;
     float4 v[2];
@@ -455,7 +635,9 @@ __global__ __launch_bounds__(1024) void rows_finish_norm_kernel(const float* __r
         const int n = tid * 4 + i * 4096;
         v[i] = make_float4(0.f, 0.f, 0.f, 0.f);
         if (n < N) {
-            float4 a = sum_slices(part + (size_t)m * N + n, (size_t)ROWS * N, KS);
+            int ks = KS;
+            if (geo.G > 0) { const int rb = n >> 8; ks = sk_last(geo, rb) - sk_first(geo, rb) + 1; }
+            float4 a = sum_slices(part + (size_t)m * N + n, (size_t)ROWS * N, ks);
             float4* hp = reinterpret_cast<float4*>(H + (size_t)m * ldh + n);
             const float4 y = *hp;
             a.x += y.x; a.y += y.y; a.z += y.z; a.w += y.w;
@@ -527,6 +709,30 @@ static int gemm_rows64_slices(int N, int K, int rows, size_t part_floats) {
     int ks = std::max(4, std::min(8, (448 + nb / 2) / nb));
     while (ks > 1 && (ks * 2 > nkb || (size_t)ks * rows * N > part_floats || (ks - 1) * ((nkb + ks - 1) / ks) >= nkb)) --ks;
     return ks;
+}
+
+// Geometry of the evenly dealt kernel for an [N][K] matrix on G thread blocks (G is lowered to the number of
+// units when there are fewer).
+static SkGeom sk_geometry(int N, int K, int G) {
+    SkGeom g;
+    const int nb = (N + 255) / 256;
+    g.nkb = K / 64;
+    g.units = nb * g.nkb;
+    g.G = std::max(1, std::min(G, g.units));
+    g.zmax = 1;
+    for (int rb = 0; rb < nb; ++rb) g.zmax = std::max(g.zmax, sk_last(g, rb) - sk_first(g, rb) + 1);
+    return g;
+}
+// Which few-row products take the evenly dealt kernel (the others keep uniform K slices), on how many thread
+// blocks, with how many W register sets.
+constexpr int kSkBlocks = 256, kSkDepth = 2;
+static bool gemm_rows_small(int N, int K);
+static bool gemm_rows_even(int N, int K) { return !gemm_rows_small(N, K); }
+template <int D>
+static void gemm_rows_sk_launch(hipStream_t st, const bf16_t* W, int N, int K, const uint16_t* Xh, const uint16_t* Xl,
+                                int M, float* part, const SkGeom& g) {
+    if (M <= 32) hipLaunchKernelGGL((gemm_rows_sk_kernel<1, D>), dim3(g.G), dim3(512), 0, st, W, N, K, Xh, Xl, part, g);
+    else         hipLaunchKernelGGL((gemm_rows_sk_kernel<2, D>), dim3(g.G), dim3(512), 0, st, W, N, K, Xh, Xl, part, g);
 }
 
 static void gemm_rows_launch(hipStream_t st, const bf16_t* W, int N, int K, const uint16_t* Xh, const uint16_t* Xl,

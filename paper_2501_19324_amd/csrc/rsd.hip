@@ -464,10 +464,10 @@ void rows_split(rsd_ctx* c, const float* X, int ldx, int M, int K, const bf16_t*
     hipLaunchKernelGGL((split_rows_kernel<bf16_t>), dim3(M), dim3(256), 0, c->st, X, ldx, K, gain, eps, c->xs_h, c->xs_l);
 }
 template <int EPI>
-void rows_finish(rsd_ctx* c, int ks, int rows, int M, int N, float* Y, int ldy) {
+void rows_finish(rsd_ctx* c, int ks, int rows, int M, int N, float* Y, int ldy, const SkGeom& geo) {
     const int NO = EPI == EPI_SWIGLU ? N / 2 : N;
     const dim3 grid((unsigned)(((size_t)M * NO / 4 + 255) / 256)), block(256);
-    hipLaunchKernelGGL((rows_finish_kernel<EPI>), grid, block, 0, c->st, c->part_k, ks, rows, M, N, Y, ldy, c->xs_h, c->xs_l);
+    hipLaunchKernelGGL((rows_finish_kernel<EPI>), grid, block, 0, c->st, c->part_k, ks, rows, M, N, Y, ldy, c->xs_h, c->xs_l, geo);
 }
 // Y (+)= halves . W^T with epilogue `epi`; EPI_SWIGLU (N = 2F) writes the activated values back as halves.
 // next_gain != nullptr (EPI_RESID): RMSNorm(Y row) * next_gain is left in the halves for the projection that
@@ -481,7 +481,16 @@ void rows_gemm(rsd_ctx* c, const Model& m, int op, int epi, const bf16_t* W, int
     const long long pb = (long long)N * K * 2 + 4LL * M * (K + (epi == EPI_SWIGLU ? N / 2 : N) + (epi == EPI_RESID ? N : 0));
     const long long pf = 2LL * M * N * K;
     int ks;
-    if (few) {
+    SkGeom geo{};                                            // G = 0: uniform K slices
+    if (few && gemm_rows_even(N, K)) {
+        geo = sk_geometry(N, K, kSkBlocks);
+        if ((size_t)geo.zmax * rows * N > c->part_k_floats) geo = SkGeom{};
+    }
+    if (few && geo.G > 0) {
+        ks = geo.zmax;
+        ProbeScope ps(c, m, op, pb, pf);
+        gemm_rows_sk_launch<kSkDepth>(c->st, W, N, K, c->xs_h, c->xs_l, M, c->part_k, geo);
+    } else if (few) {
         ks = gemm_rows_slices(N, K, rows, c->part_k_floats);
         ProbeScope ps(c, m, op, pb, pf);
         gemm_rows_launch(c->st, W, N, K, c->xs_h, c->xs_l, M, c->part_k, ks);
@@ -510,12 +519,12 @@ void rows_gemm(rsd_ctx* c, const Model& m, int op, int epi, const bf16_t* W, int
     }
     if (next_gain && N <= 8192) {
         hipLaunchKernelGGL((rows_finish_norm_kernel<bf16_t>), dim3(M), dim3(1024), 0, c->st, c->part_k, ks, rows, N, Y, ldy,
-                           next_gain, eps, c->xs_h, c->xs_l);
+                           next_gain, eps, c->xs_h, c->xs_l, geo);
         return;
     }
-    if (epi == EPI_SWIGLU) rows_finish<EPI_SWIGLU>(c, ks, rows, M, N, Y, ldy);
-    else if (epi == EPI_RESID) rows_finish<EPI_RESID>(c, ks, rows, M, N, Y, ldy);
-    else rows_finish<EPI_STORE>(c, ks, rows, M, N, Y, ldy);
+    if (epi == EPI_SWIGLU) rows_finish<EPI_SWIGLU>(c, ks, rows, M, N, Y, ldy, geo);
+    else if (epi == EPI_RESID) rows_finish<EPI_RESID>(c, ks, rows, M, N, Y, ldy, geo);
+    else rows_finish<EPI_STORE>(c, ks, rows, M, N, Y, ldy, geo);
     if (next_gain) rows_split(c, Y, ldy, M, N, next_gain, eps);
 }
 void rows_split(rsd_ctx*, const float*, int, int, int, const float*, float) {}    // fp32 weights never take this path
