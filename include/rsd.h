@@ -318,6 +318,21 @@ int rsd_iter_stats(rsd_ctx *c, int32_t model, int64_t *iterations, double *gpu_m
  * cannot hold the contexts. */
 int rsd_probe_attention(rsd_ctx *c, int32_t model, const int32_t *ctx_len_host, int32_t reps, double *total_ms);
 
+/* rsd_sample for callers that cannot allocate device memory: code recording a HIP graph, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same choice rule and arguments as rsd_sample (dev logits [n][vocab]
+ * fp32, dev uniforms [n], dev out [n]), but no context: the sampler's workspace (block maxima, radix
+ * histograms, block masses; about 49 KiB per row) is a device array built into the library, which every GPU
+ * the library runs on holds until the process ends (RSD_SAMPLE_STATIC_MAX_ROWS rows, 3.1 MiB).  The call
+ * allocates and frees nothing and does not synchronise: the kernels are enqueued on hip_stream (a
+ * hipStream_t, NULL: the default stream) and out_dev is valid once that stream has reached them.
+ * n > RSD_SAMPLE_STATIC_MAX_ROWS, n < 1, vocab < 1, NULL logits/out, sampling without uniforms or a bad
+ * temperature / top_p return RSD_EINVAL; a HIP failure returns RSD_EHIP (there is no context to hold an
+ * error text).  All calls on one GPU share that GPU's array: calls that overlap on one GPU (two streams, two
+ * threads) race; successive calls on one stream do not. */
+#define RSD_SAMPLE_STATIC_MAX_ROWS 64
+int rsd_sample_static(const float *logits_dev, const float *u_dev, int32_t n, int32_t vocab, float temperature,
+                      float top_p, int32_t *out_dev, void *hip_stream);
+
 const char *rsd_last_error(const rsd_ctx *c);
 void rsd_destroy(rsd_ctx *c);
 

@@ -17,7 +17,7 @@ __all__ = ["RSD_OK", "RSD_EINVAL", "RSD_ENOMEM", "RSD_ESTATE", "RSD_EHIP", "RSD_
            "RsdError", "Context", "load_library", "rsd_init", "rsd_set_prompts", "rsd_set_uniforms",
            "rsd_set_criterion", "rsd_step", "rsd_generate", "rsd_export_state", "rsd_export_pages",
            "rsd_set_teacher", "rsd_export_sampled", "rsd_forward", "rsd_sample", "rsd_stage_ms", "rsd_decode_stats", "rsd_destroy",
-           "rsd_probe_start", "rsd_probe_read", "rsd_iter_stats", "rsd_probe_attention",
+           "rsd_probe_start", "rsd_probe_read", "rsd_iter_stats", "rsd_probe_attention", "rsd_sample_static",
            "EXPORTED_SYMBOLS"]
 
 RSD_OK, RSD_EINVAL, RSD_ENOMEM, RSD_ESTATE, RSD_EHIP = 0, -1, -2, -3, -4
@@ -26,7 +26,7 @@ RSD_MERGE_NONE, RSD_MERGE_DRAFT, RSD_MERGE_TARGET = 0, 1, 2
 EXPORTED_SYMBOLS = ["rsd_init", "rsd_set_prompts", "rsd_set_uniforms", "rsd_set_criterion", "rsd_step",
                     "rsd_generate", "rsd_export_state", "rsd_export_pages", "rsd_set_teacher",
                     "rsd_export_sampled", "rsd_set_teacher_sd", "rsd_export_proposed", "rsd_set_uniforms_sd", "rsd_sd_verify", "rsd_forward", "rsd_sample", "rsd_stage_ms", "rsd_decode_stats", "rsd_probe_start", "rsd_probe_read",
-                    "rsd_iter_stats", "rsd_probe_attention", "rsd_last_error", "rsd_destroy"]
+                    "rsd_iter_stats", "rsd_probe_attention", "rsd_sample_static", "rsd_last_error", "rsd_destroy"]
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "librsd.so")
 
 
@@ -291,6 +291,22 @@ def rsd_sample(ctx: Context, logits, u, temperature: float, top_p: float):
     torch.cuda.current_stream().synchronize()
     ctx.check(load_library().rsd_sample(ctx.handle, _dev_ptr(logits), _dev_ptr(u), C.c_int32(n), C.c_int32(V),
                                         C.c_float(temperature), C.c_float(top_p), _dev_ptr(out)))
+    return out
+
+
+def rsd_sample_static(logits, u, temperature: float, top_p: float, out=None, stream=None):
+    """The sampler through the entry point that allocates nothing: ``out`` (device int32 [n]) is the caller's;
+    nothing is synchronised (the result is valid once ``stream`` has reached the kernels)."""
+    import torch
+
+    n, V = logits.shape
+    if out is None:
+        out = torch.empty(n, dtype=torch.int32, device=logits.device)
+    st = stream if stream is not None else torch.cuda.current_stream()
+    rc = load_library().rsd_sample_static(_dev_ptr(logits), _dev_ptr(u), C.c_int32(n), C.c_int32(V), C.c_float(temperature),
+                                          C.c_float(top_p), _dev_ptr(out), C.c_void_p(st.cuda_stream))
+    if rc != RSD_OK:
+        raise RsdError(rc, "rsd_sample_static failed (bad argument, more rows than the static workspace holds, or a HIP error)")
     return out
 
 

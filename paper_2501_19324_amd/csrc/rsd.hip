@@ -1773,6 +1773,8 @@ int rsd_sample(rsd_ctx* c, const float* logits_dev, const float* u_dev, int32_t 
 
 }  // extern "C"
 
+#include "sample_static.cuh"
+
 // --------------------------------------------------------------------------- rsd_forward
 namespace {
 
