@@ -13,6 +13,7 @@
 // Requirements checked by the caller: K % 64 == 0; N, M arbitrary.
 #pragma once
 #include <algorithm>
+#include <atomic>
 #include "common.cuh"
 #include "gemv.cuh"
 
@@ -723,11 +724,13 @@ static SkGeom sk_geometry(int N, int K, int G) {
     for (int rb = 0; rb < nb; ++rb) g.zmax = std::max(g.zmax, sk_last(g, rb) - sk_first(g, rb) + 1);
     return g;
 }
-// Which few-row products take the evenly dealt kernel (the others keep uniform K slices), on how many thread
-// blocks, with how many W register sets.
+// Which few-row products take the evenly dealt kernel: those with 200 or more 256-row blocks, which uniform K
+// slices cannot spread evenly over 256 compute units (measured at 16 rows: [59136][8192] 190 -> 183 us,
+// [151936][8192] 526 -> 457 us, [151936][1536] 112 -> 106 us; with fewer row blocks uniform slices at two
+// co-resident blocks per unit are as fast or faster: [37888][3584] 52 against 58 us).  One thread block per
+// compute unit and two W register sets: 512 thread blocks or four sets were slower or equal.
 constexpr int kSkBlocks = 256, kSkDepth = 2;
-static bool gemm_rows_small(int N, int K);
-static bool gemm_rows_even(int N, int K) { return !gemm_rows_small(N, K); }
+static bool gemm_rows_even(int N, int K) { (void)K; return (N + 255) / 256 >= 200; }
 template <int D>
 static void gemm_rows_sk_launch(hipStream_t st, const bf16_t* W, int N, int K, const uint16_t* Xh, const uint16_t* Xl,
                                 int M, float* part, const SkGeom& g) {
