@@ -23,6 +23,10 @@ What is written out here, and where the paper defines it:
   probability min(1, p/q), the first refusal is replaced by a draw from the
   normalised positive part of p - q, and a fully kept run earns one more
   target token).  The paper runs SD greedily with gamma = 7 (Section 3).
+* ``generate_sequence_bon`` - process Best-of-N, one of the paper's comparison
+  procedures (Section 3, "Baselines": sample N candidate steps and select the
+  one with the highest reward; run with a base model and a reward model only,
+  Table 3).  Every candidate continues the same committed context.
 * ``reward`` - the reward model's head (Appendix, "Model Merge"): a projection
   of the final hidden state to one scalar, mapped to [0, 1] (Section 3,
   "Models") by a logistic function.
@@ -547,6 +551,57 @@ def generate_sequence(draft: OracleModel, target: OracleModel, prm: OracleModel,
                             finished=reason))
     return dict(tokens=tokens, prompt_len=len(prompt), records=records, finished=reason,
                 kv_len=[rd.kv_len, rt.kv_len, rp.kv_len])
+
+
+def generate_sequence_bon(draft: OracleModel, prm: OracleModel, prompt: Sequence[int], u_cand: np.ndarray,
+                          P: Params, n_cand: int, max_steps: Optional[int] = None) -> dict:
+    """Process Best-of-N for one sequence (Section 3, "Baselines"): at every
+    reasoning step the base model samples ``n_cand`` candidate steps from the
+    same committed context, the reward model scores each at its last token, and
+    the candidate with the highest reward is committed (the lowest candidate
+    index among equal rewards); generation stops as in the RSD loop (EOS in the
+    committed step, context limit, step limit).
+
+    ``u_cand[n][i]`` is the uniform of the token candidate ``n`` places at
+    absolute position ``i``.  No cache is shared between candidates here: each
+    one is evaluated on the whole prefix (committed tokens + its own step), with
+    keys and values stored as ``P.kv_dtype`` says."""
+    tokens = [int(t) for t in prompt]
+    records = []
+    reason = RUNNING
+    n_steps = P.max_steps if max_steps is None else max_steps
+    if len(tokens) >= P.max_ctx:
+        reason = FIN_MAX_CTX
+    for i in range(n_steps):
+        if reason != RUNNING:
+            break
+        ctx_pre = len(tokens)
+        cands, rewards, margins = [], [], []
+        for n in range(n_cand):
+            rd = _Runner(draft, P.max_ctx, False, P.kv_dtype)
+            trial = list(tokens)
+            mg: list = []
+            step = gen_step(rd, trial, u_cand[n], P, mg)
+            y = forward_full(prm, trial, P.kv_dtype)[-1]
+            cands.append(step)
+            rewards.append(reward(prm, y))
+            margins.append(mg)
+        # the decision is taken on the rewards as fp32 numbers (the precision they are reported in)
+        r32 = np.asarray(rewards, dtype=np.float32)
+        best = int(np.argmax(r32))                 # first index of the maximum
+        tokens.extend(cands[best])
+        if P.eos_id >= 0 and P.eos_id in cands[best]:
+            reason = FIN_EOS
+        elif len(tokens) >= P.max_ctx:
+            reason = FIN_MAX_CTX
+        elif i + 1 >= P.max_steps:
+            reason = FIN_MAX_STEPS
+        # caches after the step: the base model has been fed all but the newest token, the reward model all
+        kv = [len(tokens) - 1, 0, len(tokens)]
+        records.append(dict(step=i, ctx_pre=ctx_pre, candidates=cands, rewards=rewards, chosen=best,
+                            final_tokens=list(cands[best]), ctx_len=len(tokens), kv_len=kv,
+                            n_pages=[-(-v // P.page_tokens) for v in kv], margins=margins, finished=reason))
+    return dict(tokens=tokens, prompt_len=len(prompt), records=records, finished=reason)
 
 
 def decode_plain(model: OracleModel, prompt: Sequence[int], u_row: np.ndarray, P: Params,

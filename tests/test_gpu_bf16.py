@@ -269,6 +269,71 @@ def test_long_context_split_attention(gpu, mid_models):
     s.close()
 
 
+def test_long_context_batched_steps(gpu):
+    """Contexts of 8200 tokens in a batch of 32 (the launch configuration of the long-context workload:
+    enough (sequence, KV head) pairs that the decode attention gives every sequence one block per head and
+    cuts the context in two only because a wave's page list is bounded).  Four ragged long sequences
+    (8200, 3100, 2050 and 1030 prompt tokens, the longest crossing 8192 while it decodes) are followed by
+    the checker for two teacher-forced steps; the others are short.  Exercises the chunked prefill over
+    8192-row passes with long cached prefixes (draft, reward model, target catch-up) and the decode
+    attention of draft (6 query heads per KV head) and target (7 per KV head) beyond 8192 tokens."""
+    from dataclasses import replace
+    from oracle import rsd_oracle as O
+    from rsd_inputs import ModelShape, model_weights_np
+    R, torch = gpu["R"], gpu["torch"]
+    batch = 32
+    w = mid_workload(batch, prompt_len_min=16, prompt_len_max=8200, step_cap=10, max_steps=2, deltas=(0.6,))
+    # the attention shapes of the 1.5B draft / reward model (12 query heads on 2 KV heads) and the 7B target's
+    # grouping (7 query heads per KV head), with narrow MLPs: the checker's cost is then the attention itself
+    w = replace(w, draft=replace(w.draft, d_ffn=2048), prm=replace(w.prm, d_ffn=2048),
+                target=ModelShape(2, 1792, 14, 2, 2048, w.draft.vocab))
+    models = [O.OracleModel(sh, model_weights_np(w.seed, i, sh, threads=8)) for i, sh in enumerate(w.shapes)]
+    s = gpu["Session"](w)
+    check = {0: 8200, 9: 3100, 20: 2050, 31: 1030}
+    rng = np.random.default_rng(11)
+    for b in range(batch):
+        n = check.get(b, int(rng.integers(16, 64)))
+        s.prompt_len[b] = n
+        s.tokens_host[b, :n] = rng.integers(0, w.draft.vocab - 1, size=n)
+        s.tokens_host[b, n:] = -1
+    s.tokens = torch.from_numpy(s.tokens_host).cuda()
+    P = oracle_params(O, w)
+    refs = {b: O.generate_sequence(*models, s.tokens_host[b, :s.prompt_len[b]], s.u_host["U_DRAFT"][b],
+                                   s.u_host["U_TARGET"][b], s.u_host["U_GATE"][b], P) for b in check}
+    forced, _ = teacher_arrays(w, [refs.get(b, dict(records=[])) for b in range(batch)], torch)
+    R.rsd_set_teacher(s.ctx, *forced)
+    s.reset()
+    worst = 0.0
+    for i in range(w.max_steps):
+        g = R.rsd_step(s.ctx)
+        st = R.rsd_export_state(s.ctx, want_tokens=False)
+        for b in check:
+            r = refs[b]["records"][i]
+            worst = max(worst, abs(float(g["reward"][b]) - r["reward"]))
+            assert abs(float(g["reward"][b]) - r["reward"]) < TOL, (b, i, g["reward"][b], r["reward"])
+            if abs(r["reward"] - float(np.float32(w.delta))) > 1e-3:
+                assert bool(g["own_accept"][b]) == r["accepted"]
+            assert list(g["final_tokens"][b, :g["final_len"][b]]) == r["final_tokens"]
+            assert list(st["kv_len"][:, b]) == r["kv_len"] and list(st["n_pages"][:, b]) == r["n_pages"]
+    own_d, own_t = R.rsd_export_sampled(s.ctx)
+    n_tok = excused = 0
+    for b in check:
+        for r in refs[b]["records"]:
+            for toks, margins, own in ((r["draft_tokens"], r["draft_margins"], own_d),
+                                       (r["final_tokens"] if not r["accepted"] else [], r["final_margins"], own_t)):
+                for j, t in enumerate(toks):
+                    n_tok += 1
+                    if own[b, r["step"], j] != t:
+                        assert margins[j] < 2 * TOL, (b, r["step"], j, margins[j])
+                        excused += 1
+    accs = [r["accepted"] for ref in refs.values() for r in ref["records"]]
+    print(f"long contexts: {n_tok} tokens compared, {excused} excused near-ties, max reward error {worst:.2e}, "
+          f"accepted {sum(accs)} of {len(accs)} steps; context reached {max(r['ctx_len'] for r in refs[0]['records'])}")
+    assert refs[0]["records"][-1]["ctx_len"] > 8192
+    R.rsd_set_teacher(s.ctx, None, None, None)
+    s.close()
+
+
 def test_wide_shapes_batch16(gpu):
     """Shapes of the third configuration at reduced depth: 72B-width target
     (d 8192, 64/8 heads, FFN 29568), 7B-width reward model, batch 16 (the

@@ -1,11 +1,12 @@
-"""GPU checks at the full size of configuration 1 (bf16, batch 1, 28-layer
-1.5B draft / 7B target / 1.5B reward model, vocabulary 151936), in the launch
-configuration bench.py times.
+"""GPU checks at full depth and full width (bf16, 28-layer 1.5B draft / 7B target /
+1.5B reward model, vocabulary 151936), in the launch configurations bench.py times:
+configuration 1 (batch 1), and seeded subsets of configurations 2 (batch 64, ragged
+prompts) and 4 (batch 256, 1024-token prompts).
 
-The fp64 CPU checker can still evaluate the full-depth 1.5B shapes on the
-256-token prompt (about 14 GB as fp64), so the draft's next-token logits and
-the reward model's score are compared with it directly; the 7B target does not
-fit and is covered by properties that hold at any size."""
+The fp64 CPU checker can evaluate all three full-depth models on a prompt (the 7B
+target is about 60 GB as fp64), so next-token logits and rewards are compared with
+it directly; whole free runs at this size would take the checker hours and are
+covered by properties that hold at any size."""
 import gc
 
 import numpy as np
@@ -29,30 +30,115 @@ def full():
     s.close()
 
 
-@pytest.mark.parametrize("which", [0, 2])
-def test_full_depth_prompt_against_checker(full, which):
-    """Last-position logits of the draft (which = 0) and the reward of the
-    reward model (which = 2) on the 256-token prompt, through the chunked
-    prefill kernels and through 256 single-token iterations."""
+@pytest.fixture(scope="module")
+def checker_models():
+    """Full-depth checker models, built on first use and kept for the module (the 7B target is dropped
+    again by the test that uses it)."""
     from oracle import rsd_oracle as O
-    from rsd_inputs import model_weights_np
+    from rsd_inputs import model_weights_np, workload
+    w = workload("cfg1")
+    cache = {}
+
+    def get(which):
+        if which not in cache:
+            cache[which] = O.OracleModel(w.shapes[which], model_weights_np(w.seed, which, w.shapes[which], threads=16))
+        return cache[which]
+    get.drop = lambda which: (cache.pop(which, None), gc.collect())
+    return get
+
+
+# Against the checker that keeps cache entries exact the error is dominated by the bf16 storage of keys and
+# values itself (the two checkers differ by as much): 2.3e-2 on the 1.5B logits, 1.0e-1 on the 7B logits,
+# 9e-4 on rewards when measured.  Stated bounds for the record, not the parity tolerance:
+EXACT_KV_BOUND = {0: 1e-1, 1: 3e-1, 2: 5e-3}
+
+
+@pytest.mark.parametrize("which", [0, 2, 1])
+def test_full_depth_prompt_against_checker(full, checker_models, which):
+    """Last-position logits of the draft (which = 0) and of the 7B target (1) and the reward of the
+    reward model (2) on the 256-token prompt, through the chunked prefill kernels and through 256
+    single-token iterations.  Compared with the checker that stores cache entries as bf16 (the
+    tolerance of the parity statement) and, for the record, with the checker that keeps them exact."""
+    from oracle import rsd_oracle as O
     R, s, w = full["R"], full["s"], full["w"]
-    shape = w.shapes[which]
     n = int(s.prompt_len[0])
     toks = s.tokens_host[:, :n].copy()
     lens = np.array([n], np.int32)
-    m = O.OracleModel(shape, model_weights_np(w.seed, which, shape, threads=16))
-    y = O.forward_full(m, [int(t) for t in toks[0]], "bf16")
-    ref = O.lm_logits(m, y[-1]) if which == 0 else np.array(O.reward(m, y[-1]))
-    del m, y
-    gc.collect()
+    m = checker_models(which)
+    seq = [int(t) for t in toks[0]]
+    head = (lambda y: O.lm_logits(m, y)) if which != 2 else (lambda y: np.array(O.reward(m, y)))
+    ref = head(O.forward_full(m, seq, "bf16")[-1])
+    ref_exact = head(O.forward_full(m, seq, "exact")[-1])
+    print(f"model {which}: the two checkers differ by {float(np.max(np.abs(ref - ref_exact))):.2e} (bf16 against exact cache entries)")
+    if which == 1:
+        checker_models.drop(1)
     for chunk in (n, 1):
         out = R.rsd_forward(s.ctx, which, toks, lens, chunk)
         got = out[0, n - 1].cpu().numpy()
         err = float(np.max(np.abs(got - ref)))
-        print(f"model {which} chunk {chunk}: max abs error {err:.2e}")
-        assert err < (TOL if which == 0 else 1e-3), (which, chunk, err)
+        err_exact = float(np.max(np.abs(got - ref_exact)))
+        print(f"model {which} chunk {chunk}: max abs error {err:.2e} (bf16 cache entries in the checker), "
+              f"{err_exact:.2e} (exact cache entries in the checker)")
+        assert err < (TOL if which != 2 else 1e-3), (which, chunk, err)
+        assert err_exact < EXACT_KV_BOUND[which], (which, chunk, err_exact)
     s.reset()
+
+
+@pytest.mark.parametrize("name,check", [("cfg2", [5, 40]), ("cfg4", [17])])
+def test_full_depth_batched_subset(checker_models, name, check):
+    """Configurations 2 and 4 at their own batch (64 / 256), prompts and full-depth models, steps
+    truncated to 12 tokens: the sequences in `check` are followed by the checker for two reasoning
+    steps under the teacher (draft tokens forced, delta = 0 so that the target, whose full-depth
+    checker costs minutes per step, is never needed): draft tokens (the path's own choice may differ
+    only at a near-tie), rewards, cache offsets and page counts."""
+    import torch
+    from oracle import rsd_oracle as O
+    from rsd_inputs import workload
+    from paper_2501_19324_amd import binding as R
+    from paper_2501_19324_amd.harness import Session
+    w = workload(name, step_cap=12, max_steps=2, deltas=(0.0,))
+    s = Session(w)
+    P = O.Params(delta=0.0, sep_id=w.sep_id, step_cap=w.step_cap, max_steps=w.max_steps, max_ctx=w.max_ctx, kv_dtype="bf16")
+    md, mp = checker_models(0), checker_models(2)
+    # (the target's place is taken by the draft model: with delta = 0 every step is accepted and it is never run)
+    refs = {b: O.generate_sequence(md, md, mp, s.tokens_host[b, :s.prompt_len[b]], s.u_host["U_DRAFT"][b],
+                                   s.u_host["U_TARGET"][b], s.u_host["U_GATE"][b], P) for b in check}
+    fd = np.full((w.batch, w.max_steps, w.step_cap), -1, np.int32)
+    for b, ref in refs.items():
+        for r in ref["records"]:
+            fd[b, r["step"], :len(r["draft_tokens"])] = r["draft_tokens"]
+    fd_dev = torch.from_numpy(fd).cuda()
+    R.rsd_set_teacher(s.ctx, fd_dev, None, None)
+    s.reset()
+    worst = 0.0
+    for i in range(w.max_steps):
+        g = R.rsd_step(s.ctx)
+        st = R.rsd_export_state(s.ctx, want_tokens=False)
+        assert g["accepted"].all()
+        for b in check:
+            r = refs[b]["records"][i]
+            worst = max(worst, abs(float(g["reward"][b]) - r["reward"]))
+            assert abs(float(g["reward"][b]) - r["reward"]) < TOL, (b, i, g["reward"][b], r["reward"])
+            assert list(g["final_tokens"][b, :g["final_len"][b]]) == r["final_tokens"]
+            assert list(st["kv_len"][:, b]) == r["kv_len"] and list(st["n_pages"][:, b]) == r["n_pages"]
+            assert st["ctx_len"][b] == r["ctx_len"]
+    own_d, _ = R.rsd_export_sampled(s.ctx)
+    n_tok = excused = 0
+    for b in check:
+        for r in refs[b]["records"]:
+            for j, t in enumerate(r["draft_tokens"]):
+                n_tok += 1
+                if own_d[b, r["step"], j] != t:
+                    assert r["draft_margins"][j] < 2 * TOL, (b, r["step"], j, r["draft_margins"][j])
+                    excused += 1
+    print(f"{name}: {len(check)} sequences followed, {n_tok} draft tokens compared, {excused} excused near-ties, "
+          f"max reward error {worst:.2e}")
+    for mdl in range(3):
+        pg = R.rsd_export_pages(s.ctx, mdl)
+        used = pg["block_table"][pg["block_table"] >= 0]
+        assert len(set(used.tolist())) == used.size and used.size + pg["free_pages"] == pg["pool_pages"]
+    R.rsd_set_teacher(s.ctx, None, None, None)
+    s.close()
 
 
 def test_full_size_steps_properties(full):
