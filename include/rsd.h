@@ -106,6 +106,13 @@ typedef struct rsd_params {
                                Greedy (the paper's SD setting, Section 3 "Default Setting") or
                                sampled (then rsd_set_uniforms_sd supplies two more uniform streams).
                                At most 15. */
+    int32_t bon_n;          /* > 0: the context runs process Best-of-N instead of RSD (one of the paper's comparison
+                               procedures, Section 3 "Baselines": per reasoning step the base model samples bon_n
+                               candidate steps from the same context, the reward model scores each, the best is
+                               committed).  `batch` then counts candidate lanes = sequences * bon_n (lane s * bon_n + n
+                               is candidate n of sequence s); only the draft (the base model) and the reward model are
+                               used (shape[RSD_TARGET] / w[RSD_TARGET] are ignored); merge_prm and sd_k must be 0.
+                               See rsd_bon_step.  0: RSD. */
 } rsd_params;
 
 /* Per-step record, all HOST buffers supplied by the caller (any may be NULL).
@@ -189,6 +196,45 @@ int rsd_step(rsd_ctx *c, rsd_step_out *out);
  * (<= params.max_steps, 0 = params.max_steps) steps have run since the prompts
  * were set. */
 int rsd_generate(rsd_ctx *c, int32_t max_steps, rsd_gen_out *out);
+
+/* ---- process Best-of-N (contexts created with bon_n > 0) ----
+ * Candidate n of a sequence draws the token it places at absolute position i with u_draft[s * bon_n + n][i]
+ * (rsd_set_uniforms: u_draft is [batch][max_ctx] over lanes; u_target / u_gate are unused); rsd_set_prompts
+ * takes one prompt per SEQUENCE (tokens dev [sequences][max_ctx], prompt_len host [sequences]).  The
+ * candidates of a step share the cache pages of the committed context (reference-counted; the one page a
+ * candidate would write into while others still read it is copied first), each owns the pages of its own
+ * step, and after the choice the pages of the other candidates return to the pool.
+ *
+ * Per-step record, HOST buffers (any may be NULL); N = bon_n, s = sequence. */
+typedef struct rsd_bon_out {
+    int32_t *cand_len;      /* [sequences][N]            tokens of every candidate step (0: sequence had finished) */
+    int32_t *cand_tokens;   /* [sequences][N][step_cap]                                                           */
+    float   *cand_reward;   /* [sequences][N]                                                                     */
+    int32_t *chosen;        /* [sequences]               candidate committed                                      */
+    int32_t *own_choice;    /* [sequences]               arg max of the rewards, lowest index among equals
+                                                         (differs from chosen only under a teacher)               */
+    int32_t *finished;      /* [sequences]               RSD_RUNNING or a RSD_FIN_* reason, after this step       */
+    int32_t *ctx_len;       /* [sequences]               tokens of the sequence after the step                    */
+    int32_t *kv_len;        /* [2][sequences]            leading tokens the base / the reward model hold keys and
+                                                         values for (ctx_len - 1 and ctx_len after a step)        */
+    int32_t *n_pages;       /* [2][sequences]            cache pages the sequence owns in each of the two caches  */
+} rsd_bon_out;
+
+/* One reasoning step of process Best-of-N for all unfinished sequences.  RSD_ENOMEM (a page pool ran out)
+ * leaves every sequence as before the call.  Under rsd_set_teacher the forced_draft array is indexed by lane
+ * ([batch][max_steps][step_cap]) and forced_accept ([sequences][max_steps]), when >= 0, is the candidate to
+ * commit. */
+int rsd_bon_step(rsd_ctx *c, rsd_bon_out *out);
+
+/* rsd_bon_step until every sequence has finished or max_steps (<= params.max_steps, 0 = params.max_steps)
+ * steps have run since the prompts were set.  out->tokens is [sequences][max_ctx], ctx_len / finished
+ * [sequences]; n_draft counts every candidate token sampled, n_committed the committed ones. */
+int rsd_bon_generate(rsd_ctx *c, int32_t max_steps, rsd_gen_out *out);
+
+/* Page sharing since the context was created: page references handed to candidates by sharing a committed
+ * page instead of allocating one, pages copied because a candidate had to write into a shared one, and pages
+ * taken from the pools.  Host counters. */
+int rsd_bon_stats(rsd_ctx *c, int64_t *pages_shared, int64_t *pages_copied, int64_t *pages_allocated);
 
 /* Sequence state for bit-exact checks, HOST buffers (any may be NULL):
  * ctx_len [B]; kv_len [3][B] = leading tokens each model holds keys/values

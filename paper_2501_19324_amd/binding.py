@@ -18,7 +18,7 @@ __all__ = ["RSD_OK", "RSD_EINVAL", "RSD_ENOMEM", "RSD_ESTATE", "RSD_EHIP", "RSD_
            "rsd_set_criterion", "rsd_step", "rsd_generate", "rsd_export_state", "rsd_export_pages",
            "rsd_set_teacher", "rsd_export_sampled", "rsd_forward", "rsd_sample", "rsd_stage_ms", "rsd_decode_stats", "rsd_destroy",
            "rsd_probe_start", "rsd_probe_read", "rsd_iter_stats", "rsd_probe_attention", "rsd_sample_static",
-           "EXPORTED_SYMBOLS"]
+           "rsd_bon_step", "rsd_bon_generate", "rsd_bon_stats", "EXPORTED_SYMBOLS"]
 
 RSD_OK, RSD_EINVAL, RSD_ENOMEM, RSD_ESTATE, RSD_EHIP = 0, -1, -2, -3, -4
 RSD_DRAFT, RSD_TARGET, RSD_PRM = 0, 1, 2
@@ -26,7 +26,8 @@ RSD_MERGE_NONE, RSD_MERGE_DRAFT, RSD_MERGE_TARGET = 0, 1, 2
 EXPORTED_SYMBOLS = ["rsd_init", "rsd_set_prompts", "rsd_set_uniforms", "rsd_set_criterion", "rsd_step",
                     "rsd_generate", "rsd_export_state", "rsd_export_pages", "rsd_set_teacher",
                     "rsd_export_sampled", "rsd_set_teacher_sd", "rsd_export_proposed", "rsd_set_uniforms_sd", "rsd_sd_verify", "rsd_forward", "rsd_sample", "rsd_stage_ms", "rsd_decode_stats", "rsd_probe_start", "rsd_probe_read",
-                    "rsd_iter_stats", "rsd_probe_attention", "rsd_sample_static", "rsd_last_error", "rsd_destroy"]
+                    "rsd_iter_stats", "rsd_probe_attention", "rsd_sample_static", "rsd_bon_step", "rsd_bon_generate", "rsd_bon_stats",
+                    "rsd_last_error", "rsd_destroy"]
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "librsd.so")
 
 
@@ -51,13 +52,18 @@ class _Params(C.Structure):
                 ("eos_id", C.c_int32), ("step_cap", C.c_int32), ("max_steps", C.c_int32), ("max_ctx", C.c_int32),
                 ("temperature", C.c_float), ("top_p", C.c_float), ("sep_logit_bias", C.c_float),
                 ("page_tokens", C.c_int32), ("kv_pool_bytes", C.c_uint64 * 3), ("use_graphs", C.c_int32),
-                ("merge_prm", C.c_int32), ("sd_k", C.c_int32)]
+                ("merge_prm", C.c_int32), ("sd_k", C.c_int32), ("bon_n", C.c_int32)]
 
 
 class _StepOut(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in ("draft_len", "draft_tokens", "reward", "accepted", "own_accept",
                                           "final_len", "final_tokens", "finished", "sd_rounds", "sd_proposed",
                                           "sd_kept")]
+
+
+class _BonOut(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("cand_len", "cand_tokens", "cand_reward", "chosen", "own_choice", "finished",
+                                          "ctx_len", "kv_len", "n_pages")]
 
 
 class _GenOut(C.Structure):
@@ -131,23 +137,26 @@ def _shape_struct(s) -> _Shape:
 def rsd_init(shapes: Sequence, weights: Sequence, *, batch: int, delta: float, sep_id: int, step_cap: int,
              max_steps: int, max_ctx: int, eos_id: int = -1, temperature: float = 0.0, top_p: float = 1.0,
              sep_logit_bias: float = 0.0, omega_kind: int = 0, omega_a: float = 0.0, page_tokens: int = 16,
-             kv_pool_bytes=(0, 0, 0), use_graphs: int = 1, merge_prm: int = 0, sd_k: int = 0, stream=None) -> Context:
+             kv_pool_bytes=(0, 0, 0), use_graphs: int = 1, merge_prm: int = 0, sd_k: int = 0, bon_n: int = 0,
+             stream=None) -> Context:
     """``weights``: three device tensors holding each model's blob (with ``merge_prm`` the third holds
-    only the reward projection ``w_r`` and ``b_r``)."""
+    only the reward projection ``w_r`` and ``b_r``; with ``bon_n`` the second may be ``None``)."""
     import torch
 
     lib = load_library()
     ctx = Context()
     sh = (_Shape * 3)(*[_shape_struct(s) for s in shapes])
-    ws = (_Weights * 3)(*[_Weights(w.data_ptr(), w.numel() * w.element_size()) for w in weights])
+    ws = (_Weights * 3)(*[_Weights(None, 0) if w is None else _Weights(w.data_ptr(), w.numel() * w.element_size()) for w in weights])
     p = _Params(delta, omega_kind, omega_a, sep_id, eos_id, step_cap, max_steps, max_ctx, temperature, top_p,
-                sep_logit_bias, page_tokens, (C.c_uint64 * 3)(*[int(x) for x in kv_pool_bytes]), use_graphs, merge_prm, sd_k)
+                sep_logit_bias, page_tokens, (C.c_uint64 * 3)(*[int(x) for x in kv_pool_bytes]), use_graphs, merge_prm, sd_k, bon_n)
     st = stream if stream is not None else torch.cuda.current_stream()
     ctx.keep["weights"] = list(weights)
     ctx.keep["stream"] = st
     ctx.batch, ctx.max_ctx, ctx.step_cap, ctx.max_steps, ctx.vocab = batch, max_ctx, step_cap, max_steps, shapes[0].vocab
     ctx.shapes = list(shapes)
     ctx.sd_k = sd_k
+    ctx.bon_n = bon_n
+    ctx.n_seq = batch // bon_n if bon_n else batch
     rc = lib.rsd_init(C.byref(ctx.handle), sh, ws, C.byref(p), C.c_int32(batch), C.c_void_p(st.cuda_stream))
     ctx.check(rc)
     return ctx
@@ -162,13 +171,13 @@ def rsd_destroy(ctx: Context) -> None:
 
 def rsd_set_prompts(ctx: Context, tokens_dev, prompt_len: np.ndarray) -> None:
     pl = np.ascontiguousarray(prompt_len, dtype=np.int32)
-    assert tuple(tokens_dev.shape) == (ctx.batch, ctx.max_ctx) and tokens_dev.dtype.itemsize == 4
+    assert tuple(tokens_dev.shape) == (ctx.n_seq, ctx.max_ctx) and tokens_dev.dtype.itemsize == 4 and pl.shape == (ctx.n_seq,)
     ctx.check(load_library().rsd_set_prompts(ctx.handle, _dev_ptr(tokens_dev), _np_ptr(pl)))
 
 
 def rsd_set_uniforms(ctx: Context, u_draft=None, u_target=None, u_gate=None) -> None:
     for u, cols in ((u_draft, ctx.max_ctx), (u_target, ctx.max_ctx), (u_gate, ctx.max_steps)):
-        assert u is None or tuple(u.shape) == (ctx.batch, cols)
+        assert u is None or tuple(u.shape) == (ctx.batch, cols) and u.is_contiguous()
     ctx.keep["uniforms"] = (u_draft, u_target, u_gate)
     ctx.check(load_library().rsd_set_uniforms(ctx.handle, _dev_ptr(u_draft), _dev_ptr(u_target), _dev_ptr(u_gate)))
 
@@ -206,6 +215,34 @@ def rsd_generate(ctx: Context, max_steps: int = 0, want_tokens: bool = True) -> 
                n_sd_proposed=g.n_sd_proposed, n_sd_kept=g.n_sd_kept, rc=rc)
     ctx.check(rc)
     return out
+
+
+def rsd_bon_step(ctx: Context) -> dict:
+    """One step of process Best-of-N; arrays are per sequence, candidate arrays [sequences, N, ...]."""
+    S, N, cap = ctx.n_seq, ctx.bon_n, ctx.step_cap
+    o = dict(cand_len=np.zeros((S, N), np.int32), cand_tokens=np.full((S, N, cap), -1, np.int32),
+             cand_reward=np.zeros((S, N), np.float32), chosen=np.zeros(S, np.int32), own_choice=np.zeros(S, np.int32),
+             finished=np.zeros(S, np.int32), ctx_len=np.zeros(S, np.int32), kv_len=np.zeros((2, S), np.int32),
+             n_pages=np.zeros((2, S), np.int32))
+    bo = _BonOut(*[_np_ptr(o[n]) for n, _ in _BonOut._fields_])
+    ctx.check(load_library().rsd_bon_step(ctx.handle, C.byref(bo)))
+    return o
+
+
+def rsd_bon_generate(ctx: Context, max_steps: int = 0, want_tokens: bool = True) -> dict:
+    S = ctx.n_seq
+    toks = np.zeros((S, ctx.max_ctx), np.int32) if want_tokens else None
+    cl, fin = np.zeros(S, np.int32), np.zeros(S, np.int32)
+    g = _GenOut(_np_ptr(toks), _np_ptr(cl), _np_ptr(fin), 0, 0, 0, 0, 0, 0, 0, 0, 0)
+    rc = load_library().rsd_bon_generate(ctx.handle, C.c_int32(max_steps), C.byref(g))
+    ctx.check(rc)
+    return dict(tokens=toks, ctx_len=cl, finished=fin, steps_run=g.steps_run, n_committed=g.n_committed, n_draft=g.n_draft)
+
+
+def rsd_bon_stats(ctx: Context) -> dict:
+    a, b, d = C.c_int64(), C.c_int64(), C.c_int64()
+    ctx.check(load_library().rsd_bon_stats(ctx.handle, C.byref(a), C.byref(b), C.byref(d)))
+    return dict(pages_shared=a.value, pages_copied=b.value, pages_allocated=d.value)
 
 
 def rsd_export_state(ctx: Context, want_tokens: bool = True) -> dict:

@@ -43,6 +43,7 @@ struct Model {
     size_t page_elts = 0;        // elements of one page of one layer (K and V, all KV heads)
     int pool_pages = 0, max_pages = 0, splits = 1;
     std::vector<int> free_list;
+    std::vector<int> ref;        // block-table entries that name each physical page (above 1 only while candidates share a context)
     int* bt_host = nullptr;      // pinned [B][max_pages]
     int* bt_dev = nullptr;
     std::vector<int> n_pages;
@@ -86,6 +87,12 @@ struct rsd_ctx {
     int* sd_nkept() { return sb + 16 * B + 4; }
     int* sd_nround() { return sb + 17 * B + 4; }
     std::vector<int> prompt_len;
+    // process Best-of-N: sequences, the lane holding each sequence's committed state, page-sharing counters,
+    // and the staging of page copies ([src, dst] pairs per model; pinned + device)
+    int n_seq = 0;
+    std::vector<int> canon;
+    long long bon_shared = 0, bon_copied = 0, bon_alloc = 0;
+    int *bon_copy_h = nullptr, *bon_copy_dev = nullptr, *bon_src_h = nullptr, *bon_src_dev = nullptr;
     int steps_done = 0;
     bool have_prompts = false;
     // borrowed
@@ -237,6 +244,7 @@ int setup_kv(rsd_ctx* c, Model& m, int which) {
     HIPCHK(c, hipMalloc(reinterpret_cast<void**>(&m.pool), pages * page_bytes));
     m.free_list.resize(pages);
     for (size_t i = 0; i < pages; ++i) m.free_list[i] = (int)(pages - 1 - i);   // pop_back hands out 0,1,2,...
+    m.ref.assign(pages, 0);
     HIPCHK(c, pin_alloc(&m.bt_host, (size_t)B * m.max_pages));
     HIPCHK(c, dev_alloc(&m.bt_dev, (size_t)B * m.max_pages));
     std::fill(m.bt_host, m.bt_host + (size_t)B * m.max_pages, -1);
@@ -276,18 +284,26 @@ bool ensure_pages(Model& m, int b, int need) {
         if (m.free_list.empty()) return false;
         const int pg = m.free_list.back();
         m.free_list.pop_back();
+        m.ref[pg] = 1;
         m.bt_host[(size_t)b * m.max_pages + m.n_pages[b]++] = pg;
         m.bt_dirty = true;
     }
     return true;
 }
+// a page returns to the pool when the last table entry naming it goes
 void trim_pages(Model& m, int b, int keep) {
     while (m.n_pages[b] > keep) {
         int& e = m.bt_host[(size_t)b * m.max_pages + --m.n_pages[b]];
-        m.free_list.push_back(e);
+        if (--m.ref[e] == 0) m.free_list.push_back(e);
         e = -1;
         m.bt_dirty = true;
     }
+}
+// logical page i of row b becomes another name of physical page pg
+void share_page(Model& m, int b, int pg) {
+    ++m.ref[pg];
+    m.bt_host[(size_t)b * m.max_pages + m.n_pages[b]++] = pg;
+    m.bt_dirty = true;
 }
 int upload_tables(rsd_ctx* c, Model& m) {
     if (!m.bt_dirty) return RSD_OK;
@@ -1053,6 +1069,25 @@ int sd_stage(rsd_ctx* c) {
     return RSD_OK;
 }
 
+// ---- process Best-of-N: candidates of a step fork from the sequence's committed lane
+// tokens[lane][0 .. n[lane]) = tokens[src[lane]][...] for every lane with src[lane] >= 0 and != lane
+__global__ void bon_fork_tokens_kernel(int* __restrict__ tokens, int max_ctx, const int* __restrict__ src,
+                                       const int* __restrict__ n) {
+    const int lane = blockIdx.x, from = src[lane];
+    if (from < 0 || from == lane) return;
+    const int cnt = n[lane];
+    for (int i = threadIdx.x; i < cnt; i += blockDim.x)
+        tokens[(size_t)lane * max_ctx + i] = tokens[(size_t)from * max_ctx + i];
+}
+// physical page pairs[2 i] -> pairs[2 i + 1] in every layer (blockIdx.y) of one model's pool
+__global__ void bon_copy_pages_kernel(char* __restrict__ pool, size_t layer_bytes, size_t page_bytes,
+                                      const int* __restrict__ pairs) {
+    const int from = pairs[2 * blockIdx.x], to = pairs[2 * blockIdx.x + 1];
+    const uint4* s = reinterpret_cast<const uint4*>(pool + blockIdx.y * layer_bytes + (size_t)from * page_bytes);
+    uint4* d = reinterpret_cast<uint4*>(pool + blockIdx.y * layer_bytes + (size_t)to * page_bytes);
+    for (size_t i = threadIdx.x; i < page_bytes / 16; i += blockDim.x) d[i] = s[i];
+}
+
 // Recorded decode iterations bake in the uniform and teacher arrays they were recorded with: drop those
 // whose arrays the caller has replaced, so that the cache holds at most one graph per live combination.
 int drop_stale_graphs(rsd_ctx* c) {
@@ -1101,7 +1136,7 @@ void rsd_destroy(rsd_ctx* c) {
                    c->sd_ws[0].pmax, c->sd_ws[0].pidx, c->sd_ws[0].hist, c->sd_ws[0].psum, c->sd_ws[0].sel,
                    c->sd_ws[1].pmax, c->sd_ws[1].pidx, c->sd_ws[1].hist, c->sd_ws[1].psum, c->sd_ws[1].sel, c->h, c->xn, c->qkv, c->att, c->gu, c->act,
                    c->part_acc, c->part_ml, c->part_k, c->xs_h, c->xs_l, c->smp_pmax, c->smp_pidx, c->smp_hist, c->smp_psum, c->smp_sel, c->hl, c->xl, c->logits, c->tmp_reward, c->chosen, c->steptok_dev,
-                   c->row_seq_dev, c->row_pos_dev, c->last_row_dev, c->item_row0_dev, c->item_n_dev};
+                   c->row_seq_dev, c->row_pos_dev, c->last_row_dev, c->item_row0_dev, c->item_n_dev, c->bon_copy_dev, c->bon_src_dev};
     for (void* p : dev) if (p) (void)hipFree(p);
     for (auto& q : c->probe)
         for (hipEvent_t e : q.ev) (void)hipEventDestroy(e);
@@ -1111,7 +1146,8 @@ void rsd_destroy(rsd_ctx* c) {
     }
     for (auto& g : c->graphs) { (void)hipGraphExecDestroy(g.exec); (void)hipGraphDestroy(g.graph); }
     if (c->cap_st) (void)hipStreamDestroy(c->cap_st);
-    void* pin[] = {c->sb, c->sd_rows_h, c->sd_aux_h, c->item_row0_h, c->item_n_h, c->row_seq_h, c->row_pos_h, c->last_row_h, c->steptok_h, c->poll_h};
+    void* pin[] = {c->sb, c->sd_rows_h, c->sd_aux_h, c->item_row0_h, c->item_n_h, c->row_seq_h, c->row_pos_h, c->last_row_h, c->steptok_h, c->poll_h,
+                   c->bon_copy_h, c->bon_src_h};
     for (void* p : pin) if (p) (void)hipHostFree(p);
     delete c;
 }
@@ -1135,7 +1171,15 @@ int rsd_init(rsd_ctx** out, const rsd_model_shape shape[3], const rsd_weights w[
     if (p->sd_k < 0 || p->sd_k > 15) return fail(c, RSD_EINVAL, "sd_k %d outside [0, 15]", p->sd_k);
     if (p->sd_k > 0 && (long long)batch * (p->sd_k + 1) > kMaxRows)
         return fail(c, RSD_EINVAL, "batch * (sd_k + 1) exceeds the %d rows of one verification pass", kMaxRows);
+    const bool bon = p->bon_n > 0;
+    if (p->bon_n < 0 || p->bon_n > 1024) return fail(c, RSD_EINVAL, "bon_n %d outside [0, 1024]", p->bon_n);
+    if (bon && (batch % p->bon_n || p->merge_prm != RSD_MERGE_NONE || p->sd_k != 0))
+        return fail(c, RSD_EINVAL, "Best-of-N: batch must be a multiple of bon_n, and merge_prm and sd_k must be 0");
+    c->n_seq = bon ? batch / p->bon_n : batch;
+    c->canon.resize(c->n_seq);
+    for (int s2 = 0; s2 < c->n_seq; ++s2) c->canon[s2] = bon ? s2 * p->bon_n : s2;
     for (int i = 0; i < 3; ++i) {
+        if (bon && i == RSD_TARGET) continue;           // no target model in Best-of-N
         int rc = setup_model(c, c->m[i], shape[i], w[i], i, i == RSD_PRM && p->merge_prm != RSD_MERGE_NONE);
         if (rc) return rc;
     }
@@ -1146,12 +1190,12 @@ int rsd_init(rsd_ctx** out, const rsd_model_shape shape[3], const rsd_weights w[
             a.d_ffn != r.d_ffn || a.dtype != r.dtype)
             return fail(c, RSD_EINVAL, "merged reward model: its shape must repeat the policy model's");
     }
-    if (shape[0].vocab != shape[1].vocab || shape[0].vocab != shape[2].vocab)
-        return fail(c, RSD_EINVAL, "the three models must share one vocabulary");
+    if ((!bon && shape[0].vocab != shape[1].vocab) || shape[0].vocab != shape[2].vocab)
+        return fail(c, RSD_EINVAL, "the models must share one vocabulary");
     if (p->sep_id < 0 || p->sep_id >= shape[0].vocab || p->eos_id >= shape[0].vocab)
         return fail(c, RSD_EINVAL, "sep_id/eos_id outside the vocabulary");
     for (int i = 0; i < 3; ++i) {
-        if (i == RSD_PRM && p->merge_prm != RSD_MERGE_NONE) {      // no third cache
+        if ((i == RSD_PRM && p->merge_prm != RSD_MERGE_NONE) || (bon && i == RSD_TARGET)) {      // no cache for this one
             c->m[i].n_pages.assign(batch, 0);
             continue;
         }
@@ -1272,6 +1316,12 @@ int rsd_init(rsd_ctx** out, const rsd_model_shape shape[3], const rsd_weights w[
     HIPCHK(c, pin_alloc(&c->last_row_h, (size_t)B));
     HIPCHK(c, pin_alloc(&c->steptok_h, (size_t)B * p->step_cap));
     HIPCHK(c, pin_alloc(&c->poll_h, 4));
+    if (bon) {
+        HIPCHK(c, pin_alloc(&c->bon_copy_h, (size_t)4 * B));        // [model 0: B pairs][model 2: B pairs]
+        HIPCHK(c, dev_alloc(&c->bon_copy_dev, (size_t)4 * B));
+        HIPCHK(c, pin_alloc(&c->bon_src_h, (size_t)2 * B));         // source lane and token count of every lane
+        HIPCHK(c, dev_alloc(&c->bon_src_dev, (size_t)2 * B));
+    }
     for (auto& is : c->it) {
         HIPCHK(c, hipEventCreate(&is.e0));
         HIPCHK(c, hipEventCreate(&is.e1));
@@ -1289,13 +1339,15 @@ int rsd_init(rsd_ctx** out, const rsd_model_shape shape[3], const rsd_weights w[
 int rsd_set_prompts(rsd_ctx* c, const int32_t* tokens_dev, const int32_t* prompt_len_host) {
     if (!c || !tokens_dev || !prompt_len_host) return fail(c, RSD_EINVAL, "null argument");
     const int B = c->B;
-    for (int b = 0; b < B; ++b)
+    const int N = c->p.bon_n > 0 ? c->p.bon_n : 1;      // Best-of-N: one prompt per sequence, placed in its first lane
+    for (int b = 0; b < c->n_seq; ++b)
         if (prompt_len_host[b] < 1 || prompt_len_host[b] > c->p.max_ctx)
             return fail(c, RSD_EINVAL, "prompt_len[%d] = %d outside [1, max_ctx]", b, prompt_len_host[b]);
     HIPCHK(c, hipStreamSynchronize(c->st));
     reset_sequences(c);
-    const size_t n = (size_t)B * c->p.max_ctx;
-    HIPCHK(c, hipMemcpyAsync(c->ds.tokens, tokens_dev, n * sizeof(int), hipMemcpyDeviceToDevice, c->st));
+    const size_t row = (size_t)c->p.max_ctx * sizeof(int);
+    HIPCHK(c, hipMemcpy2DAsync(c->ds.tokens, row * N, tokens_dev, row, row, c->n_seq, hipMemcpyDeviceToDevice, c->st));
+    for (int s2 = 0; s2 < c->n_seq; ++s2) c->canon[s2] = s2 * N;
     const size_t ns = (size_t)B * c->p.max_steps * c->p.step_cap;
     for (int s = 0; s < 2; ++s)
         hipLaunchKernelGGL(fill_int_kernel, dim3((unsigned)((ns + 255) / 256)), dim3(256), 0, c->st, c->ds.sampled[s], -1, ns);
@@ -1304,9 +1356,10 @@ int rsd_set_prompts(rsd_ctx* c, const int32_t* tokens_dev, const int32_t* prompt
         hipLaunchKernelGGL(fill_int_kernel, dim3((unsigned)((np + 255) / 256)), dim3(256), 0, c->st, c->sd_acc_rec, -1, np);
     }
     for (int b = 0; b < B; ++b) {
-        c->prompt_len[b] = prompt_len_host[b];
-        c->ctx_len()[b] = prompt_len_host[b];
-        c->finished()[b] = prompt_len_host[b] >= c->p.max_ctx ? RSD_FIN_MAX_CTX : RSD_RUNNING;
+        const int pl = prompt_len_host[b / N];
+        c->prompt_len[b] = pl;
+        c->ctx_len()[b] = pl;
+        c->finished()[b] = pl >= c->p.max_ctx ? RSD_FIN_MAX_CTX : RSD_RUNNING;
     }
     int rc = push_state(c);
     if (rc) return rc;
@@ -1338,6 +1391,7 @@ int rsd_set_teacher(rsd_ctx* c, const int32_t* forced_draft_dev, const int32_t* 
 int rsd_step(rsd_ctx* c, rsd_step_out* out) {
     if (!c) return RSD_EINVAL;
     if (!c->have_prompts) return fail(c, RSD_ESTATE, "no prompts set");
+    if (c->p.bon_n > 0) return fail(c, RSD_ESTATE, "this context runs Best-of-N: use rsd_bon_step");
     const int B = c->B;
     const rsd_params& P = c->p;
     const int merge = P.merge_prm;
@@ -1549,6 +1603,289 @@ int rsd_generate(rsd_ctx* c, int32_t max_steps, rsd_gen_out* out) {
         HIPCHK(c, hipStreamSynchronize(c->st));
     }
     if (out) *out = g;
+    return RSD_OK;
+}
+
+int rsd_bon_step(rsd_ctx* c, rsd_bon_out* out) {
+    if (!c) return RSD_EINVAL;
+    if (c->p.bon_n <= 0) return fail(c, RSD_ESTATE, "this context was not created for Best-of-N (bon_n = 0)");
+    if (!c->have_prompts) return fail(c, RSD_ESTATE, "no prompts set");
+    const int B = c->B, N = c->p.bon_n, S = c->n_seq;
+    const rsd_params& P = c->p;
+    if (P.temperature > 0.f && !c->u_draft) return fail(c, RSD_ESTATE, "sampling needs uniforms");
+    int n_in = 0;
+    for (int s = 0; s < S; ++s) n_in += c->finished()[c->canon[s]] == RSD_RUNNING;
+    if (!n_in) return fail(c, RSD_ESTATE, "every sequence has finished");
+    Model &md = c->m[RSD_DRAFT], &mp = c->m[RSD_PRM];
+    const bool f32 = md.s.dtype == RSD_F32;
+    int rc;
+    double t0 = now_ms();
+
+    // ---- the committed lane of every running sequence catches up: the base model holds all tokens but the
+    // newest, the reward model all of them (only the prompt of the first step is ever missing)
+    auto undo = [&]() {      // pool exhausted: candidates give their pages back, committed lanes keep what they hold tokens for
+        for (int s = 0; s < S; ++s)
+            for (int n = 0; n < N; ++n) {
+                const int L = s * N + n;
+                const bool keep = L == c->canon[s];
+                trim_pages(md, L, keep ? ceil_div(c->kv_len(RSD_DRAFT)[L], RSD_PAGE) : 0);
+                trim_pages(mp, L, keep ? ceil_div(c->kv_len(RSD_PRM)[L], RSD_PAGE) : 0);
+            }
+    };
+    {
+        std::vector<Piece> pd, pp;
+        for (int s = 0; s < S; ++s) {
+            const int L = c->canon[s];
+            if (c->finished()[L] != RSD_RUNNING) continue;
+            const int ctx = c->ctx_len()[L];
+            if (!ensure_pages(md, L, ceil_div(ctx - 1, RSD_PAGE)) || !ensure_pages(mp, L, ceil_div(ctx, RSD_PAGE))) {
+                undo();
+                return fail(c, RSD_ENOMEM, "KV pool exhausted reading the context of sequence %d", s);
+            }
+            if (c->kv_len(RSD_DRAFT)[L] < ctx - 1) pd.push_back(Piece{L, c->kv_len(RSD_DRAFT)[L], ctx - 1});
+            if (c->kv_len(RSD_PRM)[L] < ctx) pp.push_back(Piece{L, c->kv_len(RSD_PRM)[L], ctx});
+        }
+        auto nothing = [](const std::vector<Piece>&, const std::vector<int>&, int) { return RSD_OK; };
+        if (!pd.empty() || !pp.empty()) {
+            if ((rc = upload_tables(c, md))) return rc;
+            if ((rc = upload_tables(c, mp))) return rc;
+        }
+        if (!pd.empty()) {
+            rc = f32 ? prefill<float>(c, RSD_DRAFT, pd, nothing) : prefill<bf16_t>(c, RSD_DRAFT, pd, nothing);
+            if (rc) return rc;
+            for (const Piece& pc : pd) c->kv_len(RSD_DRAFT)[pc.b] = pc.end;
+        }
+        if (!pp.empty()) {
+            rc = f32 ? prefill<float>(c, RSD_PRM, pp, nothing) : prefill<bf16_t>(c, RSD_PRM, pp, nothing);
+            if (rc) return rc;
+            for (const Piece& pc : pp) c->kv_len(RSD_PRM)[pc.b] = pc.end;
+        }
+    }
+
+    // ---- fork: every candidate lane names the committed pages that are full, gets a copy of the page the
+    // step's first entries go into (if the committed context ends inside one), and reserves pages of its own
+    // for the step
+    int n_copy[2] = {0, 0};
+    for (int s = 0; s < S; ++s) {
+        const int L0 = c->canon[s];
+        const bool run = c->finished()[L0] == RSD_RUNNING;
+        for (int n = 0; n < N; ++n) {
+            const int L = s * N + n;
+            c->bon_src_h[L] = -1;
+            c->bon_src_h[B + L] = 0;
+            c->in_step()[L] = run;
+            if (!run) { c->active()[L] = 0; continue; }
+            const int ctx = c->ctx_len()[L0];
+            const int need = ceil_div(std::min(ctx + P.step_cap, P.max_ctx), RSD_PAGE);
+            bool ok = true;
+            if (L != L0) {
+                Model* ms[2] = {&md, &mp};
+                const int held[2] = {ctx - 1, ctx};           // tokens the base / the reward model hold entries for
+                for (int k = 0; k < 2 && ok; ++k) {
+                    Model& m = *ms[k];
+                    trim_pages(m, L, 0);
+                    const int full = held[k] / RSD_PAGE;
+                    const int* src = m.bt_host + (size_t)L0 * m.max_pages;
+                    for (int i = 0; i < full; ++i) share_page(m, L, src[i]);
+                    c->bon_shared += full;
+                    if (held[k] % RSD_PAGE) {
+                        ok = ensure_pages(m, L, full + 1);
+                        if (ok) {
+                            int* pr = c->bon_copy_h + (size_t)k * 2 * B + 2 * n_copy[k]++;
+                            pr[0] = src[full];
+                            pr[1] = m.bt_host[(size_t)L * m.max_pages + full];
+                            ++c->bon_copied;
+                            ++c->bon_alloc;
+                        }
+                    }
+                }
+                c->bon_src_h[L] = L0;
+                c->bon_src_h[B + L] = ctx;
+            }
+            const int had_d = md.n_pages[L], had_p = mp.n_pages[L];
+            ok = ok && ensure_pages(md, L, need) && ensure_pages(mp, L, need);
+            if (!ok) {
+                undo();
+                return fail(c, RSD_ENOMEM, "KV pool exhausted reserving candidate %d of sequence %d", n, s);
+            }
+            c->bon_alloc += (md.n_pages[L] - had_d) + (mp.n_pages[L] - had_p);
+        }
+    }
+    for (int s = 0; s < S; ++s) {
+        const int L0 = c->canon[s];
+        if (c->finished()[L0] != RSD_RUNNING) continue;
+        const int ctx = c->ctx_len()[L0];
+        for (int n = 0; n < N; ++n) {
+            const int L = s * N + n;
+            c->ctx_len()[L] = ctx;
+            c->ctx_pre()[L] = ctx;
+            c->kv_len(RSD_DRAFT)[L] = ctx - 1;
+            c->kv_len(RSD_PRM)[L] = ctx;
+            c->active()[L] = 1;
+            c->step_len()[L] = 0;
+            c->finished()[L] = RSD_RUNNING;
+            c->reward()[L] = 0.f;
+        }
+    }
+    *c->n_active() = n_in * N;
+    if ((rc = push_state(c))) return rc;
+    if ((rc = upload_tables(c, md))) return rc;
+    if ((rc = upload_tables(c, mp))) return rc;
+    HIPCHK(c, hipMemcpyAsync(c->bon_src_dev, c->bon_src_h, (size_t)2 * B * sizeof(int), hipMemcpyHostToDevice, c->st));
+    hipLaunchKernelGGL(bon_fork_tokens_kernel, dim3(B), dim3(256), 0, c->st, c->ds.tokens, P.max_ctx, c->bon_src_dev,
+                       c->bon_src_dev + B);
+    if (n_copy[0] + n_copy[1]) {
+        HIPCHK(c, hipMemcpyAsync(c->bon_copy_dev, c->bon_copy_h, (size_t)4 * B * sizeof(int), hipMemcpyHostToDevice, c->st));
+        Model* ms[2] = {&md, &mp};
+        for (int k = 0; k < 2; ++k)
+            if (n_copy[k]) {
+                Model& m = *ms[k];
+                const size_t page_bytes = m.page_elts * m.esz;
+                hipLaunchKernelGGL(bon_copy_pages_kernel, dim3(n_copy[k], m.s.n_layers), dim3(256), 0, c->st, m.pool,
+                                   (size_t)m.pool_pages * page_bytes, page_bytes, c->bon_copy_dev + (size_t)k * 2 * B);
+            }
+    }
+    double t1 = now_ms();
+    c->stage_ms[2] += t1 - t0;
+
+    // ---- every candidate's step with the base model
+    if ((rc = gen_stage_any(c, RSD_DRAFT, c->u_draft, c->forced_draft))) return rc;
+    if ((rc = fetch_step_tokens(c))) return rc;
+    if ((rc = pull_state(c))) return rc;
+    double t2 = now_ms();
+    c->stage_ms[0] += t2 - t1;
+
+    // ---- every candidate's reward
+    {
+        std::vector<Piece> pieces;
+        for (int L = 0; L < B; ++L)
+            if (c->in_step()[L]) {
+                pieces.push_back(Piece{L, c->kv_len(RSD_PRM)[L], c->ctx_len()[L]});
+                c->kv_len(RSD_PRM)[L] = c->ctx_len()[L];
+            }
+        if ((rc = push_state(c))) return rc;
+        auto after = [&](const std::vector<Piece>&, const std::vector<int>&, int) {
+            if (f32) reward_rows<float>(c, mp, c->h, B, c->last_row_dev, c->ds.reward);
+            else reward_rows<bf16_t>(c, mp, c->h, B, c->last_row_dev, c->ds.reward);
+            return RSD_OK;
+        };
+        rc = f32 ? prefill<float>(c, RSD_PRM, pieces, after) : prefill<bf16_t>(c, RSD_PRM, pieces, after);
+        if (rc) return rc;
+    }
+    if ((rc = pull_state(c))) return rc;
+    double t3 = now_ms();
+    c->stage_ms[1] += t3 - t2;
+
+    // ---- the choice, the release of the other candidates, the termination test
+    std::vector<int> forced_choice;
+    if (c->forced_accept) {
+        forced_choice.resize(S);
+        HIPCHK(c, hipMemcpy2DAsync(forced_choice.data(), sizeof(int), c->forced_accept + c->steps_done, (size_t)P.max_steps * sizeof(int),
+                                   sizeof(int), S, hipMemcpyDeviceToHost, c->st));
+        HIPCHK(c, hipStreamSynchronize(c->st));
+    }
+    c->steps_done += 1;
+    for (int s = 0; s < S; ++s) {
+        const int L0 = c->canon[s];
+        const bool run = c->in_step()[L0] != 0;
+        if (out) {
+            for (int n = 0; n < N; ++n) {
+                const int L = s * N + n;
+                const int len = run ? c->ctx_len()[L] - c->ctx_pre()[L] : 0;
+                if (out->cand_len) out->cand_len[L] = len;
+                if (out->cand_reward) out->cand_reward[L] = run ? c->reward()[L] : 0.f;
+                if (out->cand_tokens) {
+                    int* dst = out->cand_tokens + (size_t)L * P.step_cap;
+                    if (run) std::memcpy(dst, c->steptok_h + (size_t)L * P.step_cap, P.step_cap * sizeof(int));
+                    else std::fill(dst, dst + P.step_cap, -1);
+                }
+            }
+        }
+        if (!run) {
+            if (out) {
+                if (out->chosen) out->chosen[s] = -1;
+                if (out->own_choice) out->own_choice[s] = -1;
+                if (out->finished) out->finished[s] = c->finished()[L0];
+                if (out->ctx_len) out->ctx_len[s] = c->ctx_len()[L0];
+                if (out->kv_len) { out->kv_len[s] = c->kv_len(RSD_DRAFT)[L0]; out->kv_len[S + s] = c->kv_len(RSD_PRM)[L0]; }
+                if (out->n_pages) { out->n_pages[s] = md.n_pages[L0]; out->n_pages[S + s] = mp.n_pages[L0]; }
+            }
+            continue;
+        }
+        int best = 0;
+        for (int n = 1; n < N; ++n)
+            if (c->reward()[s * N + n] > c->reward()[s * N + best]) best = n;      // the first of equal maxima stays
+        int pick = best;
+        if (!forced_choice.empty() && forced_choice[s] >= 0 && forced_choice[s] < N) pick = forced_choice[s];
+        const int Lw = s * N + pick;
+        c->canon[s] = Lw;
+        for (int n = 0; n < N; ++n) {
+            const int L = s * N + n;
+            if (L == Lw) continue;
+            trim_pages(md, L, 0);
+            trim_pages(mp, L, 0);
+        }
+        trim_pages(md, Lw, ceil_div(c->kv_len(RSD_DRAFT)[Lw], RSD_PAGE));
+        trim_pages(mp, Lw, ceil_div(c->kv_len(RSD_PRM)[Lw], RSD_PAGE));
+        const int len = c->ctx_len()[Lw] - c->ctx_pre()[Lw];
+        const int last_tok = c->steptok_h[(size_t)Lw * P.step_cap + len - 1];
+        int fin = RSD_RUNNING;
+        if (P.eos_id >= 0 && last_tok == P.eos_id) fin = RSD_FIN_EOS;
+        else if (c->ctx_len()[Lw] >= P.max_ctx) fin = RSD_FIN_MAX_CTX;
+        else if (c->steps_done >= P.max_steps) fin = RSD_FIN_MAX_STEPS;
+        for (int n = 0; n < N; ++n) c->finished()[s * N + n] = fin;
+        if (out) {
+            if (out->chosen) out->chosen[s] = pick;
+            if (out->own_choice) out->own_choice[s] = best;
+            if (out->finished) out->finished[s] = fin;
+            if (out->ctx_len) out->ctx_len[s] = c->ctx_len()[Lw];
+            if (out->kv_len) { out->kv_len[s] = c->kv_len(RSD_DRAFT)[Lw]; out->kv_len[S + s] = c->kv_len(RSD_PRM)[Lw]; }
+            if (out->n_pages) { out->n_pages[s] = md.n_pages[Lw]; out->n_pages[S + s] = mp.n_pages[Lw]; }
+        }
+    }
+    c->stage_ms[2] += now_ms() - t3;
+    return RSD_OK;
+}
+
+int rsd_bon_generate(rsd_ctx* c, int32_t max_steps, rsd_gen_out* out) {
+    if (!c) return RSD_EINVAL;
+    if (c->p.bon_n <= 0) return fail(c, RSD_ESTATE, "this context was not created for Best-of-N (bon_n = 0)");
+    if (!c->have_prompts) return fail(c, RSD_ESTATE, "no prompts set");
+    const int S = c->n_seq, N = c->p.bon_n;
+    const int limit = max_steps > 0 ? std::min(max_steps, c->p.max_steps) : c->p.max_steps;
+    std::vector<int> cl((size_t)S * N);
+    rsd_bon_out bo{};
+    bo.cand_len = cl.data();
+    rsd_gen_out g{};
+    if (out) { g.tokens = out->tokens; g.ctx_len = out->ctx_len; g.finished = out->finished; }
+    while (c->steps_done < limit) {
+        bool any = false;
+        for (int s = 0; s < S; ++s) any |= c->finished()[c->canon[s]] == RSD_RUNNING;
+        if (!any) break;
+        int rc = rsd_bon_step(c, &bo);
+        if (rc) { if (out) *out = g; return rc; }
+        g.steps_run += 1;
+        for (int v : cl) g.n_draft += v;
+    }
+    for (int s = 0; s < S; ++s) {
+        const int L = c->canon[s];
+        g.n_committed += c->ctx_len()[L] - c->prompt_len[L];
+        if (g.ctx_len) g.ctx_len[s] = c->ctx_len()[L];
+        if (g.finished) g.finished[s] = c->finished()[L];
+        if (g.tokens)
+            HIPCHK(c, hipMemcpyAsync(g.tokens + (size_t)s * c->p.max_ctx, c->ds.tokens + (size_t)L * c->p.max_ctx,
+                                     (size_t)c->p.max_ctx * sizeof(int), hipMemcpyDeviceToHost, c->st));
+    }
+    HIPCHK(c, hipStreamSynchronize(c->st));
+    if (out) *out = g;
+    return RSD_OK;
+}
+
+int rsd_bon_stats(rsd_ctx* c, int64_t* pages_shared, int64_t* pages_copied, int64_t* pages_allocated) {
+    if (!c) return RSD_EINVAL;
+    if (pages_shared) *pages_shared = c->bon_shared;
+    if (pages_copied) *pages_copied = c->bon_copied;
+    if (pages_allocated) *pages_allocated = c->bon_alloc;
     return RSD_OK;
 }
 
@@ -1844,6 +2181,7 @@ extern "C" int rsd_forward(rsd_ctx* c, int32_t model, const int32_t* tokens_host
     if (T < 1 || T > c->p.max_ctx) return fail(c, RSD_EINVAL, "T outside [1, max_ctx]");
     if (model == RSD_PRM && c->p.merge_prm != RSD_MERGE_NONE)
         return fail(c, RSD_EINVAL, "the merged reward model has no layers of its own to run");
+    if (model == RSD_TARGET && c->p.bon_n > 0) return fail(c, RSD_EINVAL, "a Best-of-N context has no target model");
     return c->m[model].s.dtype == RSD_F32 ? forward_impl<float>(c, model, tokens_host, lens_host, T, chunk, out_dev)
                                            : forward_impl<bf16_t>(c, model, tokens_host, lens_host, T, chunk, out_dev);
 }

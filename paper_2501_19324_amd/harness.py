@@ -49,3 +49,35 @@ class Session:
 
     def close(self):
         R.rsd_destroy(self.ctx)
+
+
+class BonSession:
+    """A process Best-of-N context: ``w.batch`` sequences x ``n`` candidate lanes, base model = the
+    workload's draft model, its reward model; candidate ``k`` of sequence ``s`` draws with row
+    ``s * n + k`` of the U_DRAFT stream generated for ``w.batch * n`` rows."""
+
+    def __init__(self, w: Workload, n: int, weights=None, use_graphs: int = 1, kv_pool_bytes=(0, 0, 0)):
+        import torch
+        from dataclasses import replace
+
+        self.w, self.n = w, n
+        dev = torch.device("cuda:0")
+        self.weights = weights if weights is not None else [model_blob_torch(w.seed, 0, w.draft, dev), None,
+                                                            model_blob_torch(w.seed, 2, w.prm, dev)]
+        self.ctx = R.rsd_init(w.shapes, self.weights, batch=w.batch * n, bon_n=n, delta=0.0, sep_id=w.sep_id,
+                              step_cap=w.step_cap, max_steps=w.max_steps, max_ctx=w.max_ctx, eos_id=w.eos_id,
+                              temperature=w.temperature, top_p=w.top_p, sep_logit_bias=w.sep_logit_bias,
+                              kv_pool_bytes=kv_pool_bytes, use_graphs=use_graphs)
+        self.prompt_len = prompt_lengths(w)
+        self.tokens_host = prompt_tokens(w)
+        self.tokens = torch.from_numpy(self.tokens_host).to(dev)
+        self.u_host = uniforms(replace(w, batch=w.batch * n), "U_DRAFT", w.max_ctx)      # [batch * n, max_ctx]
+        self.u = torch.from_numpy(self.u_host).to(dev)
+        R.rsd_set_uniforms(self.ctx, self.u, None, None)
+        self.reset()
+
+    def reset(self):
+        R.rsd_set_prompts(self.ctx, self.tokens, self.prompt_len)
+
+    def close(self):
+        R.rsd_destroy(self.ctx)

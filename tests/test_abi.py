@@ -41,5 +41,5 @@ def test_struct_layouts_match_header_sizes():
     from paper_2501_19324_amd import binding as b
 
     assert C.sizeof(b._Shape) == 40 and C.sizeof(b._Weights) == 16
-    assert C.sizeof(b._Params) == 48 + 24 + 16
-    assert C.sizeof(b._StepOut) == 88 and C.sizeof(b._GenOut) == 24 + 8 + 40 + 24
+    assert C.sizeof(b._Params) == 48 + 24 + 16 and b._Params.bon_n.offset == 84
+    assert C.sizeof(b._StepOut) == 88 and C.sizeof(b._GenOut) == 24 + 8 + 40 + 24 and C.sizeof(b._BonOut) == 72

@@ -32,18 +32,21 @@ def full():
 
 @pytest.fixture(scope="module")
 def checker_models():
-    """Full-depth checker models, built on first use and kept for the module (the 7B target is dropped
-    again by the test that uses it)."""
+    """Full-depth checker models of a configuration (its own seed), built on first use; one configuration
+    is kept at a time."""
     from oracle import rsd_oracle as O
     from rsd_inputs import model_weights_np, workload
-    w = workload("cfg1")
     cache = {}
 
-    def get(which):
-        if which not in cache:
-            cache[which] = O.OracleModel(w.shapes[which], model_weights_np(w.seed, which, w.shapes[which], threads=16))
-        return cache[which]
-    get.drop = lambda which: (cache.pop(which, None), gc.collect())
+    def get(name, which):
+        if (name, which) not in cache:
+            for k in [k for k in cache if k[0] != name]:
+                del cache[k]
+            gc.collect()
+            w = workload(name)
+            cache[(name, which)] = O.OracleModel(w.shapes[which], model_weights_np(w.seed, which, w.shapes[which], threads=16))
+        return cache[(name, which)]
+    get.drop = lambda name, which: (cache.pop((name, which), None), gc.collect())
     return get
 
 
@@ -64,14 +67,14 @@ def test_full_depth_prompt_against_checker(full, checker_models, which):
     n = int(s.prompt_len[0])
     toks = s.tokens_host[:, :n].copy()
     lens = np.array([n], np.int32)
-    m = checker_models(which)
+    m = checker_models("cfg1", which)
     seq = [int(t) for t in toks[0]]
     head = (lambda y: O.lm_logits(m, y)) if which != 2 else (lambda y: np.array(O.reward(m, y)))
     ref = head(O.forward_full(m, seq, "bf16")[-1])
     ref_exact = head(O.forward_full(m, seq, "exact")[-1])
     print(f"model {which}: the two checkers differ by {float(np.max(np.abs(ref - ref_exact))):.2e} (bf16 against exact cache entries)")
     if which == 1:
-        checker_models.drop(1)
+        checker_models.drop("cfg1", 1)
     for chunk in (n, 1):
         out = R.rsd_forward(s.ctx, which, toks, lens, chunk)
         got = out[0, n - 1].cpu().numpy()
@@ -99,7 +102,7 @@ def test_full_depth_batched_subset(checker_models, name, check):
     w = workload(name, step_cap=12, max_steps=2, deltas=(0.0,))
     s = Session(w)
     P = O.Params(delta=0.0, sep_id=w.sep_id, step_cap=w.step_cap, max_steps=w.max_steps, max_ctx=w.max_ctx, kv_dtype="bf16")
-    md, mp = checker_models(0), checker_models(2)
+    md, mp = checker_models(name, 0), checker_models(name, 2)
     # (the target's place is taken by the draft model: with delta = 0 every step is accepted and it is never run)
     refs = {b: O.generate_sequence(md, md, mp, s.tokens_host[b, :s.prompt_len[b]], s.u_host["U_DRAFT"][b],
                                    s.u_host["U_TARGET"][b], s.u_host["U_GATE"][b], P) for b in check}
