@@ -15,6 +15,7 @@
 #include <vector>
 
 #include "rsd.h"
+#include "pages.h"
 #include "common.cuh"
 #include "gemv.cuh"
 #include "gemm.cuh"
@@ -32,7 +33,7 @@ constexpr int kPfSplits = 16;       // ... into at most this many parts
 
 struct LayerOff { size_t attn_norm, wqkv, wo, ffn_norm, wgu, wdown; };
 
-struct Model {
+struct Model : PageTable {       // page bookkeeping: pages.h
     rsd_model_shape s{};
     const char* blob = nullptr;
     int hd = 0, q_dim = 0, kv_dim = 0, n_qkv = 0, G = 0, esz = 0;
@@ -41,13 +42,8 @@ struct Model {
     // paged KV
     char* pool = nullptr;
     size_t page_elts = 0;        // elements of one page of one layer (K and V, all KV heads)
-    int pool_pages = 0, max_pages = 0, splits = 1;
-    std::vector<int> free_list;
-    std::vector<int> ref;        // block-table entries that name each physical page (above 1 only while candidates share a context)
-    int* bt_host = nullptr;      // pinned [B][max_pages]
-    int* bt_dev = nullptr;
-    std::vector<int> n_pages;
-    bool bt_dirty = false;
+    int splits = 1;
+    int* bt_dev = nullptr;       // device copy of the block table (bt_host is pinned)
     float2* rope = nullptr;      // [max_ctx][hd/2]
 };
 
@@ -240,16 +236,11 @@ int setup_kv(rsd_ctx* c, Model& m, int which) {
     size_t pages = (size_t)B * m.max_pages;
     if (c->p.kv_pool_bytes[which]) pages = std::min<size_t>(pages, c->p.kv_pool_bytes[which] / page_bytes);
     if (pages < 1) return fail(c, RSD_EINVAL, "model %d: KV pool smaller than one page", which);
-    m.pool_pages = (int)pages;
     HIPCHK(c, hipMalloc(reinterpret_cast<void**>(&m.pool), pages * page_bytes));
-    m.free_list.resize(pages);
-    for (size_t i = 0; i < pages; ++i) m.free_list[i] = (int)(pages - 1 - i);   // pop_back hands out 0,1,2,...
-    m.ref.assign(pages, 0);
-    HIPCHK(c, pin_alloc(&m.bt_host, (size_t)B * m.max_pages));
+    int* storage = nullptr;
+    HIPCHK(c, pin_alloc(&storage, (size_t)B * m.max_pages));
     HIPCHK(c, dev_alloc(&m.bt_dev, (size_t)B * m.max_pages));
-    std::fill(m.bt_host, m.bt_host + (size_t)B * m.max_pages, -1);
-    m.n_pages.assign(B, 0);
-    m.bt_dirty = true;
+    m.init_pages(B, m.max_pages, (int)pages, storage);
     // rotary table in fp64 on the host, rounded once to fp32
     const int half = m.hd / 2;
     std::vector<float2> tab((size_t)c->p.max_ctx * half);
@@ -279,32 +270,9 @@ int setup_kv(rsd_ctx* c, Model& m, int which) {
     return RSD_OK;
 }
 
-bool ensure_pages(Model& m, int b, int need) {
-    while (m.n_pages[b] < need) {
-        if (m.free_list.empty()) return false;
-        const int pg = m.free_list.back();
-        m.free_list.pop_back();
-        m.ref[pg] = 1;
-        m.bt_host[(size_t)b * m.max_pages + m.n_pages[b]++] = pg;
-        m.bt_dirty = true;
-    }
-    return true;
-}
-// a page returns to the pool when the last table entry naming it goes
-void trim_pages(Model& m, int b, int keep) {
-    while (m.n_pages[b] > keep) {
-        int& e = m.bt_host[(size_t)b * m.max_pages + --m.n_pages[b]];
-        if (--m.ref[e] == 0) m.free_list.push_back(e);
-        e = -1;
-        m.bt_dirty = true;
-    }
-}
-// logical page i of row b becomes another name of physical page pg
-void share_page(Model& m, int b, int pg) {
-    ++m.ref[pg];
-    m.bt_host[(size_t)b * m.max_pages + m.n_pages[b]++] = pg;
-    m.bt_dirty = true;
-}
+bool ensure_pages(Model& m, int b, int need) { return m.ensure(b, need); }
+void trim_pages(Model& m, int b, int keep) { m.trim(b, keep); }
+void share_page(Model& m, int b, int pg) { m.share(b, pg); }
 int upload_tables(rsd_ctx* c, Model& m) {
     if (!m.bt_dirty) return RSD_OK;
     HIPCHK(c, hipMemcpyAsync(m.bt_dev, m.bt_host, (size_t)c->B * m.max_pages * sizeof(int), hipMemcpyHostToDevice, c->st));
