@@ -412,7 +412,7 @@ def gen_step(run: _Runner, tokens: List[int], u_row: np.ndarray, P: Params, marg
 def gen_step_sd(rd: _Runner, rt: _Runner, tokens: List[int], u_prop: np.ndarray, u_acc: np.ndarray,
                 u_target: np.ndarray, P: Params, margins: Optional[list] = None,
                 rounds: Optional[list] = None, prop_margins: Optional[list] = None,
-                proposed: Optional[list] = None):
+                proposed: Optional[list] = None, draws: Optional[list] = None):
     """Generate one reasoning step of the target model by speculative decoding
     with the draft model (Section 5, "Combine RSD with SD"), appending to
     ``tokens`` in place; the step ends exactly as in ``gen_step``.
@@ -429,7 +429,12 @@ def gen_step_sd(rd: _Runner, rt: _Runner, tokens: List[int], u_prop: np.ndarray,
     ``rounds`` collects (proposed, kept) per round; ``margins`` the top-2 gap of
     the target's logits at every committed position and ``prop_margins`` that of
     the draft's at every proposal (diagnostics for parity tests); ``proposed``
-    (place in the step, token) of every proposal."""
+    (place in the step, token) of every proposal; ``draws`` one entry per random
+    decision with the logits it was taken on (what a parity test needs to judge
+    whether a differing decision of another implementation lies within the reach
+    of its logits' error): proposals ("prop"), acceptance tests up to a round's
+    first refusal ("acc"), replacement draws ("res") and the target's own draw
+    after a fully kept round ("tgt")."""
     def logits_of(run, y):
         lg = lm_logits(run.m, y).copy()
         lg[P.sep_id] += P.sep_logit_bias
@@ -448,7 +453,7 @@ def gen_step_sd(rd: _Runner, rt: _Runner, tokens: List[int], u_prop: np.ndarray,
         g = max(0, min(P.sd_k, P.step_cap - (n - start) - 1, P.max_ctx - n - 1))
         rd.truncate(n - 1)
         rt.truncate(n - 1)
-        spec, q_rows = list(tokens), []
+        spec, q_rows, q_lgs = list(tokens), [], []
         for _ in range(g):
             lg = logits_of(rd, rd.last_hidden(spec))
             q = token_distribution(lg, P.temperature, P.top_p)
@@ -457,7 +462,10 @@ def gen_step_sd(rd: _Runner, rt: _Runner, tokens: List[int], u_prop: np.ndarray,
                 prop_margins.append(gap(lg))
             if proposed is not None:
                 proposed.append((len(spec) - start, x))
+            if draws is not None:
+                draws.append(dict(kind="prop", place=len(spec) - start, lg=lg, u=uni(u_prop, len(spec)), tok=x))
             q_rows.append(q)
+            q_lgs.append(lg)
             spec.append(x)
             if x == P.sep_id or x == P.eos_id:
                 break
@@ -469,6 +477,15 @@ def gen_step_sd(rd: _Runner, rt: _Runner, tokens: List[int], u_prop: np.ndarray,
                                   [uni(u_target, n + i) for i in range(len(props) + 1)])
         if rounds is not None:
             rounds.append((len(props), kept))
+        if draws is not None:
+            for i in range(min(kept + 1, len(props))):
+                draws.append(dict(kind="acc", place=n - start + i, lg_p=lgs[i], lg_q=q_lgs[i], u=uni(u_acc, n + i),
+                                  tok=props[i], kept=i < kept))
+            if kept < len(props):
+                draws.append(dict(kind="res", place=n - start + kept, lg_p=lgs[kept], lg_q=q_lgs[kept],
+                                  u=uni(u_target, n + kept), tok=emitted[kept]))
+            else:
+                draws.append(dict(kind="tgt", place=n - start + kept, lg=lgs[kept], u=uni(u_target, n + kept), tok=emitted[kept]))
         done = False
         for i, t in enumerate(emitted):
             tokens.append(t)
@@ -487,7 +504,7 @@ def generate_sequence(draft: OracleModel, target: OracleModel, prm: OracleModel,
                       prompt: Sequence[int], u_draft: np.ndarray, u_target: np.ndarray,
                       u_gate: np.ndarray, P: Params, use_cache: bool = True,
                       max_steps: Optional[int] = None, u_prop: Optional[np.ndarray] = None,
-                      u_acc: Optional[np.ndarray] = None) -> dict:
+                      u_acc: Optional[np.ndarray] = None, keep_draws: bool = False) -> dict:
     """RSD for one sequence (Algorithm 1 with the criterion of Algorithm 2).
 
     Returns the committed tokens, the per-step records and, after every step,
@@ -517,6 +534,7 @@ def generate_sequence(draft: OracleModel, target: OracleModel, prm: OracleModel,
             break
         ctx_pre = len(tokens)
         dm, fm, pm, sd_rounds, proposed = [], [], [], [], []
+        draws = [] if keep_draws else None
         draft_step = gen_step(rd, tokens, u_draft, P, dm)
         if P.merge == "none":
             r = reward(prm, rp.last_hidden(tokens))
@@ -534,7 +552,7 @@ def generate_sequence(draft: OracleModel, target: OracleModel, prm: OracleModel,
             if P.merge == "target":
                 rt.truncate(ctx_pre - 1)
             if P.sd_k > 0:
-                final = gen_step_sd(rd, rt, tokens, u_prop, u_acc, u_target, P, fm, sd_rounds, pm, proposed)
+                final = gen_step_sd(rd, rt, tokens, u_prop, u_acc, u_target, P, fm, sd_rounds, pm, proposed, draws)
             else:
                 final = gen_step(rt, tokens, u_target, P, fm)
         if P.eos_id >= 0 and P.eos_id in final:
@@ -548,7 +566,7 @@ def generate_sequence(draft: OracleModel, target: OracleModel, prm: OracleModel,
                             accepted=bool(ok), final_tokens=list(final), ctx_len=len(tokens),
                             kv_len=kv, n_pages=[-(-n // P.page_tokens) for n in kv],
                             draft_margins=dm, final_margins=fm, sd_rounds=sd_rounds, proposal_margins=pm, proposed=proposed,
-                            finished=reason))
+                            draws=draws, finished=reason))
     return dict(tokens=tokens, prompt_len=len(prompt), records=records, finished=reason,
                 kv_len=[rd.kv_len, rt.kv_len, rp.kv_len])
 

@@ -731,6 +731,14 @@ hipGraphExec_t decode_graph(rsd_ctx* c, int which, const float* u, const int* fo
 template <typename WT, typename AfterPass>
 int prefill(rsd_ctx* c, int which, std::vector<Piece> pieces, AfterPass after_pass) {
     Model& m = c->m[which];
+    // the kernels index the block table without checks: every position a pass touches must lie on a page its
+    // row owns, and the device must hold the table the host has
+    for (const Piece& pc : pieces)
+        if (pc.b < 0 || pc.b >= c->B || pc.start < 0 || pc.end > c->p.max_ctx || pc.end < pc.start ||
+            ceil_div(pc.end, RSD_PAGE) > m.n_pages[pc.b])
+            return fail(c, RSD_ESTATE, "internal: row %d feeds positions [%d, %d) of model %d but owns %d pages", pc.b, pc.start,
+                        pc.end, which, pc.b >= 0 && pc.b < c->B ? m.n_pages[pc.b] : -1);
+    if (m.bt_dirty) return fail(c, RSD_ESTATE, "internal: block table of model %d not uploaded before a pass", which);
     size_t i = 0;
     std::vector<Piece> pass;
     std::vector<int> first_row;
@@ -797,6 +805,13 @@ int gen_stage(rsd_ctx* c, int which, const float* u, const int* forced, int mode
             pieces.push_back(Piece{b, s, e});
         }
     if (!n_act) return RSD_OK;
+    // (the decode loop appends without host checks: the pages for everything it can write must be reserved)
+    for (const Piece& pc : pieces) {
+        const int room = mode == 2 ? c->sd_lim()[pc.b] : std::min(pc.end + cap, c->p.max_ctx);
+        if (ceil_div(room, RSD_PAGE) > m.n_pages[pc.b])
+            return fail(c, RSD_ESTATE, "internal: row %d may grow to %d tokens in model %d but owns %d pages", pc.b, room, which,
+                        m.n_pages[pc.b]);
+    }
     int iters = 0;
     // decode-loop accounting (steps of the reasoning loop only): contexts before the stage
     const bool count = mode == 1 && which < 2;
