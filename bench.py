@@ -476,6 +476,27 @@ def main():
                                     "note": "each delta: prompts set, then 2 reasoning steps (contexts <= 1280); the run to the "
                                             "pool's end is a separate invocation (--workload cfg4 --until-enomem)",
                                     "delta": per_delta4}
+        # process Best-of-N (the paper's comparison procedure on the same kernels): the 1.5B base model and reward
+        # model of configuration 2, 16 sequences x 4 candidates, the paper's sampling setting for it
+        from paper_2501_19324_amd.harness import BonSession
+        wb = replace(workload("cfg2", batch=16), temperature=0.7, top_p=0.8)
+        sb = BonSession(wb, 4)
+        R.rsd_bon_generate(sb.ctx, max_steps=1, want_tokens=False)           # warm-up: first-use costs
+        sb.reset()
+        torch.cuda.synchronize()
+        tb = time.perf_counter()
+        gb = R.rsd_bon_generate(sb.ctx, max_steps=4, want_tokens=False)
+        torch.cuda.synchronize()
+        tb = time.perf_counter() - tb
+        extras["process_best_of_n"] = {"workload": f"{wb.batch} sequences x 4 candidates, draft {wb.draft.n_layers}L-d{wb.draft.d_model} as base model, "
+                                                   f"PRM {wb.prm.n_layers}L-d{wb.prm.d_model}, prompts {wb.prompt_len_min}-{wb.prompt_len_max}, "
+                                                   f"T={wb.temperature}, top_p={wb.top_p}, prompts set then 4 steps x <= {wb.step_cap} tokens",
+                                       "committed_tokens_per_s": round(gb["n_committed"] / tb, 1),
+                                       "candidate_tokens_per_s": round(gb["n_draft"] / tb, 1), "seconds": round(tb, 2),
+                                       "pages": R.rsd_bon_stats(sb.ctx)}
+        sb.close()
+        del sb
+        torch.cuda.empty_cache()
         line["config"]["other_configs"] = extras
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(w)

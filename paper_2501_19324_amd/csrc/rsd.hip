@@ -460,12 +460,12 @@ void rows_finish(rsd_ctx* c, int ks, int rows, int M, int N, float* Y, int ldy, 
 void rows_gemm(rsd_ctx* c, const Model& m, int op, int epi, const bf16_t* W, int N, int K, int M, float* Y, int ldy,
                const bf16_t* next_gain = nullptr, float eps = 0.f) {
     const bool few = M <= 64 && N % 4 == 0;
+    SkGeom geo{};                                            // G = 0: uniform K slices
     const int rows = few ? (M <= 32 ? 32 : 64) : M;          // rows of one slice of partial results
     // algorithmic traffic: the weights once, fp32 activations in and out (SwiGLU leaves N / 2 columns)
     const long long pb = (long long)N * K * 2 + 4LL * M * (K + (epi == EPI_SWIGLU ? N / 2 : N) + (epi == EPI_RESID ? N : 0));
     const long long pf = 2LL * M * N * K;
     int ks;
-    SkGeom geo{};                                            // G = 0: uniform K slices
     if (few && gemm_rows_even(N, K)) {
         geo = sk_geometry(N, K, kSkBlocks);
         if ((size_t)geo.zmax * rows * N > c->part_k_floats) geo = SkGeom{};
