@@ -84,11 +84,24 @@ __global__ __launch_bounds__(256) void sgemm_nt_kernel(const float* __restrict__
 // Partial results go to part[z][m][n]; a finish kernel adds the slices and applies the epilogue.
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));    // native vector: stays in registers across LDS stores
 
+// 16 bytes of a weight matrix that is read exactly once per launch: marked non-temporal, so that the stream of
+// weights does not push the activation tiles (re-read by every block) out of L2
+#ifndef RSD_W_NT
+#define RSD_W_NT 1
+#endif
+__device__ __forceinline__ u32x4_t load_w16(const bf16_t* p) {
+#if RSD_W_NT
+    return __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
+#else
+    return *reinterpret_cast<const u32x4_t*>(p);
+#endif
+}
+
 template <int MT>
 __global__ __launch_bounds__(512, 2) void gemm_rows_kernel(const bf16_t* __restrict__ W, int N, int K,
                                                            const uint16_t* __restrict__ Xh,
                                                            const uint16_t* __restrict__ Xl,
-                                                           float* __restrict__ part) {
+                                                           float* __restrict__ part, int M) {
     constexpr int BK = 64, NWV = 8;
     constexpr int ROWS = 32 * MT;
     __shared__ __attribute__((aligned(16))) uint16_t Ah[2][ROWS * BK];
@@ -114,8 +127,9 @@ __global__ __launch_bounds__(512, 2) void gemm_rows_kernel(const bf16_t* __restr
     const int ws_st0 = sw(lrow, lchunk), ws_st1 = sw(lrow + 8, lchunk), ws_st2 = sw(lrow + 16, lchunk), ws_st3 = sw(lrow + 24, lchunk);
     // activation tile: MT = 2: thread -> (row tid / 8, chunk tid % 8) of both halves; MT = 1: threads 0..255 the hi half, the rest lo
     const int xrow = (MT == 2) ? (tid >> 3) : ((tid & 255) >> 3);
-    const uint16_t* xp0 = ((MT == 2 || tid < 256) ? Xh : Xl) + (size_t)xrow * K + lchunk * 8;
-    const uint16_t* xp1 = Xl + (size_t)xrow * K + lchunk * 8;      // MT = 2 only
+    const int xsrc = min(xrow, M - 1);      // tile rows beyond M are never used: they repeat row M - 1 instead of fetching more of L2
+    const uint16_t* xp0 = ((MT == 2 || tid < 256) ? Xh : Xl) + (size_t)xsrc * K + lchunk * 8;
+    const uint16_t* xp1 = Xl + (size_t)xsrc * K + lchunk * 8;      // MT = 2 only
     const int x_st = sw(xrow, lchunk);
 
     f32x16_t acc[MT];
@@ -131,10 +145,10 @@ __global__ __launch_bounds__(512, 2) void gemm_rows_kernel(const bf16_t* __restr
 #define RSD_FETCH_W(kb, R)                                                                       \
     {                                                                                            \
         const size_t k0_ = (size_t)min((kb), kb_last) * BK;                                      \
-        R.w0 = *reinterpret_cast<const u32x4_t*>(wr0 + k0_);                                     \
-        R.w1 = *reinterpret_cast<const u32x4_t*>(wr1 + k0_);                                     \
-        R.w2 = *reinterpret_cast<const u32x4_t*>(wr2 + k0_);                                     \
-        R.w3 = *reinterpret_cast<const u32x4_t*>(wr3 + k0_);                                     \
+        R.w0 = load_w16(wr0 + k0_);                                     \
+        R.w1 = load_w16(wr1 + k0_);                                     \
+        R.w2 = load_w16(wr2 + k0_);                                     \
+        R.w3 = load_w16(wr3 + k0_);                                     \
     }
 #define RSD_FETCH_X(kb)                                                                          \
     {                                                                                            \
@@ -244,7 +258,7 @@ template <int MT, int D>
 __global__ __launch_bounds__(512, D == 2 ? 2 : 1) void gemm_rows_sk_kernel(const bf16_t* __restrict__ W, int N, int K,
                                                                         const uint16_t* __restrict__ Xh,
                                                                         const uint16_t* __restrict__ Xl,
-                                                                        float* __restrict__ part, SkGeom geo) {
+                                                                        float* __restrict__ part, SkGeom geo, int M) {
     constexpr int BK = 64, NWV = 8;
     constexpr int ROWS = 32 * MT;
     __shared__ __attribute__((aligned(16))) uint16_t Ah[2][ROWS * BK];
@@ -257,8 +271,9 @@ __global__ __launch_bounds__(512, D == 2 ? 2 : 1) void gemm_rows_sk_kernel(const
     auto sw = [](int r, int c) { return r * BK + ((c ^ ((r >> 1) & 7)) << 3); };
     const int ws_st0 = sw(lrow, lchunk), ws_st1 = sw(lrow + 8, lchunk), ws_st2 = sw(lrow + 16, lchunk), ws_st3 = sw(lrow + 24, lchunk);
     const int xrow = (MT == 2) ? (tid >> 3) : ((tid & 255) >> 3);
-    const uint16_t* xp0 = ((MT == 2 || tid < 256) ? Xh : Xl) + (size_t)xrow * K + lchunk * 8;
-    const uint16_t* xp1 = Xl + (size_t)xrow * K + lchunk * 8;      // MT = 2 only
+    const int xsrc = min(xrow, M - 1);      // tile rows beyond M are never used: they repeat row M - 1 instead of fetching more of L2
+    const uint16_t* xp0 = ((MT == 2 || tid < 256) ? Xh : Xl) + (size_t)xsrc * K + lchunk * 8;
+    const uint16_t* xp1 = Xl + (size_t)xsrc * K + lchunk * 8;      // MT = 2 only
     const int x_st = sw(xrow, lchunk);
 
     long long u = sk_start(geo, blockIdx.x);
@@ -287,10 +302,10 @@ __global__ __launch_bounds__(512, D == 2 ? 2 : 1) void gemm_rows_sk_kernel(const
 #define SK_FETCH_W(kb, R)                                                                        \
     {                                                                                            \
         const size_t k0_ = (size_t)min((kb), kb_last) * BK;                                      \
-        R.w0 = *reinterpret_cast<const u32x4_t*>(wr0 + k0_);                                     \
-        R.w1 = *reinterpret_cast<const u32x4_t*>(wr1 + k0_);                                     \
-        R.w2 = *reinterpret_cast<const u32x4_t*>(wr2 + k0_);                                     \
-        R.w3 = *reinterpret_cast<const u32x4_t*>(wr3 + k0_);                                     \
+        R.w0 = load_w16(wr0 + k0_);                                     \
+        R.w1 = load_w16(wr1 + k0_);                                     \
+        R.w2 = load_w16(wr2 + k0_);                                     \
+        R.w3 = load_w16(wr3 + k0_);                                     \
     }
 #define SK_FETCH_X(kb)                                                                           \
     {                                                                                            \
@@ -401,7 +416,7 @@ template <int MT>
 __global__ __launch_bounds__(512, 2) void gemm_rows64_kernel(const bf16_t* __restrict__ W, int N, int K,
                                                              const uint16_t* __restrict__ Xh,
                                                              const uint16_t* __restrict__ Xl,
-                                                             float* __restrict__ part) {
+                                                             float* __restrict__ part, int M) {
     constexpr int BK = 64, ROWS = 32 * MT, KH = 4 / MT, JS = 4 / KH;   // K parts per K block; operand steps per wave
     constexpr int WS_E = 64 * BK, XS_E = ROWS * BK;
     __shared__ __attribute__((aligned(16))) uint16_t smem[2 * WS_E + 4 * XS_E];
@@ -425,8 +440,9 @@ __global__ __launch_bounds__(512, 2) void gemm_rows64_kernel(const bf16_t* __res
     const bf16_t* wr = W + (size_t)min(n0 + lrow, N - 1) * K + lchunk * 8;
     const int w_st = sw(lrow, lchunk);
     const int xrow = (MT == 2) ? lrow : ((tid & 255) >> 3);
-    const uint16_t* xp0 = ((MT == 2 || tid < 256) ? Xh : Xl) + (size_t)xrow * K + lchunk * 8;
-    const uint16_t* xp1 = Xl + (size_t)xrow * K + lchunk * 8;      // MT = 2 only
+    const int xsrc = min(xrow, M - 1);      // as above: rows beyond M repeat row M - 1
+    const uint16_t* xp0 = ((MT == 2 || tid < 256) ? Xh : Xl) + (size_t)xsrc * K + lchunk * 8;
+    const uint16_t* xp1 = Xl + (size_t)xsrc * K + lchunk * 8;      // MT = 2 only
     const int x_st = sw(xrow, lchunk);
 
     f32x16_t acc;
@@ -434,7 +450,7 @@ __global__ __launch_bounds__(512, 2) void gemm_rows64_kernel(const bf16_t* __res
     for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
 
     u32x4_t w0, w1, w2, w3, x0, x1;       // W: four K blocks requested ahead; activations (L2-resident): one
-#define R64_FETCH_W(kb, R) { R = *reinterpret_cast<const u32x4_t*>(wr + (size_t)min((kb), kb_last) * BK); }
+#define R64_FETCH_W(kb, R) { R = load_w16(wr + (size_t)min((kb), kb_last) * BK); }
 #define R64_FETCH_X(kb)                                                                          \
     {                                                                                            \
         const size_t k0_ = (size_t)min((kb), kb_last) * BK;                                      \
@@ -734,21 +750,21 @@ static bool gemm_rows_even(int N, int K) { (void)K; return (N + 255) / 256 >= 20
 template <int D>
 static void gemm_rows_sk_launch(hipStream_t st, const bf16_t* W, int N, int K, const uint16_t* Xh, const uint16_t* Xl,
                                 int M, float* part, const SkGeom& g) {
-    if (M <= 32) hipLaunchKernelGGL((gemm_rows_sk_kernel<1, D>), dim3(g.G), dim3(512), 0, st, W, N, K, Xh, Xl, part, g);
-    else         hipLaunchKernelGGL((gemm_rows_sk_kernel<2, D>), dim3(g.G), dim3(512), 0, st, W, N, K, Xh, Xl, part, g);
+    if (M <= 32) hipLaunchKernelGGL((gemm_rows_sk_kernel<1, D>), dim3(g.G), dim3(512), 0, st, W, N, K, Xh, Xl, part, g, M);
+    else         hipLaunchKernelGGL((gemm_rows_sk_kernel<2, D>), dim3(g.G), dim3(512), 0, st, W, N, K, Xh, Xl, part, g, M);
 }
 
 static void gemm_rows_launch(hipStream_t st, const bf16_t* W, int N, int K, const uint16_t* Xh, const uint16_t* Xl,
                              int M, float* part, int ks) {
     if (gemm_rows_small(N, K)) {
         const dim3 grid((N + 63) / 64, ks), block(512);
-        if (M <= 32) hipLaunchKernelGGL((gemm_rows64_kernel<1>), grid, block, 0, st, W, N, K, Xh, Xl, part);
-        else         hipLaunchKernelGGL((gemm_rows64_kernel<2>), grid, block, 0, st, W, N, K, Xh, Xl, part);
+        if (M <= 32) hipLaunchKernelGGL((gemm_rows64_kernel<1>), grid, block, 0, st, W, N, K, Xh, Xl, part, M);
+        else         hipLaunchKernelGGL((gemm_rows64_kernel<2>), grid, block, 0, st, W, N, K, Xh, Xl, part, M);
         return;
     }
     const dim3 grid((N + 255) / 256, ks), block(512);
-    if (M <= 32) hipLaunchKernelGGL((gemm_rows_kernel<1>), grid, block, 0, st, W, N, K, Xh, Xl, part);
-    else         hipLaunchKernelGGL((gemm_rows_kernel<2>), grid, block, 0, st, W, N, K, Xh, Xl, part);
+    if (M <= 32) hipLaunchKernelGGL((gemm_rows_kernel<1>), grid, block, 0, st, W, N, K, Xh, Xl, part, M);
+    else         hipLaunchKernelGGL((gemm_rows_kernel<2>), grid, block, 0, st, W, N, K, Xh, Xl, part, M);
 }
 
 // ---------------------------------------------------------------- dispatch
@@ -909,8 +925,26 @@ __global__ __launch_bounds__(BM * 2, BM == 128 ? 2 : 1) void gemm_tile_kernel(co
         }
 }
 
-// K slices for gemm_tile_kernel: as many as bring the grid to about 512 blocks, none below 8 K blocks
+// Block tile and K slices for gemm_tile_kernel.
+// Many rows (chunked passes): as many slices as bring the grid to about 512 blocks, none below 8 K blocks; 256-row
+// tiles when they still fill the chip about twice.
+// 65..256 rows (the decode iteration of a large batch: one row tile): the kernel is MFMA-bound there, two
+// co-resident 128-row blocks run no faster than one (measured per K block of 32: 0.97 us for a 128-row block
+// alone on its unit, 2.2 us each for two, 1.37 us for a 256-row block), so the grid is kept to one round of at
+// most 256 blocks and filled with K slices: [3584][18944] at 256 rows 98 -> 72 us, [17920][1536] 53 -> 39 us,
+// [37888][3584] (148 column tiles: no slices, no finish kernel) 178 + 18 -> 170 us.
+static bool gemm_tile_decode_rows(int M) { return M <= 256; }
+static int gemm_tile_bm(int N, int M, int ks) {
+    if (gemm_tile_decode_rows(M)) return M > 128 ? 256 : 128;
+    return ((N + 255) / 256) * ((M + 255) / 256) * ks >= 400 ? 256 : 128;
+}
 static int gemm_tile_slices(int N, int K, int M, size_t part_floats) {
+    if (gemm_tile_decode_rows(M)) {
+        const int tn = (N + 255) / 256, nkb = K / 32;
+        int ks = std::max(1, std::min(std::min(256 / tn, nkb / 6), 32));
+        while (ks > 1 && ((size_t)ks * M * N > part_floats || (ks - 1) * ((nkb + ks - 1) / ks) >= nkb)) --ks;
+        return ks;
+    }
     const int tiles = ((N + 255) / 256) * ((M + 127) / 128);
     int ks = 1;
     while (ks < 32 && tiles * ks < 512 && K / 32 / (ks * 2) >= 8 && (size_t)(ks * 2) * M * N <= part_floats) ks *= 2;
@@ -920,7 +954,7 @@ static int gemm_tile_slices(int N, int K, int M, size_t part_floats) {
 static void gemm_tile_launch(hipStream_t st, int epi, const bf16_t* W, int N, int K, const uint16_t* Xh,
                              const uint16_t* Xl, int M, float* Y, int ldy, float* part, int ks) {
     const int tn = (N + 255) / 256;
-    if (tn * ((M + 255) / 256) * ks >= 400) {       // enough 256-row tiles to fill the chip (one block per compute unit) about twice
+    if (gemm_tile_bm(N, M, ks) == 256) {
         const dim3 grid(tn, (M + 255) / 256, ks), block(512);
         if (epi == EPI_RESID) hipLaunchKernelGGL((gemm_tile_kernel<EPI_RESID, 256>), grid, block, 0, st, W, N, K, Xh, Xl, M, Y, ldy, part);
         else                  hipLaunchKernelGGL((gemm_tile_kernel<EPI_STORE, 256>), grid, block, 0, st, W, N, K, Xh, Xl, M, Y, ldy, part);
