@@ -58,7 +58,7 @@ def cpu_baseline(w, budget_layers=None):
     if budget_layers or need(layers) > 0.5 * avail:      # (the 72B target alone is 580 GB in fp64)
         layers = [min(L, budget_layers or 2) for L in full]
     L = max(layers)
-    step_cap, max_steps = 4, 2
+    step_cap, max_steps = 8, 3
     ws = workload(w.name, n_layers=L, batch=1, step_cap=step_cap, max_steps=max_steps)
     threads = min(16, os.cpu_count() or 1)
     models = [O.OracleModel(s, model_weights_np(ws.seed, i, s, threads=threads)) for i, s in enumerate(ws.shapes)]
@@ -415,7 +415,10 @@ def main():
     roof = None
     pr = rec.get("probe_target_gate_up")
     if pr:
-        kern = "gemv_flat_kernel" if w.batch == 1 else ("gemm_rows_kernel" if w.batch <= 64 else "gemm_tile_kernel")
+        tgt = w.shapes[1]
+        even = (2 * tgt.d_ffn + 255) // 256 >= 200       # the library's rule for the evenly dealt few-row GEMM
+        kern = ("gemv_flat_kernel" if w.batch == 1 else "gemm_tile_kernel" if w.batch > 64
+                else "gemm_rows_sk_kernel" if even else "gemm_rows_kernel")
         roof = {"bound": "hbm", "achieved": pr["GBs"], "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": pr["frac"],
                 "traffic": measured_traffic(w.name) if not (args.layers or args.batch) else None,
                 "kernel": f"{kern} (gate+up projection of the target model, decode iteration of {w.batch} row(s))",
