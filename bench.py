@@ -58,7 +58,7 @@ def cpu_baseline(w, budget_layers=None):
     if budget_layers or need(layers) > 0.5 * avail:      # (the 72B target alone is 580 GB in fp64)
         layers = [min(L, budget_layers or 2) for L in full]
     L = max(layers)
-    step_cap, max_steps = 8, 3
+    step_cap, max_steps = 16, 4
     ws = workload(w.name, n_layers=L, batch=1, step_cap=step_cap, max_steps=max_steps)
     threads = min(16, os.cpu_count() or 1)
     models = [O.OracleModel(s, model_weights_np(ws.seed, i, s, threads=threads)) for i, s in enumerate(ws.shapes)]
@@ -168,6 +168,7 @@ def iteration_record(R, s, shapes, reset=True):
         gbs = by / (st["gpu_ms"] * 1e-3) / 1e9
         out[name] = {"iterations": st["iterations"], "ms_per_iteration": round(st["gpu_ms"] / st["iterations"], 4),
                      "mean_active_sequences": round(st["seq_iterations"] / st["iterations"], 2),
+                     "mean_rows_launched": round(st["row_iterations"] / st["iterations"], 2),
                      "mean_context": round(st["kv_tokens_read"] / max(st["seq_iterations"], 1), 1),
                      "GB_per_iteration": round(by / st["iterations"] / 1e9, 3),
                      "GBs": round(gbs, 1), "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),

@@ -354,6 +354,14 @@ int rsd_probe_read(rsd_ctx *c, int32_t slot, int64_t *n_samples, double *total_m
 int rsd_iter_stats(rsd_ctx *c, int32_t model, int64_t *iterations, double *gpu_ms, int64_t *seq_iterations,
                    int64_t *kv_tokens_read, int32_t reset);
 
+/* Rows launched by the iterations rsd_iter_stats counts: the sum over those iterations of the number of
+ * activation rows every kernel of the iteration was launched over.  A stage in which only some sequences
+ * take part (the target's stage of Algorithm 1 after the reward model accepted the other sequences' steps)
+ * packs its sequences into fewer rows than the batch has (1..8 exactly, then 32, 64, multiples of 128), so
+ * row_iterations / iterations lies between the mean number of active sequences and the batch size.
+ * Cleared together with rsd_iter_stats' counters.  Host output. */
+int rsd_iter_rows(rsd_ctx *c, int32_t model, int64_t *row_iterations);
+
 /* Timing of the decode attention kernel alone (grouped-query attention of one new token per sequence over
  * the paged cache, rotary embedding and cache write included), for roofline reports.  Sequence b gets a
  * context of ctx_len_host[b] tokens (1 .. max_ctx; HOST array [B]) in `model`'s cache, whose pool is

@@ -307,12 +307,14 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(const float* __restric
                                                           const int* __restrict__ active,
                                                           const float2* __restrict__ rope, int H, int Hkv, int S,
                                                           float scale, float* __restrict__ out, int ldo,
-                                                          float* __restrict__ part_acc, float* __restrict__ part_ml) {
+                                                          float* __restrict__ part_acc, float* __restrict__ part_ml,
+                                                          const int* __restrict__ row_seq) {
     constexpr int LPT = HD / 8, TPW = 64 / LPT;
     constexpr int ITERS = RSD_PAGE / TPW > 0 ? RSD_PAGE / TPW : 1;
     const int r = blockIdx.x, hk = blockIdx.y, sp = blockIdx.z;
-    if (!active[r]) return;
-    const int pos = kv_len[r];
+    const int seq = row_seq ? row_seq[r] : r;       // packed rows: the sequence this row stands for (< 0: none)
+    if (seq < 0 || !active[seq]) return;
+    const int pos = kv_len[seq];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int part = lane % LPT, tsub = lane / LPT;
     const float* row = qkv + (size_t)r * ldq;
@@ -355,7 +357,7 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(const float* __restric
     const int n_pages = (pos + RSD_PAGE - 1) / RSD_PAGE;      // pages holding cached positions 0..pos-1
     const int pps = (n_pages + S - 1) / S;
     const int p_begin = sp * pps, p_end = min(n_pages, p_begin + pps);
-    const int* bt = block_table + (size_t)r * max_pages;
+    const int* bt = block_table + (size_t)seq * max_pages;
     const size_t page_elts = (size_t)2 * Hkv * RSD_PAGE * HD;
     const size_t head_off = (size_t)hk * RSD_PAGE * HD, v_off = (size_t)Hkv * RSD_PAGE * HD;
 
@@ -480,25 +482,28 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void attn_decode_mfma_ker
                                                                    const float2* __restrict__ rope, int H, int Hkv,
                                                                    int S, float scale, float* __restrict__ out, int ldo,
                                                                    float* __restrict__ part_acc, float* __restrict__ part_ml,
-                                                                   uint16_t* __restrict__ out_h, uint16_t* __restrict__ out_l) {
+                                                                   uint16_t* __restrict__ out_h, uint16_t* __restrict__ out_l,
+                                                                   const int* __restrict__ row_seq) {
     constexpr int HD = 128;
     const int r = blockIdx.x, hk = blockIdx.y, sp = blockIdx.z;
+    const int seq_raw = row_seq ? row_seq[r] : r;   // packed rows: the sequence this row stands for (< 0: none)
+    const int seq = max(seq_raw, 0);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     // Pages are dealt round-robin: the i-th page of (split sp, wave w) is sp + S * (w + NW * i), whatever
     // the position turns out to be.  So the table entries (lane i holds the i-th; entries beyond the
     // sequence are never used) are requested together with the position, not after it.
-    const int is_active = active[r];
-    const int pos = kv_len[r];
+    const int is_active = seq_raw >= 0 && active[seq];
+    const int pos = kv_len[seq];
     const int pg0 = sp + S * wave, pg_step = S * NW;
     int bt_mine = -1;
-    if (pg0 + pg_step * lane < max_pages) bt_mine = block_table[(size_t)r * max_pages + pg0 + pg_step * lane];
+    if (pg0 + pg_step * lane < max_pages) bt_mine = block_table[(size_t)seq * max_pages + pg0 + pg_step * lane];
     if (!is_active) return;
     const int l16 = lane & 15, c = lane >> 4;
     const float* row = qkv + (size_t)r * ldq;
     const float2* cs = rope + (size_t)pos * (HD / 2);
 
     const int n_pages = (pos + RSD_PAGE - 1) / RSD_PAGE;      // pages holding cached positions 0..pos-1
-    const int* bt = block_table + (size_t)r * max_pages;
+    const int* bt = block_table + (size_t)seq * max_pages;
     const size_t page_elts = (size_t)2 * Hkv * RSD_PAGE * HD;
     const size_t head_off = (size_t)hk * RSD_PAGE * HD, v_off = (size_t)Hkv * RSD_PAGE * HD;
 

@@ -93,6 +93,10 @@ __device__ __forceinline__ float block256_sum(float v, float* red) {
 // Row descriptor shared by the per-row kernels.  Chunked prefill passes give
 // explicit (sequence, position) arrays; single-token decode passes leave them
 // null: row r is sequence r, fed at position kv_len[r], skipped when inactive.
+// Which sequence and which position a row of a pass stands for.
+//   chunked pass:   row_seq[r], row_pos[r] (every row is in use)
+//   decode, dense:  row r is sequence r at position kv_len[r], in use while active[r]
+//   decode, packed: row r is sequence row_seq[r] (< 0: unused row) at kv_len[seq], in use while active[seq]
 struct RowMap {
     const int* row_seq;
     const int* row_pos;
@@ -100,7 +104,13 @@ struct RowMap {
     const int* active;
 };
 __device__ __forceinline__ bool row_lookup(const RowMap& rm, int r, int& seq, int& pos) {
-    if (rm.row_seq) { seq = rm.row_seq[r]; pos = rm.row_pos[r]; return true; }
+    if (rm.row_seq) {
+        seq = rm.row_seq[r];
+        if (rm.row_pos) { pos = rm.row_pos[r]; return true; }
+        if (seq < 0) return false;
+        pos = rm.kv_len[seq];
+        return rm.active[seq] != 0;
+    }
     seq = r; pos = rm.kv_len[r];
     return rm.active[r] != 0;
 }

@@ -225,7 +225,7 @@ __global__ __launch_bounds__(512, 2) void gemm_rows_kernel(const bf16_t* __restr
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int m = t * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-                part[((size_t)blockIdx.y * ROWS + m) * N + n] = acc[t][v];
+                if (m < M) part[((size_t)blockIdx.y * ROWS + m) * N + n] = acc[t][v];      // rows beyond M are never read
             }
     }
 }
@@ -397,7 +397,7 @@ __global__ __launch_bounds__(512, D == 2 ? 2 : 1) void gemm_rows_sk_kernel(const
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const int m = t * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-                    part[((size_t)z * ROWS + m) * N + n] = acc[t][v];
+                    if (m < M) part[((size_t)z * ROWS + m) * N + n] = acc[t][v];
                 }
         }
     }
@@ -533,7 +533,7 @@ __global__ __launch_bounds__(512, 2) void gemm_rows64_kernel(const bf16_t* __res
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int m = xj * 32 + 8 * (v >> 2) + 4 * kg + (v & 3);
-                part[((size_t)blockIdx.y * ROWS + m) * N + n] = acc[v];
+                if (m < M) part[((size_t)blockIdx.y * ROWS + m) * N + n] = acc[v];
             }
         }
     }

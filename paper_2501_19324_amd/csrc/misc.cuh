@@ -57,13 +57,15 @@ __global__ void swiglu_kernel(const float* __restrict__ gu, int F, float* __rest
     *reinterpret_cast<float4*>(act + i) = o;
 }
 
-// dst[b][:] = src[src_row[b]][:] for src_row[b] >= 0
+// dst[i][:] = src[src_row[b]][:] for src_row[b] >= 0, where b = i, or b = row_seq[i] (< 0: skipped) when given
 __global__ void gather_rows_kernel(const float* __restrict__ src, const int* __restrict__ src_row, int d,
-                                   float* __restrict__ dst) {
-    const int b = blockIdx.x, r = src_row[b];
+                                   float* __restrict__ dst, const int* __restrict__ row_seq) {
+    const int i = blockIdx.x, b = row_seq ? row_seq[i] : i;
+    if (b < 0) return;
+    const int r = src_row[b];
     if (r < 0) return;
     for (int k = threadIdx.x * 4; k < d; k += blockDim.x * 4)
-        *reinterpret_cast<float4*>(dst + (size_t)b * d + k) = *reinterpret_cast<const float4*>(src + (size_t)r * d + k);
+        *reinterpret_cast<float4*>(dst + (size_t)i * d + k) = *reinterpret_cast<const float4*>(src + (size_t)r * d + k);
 }
 
 // Reward head on hidden rows: out[out_index] = logistic(w_r . RMSNorm(h[row]) + b_r).

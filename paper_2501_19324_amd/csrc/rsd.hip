@@ -122,6 +122,9 @@ struct rsd_ctx {
     int *chosen = nullptr, *steptok_dev = nullptr;
     int *row_seq_dev = nullptr, *row_pos_dev = nullptr, *last_row_dev = nullptr;
     int *row_seq_h = nullptr, *row_pos_h = nullptr, *last_row_h = nullptr, *steptok_h = nullptr;
+    // decode iterations over packed rows: row r stands for sequence dec_seq[r] (-1: unused); 0 rows = one row per sequence
+    int *dec_seq_dev = nullptr, *dec_seq_h = nullptr;
+    int dec_rows = 0;
     // chunked-prefill attention work items: first row and row count (<= 4 rows of one sequence)
     int *item_row0_dev = nullptr, *item_n_dev = nullptr, *item_row0_h = nullptr, *item_n_h = nullptr;
     int n_items = 0;
@@ -139,9 +142,9 @@ struct rsd_ctx {
     bool in_decode_loop = false;
     int cur_phase = RSD_PROBE_DECODE;                        // what run_layers is launching for
     // accounting of the decode loops of the draft and the target
-    struct IterStats { long long iters = 0, seq_iters = 0, kv_read = 0; double ms = 0; hipEvent_t e0 = nullptr, e1 = nullptr; } it[2];
+    struct IterStats { long long iters = 0, seq_iters = 0, kv_read = 0, row_iters = 0; double ms = 0; hipEvent_t e0 = nullptr, e1 = nullptr; } it[2];
     // single-token decode iterations recorded as graphs, one per (model, uniforms, teacher tokens)
-    struct DecodeGraph { int which; const float* u; const int* forced; int mode; hipGraph_t graph; hipGraphExec_t exec; };
+    struct DecodeGraph { int which; const float* u; const int* forced; int mode; int rows; hipGraph_t graph; hipGraphExec_t exec; };
     std::vector<DecodeGraph> graphs;
     hipStream_t cap_st = nullptr;          // recording stream (the caller's may be the null stream)
     bool graphs_ok = true;                 // cleared when recording fails: eager launches from then on
@@ -351,8 +354,9 @@ struct ProbeScope {
 };
 
 RowMap decode_map(rsd_ctx* c, int which) {
-    return RowMap{nullptr, nullptr, c->ds.kv_len + (size_t)which * c->B, c->ds.active};
+    return RowMap{c->dec_rows ? c->dec_seq_dev : nullptr, nullptr, c->ds.kv_len + (size_t)which * c->B, c->ds.active};
 }
+const int* decode_seq(rsd_ctx* c) { return c->dec_rows ? c->dec_seq_dev : nullptr; }
 
 template <typename KT, int HD>
 void launch_attn_decode(rsd_ctx* c, const Model& m, int l, int M, int which) {
@@ -364,7 +368,8 @@ void launch_attn_decode(rsd_ctx* c, const Model& m, int l, int M, int which) {
     case GG:                                                                                                  \
         hipLaunchKernelGGL((attn_decode_kernel<KT, HD, GG>), grid, block, 0, c->st, c->qkv, m.n_qkv, pool_l,  \
                            m.bt_dev, m.max_pages, c->ds.kv_len + (size_t)which * c->B, c->ds.active, m.rope,  \
-                           m.s.n_heads, m.s.n_kv_heads, S, scale, c->att, m.q_dim, c->part_acc, c->part_ml);  \
+                           m.s.n_heads, m.s.n_kv_heads, S, scale, c->att, m.q_dim, c->part_acc, c->part_ml,   \
+                           decode_seq(c));                                                                    \
         break;
     switch (m.G) {
         RSD_ATTN_CASE(1) RSD_ATTN_CASE(2) RSD_ATTN_CASE(4) RSD_ATTN_CASE(6) RSD_ATTN_CASE(7) RSD_ATTN_CASE(8)
@@ -388,7 +393,7 @@ void launch_attn_decode_mfma(rsd_ctx* c, const Model& m, int l, int M, int which
         hipLaunchKernelGGL((attn_decode_mfma_kernel<GG, 8>), grid, dim3(512), 0, c->st, c->qkv, m.n_qkv, pool_l,   \
                            m.bt_dev, m.max_pages, c->ds.kv_len + (size_t)which * c->B, c->ds.active, m.rope,       \
                            m.s.n_heads, m.s.n_kv_heads, S, scale, c->att, m.q_dim, c->part_acc, c->part_ml,        \
-                           halves ? c->xs_h : nullptr, halves ? c->xs_l : nullptr);                                \
+                           halves ? c->xs_h : nullptr, halves ? c->xs_l : nullptr, decode_seq(c));                 \
         break;
     switch (m.G) {
         RSD_ATTN_CASE(1) RSD_ATTN_CASE(2) RSD_ATTN_CASE(4) RSD_ATTN_CASE(6) RSD_ATTN_CASE(7) RSD_ATTN_CASE(8)
@@ -648,15 +653,17 @@ void reward_rows(rsd_ctx* c, Model& m, const float* H, int n, const int* rows, f
 }
 
 // Sample one token per row; with `ap` the chosen token is also appended to its sequence.
+// row_seq (packed rows): u, u_index, active and the appended state are indexed by the sequence of a row
 void sample_rows(rsd_ctx* c, const float* logits, int ld, int V, const float* u, const int* u_index, int u_stride,
                  float temperature, float top_p, int sep_id, float sep_bias, const int* active, int n, int* out,
-                 const AppendArgs& ap) {
+                 const AppendArgs& ap, const int* row_seq = nullptr) {
     for (int r0 = 0; r0 < n; r0 += c->smp_rows) {
         const int rows = std::min(c->smp_rows, n - r0);
-        SampleArgs a{logits + (size_t)r0 * ld, ld, V, u ? u + (size_t)r0 * u_stride : nullptr,
-                     u_index ? u_index + r0 : nullptr, u_stride, temperature, top_p, sep_id, sep_bias,
-                     active ? active + r0 : nullptr, out ? out + r0 : nullptr,
-                     c->smp_pmax, c->smp_pidx, c->smp_hist, c->smp_psum, c->smp_sel};
+        const int s0 = row_seq ? 0 : r0;         // per-sequence arrays keep their base under a row map
+        SampleArgs a{logits + (size_t)r0 * ld, ld, V, u ? u + (size_t)s0 * u_stride : nullptr,
+                     u_index ? u_index + s0 : nullptr, u_stride, temperature, top_p, sep_id, sep_bias,
+                     active ? active + s0 : nullptr, out ? out + r0 : nullptr,
+                     c->smp_pmax, c->smp_pidx, c->smp_hist, c->smp_psum, c->smp_sel, row_seq ? row_seq + r0 : nullptr};
         sample_launch(c->st, a, ap, rows);
     }
 }
@@ -693,21 +700,22 @@ void propose_stash(rsd_ctx* c, int mode) {
 template <typename WT>
 void decode_iter(rsd_ctx* c, int which, const float* u, const int* forced, int mode = 1) {
     Model& m = c->m[which];
-    run_layers<WT>(c, m, c->B, decode_map(c, which), true);
-    lm_head<WT>(c, m, c->h, c->B, c->logits, m.s.vocab);
+    const int M = c->dec_rows ? c->dec_rows : c->B;
+    run_layers<WT>(c, m, M, decode_map(c, which), true);
+    lm_head<WT>(c, m, c->h, M, c->logits, m.s.vocab);
     propose_stash(c, mode);
     sample_rows(c, c->logits, m.s.vocab, m.s.vocab, u, c->ds.ctx_len, c->p.max_ctx, c->p.temperature, c->p.top_p,
-                c->p.sep_id, c->p.sep_logit_bias, c->ds.active, c->B, nullptr, append_args(c, which, forced, mode));
+                c->p.sep_id, c->p.sep_logit_bias, c->ds.active, M, nullptr, append_args(c, which, forced, mode), decode_seq(c));
 }
 
 // The graph of one decode iteration of model `which`, recorded on first use.  Everything an
 // iteration reads that changes between replays (positions, activity flags, step index, block
 // tables, tokens) lives in device memory, so one recording serves every later iteration with the
-// same model, uniforms and teacher arrays.  nullptr: recording is not possible (eager from then on).
+// same model, uniforms, teacher arrays and row count.  nullptr: recording is not possible (eager from then on).
 template <typename WT>
 hipGraphExec_t decode_graph(rsd_ctx* c, int which, const float* u, const int* forced, int mode = 1) {
     for (const auto& g : c->graphs)
-        if (g.which == which && g.u == u && g.forced == forced && g.mode == mode) return g.exec;
+        if (g.which == which && g.u == u && g.forced == forced && g.mode == mode && g.rows == c->dec_rows) return g.exec;
     auto give_up = [&]() { (void)hipGetLastError(); c->graphs_ok = false; return (hipGraphExec_t) nullptr; };
     if (!c->cap_st && hipStreamCreateWithFlags(&c->cap_st, hipStreamNonBlocking) != hipSuccess) return give_up();
     if (hipStreamBeginCapture(c->cap_st, hipStreamCaptureModeThreadLocal) != hipSuccess) return give_up();
@@ -722,7 +730,7 @@ hipGraphExec_t decode_graph(rsd_ctx* c, int which, const float* u, const int* fo
         (void)hipGraphDestroy(graph);
         return give_up();
     }
-    c->graphs.push_back(rsd_ctx::DecodeGraph{which, u, forced, mode, graph, exec});
+    c->graphs.push_back(rsd_ctx::DecodeGraph{which, u, forced, mode, c->dec_rows, graph, exec});
     return exec;
 }
 
@@ -784,6 +792,15 @@ int prefill(rsd_ctx* c, int which, std::vector<Piece> pieces, AfterPass after_pa
     return RSD_OK;
 }
 
+// Rows of a decode iteration that serves n_act of B sequences, or 0 when one row per sequence is as cheap.
+// The sizes are those at which the matrix kernels change: up to 8 rows the exact count (single-row and
+// few-row vector kernels), 32 and 64 (one or two MFMA row tiles of the weight-streaming kernels), then whole
+// 128-row tiles.
+int packed_rows(int n_act, int B) {
+    const int r = n_act <= 8 ? n_act : n_act <= 32 ? 32 : n_act <= 64 ? 64 : (n_act + 127) / 128 * 128;
+    return r < B ? r : 0;
+}
+
 // One stage of token generation (a reasoning step) with an LM model on the
 // currently active sequences.  The first iteration feeds whatever the model
 // has not seen yet (one token, or a catch-up chunk), the rest one token each.
@@ -812,6 +829,23 @@ int gen_stage(rsd_ctx* c, int which, const float* u, const int* forced, int mode
             return fail(c, RSD_ESTATE, "internal: row %d may grow to %d tokens in model %d but owns %d pages", pc.b, room, which,
                         m.n_pages[pc.b]);
     }
+    // A stage that only some sequences take part in (the target's, after the reward model has accepted the
+    // others' steps) runs its iterations over packed rows: every launch then costs what the rows in use cost, not
+    // what the batch costs.  The row count is rounded up to the next size at which the matrix kernels change
+    // (few counts, so few recorded graphs); unused rows are marked -1.  Sequences that finish their step early
+    // keep their row until the stage ends.
+    struct PackScope {
+        rsd_ctx* c;
+        ~PackScope() { c->dec_rows = 0; }
+    } pack_scope{c};
+    c->dec_rows = mode == 1 ? packed_rows(n_act, B) : 0;
+    if (c->dec_rows) {
+        int r = 0;
+        for (const Piece& pc : pieces) c->dec_seq_h[r++] = pc.b;
+        for (; r < c->dec_rows; ++r) c->dec_seq_h[r] = -1;
+        HIPCHK(c, hipMemcpyAsync(c->dec_seq_dev, c->dec_seq_h, c->dec_rows * sizeof(int), hipMemcpyHostToDevice, c->st));
+    }
+    const int M = c->dec_rows ? c->dec_rows : B;
     int iters = 0;
     // decode-loop accounting (steps of the reasoning loop only): contexts before the stage
     const bool count = mode == 1 && which < 2;
@@ -820,14 +854,16 @@ int gen_stage(rsd_ctx* c, int which, const float* u, const int* forced, int mode
     const std::vector<int> was_active(c->active(), c->active() + B);
     if (!all_single) {
         int rc = prefill<WT>(c, which, pieces, [&](const std::vector<Piece>&, const std::vector<int>&, int) {
-            hipLaunchKernelGGL(gather_rows_kernel, dim3(B), dim3(256), 0, c->st, c->h, c->last_row_dev, m.s.d_model, c->hl);
+            hipLaunchKernelGGL(gather_rows_kernel, dim3(M), dim3(256), 0, c->st, c->h, c->last_row_dev, m.s.d_model, c->hl,
+                               decode_seq(c));
             return RSD_OK;
         });
         if (rc != RSD_OK) return rc;
-        lm_head<WT>(c, m, c->hl, B, c->logits, m.s.vocab);
+        lm_head<WT>(c, m, c->hl, M, c->logits, m.s.vocab);
         propose_stash(c, mode);
         sample_rows(c, c->logits, m.s.vocab, m.s.vocab, u, c->ds.ctx_len, c->p.max_ctx, c->p.temperature, c->p.top_p,
-                    c->p.sep_id, c->p.sep_logit_bias, c->ds.active, B, nullptr, append_args(c, which, forced, mode));
+                    c->p.sep_id, c->p.sep_logit_bias, c->ds.active, M, nullptr, append_args(c, which, forced, mode),
+                    decode_seq(c));
         iters = 1;
     }
     const int first = iters;
@@ -873,6 +909,7 @@ int gen_stage(rsd_ctx* c, int which, const float* u, const int* forced, int mode
             HIPCHK(c, hipEventElapsedTime(&ms, is.e0, is.e1));
             is.ms += ms;
             is.iters += iters - first;
+            is.row_iters += (long long)(iters - first) * M;
             for (int b = 0; b < B; ++b) {
                 if (!was_active[b]) continue;
                 // tokens this sequence sampled inside the loop; its j-th one attends to ctx0 + first + j keys
@@ -1011,7 +1048,8 @@ int sd_stage(rsd_ctx* c) {
                 for (int j = 0; j < cnt; ++j) rows[n_rows++] = first_row[i] + (pc.end - pc.start) - cnt + j;
             }
             HIPCHK(c, hipMemcpyAsync(c->sd_rows_dev, c->sd_rows_h, ((size_t)B * (k + 2)) * sizeof(int), hipMemcpyHostToDevice, c->st));
-            hipLaunchKernelGGL(gather_rows_kernel, dim3(n_rows), dim3(256), 0, c->st, c->h, c->sd_rows_dev, d, c->sd_h);
+            hipLaunchKernelGGL(gather_rows_kernel, dim3(n_rows), dim3(256), 0, c->st, c->h, c->sd_rows_dev, d, c->sd_h,
+                               (const int*)nullptr);
             return RSD_OK;
         };
         if ((rc = prefill<WT>(c, RSD_TARGET, pieces, after))) return rc;
@@ -1119,7 +1157,7 @@ void rsd_destroy(rsd_ctx* c) {
                    c->sd_ws[0].pmax, c->sd_ws[0].pidx, c->sd_ws[0].hist, c->sd_ws[0].psum, c->sd_ws[0].sel,
                    c->sd_ws[1].pmax, c->sd_ws[1].pidx, c->sd_ws[1].hist, c->sd_ws[1].psum, c->sd_ws[1].sel, c->h, c->xn, c->qkv, c->att, c->gu, c->act,
                    c->part_acc, c->part_ml, c->part_k, c->xs_h, c->xs_l, c->smp_pmax, c->smp_pidx, c->smp_hist, c->smp_psum, c->smp_sel, c->hl, c->xl, c->logits, c->tmp_reward, c->chosen, c->steptok_dev,
-                   c->row_seq_dev, c->row_pos_dev, c->last_row_dev, c->item_row0_dev, c->item_n_dev, c->bon_copy_dev, c->bon_src_dev};
+                   c->row_seq_dev, c->row_pos_dev, c->last_row_dev, c->item_row0_dev, c->item_n_dev, c->bon_copy_dev, c->bon_src_dev, c->dec_seq_dev};
     for (void* p : dev) if (p) (void)hipFree(p);
     for (auto& q : c->probe)
         for (hipEvent_t e : q.ev) (void)hipEventDestroy(e);
@@ -1130,7 +1168,7 @@ void rsd_destroy(rsd_ctx* c) {
     for (auto& g : c->graphs) { (void)hipGraphExecDestroy(g.exec); (void)hipGraphDestroy(g.graph); }
     if (c->cap_st) (void)hipStreamDestroy(c->cap_st);
     void* pin[] = {c->sb, c->sd_rows_h, c->sd_aux_h, c->item_row0_h, c->item_n_h, c->row_seq_h, c->row_pos_h, c->last_row_h, c->steptok_h, c->poll_h,
-                   c->bon_copy_h, c->bon_src_h};
+                   c->bon_copy_h, c->bon_src_h, c->dec_seq_h};
     for (void* p : pin) if (p) (void)hipHostFree(p);
     delete c;
 }
@@ -1290,6 +1328,7 @@ int rsd_init(rsd_ctx** out, const rsd_model_shape shape[3], const rsd_weights w[
     HIPCHK(c, dev_alloc(&c->row_seq_dev, R));
     HIPCHK(c, dev_alloc(&c->row_pos_dev, R));
     HIPCHK(c, dev_alloc(&c->last_row_dev, (size_t)B));
+    HIPCHK(c, dev_alloc(&c->dec_seq_dev, (size_t)B));
     HIPCHK(c, dev_alloc(&c->item_row0_dev, R));
     HIPCHK(c, dev_alloc(&c->item_n_dev, R));
     HIPCHK(c, pin_alloc(&c->item_row0_h, R));
@@ -1297,6 +1336,7 @@ int rsd_init(rsd_ctx** out, const rsd_model_shape shape[3], const rsd_weights w[
     HIPCHK(c, pin_alloc(&c->row_seq_h, R));
     HIPCHK(c, pin_alloc(&c->row_pos_h, R));
     HIPCHK(c, pin_alloc(&c->last_row_h, (size_t)B));
+    HIPCHK(c, pin_alloc(&c->dec_seq_h, (size_t)B));
     HIPCHK(c, pin_alloc(&c->steptok_h, (size_t)B * p->step_cap));
     HIPCHK(c, pin_alloc(&c->poll_h, 4));
     if (bon) {
@@ -2025,7 +2065,14 @@ int rsd_iter_stats(rsd_ctx* c, int32_t model, int64_t* iterations, double* gpu_m
     if (gpu_ms) *gpu_ms = is.ms;
     if (seq_iterations) *seq_iterations = is.seq_iters;
     if (kv_tokens_read) *kv_tokens_read = is.kv_read;
-    if (reset) { is.iters = is.seq_iters = is.kv_read = 0; is.ms = 0; }
+    if (reset) { is.iters = is.seq_iters = is.kv_read = is.row_iters = 0; is.ms = 0; }
+    return RSD_OK;
+}
+
+int rsd_iter_rows(rsd_ctx* c, int32_t model, int64_t* row_iterations) {
+    if (!c || !row_iterations) return fail(c, RSD_EINVAL, "null argument");
+    if (model != RSD_DRAFT && model != RSD_TARGET) return fail(c, RSD_EINVAL, "decode loops exist for the draft and the target only");
+    *row_iterations = c->it[model].row_iters;
     return RSD_OK;
 }
 

@@ -73,7 +73,16 @@ struct SampleArgs {
     int* out;                                            // nullable when the result is appended
     // workspace, per row: pmax[SMP_NB], pidx[SMP_NB], hist[3][SMP_BINS], psum[SMP_NB], sel[8]
     float* pmax; int* pidx; u64_t* hist; u64_t* psum; u64_t* sel;
+    // nullable: packed rows.  Row r then stands for sequence row_seq[r] (< 0: unused row); u, u_index, active and
+    // the appended state are indexed by the sequence, logits, out and the workspace by the row
+    const int* row_seq;
 };
+// the sequence of a row, or -1 when the row is unused or its sequence is not active
+__device__ __forceinline__ int smp_seq(const SampleArgs& a, int row) {
+    const int s = a.row_seq ? a.row_seq[row] : row;
+    if (s < 0 || (a.active && !a.active[s])) return -1;
+    return s;
+}
 
 // what phase F does with the chosen token besides (or instead of) storing it
 struct AppendArgs {
@@ -123,7 +132,8 @@ __device__ __forceinline__ int smp_find_bin(const u64_t* hist, u64_t thr, u64_t&
 // ---- phase A: per-block max of x (sampling) or arg max of the biased logits (greedy)
 __global__ __launch_bounds__(SMP_T) void sample_max_kernel(SampleArgs a) {
     const int row = blockIdx.y, j = blockIdx.x, tid = threadIdx.x;
-    if (a.active && !a.active[row]) return;
+    const int seq = smp_seq(a, row);
+    if (seq < 0) return;
     const float* lg = a.logits + (size_t)row * a.ld;
     const int span = (a.V + SMP_NB - 1) / SMP_NB, s0 = j * span, s1 = min(a.V, s0 + span);
     __shared__ float fred[4];
@@ -154,7 +164,8 @@ __global__ __launch_bounds__(SMP_T) void sample_max_kernel(SampleArgs a) {
 template <int LEVEL>
 __global__ __launch_bounds__(SMP_T) void sample_hist_kernel(SampleArgs a) {
     const int row = blockIdx.y, j = blockIdx.x, tid = threadIdx.x;
-    if (a.active && !a.active[row]) return;
+    const int seq = smp_seq(a, row);
+    if (seq < 0) return;
     const float* lg = a.logits + (size_t)row * a.ld;
     const int span = (a.V + SMP_NB - 1) / SMP_NB, s0 = j * span, s1 = min(a.V, s0 + span);
     __shared__ u64_t lh[SMP_BINS];
@@ -209,7 +220,8 @@ __global__ __launch_bounds__(SMP_T) void sample_hist_kernel(SampleArgs a) {
 // ---- phase E: tau and the draw target; per-block mass of the nucleus
 __global__ __launch_bounds__(SMP_T) void sample_mass_kernel(SampleArgs a) {
     const int row = blockIdx.y, j = blockIdx.x, tid = threadIdx.x;
-    if (a.active && !a.active[row]) return;
+    const int seq = smp_seq(a, row);
+    if (seq < 0) return;
     const float* lg = a.logits + (size_t)row * a.ld;
     const int span = (a.V + SMP_NB - 1) / SMP_NB, s0 = j * span, s1 = min(a.V, s0 + span);
     __shared__ u64_t wtot[4];
@@ -224,7 +236,7 @@ __global__ __launch_bounds__(SMP_T) void sample_mass_kernel(SampleArgs a) {
     const uint32_t tau = (uint32_t)sel[4] | (uint32_t)bin;
     if (j == 0 && tid == 0) {
         const u64_t zs = above + hist[2 * SMP_BINS + bin];        // ties at tau are all inside
-        const float uu = a.u[(size_t)row * a.u_stride + (a.u_index ? a.u_index[row] : 0)];
+        const float uu = a.u[(size_t)seq * a.u_stride + (a.u_index ? a.u_index[seq] : 0)];
         sel[5] = tau;
         sel[6] = (u64_t)floor((double)uu * (double)zs);           // running > u * Z  <=>  running > floor(u * Z)
     }
@@ -243,7 +255,8 @@ __global__ __launch_bounds__(SMP_T) void sample_mass_kernel(SampleArgs a) {
 // ---- phase F: one block per row: pick the token, append it, clear the histograms
 __global__ __launch_bounds__(SMP_T) void sample_finish_kernel(SampleArgs a, AppendArgs ap) {
     const int row = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    if (a.active && !a.active[row]) return;
+    const int seq = smp_seq(a, row);
+    if (seq < 0) return;
     __shared__ u64_t wtot[4];
     __shared__ float fred[4];
     __shared__ int s_tok, s_blk;
@@ -326,7 +339,7 @@ __global__ __launch_bounds__(SMP_T) void sample_finish_kernel(SampleArgs a, Appe
     if (!ap.enabled) return;
     // append the token and decide whether the step of this sequence goes on
     const SeqState& st = ap.st;
-    const int b = row;
+    const int b = seq;
     const int pos = st.ctx_len[b];
     if (ap.enabled == 2) {
         // a proposal: written behind the committed tokens and recorded as the n-th proposal of the

@@ -133,6 +133,12 @@ def run_and_compare(gpu, tiny, w, n_steps=None, models=None, merge=0):
     for b in range(w.batch):
         n = st["ctx_len"][b]
         assert list(st["tokens"][b, :n]) == refs[b]["tokens"][:n]
+    # the target's stages serve the rejected sequences only: their iterations run over packed rows, never
+    # fewer rows than sequences in them and (once a step was accepted somewhere) fewer than the batch
+    it = R.rsd_iter_stats(s.ctx, R.RSD_TARGET)
+    assert it["seq_iterations"] <= it["row_iterations"] <= w.batch * it["iterations"]
+    if n_acc >= 2 and n_rej >= 2 and merge == 0 and 4 <= w.batch <= 8 and it["iterations"]:
+        assert it["row_iterations"] < w.batch * it["iterations"], it
     s.close()
     return n_acc, n_rej
 
