@@ -788,16 +788,6 @@ static void gemm_launch(hipStream_t st, int epi, const float* W, int N, int K, c
 // line-wise writes and the operand reads are conflict-free without padding.  While one stage is
 // multiplied the next one is already on its way from global memory in registers.  gridDim.z > 1 cuts K into
 // slices whose partial tiles go to part[z][M][N] (finished by rows_finish_kernel).
-#ifndef RSD_TILE_W_NT
-#define RSD_TILE_W_NT 0
-#endif
-__device__ __forceinline__ u32x4_t load_tile_w16(const bf16_t* p) {
-#if RSD_TILE_W_NT
-    return __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
-#else
-    return *reinterpret_cast<const u32x4_t*>(p);
-#endif
-}
 template <int EPI, int BM>
 __global__ __launch_bounds__(BM * 2, BM == 128 ? 2 : 1) void gemm_tile_kernel(const bf16_t* __restrict__ W, int N, int K,
                                                            const uint16_t* __restrict__ Xh,
@@ -849,11 +839,11 @@ __global__ __launch_bounds__(BM * 2, BM == 128 ? 2 : 1) void gemm_tile_kernel(co
         R.h1 = *reinterpret_cast<const u32x4_t*>(ah1 + k0_);                                     \
         R.l0 = *reinterpret_cast<const u32x4_t*>(al0 + k0_);                                     \
         R.l1 = *reinterpret_cast<const u32x4_t*>(al1 + k0_);                                     \
-        R.b0 = load_tile_w16(b0 + k0_);                                                          \
-        R.b1 = load_tile_w16(b1 + k0_);                                                          \
+        R.b0 = *reinterpret_cast<const u32x4_t*>(b0 + k0_);                                      \
+        R.b1 = *reinterpret_cast<const u32x4_t*>(b1 + k0_);                                      \
         if (BM == 128) {                                                                         \
-            R.b2 = load_tile_w16(b2 + k0_);                                                      \
-            R.b3 = load_tile_w16(b3 + k0_);                                                      \
+            R.b2 = *reinterpret_cast<const u32x4_t*>(b2 + k0_);                                  \
+            R.b3 = *reinterpret_cast<const u32x4_t*>(b3 + k0_);                                  \
         }                                                                                        \
     }
 #define RSD_STAGE(buf, R)                                                                        \
