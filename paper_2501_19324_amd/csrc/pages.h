@@ -83,3 +83,18 @@ struct PageTable {
         return true;
     }
 };
+
+// Rows of a decode iteration that serves n_act of B sequences, or 0 when one row per sequence is as cheap.
+// The sizes are those at which the matrix kernels change: up to 8 rows the exact count (single-row and
+// few-row vector kernels), 32 and 64 (one or two MFMA row tiles of the weight-streaming kernels), then whole
+// 128-row tiles.
+inline int packed_rows(int n_act, int B) {
+    const int r = n_act <= 8 ? n_act : n_act <= 32 ? 32 : n_act <= 64 ? 64 : (n_act + 127) / 128 * 128;
+    return r < B ? r : 0;
+}
+// The row map of such an iteration: the taking-part sequences in ascending order, then -1 for the unused rows.
+inline void fill_packed_rows(const std::vector<int>& seqs, int rows, int* row_seq) {
+    int r = 0;
+    for (int b : seqs) row_seq[r++] = b;
+    for (; r < rows; ++r) row_seq[r] = -1;
+}

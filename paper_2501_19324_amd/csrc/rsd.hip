@@ -792,15 +792,6 @@ int prefill(rsd_ctx* c, int which, std::vector<Piece> pieces, AfterPass after_pa
     return RSD_OK;
 }
 
-// Rows of a decode iteration that serves n_act of B sequences, or 0 when one row per sequence is as cheap.
-// The sizes are those at which the matrix kernels change: up to 8 rows the exact count (single-row and
-// few-row vector kernels), 32 and 64 (one or two MFMA row tiles of the weight-streaming kernels), then whole
-// 128-row tiles.
-int packed_rows(int n_act, int B) {
-    const int r = n_act <= 8 ? n_act : n_act <= 32 ? 32 : n_act <= 64 ? 64 : (n_act + 127) / 128 * 128;
-    return r < B ? r : 0;
-}
-
 // One stage of token generation (a reasoning step) with an LM model on the
 // currently active sequences.  The first iteration feeds whatever the model
 // has not seen yet (one token, or a catch-up chunk), the rest one token each.
@@ -840,9 +831,9 @@ int gen_stage(rsd_ctx* c, int which, const float* u, const int* forced, int mode
     } pack_scope{c};
     c->dec_rows = mode == 1 ? packed_rows(n_act, B) : 0;
     if (c->dec_rows) {
-        int r = 0;
-        for (const Piece& pc : pieces) c->dec_seq_h[r++] = pc.b;
-        for (; r < c->dec_rows; ++r) c->dec_seq_h[r] = -1;
+        std::vector<int> seqs;
+        for (const Piece& pc : pieces) seqs.push_back(pc.b);
+        fill_packed_rows(seqs, c->dec_rows, c->dec_seq_h);
         HIPCHK(c, hipMemcpyAsync(c->dec_seq_dev, c->dec_seq_h, c->dec_rows * sizeof(int), hipMemcpyHostToDevice, c->st));
     }
     const int M = c->dec_rows ? c->dec_rows : B;

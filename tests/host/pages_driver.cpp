@@ -141,6 +141,28 @@ int main() {
         check(t);
         REQUIRE((int)t.free_list.size() == 3);
     }
+    // packed rows of a partial stage: never fewer rows than sequences, never as many as the batch, one of the
+    // sizes the matrix kernels distinguish, monotone in the number of sequences; the map lists the sequences
+    // in order and marks the rest unused
+    for (int B : {1, 2, 4, 8, 9, 16, 33, 64, 65, 192, 256, 300}) {
+        int last = 0;
+        for (int n = 1; n <= B; ++n) {
+            const int r = packed_rows(n, B);
+            REQUIRE(r == 0 || (r >= n && r < B));
+            REQUIRE(r == 0 || r <= 8 || r == 32 || r == 64 || r % 128 == 0);
+            if (r && last) REQUIRE(r >= last);
+            if (n <= 8 && n < B) REQUIRE(r == n);
+            if (n == B) REQUIRE(r == 0);
+            if (r) last = r;
+            if (r) {
+                std::vector<int> seqs, map(r, 12345);
+                for (int b = 0; b < B && (int)seqs.size() < n; ++b) if ((b * 7 + n) % 3 != 0 || B - b <= n - (int)seqs.size()) seqs.push_back(b);
+                REQUIRE((int)seqs.size() == n);
+                fill_packed_rows(seqs, r, map.data());
+                for (int i = 0; i < r; ++i) REQUIRE(map[i] == (i < n ? seqs[i] : -1));
+            }
+        }
+    }
     for (unsigned seed = 1; seed <= 300; ++seed) { rsd_pattern(seed); bon_pattern(seed); }
     std::printf("pages ok\n");
     return 0;

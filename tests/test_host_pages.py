@@ -1,6 +1,7 @@
 """Host-side safety net: the page bookkeeping of the paged KV cache (csrc/pages.h, the host-only part
 of the library's allocator) built for the CPU with AddressSanitizer and UndefinedBehaviorSanitizer and
-driven through reserve / roll back / share / exhaust sequences (tests/host/pages_driver.cpp)."""
+driven through reserve / roll back / share / exhaust sequences; the row packing of partial stages is checked there too
+(tests/host/pages_driver.cpp)."""
 import os
 import subprocess
 
