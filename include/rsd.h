@@ -362,6 +362,21 @@ int rsd_iter_stats(rsd_ctx *c, int32_t model, int64_t *iterations, double *gpu_m
  * Cleared together with rsd_iter_stats' counters.  Host output. */
 int rsd_iter_rows(rsd_ctx *c, int32_t model, int64_t *row_iterations);
 
+/* Diagnostic for the paged caches (Section 3 serves the models from a paged KV cache; the kernels index the block
+ * tables without checks): would a pass over n rows, row i standing for position pos_host[i] of sequence
+ * seq_host[i] (HOST arrays), stay inside what the device-side tables of `model` give those sequences?  Checked
+ * by a kernel that reads nothing it has not bounds-checked itself: the sequence index lies in the batch, the
+ * position in [0, max_ctx), the sequence owns the pages 0 .. pos / 16, and each of those table entries names a
+ * page of the pool.  Returns RSD_OK, or RSD_ESTATE with the first offending row in rsd_last_error.  Waits for the
+ * stream.  n in 1 .. 8192.
+ *
+ * A library compiled with -DRSD_DEBUG (rsd_debug_build() returns 1; the package builds it as librsd_debug.so)
+ * runs the same check before every chunked pass and before every single-token iteration of every entry point,
+ * on the rows and the device-side positions that pass is about to use, waits for the verdict and returns
+ * RSD_ESTATE instead of launching a pass that would leave its pages; it records no graphs.  Nothing traps. */
+int rsd_check_rows(rsd_ctx *c, int32_t model, const int32_t *seq_host, const int32_t *pos_host, int32_t n);
+int rsd_debug_build(void);
+
 /* Timing of the decode attention kernel alone (grouped-query attention of one new token per sequence over
  * the paged cache, rotary embedding and cache write included), for roofline reports.  Sequence b gets a
  * context of ctx_len_host[b] tokens (1 .. max_ctx; HOST array [B]) in `model`'s cache, whose pool is

@@ -17,7 +17,7 @@ __all__ = ["RSD_OK", "RSD_EINVAL", "RSD_ENOMEM", "RSD_ESTATE", "RSD_EHIP", "RSD_
            "RsdError", "Context", "load_library", "rsd_init", "rsd_set_prompts", "rsd_set_uniforms",
            "rsd_set_criterion", "rsd_step", "rsd_generate", "rsd_export_state", "rsd_export_pages",
            "rsd_set_teacher", "rsd_export_sampled", "rsd_forward", "rsd_sample", "rsd_stage_ms", "rsd_decode_stats", "rsd_destroy",
-           "rsd_probe_start", "rsd_probe_read", "rsd_iter_stats", "rsd_iter_rows", "rsd_probe_attention", "rsd_sample_static",
+           "rsd_probe_start", "rsd_probe_read", "rsd_iter_stats", "rsd_iter_rows", "rsd_check_rows", "rsd_debug_build", "rsd_probe_attention", "rsd_sample_static",
            "rsd_bon_step", "rsd_bon_generate", "rsd_bon_stats", "EXPORTED_SYMBOLS"]
 
 RSD_OK, RSD_EINVAL, RSD_ENOMEM, RSD_ESTATE, RSD_EHIP = 0, -1, -2, -3, -4
@@ -26,7 +26,7 @@ RSD_MERGE_NONE, RSD_MERGE_DRAFT, RSD_MERGE_TARGET = 0, 1, 2
 EXPORTED_SYMBOLS = ["rsd_init", "rsd_set_prompts", "rsd_set_uniforms", "rsd_set_criterion", "rsd_step",
                     "rsd_generate", "rsd_export_state", "rsd_export_pages", "rsd_set_teacher",
                     "rsd_export_sampled", "rsd_set_teacher_sd", "rsd_export_proposed", "rsd_set_uniforms_sd", "rsd_sd_verify", "rsd_forward", "rsd_sample", "rsd_stage_ms", "rsd_decode_stats", "rsd_probe_start", "rsd_probe_read",
-                    "rsd_iter_stats", "rsd_iter_rows", "rsd_probe_attention", "rsd_sample_static", "rsd_bon_step", "rsd_bon_generate", "rsd_bon_stats",
+                    "rsd_iter_stats", "rsd_iter_rows", "rsd_check_rows", "rsd_debug_build", "rsd_probe_attention", "rsd_sample_static", "rsd_bon_step", "rsd_bon_generate", "rsd_bon_stats",
                     "rsd_last_error", "rsd_destroy"]
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "librsd.so")
 
@@ -383,6 +383,18 @@ def rsd_iter_stats(ctx: Context, model: int, reset: bool = False) -> dict:
     ctx.check(load_library().rsd_iter_stats(ctx.handle, C.c_int32(model), C.byref(it), C.byref(ms), C.byref(si), C.byref(kv),
                                             C.c_int32(int(reset))))
     return dict(iterations=it.value, gpu_ms=ms.value, seq_iterations=si.value, kv_tokens_read=kv.value, row_iterations=rows)
+
+
+def rsd_check_rows(ctx: Context, model: int, seq: np.ndarray, pos: np.ndarray) -> None:
+    """Raises RsdError (RSD_ESTATE) when a pass over rows (seq[i], pos[i]) would leave the pages of ``model``."""
+    s = np.ascontiguousarray(seq, dtype=np.int32)
+    p = np.ascontiguousarray(pos, dtype=np.int32)
+    assert s.shape == p.shape and s.ndim == 1
+    ctx.check(load_library().rsd_check_rows(ctx.handle, C.c_int32(model), _np_ptr(s), _np_ptr(p), C.c_int32(s.size)))
+
+
+def rsd_debug_build() -> bool:
+    return bool(load_library().rsd_debug_build())
 
 
 def rsd_probe_attention(ctx: Context, model: int, ctx_len: np.ndarray, reps: int) -> float:

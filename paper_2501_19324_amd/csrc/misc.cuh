@@ -68,6 +68,38 @@ __global__ void gather_rows_kernel(const float* __restrict__ src, const int* __r
         *reinterpret_cast<float4*>(dst + (size_t)i * d + k) = *reinterpret_cast<const float4*>(src + (size_t)r * d + k);
 }
 
+// Diagnostic: do the page tables on the device cover what a pass over these rows will touch?  A row in use at
+// (seq, pos) reads the pages 0 .. pos / RSD_PAGE of its sequence and writes into the last of them, so the
+// sequence must own that many pages and every entry up to there must name a page of the pool.  The first
+// violation found is recorded in err[0..3] = (code, row, seq, pos); the kernel itself reads nothing it has not
+// bounds-checked first.  Codes: 1 sequence index outside the batch, 2 position outside [0, max_ctx), 3 position
+// beyond the pages the sequence owns (or more pages than a table row holds), 4 table entry outside the pool.
+__global__ void check_rows_kernel(RowMap rm, int M, int B, const int* __restrict__ block_table, int max_pages,
+                                  const int* __restrict__ n_pages, int pool_pages, int max_ctx, int* __restrict__ err) {
+    const int r = blockIdx.x * blockDim.x + threadIdx.x;
+    if (r >= M) return;
+    int seq, pos, bad = 0;
+    if (rm.row_seq) {                    // (row_lookup indexes kv_len / active by the sequence: check it first)
+        seq = rm.row_seq[r];
+        if (!rm.row_pos && seq < 0) return;
+        if (seq < 0 || seq >= B) { bad = 1; pos = -1; }
+    }
+    if (!bad) {
+        if (!row_lookup(rm, r, seq, pos)) return;
+        if (pos < 0 || pos >= max_ctx) bad = 2;
+        else {
+            const int np = n_pages[seq], last = pos / RSD_PAGE;
+            if (np > max_pages || last >= np) bad = 3;
+            else
+                for (int i = 0; i <= last; ++i) {
+                    const int pg = block_table[(size_t)seq * max_pages + i];
+                    if (pg < 0 || pg >= pool_pages) { bad = 4; break; }
+                }
+        }
+    }
+    if (bad && atomicCAS(&err[0], 0, bad) == 0) { err[1] = r; err[2] = seq; err[3] = pos; }
+}
+
 // Reward head on hidden rows: out[out_index] = logistic(w_r . RMSNorm(h[row]) + b_r).
 // rows == nullptr: row i -> out[i].  rows[i] < 0: skipped.
 template <typename WT>

@@ -125,6 +125,8 @@ struct rsd_ctx {
     // decode iterations over packed rows: row r stands for sequence dec_seq[r] (-1: unused); 0 rows = one row per sequence
     int *dec_seq_dev = nullptr, *dec_seq_h = nullptr;
     int dec_rows = 0;
+    // table check (rsd_check_rows; before every pass in a build with RSD_DEBUG): page counts and the error record
+    int *chk_n_pages_dev = nullptr, *chk_err_dev = nullptr, *chk_h = nullptr;
     // chunked-prefill attention work items: first row and row count (<= 4 rows of one sequence)
     int *item_row0_dev = nullptr, *item_n_dev = nullptr, *item_row0_h = nullptr, *item_n_h = nullptr;
     int n_items = 0;
@@ -293,6 +295,35 @@ int pull_state(rsd_ctx* c) {
     HIPCHK(c, hipStreamSynchronize(c->st));
     return RSD_OK;
 }
+
+// Runs the table check for M rows of a pass through model `which` and waits for its verdict: RSD_ESTATE (with
+// the first offending row in the message) when a kernel of that pass would index outside what its row owns.
+int check_rows(rsd_ctx* c, int which, const RowMap& rm, int M) {
+    Model& m = c->m[which];
+    if (M <= 0 || !m.bt_dev) return RSD_OK;
+    int rc = upload_tables(c, m);
+    if (rc) return rc;
+    std::copy(m.n_pages.begin(), m.n_pages.begin() + c->B, c->chk_h + 4);
+    c->chk_h[0] = c->chk_h[1] = c->chk_h[2] = c->chk_h[3] = 0;
+    HIPCHK(c, hipMemcpyAsync(c->chk_err_dev, c->chk_h, 4 * sizeof(int), hipMemcpyHostToDevice, c->st));
+    HIPCHK(c, hipMemcpyAsync(c->chk_n_pages_dev, c->chk_h + 4, c->B * sizeof(int), hipMemcpyHostToDevice, c->st));
+    hipLaunchKernelGGL(check_rows_kernel, dim3(ceil_div(M, 256)), dim3(256), 0, c->st, rm, M, c->B, m.bt_dev, m.max_pages,
+                       c->chk_n_pages_dev, m.pool_pages, c->p.max_ctx, c->chk_err_dev);
+    HIPCHK(c, hipMemcpyAsync(c->chk_h, c->chk_err_dev, 4 * sizeof(int), hipMemcpyDeviceToHost, c->st));
+    HIPCHK(c, hipStreamSynchronize(c->st));
+    if (c->chk_h[0]) {
+        static const char* what[] = {"", "sequence index outside the batch", "position outside the context limit",
+                                     "position beyond the pages its sequence owns", "block-table entry outside the pool"};
+        return fail(c, RSD_ESTATE, "table check, model %d: row %d (sequence %d, position %d): %s", which, c->chk_h[1],
+                    c->chk_h[2], c->chk_h[3], what[std::min(std::max(c->chk_h[0], 0), 4)]);
+    }
+    return RSD_OK;
+}
+#ifdef RSD_DEBUG
+constexpr bool kDebugChecks = true;
+#else
+constexpr bool kDebugChecks = false;
+#endif
 
 // ------------------------------------------------------------------ forward passes
 template <typename KT, int HD>
@@ -784,6 +815,10 @@ int prefill(rsd_ctx* c, int which, std::vector<Piece> pieces, AfterPass after_pa
         c->pf_max_end = 0;
         for (const Piece& pc : pass) c->pf_max_end = std::max(c->pf_max_end, pc.end);
         RowMap rm{c->row_seq_dev, c->row_pos_dev, nullptr, nullptr};
+        if (kDebugChecks) {
+            const int rc = check_rows(c, which, rm, M);
+            if (rc != RSD_OK) return rc;
+        }
         run_layers<WT>(c, m, M, rm, false);
         const int rc = after_pass(pass, first_row, M);
         if (rc != RSD_OK) return rc;
@@ -869,8 +904,12 @@ int gen_stage(rsd_ctx* c, int which, const float* u, const int* forced, int mode
                         (q.iters++ % q.stride) == 0;
             timed |= q.iter_on;
         }
+        if (kDebugChecks) {      // the positions live on the device: every iteration is checked, none is replayed
+            const int rc = check_rows(c, which, decode_map(c, which), M);
+            if (rc != RSD_OK) { c->in_decode_loop = false; return rc; }
+        }
         hipGraphExec_t exec = nullptr;
-        if (c->p.use_graphs && c->graphs_ok && !timed && c->decode_warm[which])
+        if (!kDebugChecks && c->p.use_graphs && c->graphs_ok && !timed && c->decode_warm[which])
             exec = decode_graph<WT>(c, which, u, forced, mode);
         if (exec) {
             const hipError_t e = hipGraphLaunch(exec, c->st);
@@ -1148,7 +1187,7 @@ void rsd_destroy(rsd_ctx* c) {
                    c->sd_ws[0].pmax, c->sd_ws[0].pidx, c->sd_ws[0].hist, c->sd_ws[0].psum, c->sd_ws[0].sel,
                    c->sd_ws[1].pmax, c->sd_ws[1].pidx, c->sd_ws[1].hist, c->sd_ws[1].psum, c->sd_ws[1].sel, c->h, c->xn, c->qkv, c->att, c->gu, c->act,
                    c->part_acc, c->part_ml, c->part_k, c->xs_h, c->xs_l, c->smp_pmax, c->smp_pidx, c->smp_hist, c->smp_psum, c->smp_sel, c->hl, c->xl, c->logits, c->tmp_reward, c->chosen, c->steptok_dev,
-                   c->row_seq_dev, c->row_pos_dev, c->last_row_dev, c->item_row0_dev, c->item_n_dev, c->bon_copy_dev, c->bon_src_dev, c->dec_seq_dev};
+                   c->row_seq_dev, c->row_pos_dev, c->last_row_dev, c->item_row0_dev, c->item_n_dev, c->bon_copy_dev, c->bon_src_dev, c->dec_seq_dev, c->chk_n_pages_dev, c->chk_err_dev};
     for (void* p : dev) if (p) (void)hipFree(p);
     for (auto& q : c->probe)
         for (hipEvent_t e : q.ev) (void)hipEventDestroy(e);
@@ -1159,7 +1198,7 @@ void rsd_destroy(rsd_ctx* c) {
     for (auto& g : c->graphs) { (void)hipGraphExecDestroy(g.exec); (void)hipGraphDestroy(g.graph); }
     if (c->cap_st) (void)hipStreamDestroy(c->cap_st);
     void* pin[] = {c->sb, c->sd_rows_h, c->sd_aux_h, c->item_row0_h, c->item_n_h, c->row_seq_h, c->row_pos_h, c->last_row_h, c->steptok_h, c->poll_h,
-                   c->bon_copy_h, c->bon_src_h, c->dec_seq_h};
+                   c->bon_copy_h, c->bon_src_h, c->dec_seq_h, c->chk_h};
     for (void* p : pin) if (p) (void)hipHostFree(p);
     delete c;
 }
@@ -1320,6 +1359,8 @@ int rsd_init(rsd_ctx** out, const rsd_model_shape shape[3], const rsd_weights w[
     HIPCHK(c, dev_alloc(&c->row_pos_dev, R));
     HIPCHK(c, dev_alloc(&c->last_row_dev, (size_t)B));
     HIPCHK(c, dev_alloc(&c->dec_seq_dev, (size_t)B));
+    HIPCHK(c, dev_alloc(&c->chk_n_pages_dev, (size_t)B));
+    HIPCHK(c, dev_alloc(&c->chk_err_dev, (size_t)4));
     HIPCHK(c, dev_alloc(&c->item_row0_dev, R));
     HIPCHK(c, dev_alloc(&c->item_n_dev, R));
     HIPCHK(c, pin_alloc(&c->item_row0_h, R));
@@ -1328,6 +1369,7 @@ int rsd_init(rsd_ctx** out, const rsd_model_shape shape[3], const rsd_weights w[
     HIPCHK(c, pin_alloc(&c->row_pos_h, R));
     HIPCHK(c, pin_alloc(&c->last_row_h, (size_t)B));
     HIPCHK(c, pin_alloc(&c->dec_seq_h, (size_t)B));
+    HIPCHK(c, pin_alloc(&c->chk_h, (size_t)B + 4));
     HIPCHK(c, pin_alloc(&c->steptok_h, (size_t)B * p->step_cap));
     HIPCHK(c, pin_alloc(&c->poll_h, 4));
     if (bon) {
@@ -2065,6 +2107,20 @@ int rsd_iter_rows(rsd_ctx* c, int32_t model, int64_t* row_iterations) {
     if (model != RSD_DRAFT && model != RSD_TARGET) return fail(c, RSD_EINVAL, "decode loops exist for the draft and the target only");
     *row_iterations = c->it[model].row_iters;
     return RSD_OK;
+}
+
+int rsd_debug_build(void) { return kDebugChecks ? 1 : 0; }
+
+int rsd_check_rows(rsd_ctx* c, int32_t model, const int32_t* seq_host, const int32_t* pos_host, int32_t n) {
+    if (!c || !seq_host || !pos_host) return fail(c, RSD_EINVAL, "null argument");
+    if (model < 0 || model > 2 || n < 1 || n > kMaxRows) return fail(c, RSD_EINVAL, "bad model or row count");
+    if (!c->m[model].bt_dev) return fail(c, RSD_EINVAL, "model %d has no cache", model);
+    HIPCHK(c, hipStreamSynchronize(c->st));          // the staging arrays of the last pass are free
+    std::copy(seq_host, seq_host + n, c->row_seq_h);
+    std::copy(pos_host, pos_host + n, c->row_pos_h);
+    HIPCHK(c, hipMemcpyAsync(c->row_seq_dev, c->row_seq_h, n * sizeof(int), hipMemcpyHostToDevice, c->st));
+    HIPCHK(c, hipMemcpyAsync(c->row_pos_dev, c->row_pos_h, n * sizeof(int), hipMemcpyHostToDevice, c->st));
+    return check_rows(c, model, RowMap{c->row_seq_dev, c->row_pos_dev, nullptr, nullptr}, n);
 }
 
 int rsd_probe_attention(rsd_ctx* c, int32_t model, const int32_t* ctx_len_host, int32_t reps, double* total_ms) {

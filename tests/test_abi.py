@@ -26,6 +26,11 @@ def test_library_exports_every_declared_symbol():
     for n in names:
         assert hasattr(lib, n), n
     assert sorted(binding.EXPORTED_SYMBOLS) == names
+    # the build with the table checks exports the same interface
+    import ctypes
+    dbg = ctypes.CDLL(os.path.join(os.path.dirname(binding.LIB_PATH), "librsd_debug.so"))
+    for n in names:
+        assert hasattr(dbg, n), n
 
 
 def test_missing_library_fails_loudly(tmp_path):

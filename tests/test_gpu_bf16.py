@@ -463,3 +463,20 @@ def test_graph_replay_matches_eager_launches(gpu, batch):
             assert np.array_equal(x, y)
         n_tok = max(n_tok, int(a[3].max()))
     assert n_tok > 80        # the runs did generate well past the prompts
+
+
+def test_checked_build_on_a_ragged_bf16_batch(gpu, mid_models):
+    """The 64-sequence ragged case once more on the library built with the table check before every pass
+    and every single-token iteration (librsd_debug.so): chunked passes over ragged prompts, packed target
+    stages and the MFMA attention kernels all stay inside the pages their rows own, and the results still
+    match the checker."""
+    import os
+    R = gpu["R"]
+    release = R.load_library()
+    try:
+        R.load_library(os.path.join(os.path.dirname(R.LIB_PATH), "librsd_debug.so"))
+        assert R.rsd_debug_build()
+        test_large_batch_ragged_prompts(gpu, mid_models, 64)
+    finally:
+        R._lib = release
+    assert not R.rsd_debug_build()

@@ -329,3 +329,66 @@ def test_merged_reward_head_on_gpu(gpu, tiny, merge):
     pm = O.OracleModel(w.prm, {**{k: v for k, v in trunk.items() if k != "lm_head"}, "w_r": head["w_r"], "b_r": head["b_r"]})
     n_acc, n_rej = run_and_compare(gpu, tiny, w, models=(d, t, pm), merge=merge)
     assert n_acc >= 2 and n_rej >= 2
+
+
+def test_table_check_accepts_what_is_owned_and_names_what_is_not(gpu, tiny):
+    """rsd_check_rows against the state after one reasoning step: rows inside the pages their sequences own
+    pass; a position behind the owned pages, a sequence outside the batch and a position outside the context
+    limit are each refused with RSD_ESTATE and named, by a kernel that only reads what it has checked."""
+    R = gpu["R"]
+    w = tiny["w"]
+    s = gpu["Session"](w)
+    R.rsd_step(s.ctx)
+    st = R.rsd_export_state(s.ctx, want_tokens=False)
+    for m in range(3):
+        owned = st["n_pages"][m] * w.page_tokens
+        has = np.flatnonzero(owned > 0)          # (the target owns nothing for a sequence it has not been asked about)
+        if not has.size:
+            with pytest.raises(R.RsdError) as e:
+                R.rsd_check_rows(s.ctx, m, np.array([0]), np.array([0]))
+            assert e.value.code == R.RSD_ESTATE and "beyond the pages" in str(e.value)
+            continue
+        R.rsd_check_rows(s.ctx, m, np.repeat(has, 2), np.stack([np.zeros(has.size, np.int64), owned[has] - 1], 1).reshape(-1))
+        for bad_seq, bad_pos, what in ((0, int(owned[0]), "beyond the pages"), (w.batch, 0, "outside the batch"),
+                                       (-1, 0, "outside the batch"), (1, w.max_ctx, "outside the context limit"),
+                                       (1, -1, "outside the context limit")):
+            if what == "beyond the pages" and bad_pos >= w.max_ctx:
+                continue
+            with pytest.raises(R.RsdError) as e:
+                R.rsd_check_rows(s.ctx, m, np.array([int(has[0]), bad_seq]), np.array([0, bad_pos]))
+            assert e.value.code == R.RSD_ESTATE and what in str(e.value) and "row 1" in str(e.value), str(e.value)
+    R.rsd_step(s.ctx)            # the context is still usable
+    s.close()
+
+
+def test_checked_build_runs_the_tiny_configuration(gpu, tiny):
+    """The library built with the table check before every pass and every single-token iteration
+    (librsd_debug.so): same tokens, decisions, rewards and offsets as the checker, no graph replays, and a
+    pool that runs out is still a clean RSD_ENOMEM (the check sees the state the failed call restored)."""
+    import os
+    from rsd_inputs import workload
+    R = gpu["R"]
+    path = os.path.join(os.path.dirname(R.LIB_PATH), "librsd_debug.so")
+    release = R.load_library()
+    try:
+        R.load_library(path)
+        assert R.rsd_debug_build()
+        w = workload("cfg0", sep_logit_bias=0.6, deltas=(0.55,))
+        n_acc, n_rej = run_and_compare(gpu, tiny, w)
+        assert n_acc >= 2 and n_rej >= 2
+        s = gpu["Session"](w)
+        R.rsd_generate(s.ctx)
+        ds = R.rsd_decode_stats(s.ctx)
+        assert ds["eager_iters"] > 0 and ds["graph_replays"] == 0
+        s.close()
+        page_bytes = 2 * w.draft.n_kv_heads * 16 * w.draft.head_dim * 4 * w.draft.n_layers
+        small = gpu["Session"](w, kv_pool_bytes=(page_bytes * 13, 0, 0))       # 4 sequences x 3 pages + 1
+        R.rsd_step(small.ctx)
+        with pytest.raises(R.RsdError) as e:
+            for _ in range(w.max_steps):
+                R.rsd_step(small.ctx)
+        assert e.value.code == R.RSD_ENOMEM
+        small.close()
+    finally:
+        R._lib = release
+    assert not R.rsd_debug_build()
