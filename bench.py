@@ -126,6 +126,8 @@ class Runner:
         self.left = 0           # sequences still running in the current pass
         self.exhausted = None
         self.tot = dict(steps=0, tokens=0, drafted=0, targeted=0, acc=0, rej=0, passes=0)
+        self.touched = None     # sequences of the current pass for which the target has generated a step
+        self.pass_log = []      # per pass: [index of its last step so far, sequences, sequences the target never served]
 
     def step(self):
         import numpy as np
@@ -133,7 +135,9 @@ class Runner:
         if self.left == 0:
             s.reset()
             self.running = np.ones(s.w.batch, bool)
+            self.touched = np.zeros(s.w.batch, bool)
             self.tot["passes"] += 1
+            self.pass_log.append([0, s.w.batch, s.w.batch])
         o = R.rsd_step(s.ctx)
         live = self.running
         t = self.tot
@@ -144,12 +148,23 @@ class Runner:
         t["acc"] += int(acc.sum())
         t["rej"] += int((~acc).sum())
         t["targeted"] += int(o["final_len"][live][~acc].sum())
+        idx = np.flatnonzero(live)
+        self.touched[idx[~acc]] = True
+        self.pass_log[-1][0] = t["steps"]
+        self.pass_log[-1][2] = int((~self.touched).sum())
         self.running = o["finished"] == 0
         self.left = int(self.running.sum())
         return o
 
     def snapshot(self):
         return dict(self.tot)
+
+    def draft_only_fraction(self, since_step):
+        """Share of sequences the target never generated a step for, over the passes that had a step after step
+        `since_step` (a pass the window cuts counts with all the steps it has had so far)."""
+        seen = [p for p in self.pass_log if p[0] > since_step]
+        n = sum(p[1] for p in seen)
+        return round(sum(p[2] for p in seen) / n, 4) if n else None
 
 
 def iteration_record(R, s, shapes, reset=True):
@@ -227,6 +242,8 @@ def run_steps(R, s, w, n_steps, warmup=0, probes=True, probe_stride=8):
            "draft_tokens": t["drafted"], "target_tokens": t["targeted"],
            "mean_step_tokens": round(t["tokens"] / max(t["acc"] + t["rej"], 1), 2),
            "target_token_fraction": round(t["targeted"] / max(t["tokens"], 1), 4),
+           # sequences the target never had to generate a step for (Section 4 reports this share of questions)
+           "draft_only_sequence_fraction": r.draft_only_fraction(base["steps"]),
            "stage_ms_per_step": {k: round(v / max(n_steps, 1), 2) for k, v in zip(("draft", "prm", "gate", "target"), stage)},
            "steps_after_first_tokens_per_s": round((t["tokens"] - first_tok) / (dt - first_ms * 1e-3), 2)
            if t["tokens"] > first_tok and dt > first_ms * 1e-3 else None,
@@ -259,7 +276,8 @@ def workload_text(w):
 
 def slim(rec):
     """A sub-record without the bulky parts."""
-    keep = ("tokens_per_s", "ms_per_step", "accept_rate", "mean_step_tokens", "target_token_fraction", "draft_ms_per_token",
+    keep = ("tokens_per_s", "ms_per_step", "accept_rate", "mean_step_tokens", "target_token_fraction",
+            "draft_only_sequence_fraction", "draft_ms_per_token",
             "target_ms_per_token", "draft_ms_per_iteration", "target_ms_per_iteration", "prm_ms_per_step",
             "steps_after_first_tokens_per_s", "tokens", "seconds")
     out = {k: rec[k] for k in keep if k in rec}
@@ -403,6 +421,7 @@ def main():
         rec = {"seconds": dt, "tokens": t["tokens"], "tokens_per_s": round(t["tokens"] / dt, 2),
                "ms_per_step": round(dt / max(len(per_step), 1) * 1e3, 2),
                "accept_rate": round(t["acc"] / max(t["acc"] + t["rej"], 1), 4),
+               "draft_only_sequence_fraction": r.draft_only_fraction(0),
                "steps_run": len(per_step), "note": note,
                "context_reached": [int(st["ctx_len"].min()), int(st["ctx_len"].max())],
                "kv_len_reached": {n: [int(st["kv_len"][i].min()), int(st["kv_len"][i].max())] for i, n in enumerate(("draft", "target", "prm"))},
