@@ -133,7 +133,7 @@ typedef struct rsd_step_out {
 } rsd_step_out;
 
 typedef struct rsd_gen_out {
-    int32_t *tokens;        /* host [B][max_ctx] or NULL */
+    int32_t *tokens;        /* host [B][max_ctx] or NULL: the ctx_len[b] tokens of sequence b, then -1 */
     int32_t *ctx_len;       /* host [B] or NULL */
     int32_t *finished;      /* host [B] or NULL */
     int32_t  steps_run;
@@ -238,7 +238,8 @@ int rsd_bon_stats(rsd_ctx *c, int64_t *pages_shared, int64_t *pages_copied, int6
 
 /* Sequence state for bit-exact checks, HOST buffers (any may be NULL):
  * ctx_len [B]; kv_len [3][B] = leading tokens each model holds keys/values
- * for; n_pages [3][B] = KV pages owned; tokens [B][max_ctx]. */
+ * for; n_pages [3][B] = KV pages owned; tokens [B][max_ctx] = the ctx_len[b]
+ * tokens of row b, then -1. */
 int rsd_export_state(rsd_ctx *c, int32_t *ctx_len, int32_t *kv_len, int32_t *n_pages,
                      int32_t *tokens);
 

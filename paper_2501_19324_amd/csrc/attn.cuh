@@ -473,7 +473,13 @@ __device__ __forceinline__ void split_hi_lo8(const float x[8], abf16x8_t& hi, ab
     lo = __builtin_bit_cast(abf16x8_t, make_uint4(l[0], l[1], l[2], l[3]));
 }
 
-template <int G, int NW>
+// Where the projected q, k, v of the rows come from when the projection's K slices have not been added up yet:
+// part[z][row][col], z < ks, slices `stride` floats apart (the layout the few-row and the tile GEMM leave).
+struct QkvParts { const float* part; int ks; size_t stride; };
+
+// PARTS: the kernel adds the K slices of the QKV projection itself (ascending, like the finish kernels) while
+// its first pages are in flight, which saves the launch of a finish kernel per layer; `qkv` is then unused.
+template <int G, int NW, bool PARTS>
 __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void attn_decode_mfma_kernel(const float* __restrict__ qkv, int ldq,
                                                                    bf16_t* __restrict__ pool_layer,
                                                                    const int* __restrict__ block_table, int max_pages,
@@ -483,7 +489,7 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void attn_decode_mfma_ker
                                                                    int S, float scale, float* __restrict__ out, int ldo,
                                                                    float* __restrict__ part_acc, float* __restrict__ part_ml,
                                                                    uint16_t* __restrict__ out_h, uint16_t* __restrict__ out_l,
-                                                                   const int* __restrict__ row_seq) {
+                                                                   const int* __restrict__ row_seq, QkvParts qp) {
     constexpr int HD = 128;
     const int r = blockIdx.x, hk = blockIdx.y, sp = blockIdx.z;
     const int seq_raw = row_seq ? row_seq[r] : r;   // packed rows: the sequence this row stands for (< 0: none)
@@ -527,6 +533,28 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void attn_decode_mfma_ker
     if (pg < n_pages) fetch(0, kc, vc);
     if (pg + pg_step < n_pages) fetch(1, kn, vn);
 
+    // q of the group's heads, k and v of this KV head for the row: straight from qkv, or summed into LDS
+    __shared__ float s_row[PARTS ? (G + 2) * HD : 1];
+    const float *src_q, *src_k, *src_v;
+    if constexpr (PARTS) {
+        for (int i = tid; i < (G + 2) * HD; i += NW * 64) {
+            const int col = i < G * HD ? hk * G * HD + i : (i < (G + 1) * HD ? (H + hk) * HD + (i - G * HD) : (H + Hkv + hk) * HD + (i - (G + 1) * HD));
+            const float* p = qp.part + (size_t)r * ldq + col;
+            float a = 0.0f;
+            int z = 0;
+            for (; z + 4 <= qp.ks; z += 4) {
+                const float b0 = p[(size_t)z * qp.stride], b1 = p[(size_t)(z + 1) * qp.stride];
+                const float b2 = p[(size_t)(z + 2) * qp.stride], b3 = p[(size_t)(z + 3) * qp.stride];
+                a += b0; a += b1; a += b2; a += b3;
+            }
+            for (; z < qp.ks; ++z) a += p[(size_t)z * qp.stride];
+            s_row[i] = a;
+        }
+        __syncthreads();
+        src_q = s_row; src_k = s_row + G * HD; src_v = s_row + (G + 1) * HD;
+    } else {
+        src_q = row + hk * G * HD; src_k = row + (H + hk) * HD; src_v = row + (H + Hkv + hk) * HD;
+    }
     // rotated, scaled queries of the group, computed once per block and kept in LDS as hi + lo bf16
     // (rows >= G stay zero); the waves read their MFMA operands from there for every page
     __shared__ __attribute__((aligned(16))) uint16_t s_qh[16][HD + 8];
@@ -535,8 +563,8 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void attn_decode_mfma_ker
         const int g = idx / (HD / 2), e = idx - g * (HD / 2);
         float ra = 0.0f, rb = 0.0f;
         if (g < G) {
-            const float* qp = row + (hk * G + g) * HD + e;
-            const float a = qp[0], b = qp[HD / 2];
+            const float* qe = src_q + g * HD + e;
+            const float a = qe[0], b = qe[HD / 2];
             const float2 t = cs[e];
             ra = (a * t.x - b * t.y) * scale;
             rb = (b * t.x + a * t.y) * scale;
@@ -559,7 +587,7 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void attn_decode_mfma_ker
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             float kv[8];
-            rope8<HD>(row + (H + hk) * HD, cs, j * 32 + c * 8, kv);
+            rope8<HD>(src_k, cs, j * 32 + c * 8, kv);
             uint4 pk;
             pk.x = (uint32_t)f2bf(kv[0]) | ((uint32_t)f2bf(kv[1]) << 16);
             pk.y = (uint32_t)f2bf(kv[2]) | ((uint32_t)f2bf(kv[3]) << 16);
@@ -570,8 +598,8 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void attn_decode_mfma_ker
         }
 #pragma unroll
         for (int m = 0; m < 4; ++m) {
-            const uint16_t va = f2bf(row[(H + Hkv + hk) * HD + (2 * m) * 16 + l16]);
-            const uint16_t vb = f2bf(row[(H + Hkv + hk) * HD + (2 * m + 1) * 16 + l16]);
+            const uint16_t va = f2bf(src_v[(2 * m) * 16 + l16]);
+            const uint16_t vb = f2bf(src_v[(2 * m + 1) * 16 + l16]);
             if (c == 0) {
                 kb[v_off + kv_tiled_v(slot, (2 * m) * 16 + l16)].v = va;
                 kb[v_off + kv_tiled_v(slot, (2 * m + 1) * 16 + l16)].v = vb;

@@ -413,23 +413,27 @@ void launch_attn_decode(rsd_ctx* c, const Model& m, int l, int M, int which) {
 
 // bf16 caches with head_dim 128: the MFMA kernel, 8 waves per block
 // merge_here = false leaves the partial results of the splits to the caller (S > 1 only)
+// qp.ks > 0: q, k, v are still the K slices of the QKV projection (the kernel adds them up itself)
 void launch_attn_decode_mfma(rsd_ctx* c, const Model& m, int l, int M, int which, bool merge_here = true,
-                             bool halves = false) {
+                             bool halves = false, QkvParts qp = QkvParts{nullptr, 0, 0}) {
     bf16_t* pool_l = reinterpret_cast<bf16_t*>(m.pool) + (size_t)l * m.pool_pages * m.page_elts;
     const float scale = 1.0f / std::sqrt(128.0f);
     const int S = m.splits;
     const dim3 grid(M, m.s.n_kv_heads, S);
+#define RSD_ATTN_ARGS                                                                                              \
+    grid, dim3(512), 0, c->st, c->qkv, m.n_qkv, pool_l, m.bt_dev, m.max_pages, c->ds.kv_len + (size_t)which * c->B, \
+        c->ds.active, m.rope, m.s.n_heads, m.s.n_kv_heads, S, scale, c->att, m.q_dim, c->part_acc, c->part_ml,     \
+        halves ? c->xs_h : nullptr, halves ? c->xs_l : nullptr, decode_seq(c), qp
 #define RSD_ATTN_CASE(GG)                                                                                          \
     case GG:                                                                                                       \
-        hipLaunchKernelGGL((attn_decode_mfma_kernel<GG, 8>), grid, dim3(512), 0, c->st, c->qkv, m.n_qkv, pool_l,   \
-                           m.bt_dev, m.max_pages, c->ds.kv_len + (size_t)which * c->B, c->ds.active, m.rope,       \
-                           m.s.n_heads, m.s.n_kv_heads, S, scale, c->att, m.q_dim, c->part_acc, c->part_ml,        \
-                           halves ? c->xs_h : nullptr, halves ? c->xs_l : nullptr, decode_seq(c));                 \
+        if (qp.ks > 0) hipLaunchKernelGGL((attn_decode_mfma_kernel<GG, 8, true>), RSD_ATTN_ARGS);                  \
+        else hipLaunchKernelGGL((attn_decode_mfma_kernel<GG, 8, false>), RSD_ATTN_ARGS);                           \
         break;
     switch (m.G) {
         RSD_ATTN_CASE(1) RSD_ATTN_CASE(2) RSD_ATTN_CASE(4) RSD_ATTN_CASE(6) RSD_ATTN_CASE(7) RSD_ATTN_CASE(8)
     }
 #undef RSD_ATTN_CASE
+#undef RSD_ATTN_ARGS
     if (S > 1 && merge_here)
         hipLaunchKernelGGL((attn_combine_kernel<128>), dim3(M, m.s.n_heads), dim3(128), 0, c->st, c->part_acc,
                            c->part_ml, decode_map(c, which), m.s.n_heads, S, c->att, m.q_dim,
@@ -493,8 +497,11 @@ void rows_finish(rsd_ctx* c, int ks, int rows, int M, int N, float* Y, int ldy, 
 // next_gain != nullptr (EPI_RESID): RMSNorm(Y row) * next_gain is left in the halves for the projection that
 // follows (inside the finish kernel where there is one and N <= 8192).
 // (m, op) name the projection for the timing probes: the matrix kernel alone is bracketed.
+// defer != nullptr (EPI_STORE): when the product is left as uniform K slices, they are not added up here but
+// described in *defer for a consumer that adds them itself (ks = 0: Y holds the result as usual).
 void rows_gemm(rsd_ctx* c, const Model& m, int op, int epi, const bf16_t* W, int N, int K, int M, float* Y, int ldy,
-               const bf16_t* next_gain = nullptr, float eps = 0.f) {
+               const bf16_t* next_gain = nullptr, float eps = 0.f, QkvParts* defer = nullptr) {
+    if (defer) *defer = QkvParts{nullptr, 0, 0};
     const bool few = M <= 64 && N % 4 == 0;
     SkGeom geo{};                                            // G = 0: uniform K slices
     const int rows = few ? (M <= 32 ? 32 : 64) : M;          // rows of one slice of partial results
@@ -537,6 +544,10 @@ void rows_gemm(rsd_ctx* c, const Model& m, int op, int epi, const bf16_t* W, int
         ProbeScope ps(c, m, op, pb, pf);
         gemm_tile_launch(c->st, EPI_STORE, W, N, K, c->xs_h, c->xs_l, M, nullptr, 0, c->part_k, ks);
     }
+    if (defer && geo.G == 0 && ldy == N) {
+        *defer = QkvParts{c->part_k, ks, (size_t)rows * N};
+        return;
+    }
     if (next_gain && N <= 8192) {
         hipLaunchKernelGGL((rows_finish_norm_kernel<bf16_t>), dim3(M), dim3(1024), 0, c->st, c->part_k, ks, rows, N, Y, ldy,
                            next_gain, eps, c->xs_h, c->xs_l, geo);
@@ -548,7 +559,8 @@ void rows_gemm(rsd_ctx* c, const Model& m, int op, int epi, const bf16_t* W, int
     if (next_gain) rows_split(c, Y, ldy, M, N, next_gain, eps);
 }
 void rows_split(rsd_ctx*, const float*, int, int, int, const float*, float) {}    // fp32 weights never take this path
-void rows_gemm(rsd_ctx*, const Model&, int, int, const float*, int, int, int, float*, int, const float* = nullptr, float = 0.f) {}
+void rows_gemm(rsd_ctx*, const Model&, int, int, const float*, int, int, int, float*, int, const float* = nullptr, float = 0.f,
+               QkvParts* = nullptr) {}
 
 template <typename WT>
 void run_layers(rsd_ctx* c, Model& m, int M, const RowMap& rm, bool decode) {
@@ -570,6 +582,7 @@ void run_layers(rsd_ctx* c, Model& m, int M, const RowMap& rm, bool decode) {
     for (int l = 0; l < m.s.n_layers; ++l) {
         const LayerOff& o = m.layers[l];
         const long long esz = sizeof(WT);
+        QkvParts qkv_parts{nullptr, 0, 0};
         if (fused) {
             ProbeScope ps(c, m, 0, (long long)m.n_qkv * d * esz + 4LL * M * (d + m.n_qkv), 2LL * M * m.n_qkv * d, M == 1);
             gemv_launch<WT>(st, PRO_NORM, EPI_STORE, wptr<WT>(m, o.wqkv), m.n_qkv, d, c->h, d,
@@ -577,7 +590,9 @@ void run_layers(rsd_ctx* c, Model& m, int M, const RowMap& rm, bool decode) {
         } else if (rows) {
             // (after the first layer the halves of RMSNorm(h) come from the previous layer's last finish)
             if (l == 0 || !rows_fuse_norm) rows_split(c, c->h, d, M, d, wptr<WT>(m, o.attn_norm), eps);
-            rows_gemm(c, m, 0, EPI_STORE, wptr<WT>(m, o.wqkv), m.n_qkv, d, M, c->qkv, m.n_qkv);
+            // (the batched decode attention over a bf16 cache adds the projection's K slices itself)
+            rows_gemm(c, m, 0, EPI_STORE, wptr<WT>(m, o.wqkv), m.n_qkv, d, M, c->qkv, m.n_qkv, nullptr, 0.f,
+                      att_halves ? &qkv_parts : nullptr);
         } else if constexpr (std::is_same<WT, float>::value) {
             hipLaunchKernelGGL((rmsnorm_kernel<WT>), dim3(M), dim3(256), 0, st, c->h, d, wptr<WT>(m, o.attn_norm), eps, c->xn);
             gemm_launch(st, EPI_STORE, wptr<WT>(m, o.wqkv), m.n_qkv, d, c->xn, d, c->qkv, m.n_qkv, M, c->part_k, c->part_k_floats);
@@ -585,7 +600,7 @@ void run_layers(rsd_ctx* c, Model& m, int M, const RowMap& rm, bool decode) {
         WT* pool_l = reinterpret_cast<WT*>(m.pool) + (size_t)l * m.pool_pages * m.page_elts;
         if (decode) {
             const int which = (int)(&m - &c->m[0]);
-            if (m.s.dtype == RSD_BF16) launch_attn_decode_mfma(c, m, l, M, which, !parts_to_o, att_halves);
+            if (m.s.dtype == RSD_BF16) launch_attn_decode_mfma(c, m, l, M, which, !parts_to_o, att_halves, qkv_parts);
             else if (m.hd == 128) launch_attn_decode<WT, 128>(c, m, l, M, which);
             else launch_attn_decode<WT, 32>(c, m, l, M, which);
         } else if (m.hd == 128) {
@@ -951,6 +966,15 @@ int gen_stage(rsd_ctx* c, int which, const float* u, const int* forced, int mode
     }
     HIPCHK(c, hipGetLastError());
     return RSD_OK;
+}
+
+// Token rows as handed to the caller: the committed tokens, then -1 (what lies behind them in the device buffer
+// - rolled-back steps, losing candidates, memory never written - is nobody's business)
+void blank_tails(int32_t* tokens, int rows, int max_ctx, const int* ctx_len_of_row) {
+    for (int r = 0; r < rows; ++r) {
+        const int n = std::min(std::max(ctx_len_of_row[r], 0), max_ctx);
+        std::fill(tokens + (size_t)r * max_ctx + n, tokens + (size_t)(r + 1) * max_ctx, -1);
+    }
 }
 
 int gen_stage_any(rsd_ctx* c, int which, const float* u, const int* forced, int mode = 1, int max_iters = 0) {
@@ -1657,6 +1681,7 @@ int rsd_generate(rsd_ctx* c, int32_t max_steps, rsd_gen_out* out) {
     if (g.tokens) {
         HIPCHK(c, hipMemcpyAsync(g.tokens, c->ds.tokens, (size_t)B * c->p.max_ctx * sizeof(int), hipMemcpyDeviceToHost, c->st));
         HIPCHK(c, hipStreamSynchronize(c->st));
+        blank_tails(g.tokens, B, c->p.max_ctx, c->ctx_len());
     }
     if (out) *out = g;
     return RSD_OK;
@@ -1933,6 +1958,11 @@ int rsd_bon_generate(rsd_ctx* c, int32_t max_steps, rsd_gen_out* out) {
                                      (size_t)c->p.max_ctx * sizeof(int), hipMemcpyDeviceToHost, c->st));
     }
     HIPCHK(c, hipStreamSynchronize(c->st));
+    if (g.tokens) {
+        std::vector<int> len(S);
+        for (int s = 0; s < S; ++s) len[s] = c->ctx_len()[c->canon[s]];
+        blank_tails(g.tokens, S, c->p.max_ctx, len.data());
+    }
     if (out) *out = g;
     return RSD_OK;
 }
@@ -1956,6 +1986,7 @@ int rsd_export_state(rsd_ctx* c, int32_t* ctx_len, int32_t* kv_len, int32_t* n_p
     if (tokens) {
         HIPCHK(c, hipMemcpyAsync(tokens, c->ds.tokens, (size_t)B * c->p.max_ctx * sizeof(int), hipMemcpyDeviceToHost, c->st));
         HIPCHK(c, hipStreamSynchronize(c->st));
+        blank_tails(tokens, B, c->p.max_ctx, c->ctx_len());
     }
     return RSD_OK;
 }
