@@ -479,6 +479,21 @@ struct QkvParts { const float* part; int ks; size_t stride; };
 
 // PARTS: the kernel adds the K slices of the QKV projection itself (ascending, like the finish kernels) while
 // its first pages are in flight, which saves the launch of a finish kernel per layer; `qkv` is then unused.
+// 16 bytes of a cache page in the decode kernel: every page is read once per launch, so the loads are marked
+// non-temporal and leave the caches to what is used again (batch 256 at 4096 tokens: 392 -> 367 us per 7B
+// layer, 200 -> 180 us per 1.5B layer; the 7B iteration at batch 64: 5.27 -> 4.94 ms)
+#ifndef RSD_KV_NT
+#define RSD_KV_NT 1
+#endif
+__device__ __forceinline__ uint4 load_kv16(const bf16_t* p) {
+#if RSD_KV_NT
+    typedef uint32_t nt_u32x4 __attribute__((ext_vector_type(4)));
+    const nt_u32x4 t = __builtin_nontemporal_load(reinterpret_cast<const nt_u32x4*>(p));
+    return make_uint4(t.x, t.y, t.z, t.w);
+#else
+    return *reinterpret_cast<const uint4*>(p);
+#endif
+}
 template <int G, int NW, bool PARTS>
 __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void attn_decode_mfma_kernel(const float* __restrict__ qkv, int ldq,
                                                                    bf16_t* __restrict__ pool_layer,
@@ -521,9 +536,9 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void attn_decode_mfma_ker
     auto fetch_phys = [&](int phys, uint4 k[4], uint4 v[4]) {
         const bf16_t* kb = pool_layer + (size_t)phys * page_elts + head_off;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) k[j] = *reinterpret_cast<const uint4*>(kb + (j * 64 + lane) * 8);
+        for (int j = 0; j < 4; ++j) k[j] = load_kv16(kb + (j * 64 + lane) * 8);
 #pragma unroll
-        for (int m = 0; m < 4; ++m) v[m] = *reinterpret_cast<const uint4*>(kb + v_off + (m * 64 + lane) * 8);
+        for (int m = 0; m < 4; ++m) v[m] = load_kv16(kb + v_off + (m * 64 + lane) * 8);
     };
     // i-th page of this wave (i < 64: a wave never holds more than 64 pages)
     auto fetch = [&](int i, uint4 k[4], uint4 v[4]) { fetch_phys(__shfl(bt_mine, i, RSD_WAVE), k, v); };

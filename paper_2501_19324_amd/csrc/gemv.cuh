@@ -127,11 +127,24 @@ __global__ __launch_bounds__(256) void gemv_kernel(const WT* __restrict__ W, int
     }
 }
 
-// Raw 8-element weight loads (kept packed in registers until they are used).
+// Raw 8-element weight loads (kept packed in registers until they are used).  bf16 weights are marked
+// non-temporal: every byte is read once per launch and should not displace anything in the caches
+// (7B gate/up at one row: 48.9 -> 45.0 us; the whole 7B iteration 3.26 -> 2.99 ms).
+#ifndef RSD_GEMV_NT
+#define RSD_GEMV_NT 1
+#endif
 template <typename WT> struct Raw8;
 template <> struct Raw8<bf16_t> {
     uint4 v;
-    __device__ __forceinline__ void load(const bf16_t* p) { v = *reinterpret_cast<const uint4*>(p); }
+    __device__ __forceinline__ void load(const bf16_t* p) {
+#if RSD_GEMV_NT
+        typedef uint32_t nt_u32x4 __attribute__((ext_vector_type(4)));
+        const nt_u32x4 t = __builtin_nontemporal_load(reinterpret_cast<const nt_u32x4*>(p));
+        v = make_uint4(t.x, t.y, t.z, t.w);
+#else
+        v = *reinterpret_cast<const uint4*>(p);
+#endif
+    }
     __device__ __forceinline__ void unpack(float o[8]) const { unpack8(v, o); }
 };
 template <> struct Raw8<float> {
