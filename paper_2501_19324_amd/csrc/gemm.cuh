@@ -966,8 +966,9 @@ static int gemm_tile_bm(int N, int M, int ks) {
 }
 static int gemm_tile_slices(int N, int K, int M, size_t part_floats) {
     if (gemm_tile_decode_rows(M)) {
-        const int tn = (N + 255) / 256, nkb = K / 32;
-        int ks = std::max(1, std::min(std::min(256 / tn, nkb / 6), 32));
+        // (a compute unit holds one block of the 256-row tile or two of the 128-row tile)
+        const int tn = (N + 255) / 256, nkb = K / 32, room = M > 128 ? 256 : 512;
+        int ks = std::max(1, std::min(std::min(room / tn, nkb / 6), 32));
         while (ks > 1 && ((size_t)ks * M * N > part_floats || (ks - 1) * ((nkb + ks - 1) / ks) >= nkb)) --ks;
         return ks;
     }
