@@ -960,15 +960,23 @@ __global__ __launch_bounds__(BM * 2, BM == 128 ? 2 : 1) void gemm_tile_kernel(co
 // most 256 blocks and filled with K slices: [3584][18944] at 256 rows 98 -> 72 us, [17920][1536] 53 -> 39 us,
 // [37888][3584] (148 column tiles: no slices, no finish kernel) 178 + 18 -> 170 us.
 static bool gemm_tile_decode_rows(int M) { return M <= 256; }
-static int gemm_tile_bm(int N, int M, int ks) {
-    if (gemm_tile_decode_rows(M)) return M > 128 ? 256 : 128;
+// Decode-size launches (one row tile of the batch): the 256-row tile wherever its N tiles x K slices (at least six
+// K blocks each) give 128 blocks or more, else two 128-row tiles (small matrices: the 1.5B attention projections
+// at 256 rows 22 -> 17 us).  A compute unit holds one block of the 256-row tile or two of the 128-row tile.
+static int gemm_tile_bm(int N, int K, int M, int ks) {
+    if (gemm_tile_decode_rows(M)) {
+        const int tn = (N + 255) / 256, nkb = K / 32;
+        if (M <= 128) return 128;
+        return tn * std::max(1, std::min(std::min(256 / tn, nkb / 6), 32)) >= 128 ? 256 : 128;
+    }
     return ((N + 255) / 256) * ((M + 255) / 256) * ks >= 400 ? 256 : 128;
 }
 static int gemm_tile_slices(int N, int K, int M, size_t part_floats) {
     if (gemm_tile_decode_rows(M)) {
-        // (a compute unit holds one block of the 256-row tile or two of the 128-row tile)
-        const int tn = (N + 255) / 256, nkb = K / 32, room = M > 128 ? 256 : 512;
-        int ks = std::max(1, std::min(std::min(room / tn, nkb / 6), 32));
+        const int tn = (N + 255) / 256, nkb = K / 32;
+        const int bm = gemm_tile_bm(N, K, M, 1);
+        const int room = bm == 256 ? 256 / tn : 512 / (tn * ((M + 127) / 128));
+        int ks = std::max(1, std::min(std::min(room, nkb / 6), 32));
         while (ks > 1 && ((size_t)ks * M * N > part_floats || (ks - 1) * ((nkb + ks - 1) / ks) >= nkb)) --ks;
         return ks;
     }
@@ -981,7 +989,7 @@ static int gemm_tile_slices(int N, int K, int M, size_t part_floats) {
 static void gemm_tile_launch(hipStream_t st, int epi, const bf16_t* W, int N, int K, const uint16_t* Xh,
                              const uint16_t* Xl, int M, float* Y, int ldy, float* part, int ks) {
     const int tn = (N + 255) / 256;
-    if (gemm_tile_bm(N, M, ks) == 256) {
+    if (gemm_tile_bm(N, K, M, ks) == 256) {
         const dim3 grid(tn, (M + 255) / 256, ks), block(512);
         if (epi == EPI_RESID) hipLaunchKernelGGL((gemm_tile_kernel<EPI_RESID, 256>), grid, block, 0, st, W, N, K, Xh, Xl, M, Y, ldy, part);
         else                  hipLaunchKernelGGL((gemm_tile_kernel<EPI_STORE, 256>), grid, block, 0, st, W, N, K, Xh, Xl, M, Y, ldy, part);
