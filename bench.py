@@ -56,22 +56,25 @@ def cpu_baseline(w, budget_layers=None):
         return tot
     layers = list(full)
     if budget_layers or need(layers) > 0.5 * avail:      # (the 72B target alone is 580 GB in fp64)
-        layers = [min(L, budget_layers or 2) for L in full]
+        layers = [min(L, budget_layers or 4) for L in full]
+        while max(layers) > 1 and need(layers) > 0.5 * avail:
+            layers = [max(1, L - 1) for L in layers]
     L = max(layers)
-    step_cap, max_steps = 16, 4
-    ws = workload(w.name, n_layers=L, batch=1, step_cap=step_cap, max_steps=max_steps)
+    step_cap, max_steps, n_seq = 16, 6, 2
+    ws = workload(w.name, n_layers=L, batch=n_seq, step_cap=step_cap, max_steps=max_steps)
     threads = min(16, os.cpu_count() or 1)
     models = [O.OracleModel(s, model_weights_np(ws.seed, i, s, threads=threads)) for i, s in enumerate(ws.shapes)]
     toks, lens = prompt_tokens(ws), prompt_lengths(ws)
     P = O.Params(delta=ws.delta, sep_id=ws.sep_id, step_cap=ws.step_cap, max_steps=ws.max_steps, max_ctx=ws.max_ctx,
                  temperature=float(np.float32(ws.temperature)), top_p=float(np.float32(ws.top_p)))
     cores = blas_threads()
+    ud, ut, ug = uniforms(ws, "U_DRAFT", ws.max_ctx), uniforms(ws, "U_TARGET", ws.max_ctx), uniforms(ws, "U_GATE", ws.max_steps)
     t0 = time.time()
-    out = O.generate_sequence(models[0], models[1], models[2], toks[0, :lens[0]],
-                              uniforms(ws, "U_DRAFT", ws.max_ctx)[0], uniforms(ws, "U_TARGET", ws.max_ctx)[0],
-                              uniforms(ws, "U_GATE", ws.max_steps)[0], P)
+    n = 0
+    for b in range(n_seq):
+        out = O.generate_sequence(models[0], models[1], models[2], toks[b, :lens[b]], ud[b], ut[b], ug[b], P)
+        n += len(out["tokens"]) - int(lens[b])
     dt = time.time() - t0
-    n = len(out["tokens"]) - int(lens[0])
     used = [min(f, L) for f in full]
     scale = ""
     if used != full:
@@ -79,7 +82,7 @@ def cpu_baseline(w, budget_layers=None):
                  + ": the layer part of the cost grows in proportion, so at full depth the rate is roughly "
                  + f"{max(f / u for f, u in zip(full, used)):.0f}x lower for the deepest model")
     return {"value": n / dt, "unit": "tokens/s", "cores": cores, "kind": "oracle",
-            "sample": f"{ws.name} shapes at full width and vocabulary, 1 sequence, prompt {int(lens[0])} tokens + the first "
+            "sample": f"{ws.name} shapes at full width and vocabulary, {n_seq} sequences one after the other, prompt {int(lens[0])} tokens + the first "
                       f"{ws.max_steps} reasoning steps of <= {ws.step_cap} tokens ({n} tokens; prompt prefill of all touched "
                       f"models included), {dt:.1f} s" + scale}
 
