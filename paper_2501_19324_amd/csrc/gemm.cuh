@@ -812,7 +812,8 @@ __global__ __launch_bounds__(BM * 2, BM == 128 ? 2 : 1) void gemm_tile_kernel(co
                                                            const uint16_t* __restrict__ Xh,
                                                            const uint16_t* __restrict__ Xl, int M,
                                                            float* __restrict__ Y, int ldy,
-                                                           float* __restrict__ part) {
+                                                           float* __restrict__ part,
+                                                           uint16_t* __restrict__ Oh, uint16_t* __restrict__ Ol) {
     constexpr int BN = 256, BK = 32, CR = BM / 2;        // CR: rows covered by one round of copies (threads / 4)
     __shared__ __attribute__((aligned(16))) uint16_t Ah[2][BM * BK];
     __shared__ __attribute__((aligned(16))) uint16_t Al[2][BM * BK];
@@ -841,10 +842,17 @@ __global__ __launch_bounds__(BM * 2, BM == 128 ? 2 : 1) void gemm_tile_kernel(co
     const uint16_t* ah1 = Xh + (size_t)min(m0 + crow + CR, M - 1) * K + cch * 8;
     const uint16_t* al0 = Xl + (size_t)min(m0 + crow, M - 1) * K + cch * 8;
     const uint16_t* al1 = Xl + (size_t)min(m0 + crow + CR, M - 1) * K + cch * 8;
-    const bf16_t* b0 = W + (size_t)min(n0 + crow, N - 1) * K + cch * 8;
-    const bf16_t* b1 = W + (size_t)min(n0 + crow + CR, N - 1) * K + cch * 8;
-    const bf16_t* b2 = W + (size_t)min(n0 + crow + 128, N - 1) * K + cch * 8;       // BM = 128 only
-    const bf16_t* b3 = W + (size_t)min(n0 + crow + 192, N - 1) * K + cch * 8;
+    // W row behind tile column r.  EPI_SWIGLU (W = [gate | up], N = 2F, never K-sliced): the tile's columns are 128
+    // gate rows and the 128 up rows of the same units, arranged so that a wave's column groups j and j + 2 hold
+    // gate and up of one unit: columns 128 w + 64 h + i (w = wave column, h = 0 gate / 1 up) <- row h F + 128 bx + 64 w + i
+    auto wrow = [&](int r) {
+        if (EPI == EPI_SWIGLU) return min(((r >> 6) & 1) * (N / 2) + bx * 128 + (r >> 7) * 64 + (r & 63), N - 1);
+        return min(n0 + r, N - 1);
+    };
+    const bf16_t* b0 = W + (size_t)wrow(crow) * K + cch * 8;
+    const bf16_t* b1 = W + (size_t)wrow(crow + CR) * K + cch * 8;
+    const bf16_t* b2 = W + (size_t)wrow(crow + 128) * K + cch * 8;       // BM = 128 only
+    const bf16_t* b3 = W + (size_t)wrow(crow + 192) * K + cch * 8;
     const int st0 = sw(crow, cch), st1 = sw(crow + CR, cch), st2 = sw(crow + 128, cch), st3 = sw(crow + 192, cch);
 
     f32x16_t acc[2][4];
@@ -930,6 +938,28 @@ __global__ __launch_bounds__(BM * 2, BM == 128 ? 2 : 1) void gemm_tile_kernel(co
 #undef RSD_STAGE
 #undef RSD_COMPUTE
 
+    if (EPI == EPI_SWIGLU) {
+        // silu(gate) * up of the units this wave holds, straight into the hi / lo halves the down projection reads
+        const int F = N / 2;
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int col = bx * 128 + wn * 64 + j * 32 + l32;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int m = m0 + wm * 64 + i * 32 + 8 * (v >> 2) + 4 * kg + (v & 3);
+                    if (m < M && col < F) {
+                        const float g = acc[i][j][v], u = acc[i][j + 2][v];
+                        const float x = g / (1.0f + expf(-g)) * u;
+                        const uint16_t hi = f2bf(x);
+                        Oh[(size_t)m * F + col] = hi;
+                        Ol[(size_t)m * F + col] = f2bf(x - bf2f(hi));
+                    }
+                }
+            }
+        return;
+    }
     const bool sliced = gridDim.z > 1;
 #pragma unroll
     for (int i = 0; i < 2; ++i)
@@ -986,35 +1016,21 @@ static int gemm_tile_slices(int N, int K, int M, size_t part_floats) {
     return ks;
 }
 
+// epi == EPI_SWIGLU (W = [gate | up], ks = 1): the activated values go to Oh / Ol [M][N / 2] as hi / lo halves
 static void gemm_tile_launch(hipStream_t st, int epi, const bf16_t* W, int N, int K, const uint16_t* Xh,
-                             const uint16_t* Xl, int M, float* Y, int ldy, float* part, int ks) {
+                             const uint16_t* Xl, int M, float* Y, int ldy, float* part, int ks,
+                             uint16_t* Oh = nullptr, uint16_t* Ol = nullptr) {
     const int tn = (N + 255) / 256;
     if (gemm_tile_bm(N, K, M, ks) == 256) {
         const dim3 grid(tn, (M + 255) / 256, ks), block(512);
-        if (epi == EPI_RESID) hipLaunchKernelGGL((gemm_tile_kernel<EPI_RESID, 256>), grid, block, 0, st, W, N, K, Xh, Xl, M, Y, ldy, part);
-        else                  hipLaunchKernelGGL((gemm_tile_kernel<EPI_STORE, 256>), grid, block, 0, st, W, N, K, Xh, Xl, M, Y, ldy, part);
+        if (epi == EPI_SWIGLU)     hipLaunchKernelGGL((gemm_tile_kernel<EPI_SWIGLU, 256>), grid, block, 0, st, W, N, K, Xh, Xl, M, Y, ldy, part, Oh, Ol);
+        else if (epi == EPI_RESID) hipLaunchKernelGGL((gemm_tile_kernel<EPI_RESID, 256>), grid, block, 0, st, W, N, K, Xh, Xl, M, Y, ldy, part, Oh, Ol);
+        else                       hipLaunchKernelGGL((gemm_tile_kernel<EPI_STORE, 256>), grid, block, 0, st, W, N, K, Xh, Xl, M, Y, ldy, part, Oh, Ol);
         return;
     }
     const dim3 grid(tn, (M + 127) / 128, ks), block(256);
-    if (epi == EPI_RESID) hipLaunchKernelGGL((gemm_tile_kernel<EPI_RESID, 128>), grid, block, 0, st, W, N, K, Xh, Xl, M, Y, ldy, part);
-    else                  hipLaunchKernelGGL((gemm_tile_kernel<EPI_STORE, 128>), grid, block, 0, st, W, N, K, Xh, Xl, M, Y, ldy, part);
+    if (epi == EPI_SWIGLU)     hipLaunchKernelGGL((gemm_tile_kernel<EPI_SWIGLU, 128>), grid, block, 0, st, W, N, K, Xh, Xl, M, Y, ldy, part, Oh, Ol);
+    else if (epi == EPI_RESID) hipLaunchKernelGGL((gemm_tile_kernel<EPI_RESID, 128>), grid, block, 0, st, W, N, K, Xh, Xl, M, Y, ldy, part, Oh, Ol);
+    else                       hipLaunchKernelGGL((gemm_tile_kernel<EPI_STORE, 128>), grid, block, 0, st, W, N, K, Xh, Xl, M, Y, ldy, part, Oh, Ol);
 }
 
-// act = silu(gate) * up for gu[M][2F] = [gate | up], written as hi + lo bf16 halves [M][F]
-__global__ void swiglu_split_kernel(const float* __restrict__ gu, int F, uint16_t* __restrict__ Oh,
-                                    uint16_t* __restrict__ Ol, size_t total) {
-    const size_t i = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
-    if (i >= total) return;
-    const size_t r = i / F, f = i - r * F;
-    const float4 g = *reinterpret_cast<const float4*>(gu + r * 2 * F + f);
-    const float4 u = *reinterpret_cast<const float4*>(gu + r * 2 * F + F + f);
-    const float x[4] = {g.x / (1.0f + expf(-g.x)) * u.x, g.y / (1.0f + expf(-g.y)) * u.y,
-                        g.z / (1.0f + expf(-g.z)) * u.z, g.w / (1.0f + expf(-g.w)) * u.w};
-    uint16_t hi[4], lo[4];
-#pragma unroll
-    for (int e = 0; e < 4; ++e) { hi[e] = f2bf(x[e]); lo[e] = f2bf(x[e] - bf2f(hi[e])); }
-    *reinterpret_cast<uint2*>(Oh + i) =
-        make_uint2((uint32_t)hi[0] | ((uint32_t)hi[1] << 16), (uint32_t)hi[2] | ((uint32_t)hi[3] << 16));
-    *reinterpret_cast<uint2*>(Ol + i) =
-        make_uint2((uint32_t)lo[0] | ((uint32_t)lo[1] << 16), (uint32_t)lo[2] | ((uint32_t)lo[3] << 16));
-}

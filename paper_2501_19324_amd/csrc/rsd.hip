@@ -127,6 +127,8 @@ struct rsd_ctx {
     int dec_rows = 0;
     // table check (rsd_check_rows; before every pass in a build with RSD_DEBUG): page counts and the error record
     int *chk_n_pages_dev = nullptr, *chk_err_dev = nullptr, *chk_h = nullptr;
+    // halves the next MFMA GEMM reads instead of xs_h / xs_l (set by a producer that could not write there; used once)
+    const uint16_t *xin_h = nullptr, *xin_l = nullptr;
     // chunked-prefill attention work items: first row and row count (<= 4 rows of one sequence)
     int *item_row0_dev = nullptr, *item_n_dev = nullptr, *item_row0_h = nullptr, *item_n_h = nullptr;
     int n_items = 0;
@@ -502,6 +504,9 @@ void rows_finish(rsd_ctx* c, int ks, int rows, int M, int N, float* Y, int ldy, 
 void rows_gemm(rsd_ctx* c, const Model& m, int op, int epi, const bf16_t* W, int N, int K, int M, float* Y, int ldy,
                const bf16_t* next_gain = nullptr, float eps = 0.f, QkvParts* defer = nullptr) {
     if (defer) *defer = QkvParts{nullptr, 0, 0};
+    const uint16_t* Xh = c->xin_h ? c->xin_h : c->xs_h;
+    const uint16_t* Xl = c->xin_l ? c->xin_l : c->xs_l;
+    c->xin_h = c->xin_l = nullptr;
     const bool few = M <= 64 && N % 4 == 0;
     SkGeom geo{};                                            // G = 0: uniform K slices
     const int rows = few ? (M <= 32 ? 32 : 64) : M;          // rows of one slice of partial results
@@ -516,33 +521,34 @@ void rows_gemm(rsd_ctx* c, const Model& m, int op, int epi, const bf16_t* W, int
     if (few && geo.G > 0) {
         ks = geo.zmax;
         ProbeScope ps(c, m, op, pb, pf);
-        gemm_rows_sk_launch<kSkDepth>(c->st, W, N, K, c->xs_h, c->xs_l, M, c->part_k, geo);
+        gemm_rows_sk_launch<kSkDepth>(c->st, W, N, K, Xh, Xl, M, c->part_k, geo);
     } else if (few) {
         ks = gemm_rows_slices(N, K, rows, c->part_k_floats);
         ProbeScope ps(c, m, op, pb, pf);
-        gemm_rows_launch(c->st, W, N, K, c->xs_h, c->xs_l, M, c->part_k, ks);
+        gemm_rows_launch(c->st, W, N, K, Xh, Xl, M, c->part_k, ks);
     } else {
         ks = N % 4 ? 1 : gemm_tile_slices(N, K, M, c->part_k_floats);
         if (ks == 1) {      // the tile kernel finishes by itself
             if (epi == EPI_SWIGLU) {
-                {
-                    ProbeScope ps(c, m, op, pb, pf);
-                    gemm_tile_launch(c->st, EPI_STORE, W, N, K, c->xs_h, c->xs_l, M, c->gu, N, nullptr, 1);
-                }
-                const size_t total = (size_t)M * (N / 2);
-                hipLaunchKernelGGL(swiglu_split_kernel, dim3((unsigned)((total / 4 + 255) / 256)), dim3(256), 0, c->st,
-                                   c->gu, N / 2, c->xs_h, c->xs_l, total);
+                // the kernel activates in its epilogue; the halves cannot go to xs_h / xs_l, which other blocks still
+                // read as this product's input, so they go to the (otherwise unused) gate/up workspace and the down
+                // projection that follows is pointed there
+                uint16_t* oh = reinterpret_cast<uint16_t*>(c->gu);
+                uint16_t* ol = oh + (size_t)M * (N / 2);
+                ProbeScope ps(c, m, op, pb, pf);
+                gemm_tile_launch(c->st, EPI_SWIGLU, W, N, K, Xh, Xl, M, nullptr, 0, nullptr, 1, oh, ol);
+                c->xin_h = oh; c->xin_l = ol;
             } else {
                 {
                     ProbeScope ps(c, m, op, pb, pf);
-                    gemm_tile_launch(c->st, epi, W, N, K, c->xs_h, c->xs_l, M, Y, ldy, nullptr, 1);
+                    gemm_tile_launch(c->st, epi, W, N, K, Xh, Xl, M, Y, ldy, nullptr, 1);
                 }
                 if (next_gain) rows_split(c, Y, ldy, M, N, next_gain, eps);
             }
             return;
         }
         ProbeScope ps(c, m, op, pb, pf);
-        gemm_tile_launch(c->st, EPI_STORE, W, N, K, c->xs_h, c->xs_l, M, nullptr, 0, c->part_k, ks);
+        gemm_tile_launch(c->st, EPI_STORE, W, N, K, Xh, Xl, M, nullptr, 0, c->part_k, ks);
     }
     if (defer && geo.G == 0 && ldy == N) {
         *defer = QkvParts{c->part_k, ks, (size_t)rows * N};
