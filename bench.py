@@ -356,7 +356,7 @@ def main():
     ap.add_argument("--reps", type=int, default=200)
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on exactly one GPU (sequences are independent; more GPUs would shard the "
+        print("bench.py: this library runs on exactly one GPU (sequences are independent; more GPUs would shard the "
               "batch with no communication); --gpus must be 1", file=sys.stderr)
         sys.exit(2)
     if args.probe == "attention":

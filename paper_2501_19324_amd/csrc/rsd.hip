@@ -573,6 +573,7 @@ void run_layers(rsd_ctx* c, Model& m, int M, const RowMap& rm, bool decode) {
     hipStream_t st = c->st;
     const int d = m.s.d_model, F = m.s.d_ffn;
     const float eps = m.s.rms_eps;
+    c->xin_h = c->xin_l = nullptr;          // (a redirection is only ever meant for the projection right after its producer)
     hipLaunchKernelGGL((embed_kernel<WT>), dim3(M), dim3(256), 0, st, wptr<WT>(m, m.off_embed), d, c->ds.tokens,
                        c->p.max_ctx, rm, c->h);
     const int S = decode ? m.splits : 1;
