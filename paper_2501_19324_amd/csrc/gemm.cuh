@@ -993,13 +993,53 @@ static bool gemm_tile_decode_rows(int M) { return M <= 256; }
 // Decode-size launches (one row tile of the batch): the 256-row tile wherever its N tiles x K slices (at least six
 // K blocks each) give 128 blocks or more, else two 128-row tiles (small matrices: the 1.5B attention projections
 // at 256 rows 22 -> 17 us).  A compute unit holds one block of the 256-row tile or two of the 128-row tile.
+// Chunked passes (more than 256 rows): tile height and K slices by a small cost model in units of the measured
+// time per K block (1.37 us for a 256-row block, one per compute unit; 2.2 us for two co-resident 128-row blocks,
+// 0.97 us for one alone): rounds of resident blocks x K blocks per slice (+ 3 for filling and draining the
+// pipeline), plus what the finish kernel pays to read the slices' partial sums back.
+struct TilePlan { int bm, ks; };
+static TilePlan gemm_tile_plan_chunked(int N, int K, int M, size_t part_floats) {
+    const int tn = (N + 255) / 256, nkb = K / 32;
+    TilePlan best{256, 1};
+    double best_t = 1e30;
+    for (int bm : {256, 128})
+        for (int ks = 1; ks <= 32; ks *= 2) {
+            if (ks > 1 && (nkb / ks < 8 || (size_t)ks * M * N > part_floats)) break;
+            const long long blocks = (long long)tn * ((M + bm - 1) / bm) * ks;
+            const double kb = (nkb + ks - 1) / ks + 3;
+            double us;
+            if (bm == 256) us = (double)((blocks + 255) / 256) * kb * 1.37;
+            else {
+                const long long rem = blocks % 512;
+                us = (double)(blocks / 512) * kb * 2.2 + (rem == 0 ? 0.0 : rem <= 256 ? kb * 0.97 : kb * 2.2);
+            }
+            if (ks > 1) us += 4.0 + (double)ks * M * N * 8.0 / 5.0e6;
+            if (us < best_t) { best_t = us; best = TilePlan{bm, ks}; }
+        }
+    return best;
+}
 static int gemm_tile_bm(int N, int K, int M, int ks) {
     if (gemm_tile_decode_rows(M)) {
         const int tn = (N + 255) / 256, nkb = K / 32;
         if (M <= 128) return 128;
         return tn * std::max(1, std::min(std::min(256 / tn, nkb / 6), 32)) >= 128 ? 256 : 128;
     }
-    return ((N + 255) / 256) * ((M + 255) / 256) * ks >= 400 ? 256 : 128;
+    // (chunked: the height the plan chose for this slice count)
+    TilePlan best{256, ks};
+    double best_t = 1e30;
+    const int tn = (N + 255) / 256, nkb = K / 32;
+    for (int bm : {256, 128}) {
+        const long long blocks = (long long)tn * ((M + bm - 1) / bm) * ks;
+        const double kb = (nkb + ks - 1) / ks + 3;
+        double us;
+        if (bm == 256) us = (double)((blocks + 255) / 256) * kb * 1.37;
+        else {
+            const long long rem = blocks % 512;
+            us = (double)(blocks / 512) * kb * 2.2 + (rem == 0 ? 0.0 : rem <= 256 ? kb * 0.97 : kb * 2.2);
+        }
+        if (us < best_t) { best_t = us; best.bm = bm; }
+    }
+    return best.bm;
 }
 static int gemm_tile_slices(int N, int K, int M, size_t part_floats) {
     if (gemm_tile_decode_rows(M)) {
@@ -1010,10 +1050,7 @@ static int gemm_tile_slices(int N, int K, int M, size_t part_floats) {
         while (ks > 1 && ((size_t)ks * M * N > part_floats || (ks - 1) * ((nkb + ks - 1) / ks) >= nkb)) --ks;
         return ks;
     }
-    const int tiles = ((N + 255) / 256) * ((M + 127) / 128);
-    int ks = 1;
-    while (ks < 32 && tiles * ks < 512 && K / 32 / (ks * 2) >= 8 && (size_t)(ks * 2) * M * N <= part_floats) ks *= 2;
-    return ks;
+    return gemm_tile_plan_chunked(N, K, M, part_floats).ks;
 }
 
 // epi == EPI_SWIGLU (W = [gate | up], ks = 1): the activated values go to Oh / Ol [M][N / 2] as hi / lo halves
