@@ -982,8 +982,7 @@ __global__ __launch_bounds__(BM * 2, BM == 128 ? 2 : 1) void gemm_tile_kernel(co
 }
 
 // Block tile and K slices for gemm_tile_kernel.
-// Many rows (chunked passes): as many slices as bring the grid to about 512 blocks, none below 8 K blocks; 256-row
-// tiles when they still fill the chip about twice.
+// Many rows (chunked passes): gemm_tile_plan_chunked below.
 // 65..256 rows (the decode iteration of a large batch: one row tile): the kernel is MFMA-bound there, two
 // co-resident 128-row blocks run no faster than one (measured per K block of 32: 0.97 us for a 128-row block
 // alone on its unit, 2.2 us each for two, 1.37 us for a 256-row block), so the grid is kept to one round of at
