@@ -1,7 +1,8 @@
 """GPU checks at full depth and full width (bf16, 28-layer 1.5B draft / 7B target /
 1.5B reward model, vocabulary 151936), in the launch configurations bench.py times:
-configuration 1 (batch 1), and seeded subsets of configurations 2 (batch 64, ragged
-prompts) and 4 (batch 256, 1024-token prompts).
+configuration 1 (batch 1), seeded subsets of configurations 2 (batch 64, ragged
+prompts), 4 (batch 256, 1024-token prompts) and 3 (batch 16, 72B target resident, 7B
+reward model), and two whole reasoning steps of configuration 3 checked by properties.
 
 The fp64 CPU checker can evaluate all three full-depth models on a prompt (the 7B
 target is about 60 GB as fp64), so next-token logits and rewards are compared with
@@ -87,9 +88,10 @@ def test_full_depth_prompt_against_checker(full, checker_models, which):
     s.reset()
 
 
-@pytest.mark.parametrize("name,check", [("cfg2", [5, 40]), ("cfg4", [17])])
+@pytest.mark.parametrize("name,check", [("cfg2", [5, 40]), ("cfg4", [17]), ("cfg3", [3])])
 def test_full_depth_batched_subset(checker_models, name, check):
-    """Configurations 2 and 4 at their own batch (64 / 256), prompts and full-depth models, steps
+    """Configurations 2, 4 and 3 at their own batch (64 / 256 / 16; configuration 3 with its 72B target
+    resident and its 7B reward model scoring), prompts and full-depth models, steps
     truncated to 12 tokens: the sequences in `check` are followed by the checker for two reasoning
     steps under the teacher (draft tokens forced, delta = 0 so that the target, whose full-depth
     checker costs minutes per step, is never needed): draft tokens (the path's own choice may differ
@@ -181,3 +183,63 @@ def test_full_size_steps_properties(full):
         pg = R.rsd_export_pages(s.ctx, mdl)
         used = pg["block_table"][pg["block_table"] >= 0]
         assert len(set(used.tolist())) == used.size and used.size + pg["free_pages"] == pg["pool_pages"]
+
+
+def test_largest_configuration_steps_properties():
+    """Configuration 3 as bench.py times it (batch 16, 1.5B draft, 72B target, 7B reward model, 512-token
+    prompts, steps of up to 128 tokens): two reasoning steps, twice.  The 72B target is beyond the checker
+    (580 GB in fp64), so what holds at any size is checked for every sequence: identical results on the
+    second run, decisions equal to the threshold rule on the exported rewards, the cache-offset and page
+    contract of accepted and rejected steps, no page owned twice, and rows of the target's stages packed
+    to the rejected sequences."""
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from rsd_inputs import workload
+    from paper_2501_19324_amd import binding as R
+    from paper_2501_19324_amd.harness import Session
+    w = workload("cfg3", max_steps=2)
+    s = Session(w)
+    runs = []
+    for _ in range(2):
+        s.reset()
+        R.rsd_iter_stats(s.ctx, R.RSD_TARGET, reset=True)
+        recs, states = [], []
+        for _i in range(w.max_steps):
+            recs.append(R.rsd_step(s.ctx))
+            states.append(R.rsd_export_state(s.ctx, want_tokens=False))
+        runs.append((recs, states, R.rsd_export_state(s.ctx)["tokens"].copy(), R.rsd_iter_stats(s.ctx, R.RSD_TARGET)))
+    (ra, sa, ta, ia), (rb, sb, tb, ib) = runs
+    assert np.array_equal(ta, tb)
+    for x, y in zip(ra, rb):
+        for k in x:
+            assert np.array_equal(x[k], y[k]), k
+    ctx = s.prompt_len.astype(np.int64).copy()
+    kv_t_prev = np.zeros(w.batch, np.int64)
+    n_rej = 0
+    for g, st in zip(ra, sa):
+        assert ((g["reward"] > 0.0) & (g["reward"] < 1.0)).all()
+        assert np.array_equal(g["accepted"] != 0, g["reward"] >= np.float32(w.delta))
+        assert np.array_equal(g["accepted"], g["own_accept"])
+        assert ((g["draft_len"] >= 1) & (g["draft_len"] <= w.step_cap) & (g["final_len"] >= 1) & (g["final_len"] <= w.step_cap)).all()
+        pre, ctx = ctx, ctx + g["final_len"]
+        assert np.array_equal(st["ctx_len"], ctx)
+        for b in range(w.batch):
+            kd, kt, kp = (int(v) for v in st["kv_len"][:, b])
+            if g["accepted"][b]:
+                assert (kd, kt, kp) == (ctx[b] - 1, kv_t_prev[b], ctx[b]), b
+                assert np.array_equal(g["draft_tokens"][b], g["final_tokens"][b])
+            else:
+                assert (kd, kt, kp) == (pre[b], ctx[b] - 1, pre[b]), b
+                n_rej += 1
+            assert list(st["n_pages"][:, b]) == [-(-v // 16) for v in (kd, kt, kp)]
+        kv_t_prev = st["kv_len"][1].astype(np.int64)
+    assert n_rej > 0, "the target never ran"
+    assert ia["iterations"] > 0 and ia["seq_iterations"] <= ia["row_iterations"] <= w.batch * ia["iterations"]
+    assert ia == {**ib, "gpu_ms": ia["gpu_ms"]}
+    for mdl in range(3):
+        pg = R.rsd_export_pages(s.ctx, mdl)
+        used = pg["block_table"][pg["block_table"] >= 0]
+        assert len(set(used.tolist())) == used.size and used.size + pg["free_pages"] == pg["pool_pages"]
+    print(f"configuration 3: {n_rej} of {2 * w.batch} steps regenerated by the 72B target; its iterations ran on "
+          f"{ia['row_iterations'] / ia['iterations']:.1f} rows on average for {ia['seq_iterations'] / ia['iterations']:.1f} sequences")
+    s.close()
