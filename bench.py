@@ -102,7 +102,7 @@ def blas_threads():
 def kernel_sources_sha():
     import hashlib
     h = hashlib.sha256()
-    for p in ("paper_2501_19324_amd/csrc/gemm.cuh", "paper_2501_19324_amd/csrc/gemv.cuh", "paper_2501_19324_amd/csrc/common.cuh"):
+    for p in ("paper_2501_19324_amd/csrc/gemm.h", "paper_2501_19324_amd/csrc/gemv.h", "paper_2501_19324_amd/csrc/common.h"):
         h.update(open(os.path.join(ROOT, p), "rb").read())
     return h.hexdigest()
 

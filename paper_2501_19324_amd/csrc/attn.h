@@ -7,7 +7,7 @@
 // KvTraits / KvTiled below).  Token at position p of a sequence lives in logical
 // page p / 16, slot p % 16; block_table[seq][logical page] gives the physical page.
 #pragma once
-#include "common.cuh"
+#include "common.h"
 
 #define RSD_PAGE 16
 

@@ -14,8 +14,8 @@
 #pragma once
 #include <algorithm>
 #include <atomic>
-#include "common.cuh"
-#include "gemv.cuh"
+#include "common.h"
+#include "gemv.h"
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;

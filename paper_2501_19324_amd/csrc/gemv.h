@@ -11,7 +11,7 @@
 #include <algorithm>
 #include <atomic>
 #include <hip/hip_ext.h>
-#include "common.cuh"
+#include "common.h"
 
 enum { PRO_NONE = 0, PRO_NORM = 1, PRO_SWIGLU = 2, PRO_ATTN = 3 };
 

@@ -2,7 +2,7 @@
 // gather, reward head, per-token step bookkeeping, acceptance criterion with
 // rollback.
 #pragma once
-#include "common.cuh"
+#include "common.h"
 
 template <typename WT>
 __global__ void embed_kernel(const WT* __restrict__ E, int d, const int* __restrict__ tokens, int max_ctx,

@@ -16,13 +16,13 @@
 
 #include "rsd.h"
 #include "pages.h"
-#include "common.cuh"
-#include "gemv.cuh"
-#include "gemm.cuh"
-#include "attn.cuh"
-#include "misc.cuh"
-#include "sample.cuh"
-#include "specdec.cuh"
+#include "common.h"
+#include "gemv.h"
+#include "gemm.h"
+#include "attn.h"
+#include "misc.h"
+#include "sample.h"
+#include "specdec.h"
 
 namespace {
 
@@ -2225,7 +2225,7 @@ int rsd_sample(rsd_ctx* c, const float* logits_dev, const float* u_dev, int32_t 
 
 }  // extern "C"
 
-#include "sample_static.cuh"
+#include "sample_static.h"
 
 // --------------------------------------------------------------------------- rsd_forward
 namespace {

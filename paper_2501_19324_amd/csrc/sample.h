@@ -18,8 +18,8 @@
 // C  level 2 ->  D  level 3 ->  E  per-block nucleus mass ->  F  locate the
 // draw, append the token to its sequence, clear the histograms.
 #pragma once
-#include "common.cuh"
-#include "misc.cuh"
+#include "common.h"
+#include "misc.h"
 
 typedef unsigned long long u64_t;
 

@@ -1,9 +1,9 @@
-// rsd_sample_static: the sampler of sample.cuh behind an entry point that allocates nothing.
-// Included by rsd.hip (one translation unit: the kernels of sample.cuh are defined there).
+// rsd_sample_static: the sampler of sample.h behind an entry point that allocates nothing.
+// Included by rsd.hip (one translation unit: the kernels of sample.h are defined there).
 #pragma once
 #include <mutex>
 #include "rsd.h"
-#include "sample.cuh"
+#include "sample.h"
 
 // The sampler for callers that cannot allocate: its workspace is a file-scope device array instead of
 // the context's buffers.  Every device holds its own copy of the array at its own address; host code

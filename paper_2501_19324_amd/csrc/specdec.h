@@ -5,7 +5,7 @@
 // from the normalised positive part of p - q; after a fully kept run one more token is drawn
 // from the target's next distribution.
 //
-// p and q are the distributions the sampler draws from (sample.cuh): e_t = exp(x_t - max x),
+// p and q are the distributions the sampler draws from (sample.h): e_t = exp(x_t - max x),
 // x = (logit + separator bias) / temperature, restricted to the nucleus {e_t >= tau} and
 // divided by the nucleus mass Z.  The sampler's phases A-E run first on every row and leave
 // max x (per-block maxima), tau and the per-block masses in its workspace; masses are 2^40
@@ -13,7 +13,7 @@
 // integers, and the positive part of p - q is summed as 2^50 fixed point, so that every sum is
 // exact and order-independent and the draw is reproducible.
 #pragma once
-#include "sample.cuh"
+#include "sample.h"
 
 struct SdRowSet {                 // rows the sampler has prepared (phases A-E)
     const float* logits; int ld;
