@@ -195,6 +195,7 @@ def iteration_record(R, s, shapes, reset=True):
 
 
 def probe_record(R, s, slot, kind):
+    clk = R.rsd_probe_clock(s.ctx, slot) if kind == "mfma" else None
     p = R.rsd_probe_read(s.ctx, slot)
     if p["n"] == 0 or p["total_ms"] <= 0:
         return None
@@ -204,9 +205,17 @@ def probe_record(R, s, slot, kind):
         return {"launches_timed": p["n"], "avg_launch_us": round(sec / p["n"] * 1e6, 2),
                 "bytes_per_launch": p["total_bytes"] // p["n"], "GBs": round(gbs, 1), "frac": round(gbs / HBM_PEAK_GBS, 4)}
     tf = p["total_flops"] / sec / 1e12
-    return {"launches_timed": p["n"], "avg_launch_us": round(sec / p["n"] * 1e6, 2),
-            "flops_per_launch": p["total_flops"] // p["n"], "TFLOPs": round(tf, 1),
-            "frac_of_bf16_mfma_peak": round(tf / MFMA_BF16_PEAK_TFLOPS, 4)}
+    rec = {"launches_timed": p["n"], "avg_launch_us": round(sec / p["n"] * 1e6, 2),
+           "flops_per_launch": p["total_flops"] // p["n"], "TFLOPs": round(tf, 1),
+           "frac_of_bf16_mfma_peak": round(tf / MFMA_BF16_PEAK_TFLOPS, 4)}
+    if clk and clk["launches"] > 0 and clk["ref_ticks"] > 0:
+        # shader clock read inside the probed launches (against the constant 100 MHz counter); the published
+        # peak is quoted at 2400 MHz, so the second figure is the fraction of what the MFMA units can issue
+        # at the clock the chip actually held
+        mhz = clk["shader_ticks"] / clk["ref_ticks"] * 100.0
+        rec["shader_clock_mhz"] = round(mhz, 1)
+        rec["frac_of_mfma_peak_at_that_clock"] = round(tf / (MFMA_BF16_PEAK_TFLOPS * mhz / 2400.0), 4)
+    return rec
 
 
 def run_steps(R, s, w, n_steps, warmup=0, probes=True, probe_stride=8):

@@ -344,6 +344,15 @@ int rsd_probe_start(rsd_ctx *c, int32_t slot, int32_t model, int32_t phase, int3
 int rsd_probe_read(rsd_ctx *c, int32_t slot, int64_t *n_samples, double *total_ms, int64_t *total_bytes,
                    int64_t *total_flops);
 
+/* The clock the chip sustains under the probed many-row (chunked-pass) GEMMs.  While slot `slot` is armed with
+ * phase RSD_PROBE_PREFILL, every probed launch of the tile GEMM has the thread block in the middle of its grid
+ * read the shader clock counter and the constant 100 MHz reference counter around its K loop; the differences
+ * are summed per slot (cleared by rsd_probe_start, kept across rsd_probe_read).  Returns the number of launches
+ * that reported, the summed shader ticks and the summed reference ticks: shader_ticks / ref_ticks * 100 MHz is
+ * the mean shader clock during those launches (the published MFMA peak assumes 2400 MHz).  Launches served by
+ * the few-row kernels (<= 64 rows) report nothing.  Synchronises the stream; host pointers; any may be NULL. */
+int rsd_probe_clock(rsd_ctx *c, int32_t slot, int64_t *launches, int64_t *shader_ticks, int64_t *ref_ticks);
+
 /* Accounting of the single-token decode loop of one policy model (RSD_DRAFT or RSD_TARGET; the loop that
  * generates a reasoning step token by token, Algorithm 1) since the context was created or the counters
  * were last reset: iterations launched (each streams the model's weights once, whatever the number of

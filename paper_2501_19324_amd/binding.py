@@ -17,7 +17,7 @@ __all__ = ["RSD_OK", "RSD_EINVAL", "RSD_ENOMEM", "RSD_ESTATE", "RSD_EHIP", "RSD_
            "RsdError", "Context", "load_library", "rsd_init", "rsd_set_prompts", "rsd_set_uniforms",
            "rsd_set_criterion", "rsd_step", "rsd_generate", "rsd_export_state", "rsd_export_pages",
            "rsd_set_teacher", "rsd_export_sampled", "rsd_forward", "rsd_sample", "rsd_stage_ms", "rsd_decode_stats", "rsd_destroy",
-           "rsd_probe_start", "rsd_probe_read", "rsd_iter_stats", "rsd_iter_rows", "rsd_check_rows", "rsd_debug_build", "rsd_probe_attention", "rsd_sample_static",
+           "rsd_probe_start", "rsd_probe_read", "rsd_probe_clock", "rsd_iter_stats", "rsd_iter_rows", "rsd_check_rows", "rsd_debug_build", "rsd_probe_attention", "rsd_sample_static",
            "rsd_bon_step", "rsd_bon_generate", "rsd_bon_stats", "EXPORTED_SYMBOLS"]
 
 RSD_OK, RSD_EINVAL, RSD_ENOMEM, RSD_ESTATE, RSD_EHIP = 0, -1, -2, -3, -4
@@ -25,7 +25,7 @@ RSD_DRAFT, RSD_TARGET, RSD_PRM = 0, 1, 2
 RSD_MERGE_NONE, RSD_MERGE_DRAFT, RSD_MERGE_TARGET = 0, 1, 2
 EXPORTED_SYMBOLS = ["rsd_init", "rsd_set_prompts", "rsd_set_uniforms", "rsd_set_criterion", "rsd_step",
                     "rsd_generate", "rsd_export_state", "rsd_export_pages", "rsd_set_teacher",
-                    "rsd_export_sampled", "rsd_set_teacher_sd", "rsd_export_proposed", "rsd_set_uniforms_sd", "rsd_sd_verify", "rsd_forward", "rsd_sample", "rsd_stage_ms", "rsd_decode_stats", "rsd_probe_start", "rsd_probe_read",
+                    "rsd_export_sampled", "rsd_set_teacher_sd", "rsd_export_proposed", "rsd_set_uniforms_sd", "rsd_sd_verify", "rsd_forward", "rsd_sample", "rsd_stage_ms", "rsd_decode_stats", "rsd_probe_start", "rsd_probe_read", "rsd_probe_clock",
                     "rsd_iter_stats", "rsd_iter_rows", "rsd_check_rows", "rsd_debug_build", "rsd_probe_attention", "rsd_sample_static", "rsd_bon_step", "rsd_bon_generate", "rsd_bon_stats",
                     "rsd_last_error", "rsd_destroy"]
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "librsd.so")
@@ -368,6 +368,12 @@ def rsd_probe_read(ctx: Context, slot: int) -> dict:
     n, ms, by, fl = C.c_int64(), C.c_double(), C.c_int64(), C.c_int64()
     ctx.check(load_library().rsd_probe_read(ctx.handle, C.c_int32(slot), C.byref(n), C.byref(ms), C.byref(by), C.byref(fl)))
     return dict(n=n.value, total_ms=ms.value, total_bytes=by.value, total_flops=fl.value)
+
+
+def rsd_probe_clock(ctx: Context, slot: int) -> dict:
+    n, sh, ref = C.c_int64(), C.c_int64(), C.c_int64()
+    ctx.check(load_library().rsd_probe_clock(ctx.handle, C.c_int32(slot), C.byref(n), C.byref(sh), C.byref(ref)))
+    return dict(launches=n.value, shader_ticks=sh.value, ref_ticks=ref.value)
 
 
 def rsd_iter_rows(ctx: Context, model: int) -> int:

@@ -813,7 +813,13 @@ __global__ __launch_bounds__(BM * 2, BM == 128 ? 2 : 1) void gemm_tile_kernel(co
                                                            const uint16_t* __restrict__ Xl, int M,
                                                            float* __restrict__ Y, int ldy,
                                                            float* __restrict__ part,
-                                                           uint16_t* __restrict__ Oh, uint16_t* __restrict__ Ol) {
+                                                           uint16_t* __restrict__ Oh, uint16_t* __restrict__ Ol,
+                                                           unsigned long long* __restrict__ clk) {
+    // clk != nullptr (a timing probe is armed): the block in the middle of the grid reports how many shader clock
+    // ticks and how many ticks of the constant 100 MHz counter its K loop took: {shader ticks, reference ticks,
+    // launches} are added to clk[0..2], which gives the clock the chip sustains while this kernel runs
+    long long clk_c0 = 0, clk_w0 = 0;
+    if (clk) { clk_c0 = clock64(); clk_w0 = wall_clock64(); }
     constexpr int BN = 256, BK = 32, CR = BM / 2;        // CR: rows covered by one round of copies (threads / 4)
     __shared__ __attribute__((aligned(16))) uint16_t Ah[2][BM * BK];
     __shared__ __attribute__((aligned(16))) uint16_t Al[2][BM * BK];
@@ -937,6 +943,11 @@ __global__ __launch_bounds__(BM * 2, BM == 128 ? 2 : 1) void gemm_tile_kernel(co
 #undef RSD_FETCH
 #undef RSD_STAGE
 #undef RSD_COMPUTE
+    if (clk && tid == 0 && blockIdx.x == gridDim.x / 2 && blockIdx.y == gridDim.y / 2 && blockIdx.z == 0) {
+        atomicAdd(&clk[0], (unsigned long long)(clock64() - clk_c0));
+        atomicAdd(&clk[1], (unsigned long long)(wall_clock64() - clk_w0));
+        atomicAdd(&clk[2], 1ull);
+    }
 
     if (EPI == EPI_SWIGLU) {
         // silu(gate) * up of the units this wave holds, straight into the hi / lo halves the down projection reads
@@ -1055,18 +1066,18 @@ static int gemm_tile_slices(int N, int K, int M, size_t part_floats) {
 // epi == EPI_SWIGLU (W = [gate | up], ks = 1): the activated values go to Oh / Ol [M][N / 2] as hi / lo halves
 static void gemm_tile_launch(hipStream_t st, int epi, const bf16_t* W, int N, int K, const uint16_t* Xh,
                              const uint16_t* Xl, int M, float* Y, int ldy, float* part, int ks,
-                             uint16_t* Oh = nullptr, uint16_t* Ol = nullptr) {
+                             uint16_t* Oh = nullptr, uint16_t* Ol = nullptr, unsigned long long* clk = nullptr) {
     const int tn = (N + 255) / 256;
     if (gemm_tile_bm(N, K, M, ks) == 256) {
         const dim3 grid(tn, (M + 255) / 256, ks), block(512);
-        if (epi == EPI_SWIGLU)     hipLaunchKernelGGL((gemm_tile_kernel<EPI_SWIGLU, 256>), grid, block, 0, st, W, N, K, Xh, Xl, M, Y, ldy, part, Oh, Ol);
-        else if (epi == EPI_RESID) hipLaunchKernelGGL((gemm_tile_kernel<EPI_RESID, 256>), grid, block, 0, st, W, N, K, Xh, Xl, M, Y, ldy, part, Oh, Ol);
-        else                       hipLaunchKernelGGL((gemm_tile_kernel<EPI_STORE, 256>), grid, block, 0, st, W, N, K, Xh, Xl, M, Y, ldy, part, Oh, Ol);
+        if (epi == EPI_SWIGLU)     hipLaunchKernelGGL((gemm_tile_kernel<EPI_SWIGLU, 256>), grid, block, 0, st, W, N, K, Xh, Xl, M, Y, ldy, part, Oh, Ol, clk);
+        else if (epi == EPI_RESID) hipLaunchKernelGGL((gemm_tile_kernel<EPI_RESID, 256>), grid, block, 0, st, W, N, K, Xh, Xl, M, Y, ldy, part, Oh, Ol, clk);
+        else                       hipLaunchKernelGGL((gemm_tile_kernel<EPI_STORE, 256>), grid, block, 0, st, W, N, K, Xh, Xl, M, Y, ldy, part, Oh, Ol, clk);
         return;
     }
     const dim3 grid(tn, (M + 127) / 128, ks), block(256);
-    if (epi == EPI_SWIGLU)     hipLaunchKernelGGL((gemm_tile_kernel<EPI_SWIGLU, 128>), grid, block, 0, st, W, N, K, Xh, Xl, M, Y, ldy, part, Oh, Ol);
-    else if (epi == EPI_RESID) hipLaunchKernelGGL((gemm_tile_kernel<EPI_RESID, 128>), grid, block, 0, st, W, N, K, Xh, Xl, M, Y, ldy, part, Oh, Ol);
-    else                       hipLaunchKernelGGL((gemm_tile_kernel<EPI_STORE, 128>), grid, block, 0, st, W, N, K, Xh, Xl, M, Y, ldy, part, Oh, Ol);
+    if (epi == EPI_SWIGLU)     hipLaunchKernelGGL((gemm_tile_kernel<EPI_SWIGLU, 128>), grid, block, 0, st, W, N, K, Xh, Xl, M, Y, ldy, part, Oh, Ol, clk);
+    else if (epi == EPI_RESID) hipLaunchKernelGGL((gemm_tile_kernel<EPI_RESID, 128>), grid, block, 0, st, W, N, K, Xh, Xl, M, Y, ldy, part, Oh, Ol, clk);
+    else                       hipLaunchKernelGGL((gemm_tile_kernel<EPI_STORE, 128>), grid, block, 0, st, W, N, K, Xh, Xl, M, Y, ldy, part, Oh, Ol, clk);
 }
 

@@ -143,6 +143,7 @@ struct rsd_ctx {
         long long bytes = 0, flops = 0;
         std::vector<hipEvent_t> ev;
     } probe[RSD_PROBE_SLOTS];
+    unsigned long long* clk_dev = nullptr;                  // per probe slot: {shader ticks, 100 MHz ticks, launches} of probed tile GEMMs
     bool in_decode_loop = false;
     int cur_phase = RSD_PROBE_DECODE;                        // what run_layers is launching for
     // accounting of the decode loops of the draft and the target
@@ -371,6 +372,8 @@ struct ProbeScope {
         if (direct) gemv_timing = GemvTiming{p->ev[p->used], p->ev[p->used + 1]};
         else (void)hipEventRecord(p->ev[p->used], c->st);
     }
+    // where a probed many-row GEMM adds its clock readings (nullptr: no probe armed for this launch)
+    unsigned long long* clk() const { return p ? c->clk_dev + 3 * (p - c->probe) : nullptr; }
     ~ProbeScope() {
         if (!p) return;
         if (direct) {
@@ -536,19 +539,19 @@ void rows_gemm(rsd_ctx* c, const Model& m, int op, int epi, const bf16_t* W, int
                 uint16_t* oh = reinterpret_cast<uint16_t*>(c->gu);
                 uint16_t* ol = oh + (size_t)M * (N / 2);
                 ProbeScope ps(c, m, op, pb, pf);
-                gemm_tile_launch(c->st, EPI_SWIGLU, W, N, K, Xh, Xl, M, nullptr, 0, nullptr, 1, oh, ol);
+                gemm_tile_launch(c->st, EPI_SWIGLU, W, N, K, Xh, Xl, M, nullptr, 0, nullptr, 1, oh, ol, ps.clk());
                 c->xin_h = oh; c->xin_l = ol;
             } else {
                 {
                     ProbeScope ps(c, m, op, pb, pf);
-                    gemm_tile_launch(c->st, epi, W, N, K, Xh, Xl, M, Y, ldy, nullptr, 1);
+                    gemm_tile_launch(c->st, epi, W, N, K, Xh, Xl, M, Y, ldy, nullptr, 1, nullptr, nullptr, ps.clk());
                 }
                 if (next_gain) rows_split(c, Y, ldy, M, N, next_gain, eps);
             }
             return;
         }
         ProbeScope ps(c, m, op, pb, pf);
-        gemm_tile_launch(c->st, EPI_STORE, W, N, K, Xh, Xl, M, nullptr, 0, c->part_k, ks);
+        gemm_tile_launch(c->st, EPI_STORE, W, N, K, Xh, Xl, M, nullptr, 0, c->part_k, ks, nullptr, nullptr, ps.clk());
     }
     if (defer && geo.G == 0 && ldy == N) {
         *defer = QkvParts{c->part_k, ks, (size_t)rows * N};
@@ -1218,7 +1221,7 @@ void rsd_destroy(rsd_ctx* c) {
                    c->sd_ws[0].pmax, c->sd_ws[0].pidx, c->sd_ws[0].hist, c->sd_ws[0].psum, c->sd_ws[0].sel,
                    c->sd_ws[1].pmax, c->sd_ws[1].pidx, c->sd_ws[1].hist, c->sd_ws[1].psum, c->sd_ws[1].sel, c->h, c->xn, c->qkv, c->att, c->gu, c->act,
                    c->part_acc, c->part_ml, c->part_k, c->xs_h, c->xs_l, c->smp_pmax, c->smp_pidx, c->smp_hist, c->smp_psum, c->smp_sel, c->hl, c->xl, c->logits, c->tmp_reward, c->chosen, c->steptok_dev,
-                   c->row_seq_dev, c->row_pos_dev, c->last_row_dev, c->item_row0_dev, c->item_n_dev, c->bon_copy_dev, c->bon_src_dev, c->dec_seq_dev, c->chk_n_pages_dev, c->chk_err_dev};
+                   c->row_seq_dev, c->row_pos_dev, c->last_row_dev, c->item_row0_dev, c->item_n_dev, c->bon_copy_dev, c->bon_src_dev, c->dec_seq_dev, c->chk_n_pages_dev, c->chk_err_dev, c->clk_dev};
     for (void* p : dev) if (p) (void)hipFree(p);
     for (auto& q : c->probe)
         for (hipEvent_t e : q.ev) (void)hipEventDestroy(e);
@@ -1333,6 +1336,8 @@ int rsd_init(rsd_ctx** out, const rsd_model_shape shape[3], const rsd_weights w[
     HIPCHK(c, dev_alloc(&c->part_ml, part));
     c->part_k_floats = (size_t)48 << 20;
     HIPCHK(c, dev_alloc(&c->part_k, c->part_k_floats));
+    HIPCHK(c, dev_alloc(&c->clk_dev, 3 * RSD_PROBE_SLOTS));
+    HIPCHK(c, hipMemset(c->clk_dev, 0, 3 * RSD_PROBE_SLOTS * sizeof(unsigned long long)));
     {
         const size_t kmax = (size_t)std::max(std::max(d, qd), F), xr = std::max<size_t>(R, 64);
         HIPCHK(c, dev_alloc(&c->xs_h, xr * kmax));
@@ -2104,6 +2109,19 @@ int rsd_probe_start(rsd_ctx* c, int32_t slot, int32_t model, int32_t phase, int3
     }
     q.model = model; q.phase = phase; q.op = op; q.stride = stride;
     q.seen = 0; q.iters = 0; q.used = 0; q.bytes = 0; q.flops = 0; q.iter_on = false;
+    HIPCHK(c, hipMemset(c->clk_dev + 3 * slot, 0, 3 * sizeof(unsigned long long)));     // the stream is idle here
+    return RSD_OK;
+}
+
+int rsd_probe_clock(rsd_ctx* c, int32_t slot, int64_t* launches, int64_t* shader_ticks, int64_t* ref_ticks) {
+    if (!c) return RSD_EINVAL;
+    if (slot < 0 || slot >= RSD_PROBE_SLOTS) return fail(c, RSD_EINVAL, "bad probe slot");
+    HIPCHK(c, hipStreamSynchronize(c->st));
+    unsigned long long h[3] = {0, 0, 0};
+    HIPCHK(c, hipMemcpy(h, c->clk_dev + 3 * slot, sizeof(h), hipMemcpyDeviceToHost));
+    if (shader_ticks) *shader_ticks = (int64_t)h[0];
+    if (ref_ticks) *ref_ticks = (int64_t)h[1];
+    if (launches) *launches = (int64_t)h[2];
     return RSD_OK;
 }
 
