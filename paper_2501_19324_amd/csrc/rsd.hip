@@ -1337,7 +1337,7 @@ int rsd_init(rsd_ctx** out, const rsd_model_shape shape[3], const rsd_weights w[
     c->part_k_floats = (size_t)48 << 20;
     HIPCHK(c, dev_alloc(&c->part_k, c->part_k_floats));
     HIPCHK(c, dev_alloc(&c->clk_dev, 3 * RSD_PROBE_SLOTS));
-    HIPCHK(c, hipMemset(c->clk_dev, 0, 3 * RSD_PROBE_SLOTS * sizeof(unsigned long long)));
+    HIPCHK(c, hipMemsetAsync(c->clk_dev, 0, 3 * RSD_PROBE_SLOTS * sizeof(unsigned long long), c->st));
     {
         const size_t kmax = (size_t)std::max(std::max(d, qd), F), xr = std::max<size_t>(R, 64);
         HIPCHK(c, dev_alloc(&c->xs_h, xr * kmax));
@@ -2109,7 +2109,7 @@ int rsd_probe_start(rsd_ctx* c, int32_t slot, int32_t model, int32_t phase, int3
     }
     q.model = model; q.phase = phase; q.op = op; q.stride = stride;
     q.seen = 0; q.iters = 0; q.used = 0; q.bytes = 0; q.flops = 0; q.iter_on = false;
-    HIPCHK(c, hipMemset(c->clk_dev + 3 * slot, 0, 3 * sizeof(unsigned long long)));     // the stream is idle here
+    HIPCHK(c, hipMemsetAsync(c->clk_dev + 3 * slot, 0, 3 * sizeof(unsigned long long), c->st));   // ordered before the probed launches
     return RSD_OK;
 }
 
@@ -2118,7 +2118,8 @@ int rsd_probe_clock(rsd_ctx* c, int32_t slot, int64_t* launches, int64_t* shader
     if (slot < 0 || slot >= RSD_PROBE_SLOTS) return fail(c, RSD_EINVAL, "bad probe slot");
     HIPCHK(c, hipStreamSynchronize(c->st));
     unsigned long long h[3] = {0, 0, 0};
-    HIPCHK(c, hipMemcpy(h, c->clk_dev + 3 * slot, sizeof(h), hipMemcpyDeviceToHost));
+    HIPCHK(c, hipMemcpyAsync(h, c->clk_dev + 3 * slot, sizeof(h), hipMemcpyDeviceToHost, c->st));
+    HIPCHK(c, hipStreamSynchronize(c->st));
     if (shader_ticks) *shader_ticks = (int64_t)h[0];
     if (ref_ticks) *ref_ticks = (int64_t)h[1];
     if (launches) *launches = (int64_t)h[2];
