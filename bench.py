@@ -504,13 +504,28 @@ def main():
         for d in w4.deltas:
             R.rsd_set_criterion(s4.ctx, d)
             per_delta4[str(d)] = slim(run_steps(R, s4, w4, 2, 0, probes=False))
+        # the decode attention kernel alone on the same caches, every sequence at a context of 4096 tokens (the
+        # middle of this configuration's range): one layer launch reads sum(context) x 2 x kv heads x head dim x 2 B
+        import numpy as np
+        attn4 = {}
+        ctx4 = np.full(w4.batch, min(4096, w4.max_ctx), np.int32)
+        for which, name in ((0, "draft"), (1, "target")):
+            try:
+                ms = R.rsd_probe_attention(s4.ctx, which, ctx4, 56)
+            except R.RsdError as e:
+                attn4[name] = {"error": str(e)}
+                continue
+            by = int(ctx4.sum()) * 2 * w4.shapes[which].kv_dim * 2
+            us = ms / 56 * 1e3
+            attn4[name] = {"context": int(ctx4[0]), "bytes_per_launch": by, "avg_launch_us": round(us, 2),
+                           "GBs": round(by / us / 1e3, 1), "frac_of_hbm_peak": round(by / us / 1e3 / HBM_PEAK_GBS, 4)}
         s4.close()
         del s4
         torch.cuda.empty_cache()
         extras["cfg4_per_delta"] = {"workload": workload_text(w4), "steps_timed": 2, "kv_pools_GB": [50, 100, 50],
                                     "note": "each delta: prompts set, then 2 reasoning steps (contexts <= 1280); the run to the "
                                             "pool's end is a separate invocation (--workload cfg4 --until-enomem)",
-                                    "delta": per_delta4}
+                                    "delta": per_delta4, "decode_attention_kernel": attn4}
         # process Best-of-N (the paper's comparison procedure on the same kernels): the 1.5B base model and reward
         # model of configuration 2, 16 sequences x 4 candidates, the paper's sampling setting for it
         from paper_2501_19324_amd.harness import BonSession
