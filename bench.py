@@ -64,6 +64,7 @@ def cpu_baseline(w, budget_layers=None):
     ws = workload(w.name, n_layers=L, batch=n_seq, step_cap=step_cap, max_steps=max_steps)
     threads = min(16, os.cpu_count() or 1)
     models = [O.OracleModel(s, model_weights_np(ws.seed, i, s, threads=threads)) for i, s in enumerate(ws.shapes)]
+    progress("CPU checker: fp64 models generated")
     toks, lens = prompt_tokens(ws), prompt_lengths(ws)
     P = O.Params(delta=ws.delta, sep_id=ws.sep_id, step_cap=ws.step_cap, max_steps=ws.max_steps, max_ctx=ws.max_ctx,
                  temperature=float(np.float32(ws.temperature)), top_p=float(np.float32(ws.top_p)))
@@ -74,6 +75,7 @@ def cpu_baseline(w, budget_layers=None):
     for b in range(n_seq):
         out = O.generate_sequence(models[0], models[1], models[2], toks[b, :lens[b]], ud[b], ut[b], ug[b], P)
         n += len(out["tokens"]) - int(lens[b])
+        progress(f"CPU checker: sequence {b + 1} of {n_seq} done")
     dt = time.time() - t0
     used = [min(f, L) for f in full]
     scale = ""
@@ -85,6 +87,11 @@ def cpu_baseline(w, budget_layers=None):
             "sample": f"{ws.name} shapes at full width and vocabulary, {n_seq} sequences one after the other, prompt {int(lens[0])} tokens + the first "
                       f"{ws.max_steps} reasoning steps of <= {ws.step_cap} tokens ({n} tokens; prompt prefill of all touched "
                       f"models included), {dt:.1f} s" + scale}
+
+
+def progress(msg):
+    """One line on stderr (stdout carries the single JSON record): a run of several minutes shows where it is."""
+    print(f"# [{time.strftime('%H:%M:%S')}] {msg}", file=sys.stderr, flush=True)
 
 
 def blas_threads():
@@ -222,8 +229,9 @@ def run_steps(R, s, w, n_steps, warmup=0, probes=True, probe_stride=8):
     """Warm up, then time n_steps reasoning steps; returns the record of the timed region."""
     import torch
     r = Runner(R, s)
-    for _ in range(warmup):
+    for i in range(warmup):
         r.step()
+        progress(f"warm-up step {i + 1} of {warmup} done")
     base = r.snapshot()
     R.rsd_stage_ms(s.ctx, reset=True)
     for which in (0, 1):
@@ -236,7 +244,8 @@ def run_steps(R, s, w, n_steps, warmup=0, probes=True, probe_stride=8):
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     first_ms, first_tok = 0.0, 0
-    for _ in range(n_steps):
+    t_said = time.perf_counter()
+    for i in range(n_steps):
         new_pass = r.left == 0
         ta = time.perf_counter()
         before = r.tot["tokens"]
@@ -244,6 +253,9 @@ def run_steps(R, s, w, n_steps, warmup=0, probes=True, probe_stride=8):
         if new_pass:            # the first step of a pass holds the prompt prefills
             first_ms += (time.perf_counter() - ta) * 1e3
             first_tok += r.tot["tokens"] - before
+        if time.perf_counter() - t_said > 20.0:       # (the step has ended on the host: rsd_step returns its records)
+            t_said = time.perf_counter()
+            progress(f"timed step {i + 1} of {n_steps} done")
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     t = {k: r.tot[k] - base[k] for k in base}
@@ -391,11 +403,13 @@ def main():
     if merge:
         w = replace(w, prm=replace(w.draft if merge == 1 else w.target, head_kind="reward"))
     delta = w.delta if args.delta is None else args.delta
+    progress(f"{w.name}: generating weights and creating the context")
     t_setup = time.time()
     pools = tuple(int(float(x) * 1e9) for x in args.kv_pool_gb.split(",")) if args.kv_pool_gb else (0, 0, 0)
     s = Session(w, delta=delta, use_graphs=0 if args.no_graphs else 1, kv_pool_bytes=pools, merge_prm=merge, sd_k=args.sd_k)
     torch.cuda.synchronize()
     t_setup = time.time() - t_setup
+    progress(f"set up in {t_setup:.1f} s; stepping")
 
     if args.calib_copy:
         src = torch.ones(64 << 20, dtype=torch.float32, device="cuda")
@@ -477,12 +491,14 @@ def main():
     if not args.no_extras and not args.until_enomem:
         extras = {}
         # configuration 2 (batch 64, ragged prompts): every delta of its sweep, prompt prefill + a few steps each
+        progress("main record done; configuration 2, every delta")
         w2 = workload("cfg2")
         s2 = Session(w2)
         per_delta = {}
         for d in (0.0, 0.5, 0.7, 0.9, 1.01):
             R.rsd_set_criterion(s2.ctx, d)
             per_delta[str(d)] = slim(run_steps(R, s2, w2, 3, 0, probes=(d == 0.7)))
+            progress(f"configuration 2, delta {d} done")
         s2.close()
         del s2
         torch.cuda.empty_cache()
@@ -490,6 +506,7 @@ def main():
                                     "note": "each delta: prompts set, then 3 reasoning steps, the first of which holds the prompt prefills",
                                     "delta": per_delta}
         # configuration 1 (batch 1, top-p sampling): one whole pass
+        progress("configuration 1")
         w1 = workload("cfg1")
         s1 = Session(w1)
         extras["cfg1"] = dict(slim(run_steps(R, s1, w1, w1.max_steps, 2, probes=True, probe_stride=4)), workload=workload_text(w1),
@@ -498,12 +515,14 @@ def main():
         del s1
         torch.cuda.empty_cache()
         # configuration 4 (batch 256, 1024-token prompts, 200 GB of KV pools): prompt prefill + 2 steps per delta
+        progress("configuration 4")
         w4 = workload("cfg4")
         s4 = Session(w4, kv_pool_bytes=(int(50e9), int(100e9), int(50e9)))
         per_delta4 = {}
         for d in w4.deltas:
             R.rsd_set_criterion(s4.ctx, d)
             per_delta4[str(d)] = slim(run_steps(R, s4, w4, 2, 0, probes=False))
+            progress(f"configuration 4, delta {d} done")
         # the decode attention kernel alone on the same caches, every sequence at a context of 4096 tokens (the
         # middle of this configuration's range): one layer launch reads sum(context) x 2 x kv heads x head dim x 2 B
         import numpy as np
@@ -528,6 +547,7 @@ def main():
                                     "delta": per_delta4, "decode_attention_kernel": attn4}
         # process Best-of-N (the paper's comparison procedure on the same kernels): the 1.5B base model and reward
         # model of configuration 2, 16 sequences x 4 candidates, the paper's sampling setting for it
+        progress("process Best-of-N")
         from paper_2501_19324_amd.harness import BonSession
         wb = replace(workload("cfg2", batch=16), temperature=0.7, top_p=0.8)
         sb = BonSession(wb, 4)
@@ -549,6 +569,7 @@ def main():
         torch.cuda.empty_cache()
         line["config"]["other_configs"] = extras
     if not args.no_cpu_baseline:
+        progress("GPU records done; timing the CPU checker on its sample (about half a minute)")
         line["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(line))
 
