@@ -736,10 +736,12 @@ static int gemm_rows_slices(int N, int K, int rows, size_t part_floats) {
     return best;
 }
 
-// Small matrices (at most 14 M weights: the 7B output projection, the 1.5B down and attention projections;
-// from the 7B QKV with 16.5 M on, 256-row blocks at one block per unit are faster) go to the 64-row kernel,
-// with as many K slices as bring the grid to about 450 blocks (4..8, and at least two K blocks each).
-static bool gemm_rows_small(int N, int K) { return (size_t)N * K <= ((size_t)14 << 20); }
+// Small matrices (at most 17 M weights: the 7B QKV and output projections, the 1.5B down and attention
+// projections) go to the 64-row kernel, with as many K slices as bring the grid to about 450 blocks (4..8, and
+// at least two K blocks each).  The 7B QKV (16.5 M) is the largest of them: 16.5 us there against 18.0 us on
+// 256-row blocks at 64 rows, and its 6 instead of 14 K slices make the attention kernel that adds them
+// 2 us faster.
+static bool gemm_rows_small(int N, int K) { return (size_t)N * K <= ((size_t)17 << 20); }
 static int gemm_rows64_slices(int N, int K, int rows, size_t part_floats) {
     const int nb = (N + 63) / 64, nkb = K / 64;
     int ks = std::max(4, std::min(8, (448 + nb / 2) / nb));
