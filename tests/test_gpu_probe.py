@@ -49,7 +49,7 @@ def test_chunked_pass_probe_counts_flops_and_reads_the_clock(gpu):
         assert c["launches"] == r["n"]
         mhz = c["shader_ticks"] / c["ref_ticks"] * 100.0
         print(f"shader clock inside the probed GEMM: {mhz:.0f} MHz over {c['launches']} launches")
-        assert 300.0 < mhz < 2600.0
+        assert 50.0 < mhz < 3000.0          # a clock, not garbage; the value itself is a measurement, not a contract
     # a second arming starts from zero, and a pass of few rows (the weight-streaming kernels) reports no clock
     R.rsd_probe_start(s.ctx, 0, prm, PREFILL, OP_GATE_UP, 64, 1)
     R.rsd_forward(s.ctx, prm, toks[:, :8].copy(), np.full(4, 8, dtype=np.int32), 8)       # 32 rows
